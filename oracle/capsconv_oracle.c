@@ -1,0 +1,179 @@
+/*
+ * Capsule-convolution forward pass: plain CPU oracle.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, obviously-correct statement of what the operator computes.  Only the
+ * tests, the smoke check and the CPU-baseline leg of the bench may call it; the GPU library
+ * never does, and the two share no code.
+ *
+ * Definition followed (paper Sec. 1.2, Algorithm 2 "General capsule convolution", and the
+ * worked example of Fig. 2): every output capsule is the sum, over the kernel window and
+ * the input channels, of (input capsule matrix) x (kernel capsule matrix).  A capsule with a
+ * leading dimension D0 (Fig. 2 uses 3x3x3 capsules) is a batch of D0 independent D1xD2
+ * matrices; the leading index is carried through, never contracted (Algorithm 2's innermost
+ * loop variable c selects one matrix of the batch for input, kernel and output alike).
+ *
+ * Readings of the paper taken here:
+ *   - indices are 0-based; the loops accumulate into an output that starts at zero;
+ *   - the product is  O_caps (D1xD3) += I_caps (D1xD2) . K_caps (D2xD3)   (Sec. 1.2);
+ *   - cross-correlation: input row = row_offset + tap row, no kernel flip (Algorithm 2);
+ *   - row_offset = x * stride (Algorithm 2); symmetric zero padding `pad` is an extension,
+ *     pad = 0 is the paper's operator;  H' = floor((H + 2 pad - kh) / stride) + 1;
+ *   - a batch dimension N is added outermost; images are independent.
+ *
+ * Logical tensors (dense, row-major, last index fastest):
+ *   I[n][h][w][c][d0][d1][d2]      N x H  x W  x C x D0 x D1 x D2
+ *   K[p][q][c][m][d0][d2][d3]      kh x kw x C x M x D0 x D2 x D3   (order of Fig. 2's caption)
+ *   O[n][x][y][m][d0][d1][d3]      N x H' x W' x M x D0 x D1 x D3
+ *
+ * Element values arrive as float (already rounded to the run's storage type by the caller);
+ * every product and every sum is formed in double.  Results are returned in double.
+ * Optionally the sum of absolute values of the products, S = sum |I| * |K|, is returned per
+ * output element: it is the natural scale for a summation-order error bound.
+ */
+#include <stddef.h>
+#include <stdlib.h>
+
+typedef struct {
+    int N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3;
+} capsconv_dims;
+
+static int out_extent(int in, int k, int stride, int pad)
+{
+    int span = in + 2 * pad - k;
+    if (span < 0) return 0;
+    return span / stride + 1;
+}
+
+/* logical-index accessors: no flattening tricks anywhere else */
+static double I_at(const float *I, const capsconv_dims *g, int n, int h, int w, int c, int d0,
+                   int d1, int d2)
+{
+    size_t idx = ((((((size_t)n * g->H + h) * g->W + w) * g->C + c) * g->D0 + d0) * g->D1 + d1) *
+                     g->D2 + d2;
+    return (double)I[idx];
+}
+
+static double K_at(const float *K, const capsconv_dims *g, int p, int q, int c, int m, int d0,
+                   int d2, int d3)
+{
+    size_t idx = ((((((size_t)p * g->kw + q) * g->C + c) * g->M + m) * g->D0 + d0) * g->D2 + d2) *
+                     g->D3 + d3;
+    return (double)K[idx];
+}
+
+/*
+ * One output capsule (n, x, y, m): all D0 x D1 x D3 elements, written to o[d0][d1][d3]
+ * (and s[d0][d1][d3] if s is not NULL).  Algorithm 2's body: for every input channel and
+ * every window tap, one small matrix product per leading index d0, accumulated.
+ */
+static void one_capsule(const float *I, const float *K, const capsconv_dims *g, int n, int x,
+                        int y, int m, double *o, double *s)
+{
+    const int D0 = g->D0, D1 = g->D1, D2 = g->D2, D3 = g->D3;
+    for (int e = 0; e < D0 * D1 * D3; ++e) {
+        o[e] = 0.0;
+        if (s) s[e] = 0.0;
+    }
+    const int row_offset = x * g->stride - g->pad;
+    const int col_offset = y * g->stride - g->pad;
+    for (int c = 0; c < g->C; ++c) {
+        for (int p = 0; p < g->kh; ++p) {
+            for (int q = 0; q < g->kw; ++q) {
+                const int h = row_offset + p;
+                const int w = col_offset + q;
+                if (h < 0 || h >= g->H || w < 0 || w >= g->W) continue; /* zero padding */
+                for (int d0 = 0; d0 < D0; ++d0) {
+                    /* matrix_multiply(I-capsule, K-capsule) accumulated into the O-capsule */
+                    for (int d1 = 0; d1 < D1; ++d1) {
+                        for (int d3 = 0; d3 < D3; ++d3) {
+                            double acc = 0.0, absacc = 0.0;
+                            for (int d2 = 0; d2 < D2; ++d2) {
+                                double a = I_at(I, g, n, h, w, c, d0, d1, d2);
+                                double b = K_at(K, g, p, q, c, m, d0, d2, d3);
+                                double prod = a * b;
+                                acc += prod;
+                                absacc += prod < 0 ? -prod : prod;
+                            }
+                            o[(d0 * D1 + d1) * D3 + d3] += acc;
+                            if (s) s[(d0 * D1 + d1) * D3 + d3] += absacc;
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+/* Output extents; returns 0 on success, -1 if the arguments describe no valid operator. */
+int capsconv_oracle_out_shape(int H, int W, int kh, int kw, int stride, int pad, int *Ho, int *Wo)
+{
+    if (H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0) return -1;
+    if (kh > H + 2 * pad || kw > W + 2 * pad) return -1;
+    *Ho = out_extent(H, kh, stride, pad);
+    *Wo = out_extent(W, kw, stride, pad);
+    return 0;
+}
+
+/*
+ * Full tensor.  O (and S, if not NULL) must hold N*H'*W'*M*D0*D1*D3 doubles.
+ * Returns 0, or -1 on invalid dimensions.
+ */
+int capsconv_oracle_fwd(const float *I, const float *K, double *O, double *S, int N, int H, int W,
+                        int C, int M, int kh, int kw, int stride, int pad, int D0, int D1, int D2,
+                        int D3)
+{
+    capsconv_dims g = {N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3};
+    int Ho, Wo;
+    if (N <= 0 || C <= 0 || M <= 0 || D0 <= 0 || D1 <= 0 || D2 <= 0 || D3 <= 0) return -1;
+    if (capsconv_oracle_out_shape(H, W, kh, kw, stride, pad, &Ho, &Wo)) return -1;
+    const size_t caps = (size_t)D0 * D1 * D3;
+    const long long npix = (long long)N * Ho * Wo;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (long long pix = 0; pix < npix; ++pix) {
+        const int n = (int)(pix / ((long long)Ho * Wo));
+        const int x = (int)((pix / Wo) % Ho);
+        const int y = (int)(pix % Wo);
+        for (int m = 0; m < M; ++m) {
+            size_t base = ((size_t)pix * M + m) * caps;
+            one_capsule(I, K, &g, n, x, y, m, O + base, S ? S + base : NULL);
+        }
+    }
+    return 0;
+}
+
+/*
+ * Subset: `count` output capsules listed as quadruples (n, x, y, m) in `which`
+ * (4*count ints).  O (and S) receive count * D0*D1*D3 doubles, in list order.
+ * Returns 0, -1 on invalid dimensions, -2 if a listed capsule is out of range.
+ */
+int capsconv_oracle_fwd_subset(const float *I, const float *K, double *O, double *S, int N, int H,
+                               int W, int C, int M, int kh, int kw, int stride, int pad, int D0,
+                               int D1, int D2, int D3, const int *which, long long count)
+{
+    capsconv_dims g = {N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3};
+    int Ho, Wo;
+    if (N <= 0 || C <= 0 || M <= 0 || D0 <= 0 || D1 <= 0 || D2 <= 0 || D3 <= 0) return -1;
+    if (capsconv_oracle_out_shape(H, W, kh, kw, stride, pad, &Ho, &Wo)) return -1;
+    for (long long i = 0; i < count; ++i) {
+        const int *w4 = which + 4 * i;
+        if (w4[0] < 0 || w4[0] >= N || w4[1] < 0 || w4[1] >= Ho || w4[2] < 0 || w4[2] >= Wo ||
+            w4[3] < 0 || w4[3] >= M)
+            return -2;
+    }
+    const size_t caps = (size_t)D0 * D1 * D3;
+#pragma omp parallel for schedule(dynamic, 8)
+    for (long long i = 0; i < count; ++i) {
+        const int *w4 = which + 4 * i;
+        one_capsule(I, K, &g, w4[0], w4[1], w4[2], w4[3], O + (size_t)i * caps,
+                    S ? S + (size_t)i * caps : NULL);
+    }
+    return 0;
+}
+
+/* Number of OpenMP threads the loops above will use (for reporting). */
+#ifdef _OPENMP
+#include <omp.h>
+int capsconv_oracle_threads(void) { return omp_get_max_threads(); }
+#else
+int capsconv_oracle_threads(void) { return 1; }
+#endif
