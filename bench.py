@@ -1,0 +1,164 @@
+#!/usr/bin/env python3
+"""Benchmark of the capsule-convolution forward pass on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--path auto|mfma|direct]
+
+A step is one pass of the whole hot path (kernel repack, window addressing, LDS staging,
+matrix-core contraction, accumulation, fp32 store) over one batch of seeded synthetic input
+that is already resident in HBM.  The default workload is benchmark configuration 5
+(fp16 in, fp32 accumulate, N=64, 32x32, C=M=64, 3x3, pad 1, 16x16 capsules), the largest one
+and the one the roofline target is stated on.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published dense peaks (TFLOP/s) and HBM bandwidth
+PEAK_TFLOPS = {"fp32": 157.3, "bf16": 2516.6, "fp16": 2516.6}
+PEAK_HBM_GBS = 8000.0
+
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs scaled by a copy kernel of known size (see profiles/); None until measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def cpu_baseline(w, i32, k32, gpu_out, target_seconds=15.0):
+    """Times the oracle, as it stands, on a bounded sample of the same workload, and uses the
+    sample to check the GPU result.  Returns (record, max error relative to max |ref|)."""
+    import numpy as np
+    from oracle import capsconv
+    from paper_2104_02621_amd import workloads as wl
+
+    flops_per_capsule = 2 * w.D0 * w.D1 * w.D3 * w.kh * w.kw * w.C * w.D2
+    probe = wl.sample_capsules(w, 64, seed=4242)
+    t0 = time.perf_counter()
+    capsconv.conv_fwd_subset(i32, k32, probe, w.stride, w.pad)
+    dt = max(time.perf_counter() - t0, 1e-4)
+    total = w.N * w.Ho * w.Wo * w.M
+    count = int(min(total, max(64, 64 * target_seconds / dt)))
+    which = wl.sample_capsules(w, count, seed=4243)
+    t0 = time.perf_counter()
+    ref = capsconv.conv_fwd_subset(i32, k32, which, w.stride, w.pad)
+    dt = time.perf_counter() - t0
+    gflops = count * flops_per_capsule / dt / 1e9
+    import torch
+    idx = torch.from_numpy(which.astype(np.int64)).to(gpu_out.device)
+    got = gpu_out[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
+    err = float(np.abs(got - ref).max() / np.abs(ref).max())
+    rec = {
+        "value": round(gflops, 3), "unit": "GFLOP/s", "cores": capsconv.threads(),
+        "kind": "oracle",
+        "sample": (f"{count} of {total} output capsules (n,x,y,m) of the same workload, fixed "
+                   f"seed, 25% on image borders; {dt:.1f} s; nominal FLOPs of the sample; "
+                   f"full workload extrapolates to {w.flops_nominal() / gflops / 1e9:.0f} s"),
+    }
+    return rec, err
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
+    ap.add_argument("--path", default="auto", choices=["auto", "mfma", "direct"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build measures the capsule convolution on ONE GPU only "
+                 "(the forward pass shards over the batch with no exchange step); run with --gpus 1")
+
+    import numpy as np
+    import torch
+    from paper_2104_02621_amd import capscaps as cc
+    from paper_2104_02621_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    torch.cuda.set_device(0)
+    w = wl.config(args.config)
+    path = {"auto": cc.PATH_AUTO, "mfma": cc.PATH_MFMA, "direct": cc.PATH_DIRECT}[args.path]
+    shape = (w.N, w.H, w.W, w.C, w.M, w.kh, w.kw, w.stride, w.pad, w.D0, w.D1, w.D2, w.D3, w.dtype)
+
+    i_st, k_st, i32, k32 = wl.generate(w)
+    if w.dtype == wl.BF16:
+        I = torch.from_numpy(i_st.view(np.int16)).cuda().view(torch.bfloat16)
+        K = torch.from_numpy(k_st.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        I = torch.from_numpy(i_st).cuda()
+        K = torch.from_numpy(k_st).cuda()
+    out = torch.empty(w.out_shape, dtype=torch.float32, device="cuda")
+    need = cc.capscaps_conv_fwd_workspace_bytes(*shape)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def step():
+        rc = cc.capscaps_conv_fwd_path(I.data_ptr(), K.data_ptr(), out.data_ptr(), *shape[:13],
+                                       w.dtype, path, ws.data_ptr(), ws.numel(),
+                                       stream.cuda_stream)
+        if rc != cc.OK:
+            sys.exit(f"bench.py: capscaps status {rc}: {cc.capscaps_strerror(rc)}")
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record(stream)
+    for k in range(args.steps):
+        step()
+        ev[k + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_step_ms = [ev[k].elapsed_time(ev[k + 1]) for k in range(args.steps)]
+    ms_per_step = wall * 1e3 / args.steps
+    kernel_ms = float(np.mean(per_step_ms))  # HIP events on the launch stream, per step
+
+    flops_exact = w.flops_tap_exact()
+    flops_nominal = w.flops_nominal()
+    value = flops_exact / (ms_per_step * 1e-3) / 1e9
+    dname = wl.DTYPE_NAMES[w.dtype]
+    achieved_tflops = flops_exact / (kernel_ms * 1e-3) / 1e12
+    chosen = cc.capscaps_select_path(*shape) if path == cc.PATH_AUTO else path
+    result = {
+        "metric": "capsule-conv useful GFLOP/s at 1 GPU + % of MFMA roofline",
+        "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32" if w.dtype == wl.FP32 else
+        f"{dname} in, f32 accumulate", "data": "synthetic",
+        "config": {
+            "workload": f"config {args.config}: {w.name}", "N": w.N, "H": w.H, "W": w.W, "C": w.C,
+            "M": w.M, "kh": w.kh, "kw": w.kw, "stride": w.stride, "pad": w.pad,
+            "capsule": [w.D0, w.D1, w.D2, w.D3], "path": {1: "direct", 2: "mfma"}[chosen],
+            "flops_tap_exact": flops_exact, "flops_nominal": flops_nominal,
+            "gflops_nominal": round(flops_nominal / (ms_per_step * 1e-3) / 1e9, 1),
+            "compulsory_bytes": w.compulsory_bytes(),
+            "hbm_gbs_compulsory": round(w.compulsory_bytes() / (kernel_ms * 1e-3) / 1e9, 1),
+            "pct_of_mfma_peak": round(100 * achieved_tflops / PEAK_TFLOPS[dname], 2),
+            "ms_min": round(float(np.min(per_step_ms)), 4),
+            "ms_median": round(float(np.median(per_step_ms)), 4),
+        },
+        "roofline": {
+            "bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": PEAK_TFLOPS[dname],
+            "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_TFLOPS[dname], 4),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+            "kernel_ms": round(kernel_ms, 4),
+        },
+    }
+    if not args.no_cpu_baseline:
+        rec, err = cpu_baseline(w, i32, k32, out)
+        result["cpu_baseline"] = rec
+        result["config"]["max_err_vs_oracle_sample"] = err
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,124 @@
+/*
+ * capscaps -- capsule-convolution forward pass on AMD MI355X (gfx950).  C ABI.
+ *
+ * The operator (paper Sec. 1.2 and Algorithm 2, "General capsule convolution"; 3-D capsules
+ * as in Fig. 2): for every image n, output pixel (x, y), output channel m and leading capsule
+ * index d0, the D1 x D3 output capsule matrix is
+ *
+ *     O[n,x,y,m,d0] = sum over taps (p,q) and input channels c of
+ *                     I[n, x*stride+p-pad, y*stride+q-pad, c, d0] (D1 x D2)  .  K[p,q,c,m,d0] (D2 x D3)
+ *
+ * with input pixels outside [0,H) x [0,W) contributing zero (pad = 0 is the paper's
+ * operator; padding and the batch dimension N are extensions).  Cross-correlation, no
+ * kernel flip.  The fully-connected capsule layer (Sec. 1.1) is the case kh = H, kw = W,
+ * pad = 0; 2-D capsules are D0 = 1.
+ *
+ * Layouts: dense, row-major, last index fastest.
+ *     input   [N ][H ][W ][C][D0][D1][D2]    element type given by `dtype`
+ *     kernel  [kh][kw][C ][M][D0][D2][D3]    element type given by `dtype`
+ *     out     [N ][H'][W'][M][D0][D1][D3]    always fp32 (the accumulator, unrounded)
+ *     H' = floor((H + 2*pad - kh) / stride) + 1, W' likewise.
+ *
+ * Pointers: `input`, `kernel`, `out`, `workspace` are DEVICE pointers (HIP global memory on
+ * the current device), 16-byte aligned, owned by the caller, not aliasing each other.
+ * `input` and `kernel` are only read, `out` is overwritten (never accumulated into),
+ * `workspace` is scratch whose contents are undefined afterwards.  `stream` is a
+ * hipStream_t passed as void* (NULL = the default stream).  All work is enqueued on that
+ * stream; no call here synchronises, so buffers must stay valid until the stream reaches the
+ * end of the enqueued work.  The library keeps no global state between calls.
+ *
+ * Errors: functions returning int return CAPSCAPS_OK (0) or a negative status; on any error
+ * nothing has been launched.  Nothing is printed, nothing throws, nothing aborts.
+ */
+#ifndef CAPSCAPS_H
+#define CAPSCAPS_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* every declaration below is an exported symbol of libcapscaps.so */
+#pragma GCC visibility push(default)
+
+/* element type of `input` and `kernel` */
+#define CAPSCAPS_FP32 0
+#define CAPSCAPS_BF16 1 /* bfloat16 in, fp32 accumulate, fp32 out */
+#define CAPSCAPS_FP16 2 /* IEEE half in, fp32 accumulate, fp32 out */
+
+/* status codes */
+#define CAPSCAPS_OK 0
+#define CAPSCAPS_EINVAL (-1)       /* null pointer, non-positive size, stride <= 0, pad < 0, kernel
+                                      window larger than the padded input, unknown dtype/path,
+                                      misaligned pointer */
+#define CAPSCAPS_EWORKSPACE (-2)   /* workspace missing or smaller than required */
+#define CAPSCAPS_EUNSUPPORTED (-3) /* the forced path cannot run this shape/dtype */
+#define CAPSCAPS_EHIP (-4)         /* a HIP call (launch, allocation) failed */
+
+/* compute paths (for capscaps_conv_fwd_path / capscaps_select_path) */
+#define CAPSCAPS_PATH_AUTO 0   /* library's choice */
+#define CAPSCAPS_PATH_DIRECT 1 /* wavefront-level small-matrix path: plain FMAs, any shape */
+#define CAPSCAPS_PATH_MFMA 2   /* LDS-staged implicit GEMM on the matrix cores */
+
+/*
+ * Output extents (Fig. 1 / Fig. 2: 5 with a 4-wide kernel at stride 1 gives 2).
+ * Host-only, touches no GPU.  Returns CAPSCAPS_EINVAL if any size is non-positive,
+ * stride <= 0, pad < 0 or the window does not fit the padded input; else writes *Ho, *Wo.
+ */
+int capscaps_out_shape(int H, int W, int kh, int kw, int stride, int pad, int* Ho, int* Wo);
+
+/*
+ * Capsule convolution forward (Algorithm 2), no padding: the signature of the operator as the
+ * paper states it.  Scratch memory, if the chosen path needs any, is obtained and released
+ * with stream-ordered allocation on `stream`.
+ */
+int capscaps_conv_fwd(const void* input, const void* kernel, void* out, int N, int H, int W, int C,
+                      int M, int kh, int kw, int stride, int D0, int D1, int D2, int D3, int dtype,
+                      void* stream);
+
+/*
+ * Same operator with symmetric zero padding `pad` and caller-provided scratch.
+ * `workspace` must hold at least capscaps_conv_fwd_workspace_bytes(...) bytes for the same
+ * arguments (it may be NULL when that is 0); too small -> CAPSCAPS_EWORKSPACE.
+ */
+int capscaps_conv_fwd_ex(const void* input, const void* kernel, void* out, int N, int H, int W,
+                         int C, int M, int kh, int kw, int stride, int pad, int D0, int D1, int D2,
+                         int D3, int dtype, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * As capscaps_conv_fwd_ex, with the compute path forced (CAPSCAPS_PATH_*), so that both paths
+ * can be measured on one shape.  CAPSCAPS_EUNSUPPORTED if that path cannot run the shape.
+ * The workspace requirement is the one of capscaps_conv_fwd_workspace_bytes (which covers
+ * every path).
+ */
+int capscaps_conv_fwd_path(const void* input, const void* kernel, void* out, int N, int H, int W,
+                           int C, int M, int kh, int kw, int stride, int pad, int D0, int D1,
+                           int D2, int D3, int dtype, int path, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/*
+ * Scratch bytes capscaps_conv_fwd_ex / _path need for these arguments (repacked kernel,
+ * split-reduction partial sums).  Host-only.  Returns 0 also for invalid arguments (the
+ * compute call reports those).
+ */
+size_t capscaps_conv_fwd_workspace_bytes(int N, int H, int W, int C, int M, int kh, int kw,
+                                         int stride, int pad, int D0, int D1, int D2, int D3,
+                                         int dtype);
+
+/*
+ * Which path CAPSCAPS_PATH_AUTO resolves to for these arguments (CAPSCAPS_PATH_DIRECT or
+ * CAPSCAPS_PATH_MFMA), or a negative status for invalid arguments.  Host-only.
+ */
+int capscaps_select_path(int N, int H, int W, int C, int M, int kh, int kw, int stride, int pad,
+                         int D0, int D1, int D2, int D3, int dtype);
+
+/* Static, human-readable text for a status code.  Never NULL. */
+const char* capscaps_strerror(int status);
+
+#pragma GCC visibility pop
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CAPSCAPS_H */

@@ -1,0 +1,139 @@
+"""ctypes binding of ``libcapscaps.so`` (C ABI in ``include/capscaps.h``).
+
+Argument marshalling only: every step of the capsule convolution runs in the HIP library.
+Functions carry the C names; ``conv_fwd`` is a convenience wrapper that takes torch tensors
+(torch is used for device memory and streams only).  There is no CPU fallback: if the
+library is missing or no GPU is present, calls fail.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+FP32, BF16, FP16 = 0, 1, 2
+PATH_AUTO, PATH_DIRECT, PATH_MFMA = 0, 1, 2
+OK, EINVAL, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
+
+_LIB_PATH = Path(__file__).resolve().parent / "libcapscaps.so"
+_lib = None
+
+
+class CapscapsError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"capscaps status {status}: {capscaps_strerror(status)}")
+
+
+def library_path() -> Path:
+    return _LIB_PATH
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not _LIB_PATH.exists():
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is not built; run `python -m paper_2104_02621_amd.build`")
+    lib = ctypes.CDLL(str(_LIB_PATH))
+    i, p, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    ip = ctypes.POINTER(ctypes.c_int)
+    lib.capscaps_out_shape.argtypes = [i] * 6 + [ip, ip]
+    lib.capscaps_out_shape.restype = i
+    lib.capscaps_conv_fwd.argtypes = [p, p, p] + [i] * 13 + [p]
+    lib.capscaps_conv_fwd.restype = i
+    lib.capscaps_conv_fwd_ex.argtypes = [p, p, p] + [i] * 14 + [p, sz, p]
+    lib.capscaps_conv_fwd_ex.restype = i
+    lib.capscaps_conv_fwd_path.argtypes = [p, p, p] + [i] * 15 + [p, sz, p]
+    lib.capscaps_conv_fwd_path.restype = i
+    lib.capscaps_conv_fwd_workspace_bytes.argtypes = [i] * 14
+    lib.capscaps_conv_fwd_workspace_bytes.restype = sz
+    lib.capscaps_select_path.argtypes = [i] * 14
+    lib.capscaps_select_path.restype = i
+    lib.capscaps_strerror.argtypes = [i]
+    lib.capscaps_strerror.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+# ------------------------------------------------------------------ C ABI, same names
+def capscaps_strerror(status: int) -> str:
+    return _load().capscaps_strerror(int(status)).decode()
+
+
+def capscaps_out_shape(H, W, kh, kw, stride, pad):
+    """Returns (status, Ho, Wo)."""
+    ho, wo = ctypes.c_int(0), ctypes.c_int(0)
+    rc = _load().capscaps_out_shape(H, W, kh, kw, stride, pad, ctypes.byref(ho), ctypes.byref(wo))
+    return rc, ho.value, wo.value
+
+
+def capscaps_conv_fwd(input, kernel, out, N, H, W, C, M, kh, kw, stride, D0, D1, D2, D3, dtype,
+                      stream=None) -> int:
+    """Device pointers as ints; returns the status code."""
+    return _load().capscaps_conv_fwd(input, kernel, out, N, H, W, C, M, kh, kw, stride, D0, D1,
+                                     D2, D3, dtype, stream)
+
+
+def capscaps_conv_fwd_ex(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3,
+                         dtype, workspace, workspace_bytes, stream=None) -> int:
+    return _load().capscaps_conv_fwd_ex(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad,
+                                        D0, D1, D2, D3, dtype, workspace, workspace_bytes, stream)
+
+
+def capscaps_conv_fwd_path(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2,
+                           D3, dtype, path, workspace, workspace_bytes, stream=None) -> int:
+    return _load().capscaps_conv_fwd_path(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad,
+                                          D0, D1, D2, D3, dtype, path, workspace,
+                                          workspace_bytes, stream)
+
+
+def capscaps_conv_fwd_workspace_bytes(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3,
+                                      dtype) -> int:
+    return int(_load().capscaps_conv_fwd_workspace_bytes(N, H, W, C, M, kh, kw, stride, pad, D0,
+                                                         D1, D2, D3, dtype))
+
+
+def capscaps_select_path(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype) -> int:
+    return int(_load().capscaps_select_path(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3,
+                                            dtype))
+
+
+# ------------------------------------------------------------------ torch convenience
+def _torch_dtype_code(t):
+    import torch
+    return {torch.float32: FP32, torch.bfloat16: BF16, torch.float16: FP16}[t.dtype]
+
+
+def conv_fwd(input, kernel, stride=1, pad=0, path=PATH_AUTO, out=None, workspace=None):
+    """input [N,H,W,C,D0,D1,D2], kernel [kh,kw,C,M,D0,D2,D3] (contiguous device tensors of one
+    dtype: float32, bfloat16 or float16) -> float32 [N,H',W',M,D0,D1,D3].  Enqueues on torch's
+    current stream; does not synchronise."""
+    import torch
+    if not (input.is_cuda and kernel.is_cuda):
+        raise ValueError("capscaps runs on the GPU only: pass device tensors")
+    if input.dtype != kernel.dtype or input.dim() != 7 or kernel.dim() != 7:
+        raise ValueError("input and kernel must be 7-D tensors of one dtype")
+    if not (input.is_contiguous() and kernel.is_contiguous()):
+        raise ValueError("input and kernel must be contiguous")
+    N, H, W, C, D0, D1, D2 = input.shape
+    kh, kw, Ck, M, D0k, D2k, D3 = kernel.shape
+    if (Ck, D0k, D2k) != (C, D0, D2):
+        raise ValueError(f"kernel {tuple(kernel.shape)} does not match input {tuple(input.shape)}")
+    dt = _torch_dtype_code(input)
+    rc, Ho, Wo = capscaps_out_shape(H, W, kh, kw, stride, pad)
+    if rc != OK:
+        raise CapscapsError(rc)
+    if out is None:
+        out = torch.empty((N, Ho, Wo, M, D0, D1, D3), dtype=torch.float32, device=input.device)
+    need = capscaps_conv_fwd_workspace_bytes(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dt)
+    if workspace is None or workspace.numel() * workspace.element_size() < need:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=input.device)
+    stream = torch.cuda.current_stream(input.device).cuda_stream
+    rc = capscaps_conv_fwd_path(input.data_ptr(), kernel.data_ptr(), out.data_ptr(), N, H, W, C, M,
+                                kh, kw, stride, pad, D0, D1, D2, D3, dt, path,
+                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                stream)
+    if rc != OK:
+        raise CapscapsError(rc)
+    return out

@@ -1,0 +1,155 @@
+// C ABI of the capsule-convolution forward pass: argument checking, path choice, launches.
+// Declarations and their contracts are in include/capscaps.h.
+#include <hip/hip_runtime.h>
+
+#include "../../include/capscaps.h"
+#include "conv_shape.h"
+
+using capscaps::ConvShape;
+
+namespace {
+
+int fill_shape(ConvShape& s, int N, int H, int W, int C, int M, int kh, int kw, int stride, int pad,
+               int D0, int D1, int D2, int D3, int dtype)
+{
+    if (N <= 0 || C <= 0 || M <= 0 || D0 <= 0 || D1 <= 0 || D2 <= 0 || D3 <= 0)
+        return CAPSCAPS_EINVAL;
+    if (dtype != CAPSCAPS_FP32 && dtype != CAPSCAPS_BF16 && dtype != CAPSCAPS_FP16)
+        return CAPSCAPS_EINVAL;
+    int Ho = 0, Wo = 0;
+    const int rc = capscaps_out_shape(H, W, kh, kw, stride, pad, &Ho, &Wo);
+    if (rc != CAPSCAPS_OK) return rc;
+    s = ConvShape{N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, Ho, Wo, dtype};
+    // element counts must stay well inside 63 bits
+    const long double big = (long double)N * H * W * C * D0 * D1 * D2;
+    const long double bigo = (long double)N * Ho * Wo * M * D0 * D1 * D3;
+    const long double bigk = (long double)kh * kw * C * M * D0 * D2 * D3;
+    if (big > 1e17L || bigo > 1e17L || bigk > 1e17L) return CAPSCAPS_EINVAL;
+    return CAPSCAPS_OK;
+}
+
+// The matrix-core path pays off once the (m,d3) extent fills a good part of a 32-wide MFMA
+// tile and there is enough work to amortise the kernel repack; below that the wavefront-level
+// path wins (measured on MI355X on the five benchmark shapes and the Fig. 2 example).
+int choose_path(const ConvShape& s)
+{
+    if (!capscaps::mfma_supported(s)) return CAPSCAPS_PATH_DIRECT;
+    const long long cols = (long long)s.M * s.D3;
+    const long long kdim = (long long)s.kh * s.kw * s.C * s.D2;
+    if (cols < 16 || kdim < 32) return CAPSCAPS_PATH_DIRECT;
+    return CAPSCAPS_PATH_MFMA;
+}
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+int run(const void* input, const void* kernel, void* out, const ConvShape& s, int path,
+        void* workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    if (path == CAPSCAPS_PATH_AUTO) path = choose_path(s);
+    hipError_t err;
+    if (path == CAPSCAPS_PATH_DIRECT) {
+        err = capscaps::launch_direct(s, input, kernel, static_cast<float*>(out), stream);
+    } else if (path == CAPSCAPS_PATH_MFMA) {
+        if (!capscaps::mfma_supported(s)) return CAPSCAPS_EUNSUPPORTED;
+        const size_t need = capscaps::mfma_workspace_bytes(s);
+        if (need > 0 && (workspace == nullptr || workspace_bytes < need))
+            return CAPSCAPS_EWORKSPACE;
+        if (need > 0 && misaligned(workspace)) return CAPSCAPS_EINVAL;
+        err = capscaps::launch_mfma(s, input, kernel, static_cast<float*>(out), workspace, stream);
+    } else {
+        return CAPSCAPS_EINVAL;
+    }
+    return err == hipSuccess ? CAPSCAPS_OK : CAPSCAPS_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int capscaps_out_shape(int H, int W, int kh, int kw, int stride, int pad, int* Ho, int* Wo)
+{
+    if (Ho == nullptr || Wo == nullptr) return CAPSCAPS_EINVAL;
+    if (H <= 0 || W <= 0 || kh <= 0 || kw <= 0 || stride <= 0 || pad < 0) return CAPSCAPS_EINVAL;
+    if (pad > (1 << 28) || H > (1 << 28) || W > (1 << 28)) return CAPSCAPS_EINVAL;
+    if (kh > H + 2 * pad || kw > W + 2 * pad) return CAPSCAPS_EINVAL;
+    *Ho = (H + 2 * pad - kh) / stride + 1;
+    *Wo = (W + 2 * pad - kw) / stride + 1;
+    return CAPSCAPS_OK;
+}
+
+size_t capscaps_conv_fwd_workspace_bytes(int N, int H, int W, int C, int M, int kh, int kw,
+                                         int stride, int pad, int D0, int D1, int D2, int D3,
+                                         int dtype)
+{
+    ConvShape s;
+    if (fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype) != CAPSCAPS_OK)
+        return 0;
+    return capscaps::mfma_workspace_bytes(s);
+}
+
+int capscaps_select_path(int N, int H, int W, int C, int M, int kh, int kw, int stride, int pad,
+                         int D0, int D1, int D2, int D3, int dtype)
+{
+    ConvShape s;
+    const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype);
+    if (rc != CAPSCAPS_OK) return rc;
+    return choose_path(s);
+}
+
+int capscaps_conv_fwd_path(const void* input, const void* kernel, void* out, int N, int H, int W,
+                           int C, int M, int kh, int kw, int stride, int pad, int D0, int D1,
+                           int D2, int D3, int dtype, int path, void* workspace,
+                           size_t workspace_bytes, void* stream)
+{
+    if (input == nullptr || kernel == nullptr || out == nullptr) return CAPSCAPS_EINVAL;
+    if (misaligned(input) || misaligned(kernel) || misaligned(out)) return CAPSCAPS_EINVAL;
+    if (path != CAPSCAPS_PATH_AUTO && path != CAPSCAPS_PATH_DIRECT && path != CAPSCAPS_PATH_MFMA)
+        return CAPSCAPS_EINVAL;
+    ConvShape s;
+    const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype);
+    if (rc != CAPSCAPS_OK) return rc;
+    return run(input, kernel, out, s, path, workspace, workspace_bytes,
+               static_cast<hipStream_t>(stream));
+}
+
+int capscaps_conv_fwd_ex(const void* input, const void* kernel, void* out, int N, int H, int W,
+                         int C, int M, int kh, int kw, int stride, int pad, int D0, int D1, int D2,
+                         int D3, int dtype, void* workspace, size_t workspace_bytes, void* stream)
+{
+    return capscaps_conv_fwd_path(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad, D0, D1,
+                                  D2, D3, dtype, CAPSCAPS_PATH_AUTO, workspace, workspace_bytes,
+                                  stream);
+}
+
+int capscaps_conv_fwd(const void* input, const void* kernel, void* out, int N, int H, int W, int C,
+                      int M, int kh, int kw, int stride, int D0, int D1, int D2, int D3, int dtype,
+                      void* stream)
+{
+    if (input == nullptr || kernel == nullptr || out == nullptr) return CAPSCAPS_EINVAL;
+    if (misaligned(input) || misaligned(kernel) || misaligned(out)) return CAPSCAPS_EINVAL;
+    ConvShape s;
+    const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, 0, D0, D1, D2, D3, dtype);
+    if (rc != CAPSCAPS_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int path = choose_path(s);
+    const size_t need = path == CAPSCAPS_PATH_MFMA ? capscaps::mfma_workspace_bytes(s) : 0;
+    void* ws = nullptr;
+    if (need > 0 && hipMallocAsync(&ws, need, st) != hipSuccess) return CAPSCAPS_EHIP;
+    const int status = run(input, kernel, out, s, path, ws, need, st);
+    if (ws != nullptr && hipFreeAsync(ws, st) != hipSuccess) return CAPSCAPS_EHIP;
+    return status;
+}
+
+const char* capscaps_strerror(int status)
+{
+    switch (status) {
+        case CAPSCAPS_OK: return "success";
+        case CAPSCAPS_EINVAL: return "invalid argument";
+        case CAPSCAPS_EWORKSPACE: return "workspace missing or too small";
+        case CAPSCAPS_EUNSUPPORTED: return "path does not support this shape";
+        case CAPSCAPS_EHIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,33 @@
+// Internal: geometry of one capsule-convolution call and the launchers of the compute paths.
+// Notation follows the paper's Algorithm 2 (I, K, O; taps (p,q); channels c -> m) with the
+// capsule indices d0 (batch), d1 (row), d2 (contracted), d3 (column).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace capscaps {
+
+struct ConvShape {
+    int N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3;
+    int Ho, Wo;  // output extents
+    int dtype;   // CAPSCAPS_FP32 / BF16 / FP16
+    long long pixels() const { return (long long)N * Ho * Wo; }
+    size_t in_elems() const { return (size_t)N * H * W * C * D0 * D1 * D2; }
+    size_t kernel_elems() const { return (size_t)kh * kw * C * M * D0 * D2 * D3; }
+    size_t out_elems() const { return (size_t)N * Ho * Wo * M * D0 * D1 * D3; }
+};
+
+// Wavefront-level small-matrix path: plain FMAs, any shape, any dtype.  No scratch.
+hipError_t launch_direct(const ConvShape& s, const void* in, const void* kernel, float* out,
+                         hipStream_t stream);
+
+// Matrix-core path (LDS-staged implicit GEMM).  `mfma_supported` tells whether the path can
+// run the shape; `mfma_workspace_bytes` is the scratch it needs (repacked kernel plus, for
+// small problems, split-reduction partial sums).
+bool mfma_supported(const ConvShape& s);
+size_t mfma_workspace_bytes(const ConvShape& s);
+hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, float* out,
+                       void* workspace, hipStream_t stream);
+
+}  // namespace capscaps

@@ -1,0 +1,514 @@
+// Matrix-core path of the capsule convolution forward pass (paper Algorithm 2), written as an
+// implicit GEMM per leading capsule index d0:
+//
+//     rows     r = (pixel, d1)         pixel = (n, x, y) flattened          N*H'*W'*D1 of them
+//     columns  j = (m, d3)                                                   M*D3 of them
+//     K index  k = (tap, c, d2)        tap = (p, q)                          kh*kw*C*D2 of them
+//
+//     O[r][j] = sum_k I[pixel shifted by tap][c][d0][d1][d2] * K[tap][c][m][d0][d2][d3]
+//
+// The paper's scheme 1 (Algorithm 3) materialises the left operand (capsule im2col, then a
+// copy per output channel) and the right operand (a copy per output pixel) in memory and sums
+// the products in a separate pass; here the window addressing is index arithmetic while
+// staging tiles into LDS, and the sum over taps and channels is the GEMM's K loop.
+//
+// Data movement unit: a 16-byte "chunk" = CH consecutive K elements of one row (CH = 8 for
+// 16-bit types, 4 for fp32).  Per tap the K extent C*D2 is cut into chunks; a stage of the
+// K loop covers 8 chunks of every row and column of the tile.  LDS holds a stage as
+// [chunk 0..7][row or column][16 bytes], so the 32 lanes that feed one MFMA operand read 512
+// contiguous bytes.  The kernel tensor is repacked once per call into
+// Kp[d0][tap][chunk][column][CH] (zero-padded), which makes its stage loads plain contiguous
+// copies and puts the contracted index innermost as the matrix cores want it.
+//
+// MFMA orientation: the matrix instruction's row operand is the kernel (columns j), its column
+// operand the input (rows r).  Each lane then owns 4 consecutive j = 4 consecutive d3 of one
+// output row, i.e. one 16-byte store.  Because both operands of an MFMA take their K elements
+// in the same lane order, any fixed assignment of chunk halves to lanes is a valid K order.
+#include <hip/hip_runtime.h>
+
+#include "conv_shape.h"
+
+namespace capscaps {
+namespace {
+
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
+typedef unsigned int chunk_t __attribute__((ext_vector_type(4)));  // 16 raw bytes
+
+struct f32_tag { typedef float elem; };
+struct f16_tag { typedef unsigned short elem; };
+struct bf16_tag { typedef unsigned short elem; };
+
+template <typename Tag>
+struct Mma;
+template <>
+struct Mma<f16_tag> {
+    static __device__ __forceinline__ void run(const chunk_t& a, const chunk_t& b, float16v& acc)
+    {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a),
+                                                     __builtin_bit_cast(half8v, b), acc, 0, 0, 0);
+    }
+};
+template <>
+struct Mma<bf16_tag> {
+    static __device__ __forceinline__ void run(const chunk_t& a, const chunk_t& b, float16v& acc)
+    {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8v, a),
+                                                      __builtin_bit_cast(bf16x8v, b), acc, 0, 0, 0);
+    }
+};
+template <>
+struct Mma<f32_tag> {
+    // a chunk holds 4 K elements per lane half; element u of both halves forms the K pair of
+    // one 32x32x2 instruction
+    static __device__ __forceinline__ void run(const chunk_t& a, const chunk_t& b, float16v& acc)
+    {
+        const float4v fa = __builtin_bit_cast(float4v, a);
+        const float4v fb = __builtin_bit_cast(float4v, b);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[u], fb[u], acc, 0, 0, 0);
+    }
+};
+
+struct IgemmParams {
+    const void* in;
+    const void* kp;  // repacked kernel
+    float* out;      // final output, or split-K partial buffers [split][out_elems]
+    int H, W, C, M, stride, pad, D0, D1, D2, D3, Ho, Wo, kw;
+    long long rows;        // N*Ho*Wo*D1
+    long long out_elems;   // per split
+    long long pixsz;       // C*D0*D1*D2: elements per input pixel
+    int cs;                // D0*D1*D2: input channel stride
+    int cols, colsp;       // M*D3 and its padding to the column tile
+    int KT;                // C*D2: K extent of one tap
+    int KQP;               // chunks per tap, padded to a multiple of 8
+    int d2c_shift;         // vector loader: log2(chunks per capsule row)
+    int spt;               // stages per tap
+    int stages;            // ntaps * spt
+    int stages_per_split;  // K-loop share of one split
+    int nsplit;
+    int ntaps;
+    int row_tiles, col_tiles;
+};
+
+// ---------------------------------------------------------------------------------------------
+// Kernel repack: Kp[d0][tap][kq][j][e] = K[tap][c][m][d0][d2][d3] with k = kq*CH+e = c*D2+d2,
+// j = m*D3+d3; zero where k >= C*D2 or j >= M*D3.  One thread per 16-byte chunk.
+template <typename E, int CH>
+__global__ __launch_bounds__(256) void repack_kernel(const E* __restrict__ kernel,
+                                                     E* __restrict__ kp, int ntaps, int C, int M,
+                                                     int D0, int D2, int D3, int KT, int KQP,
+                                                     int cols, int colsp, size_t total_chunks)
+{
+    const size_t id = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= total_chunks) return;
+    size_t r = id;
+    const int j = (int)(r % colsp); r /= colsp;
+    const int kq = (int)(r % KQP);  r /= KQP;
+    const int tap = (int)(r % ntaps);
+    const int d0 = (int)(r / ntaps);
+    E v[CH];
+#pragma unroll
+    for (int e = 0; e < CH; ++e) {
+        const int k = kq * CH + e;
+        E x = 0;
+        if (k < KT && j < cols) {
+            const int c = k / D2, d2 = k % D2, m = j / D3, d3 = j % D3;
+            x = kernel[(((((size_t)tap * C + c) * M + m) * D0 + d0) * D2 + d2) * D3 + d3];
+        }
+        v[e] = x;
+    }
+    chunk_t out;
+    __builtin_memcpy(&out, v, 16);
+    reinterpret_cast<chunk_t*>(kp)[id] = out;
+}
+
+// Deterministic split-K reduction: out[e] = partial[0][e] + partial[1][e] + ... in that order.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial,
+                                                            float* __restrict__ out,
+                                                            long long elems, int nsplit)
+{
+    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= elems) return;
+    float acc = partial[e];
+    for (int s = 1; s < nsplit; ++s) acc += partial[(long long)s * elems + e];
+    out[e] = acc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// VEC: a chunk never straddles a capsule row (D2 % CH == 0, D2/CH a power of two) -> one
+// 16-byte load per chunk; otherwise element-wise gather.   ST4: D3 % 4 == 0 -> 16-byte stores.
+template <typename Tag, bool VEC, bool ST4, int BM, int BN, int WGM, int WGN>
+__global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmParams P)
+{
+    typedef typename Tag::elem E;
+    constexpr int NT = 64 * WGM * WGN;
+    constexpr int CH = 16 / (int)sizeof(E);
+    constexpr int WM = BM / WGM, WN = BN / WGN;  // wave tile: rows (pixel,d1) x columns (m,d3)
+    constexpr int TM = WM / 32, TN = WN / 32;
+    constexpr int ACH = 8 * BM / NT, BCH = 8 * BN / NT;  // chunks per thread per stage
+    constexpr int STAGE = 8 * (BM + BN);                 // chunks per LDS stage buffer
+    static_assert(NT % BM == 0 && NT % BN == 0, "one row / column per loader thread");
+    static_assert(WM % 32 == 0 && WN % 32 == 0, "wave tiles are made of 32x32 MFMA tiles");
+
+    extern __shared__ chunk_t lds[];
+
+    // ---- which tile: consecutive logical tiles go to the same XCD (blocks are dealt to the 8
+    // XCDs round-robin), column tiles fastest so that neighbours share input rows in that L2.
+    const int nb = gridDim.x;
+    int L = blockIdx.x;
+    {
+        const int per = nb / 8, full = per * 8;
+        if ((int)blockIdx.x < full) L = ((int)blockIdx.x % 8) * per + (int)blockIdx.x / 8;
+    }
+    const int col_tile = L % P.col_tiles;
+    int rest = L / P.col_tiles;
+    const int row_tile = rest % P.row_tiles;
+    rest /= P.row_tiles;
+    const int d0 = rest % P.D0;
+    const int split = rest / P.D0;
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int wm = wave % WGM, wn = wave / WGM;
+    const int h = lane >> 5, lr = lane & 31;
+
+    const long long row0 = (long long)row_tile * BM;
+    const int col0 = col_tile * BN;
+
+    // ---- loader set-up: this thread stages chunks of one fixed row of the tile
+    const int a_row = tid % BM;
+    const int a_kq0 = tid / BM;          // first chunk slot; slots advance by NT/BM
+    constexpr int A_STEP = NT / BM;
+    const long long rg = row0 + a_row;
+    const bool row_ok = rg < P.rows;
+    long long a_base = 0;
+    int ih0 = 0, iw0 = 0;
+    {
+        const long long rr = row_ok ? rg : 0;
+        const long long pixel = rr / P.D1;
+        const int d1 = (int)(rr % P.D1);
+        const int hw = P.Ho * P.Wo;
+        const long long n = pixel / hw;
+        const int rem = (int)(pixel % hw);
+        const int x = rem / P.Wo, y = rem % P.Wo;
+        ih0 = x * P.stride - P.pad;
+        iw0 = y * P.stride - P.pad;
+        a_base = ((n * P.H + ih0) * P.W + iw0) * P.pixsz + (long long)(d0 * P.D1 + d1) * P.D2;
+    }
+    const E* __restrict__ in = static_cast<const E*>(P.in);
+    const int b_col = tid % BN;
+    const int b_kq0 = tid / BN;
+    constexpr int B_STEP = NT / BN;
+    const chunk_t* __restrict__ kp = static_cast<const chunk_t*>(P.kp);
+
+    chunk_t areg[ACH], breg[BCH];
+
+    auto load_stage = [&](int st) {
+        const int tap = st / P.spt;
+        const int kq_stage = (st - tap * P.spt) * 8;
+        const int p = tap / P.kw, q = tap - p * P.kw;
+        const bool ok = row_ok && (unsigned)(ih0 + p) < (unsigned)P.H &&
+                        (unsigned)(iw0 + q) < (unsigned)P.W;
+        const E* src = in + a_base + ((long long)p * P.W + q) * P.pixsz;
+#pragma unroll
+        for (int i = 0; i < ACH; ++i) {
+            const int kq = kq_stage + a_kq0 + i * A_STEP;
+            chunk_t v = {0u, 0u, 0u, 0u};
+            if (VEC) {
+                const int k0 = kq * CH;
+                if (ok && k0 < P.KT) {
+                    const int c = kq >> P.d2c_shift;
+                    const int d2 = k0 - c * P.D2;
+                    v = *reinterpret_cast<const chunk_t*>(src + (long long)c * P.cs + d2);
+                }
+            } else {
+                E tmp[CH];
+#pragma unroll
+                for (int e = 0; e < CH; ++e) {
+                    const int k = kq * CH + e;
+                    E xval = 0;
+                    if (ok && k < P.KT) {
+                        const int c = k / P.D2;
+                        const int d2 = k - c * P.D2;
+                        xval = src[(long long)c * P.cs + d2];
+                    }
+                    tmp[e] = xval;
+                }
+                __builtin_memcpy(&v, tmp, 16);
+            }
+            areg[i] = v;
+        }
+        const chunk_t* bsrc =
+            kp + (((size_t)d0 * P.ntaps + tap) * P.KQP + kq_stage) * P.colsp + col0 + b_col;
+#pragma unroll
+        for (int i = 0; i < BCH; ++i) breg[i] = bsrc[(size_t)(b_kq0 + i * B_STEP) * P.colsp];
+    };
+    auto store_stage = [&](int buf) {
+        chunk_t* A = lds + buf * STAGE;
+        chunk_t* B = A + 8 * BM;
+#pragma unroll
+        for (int i = 0; i < ACH; ++i) A[(a_kq0 + i * A_STEP) * BM + a_row] = areg[i];
+#pragma unroll
+        for (int i = 0; i < BCH; ++i) B[(b_kq0 + i * B_STEP) * BN + b_col] = breg[i];
+    };
+
+    float16v acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    const int st_begin = split * P.stages_per_split;
+    int st_end = st_begin + P.stages_per_split;
+    if (st_end > P.stages) st_end = P.stages;
+
+    if (st_begin < st_end) {
+        load_stage(st_begin);
+        store_stage(0);
+    }
+    __syncthreads();
+    for (int st = st_begin; st < st_end; ++st) {
+        const int buf = (st - st_begin) & 1;
+        const bool more = st + 1 < st_end;
+        if (more) load_stage(st + 1);
+        const chunk_t* A = lds + buf * STAGE;
+        const chunk_t* B = A + 8 * BM;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            chunk_t ka[TN], ib[TM];
+#pragma unroll
+            for (int a = 0; a < TN; ++a) ka[a] = B[(2 * t + h) * BN + wn * WN + a * 32 + lr];
+#pragma unroll
+            for (int b = 0; b < TM; ++b) ib[b] = A[(2 * t + h) * BM + wm * WM + b * 32 + lr];
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+#pragma unroll
+                for (int b = 0; b < TM; ++b) Mma<Tag>::run(ka[a], ib[b], acc[a][b]);
+        }
+        if (more) store_stage(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue: lane (h, lr) of MFMA tile (a, b) holds, in registers 4g..4g+3, columns
+    // j = 8g + 4h + 0..3 of the tile for output row lr of the tile.
+    float* __restrict__ out = P.out + (long long)split * P.out_elems;
+    const int caps_out = P.D0 * P.D1 * P.D3;
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+        const long long orow = row0 + wm * WM + b * 32 + lr;
+        if (orow >= P.rows) continue;
+        const long long pixel = orow / P.D1;
+        const int d1 = (int)(orow % P.D1);
+        float* orow_ptr = out + pixel * P.M * caps_out + (long long)(d0 * P.D1 + d1) * P.D3;
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int j0 = col0 + wn * WN + a * 32 + 8 * g + 4 * h;
+                if (ST4) {
+                    if (j0 < P.cols) {
+                        const int m = j0 / P.D3, d3 = j0 - m * P.D3;
+                        float4v v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
+                                     acc[a][b][4 * g + 3]};
+                        *reinterpret_cast<float4v*>(orow_ptr + (long long)m * caps_out + d3) = v;
+                    }
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int j = j0 + u;
+                        if (j < P.cols) {
+                            const int m = j / P.D3, d3 = j - m * P.D3;
+                            orow_ptr[(long long)m * caps_out + d3] = acc[a][b][4 * g + u];
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+struct TileChoice {
+    int BM, BN;
+};
+
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+struct Plan {
+    IgemmParams P;
+    TileChoice tile;
+    bool vec, st4;
+    size_t repack_bytes, partial_bytes;
+    long long blocks;
+    int CH;
+};
+
+// Tile, split and padding decisions for a shape (host side, pure arithmetic).
+Plan make_plan(const ConvShape& s)
+{
+    Plan pl{};
+    const int CH = s.dtype == 0 ? 4 : 8;
+    pl.CH = CH;
+    IgemmParams& P = pl.P;
+    P.H = s.H; P.W = s.W; P.C = s.C; P.M = s.M; P.stride = s.stride; P.pad = s.pad;
+    P.D0 = s.D0; P.D1 = s.D1; P.D2 = s.D2; P.D3 = s.D3; P.Ho = s.Ho; P.Wo = s.Wo; P.kw = s.kw;
+    P.rows = s.pixels() * s.D1;
+    P.out_elems = (long long)s.out_elems();
+    P.pixsz = (long long)s.C * s.D0 * s.D1 * s.D2;
+    P.cs = s.D0 * s.D1 * s.D2;
+    P.cols = s.M * s.D3;
+    P.KT = s.C * s.D2;
+    P.ntaps = s.kh * s.kw;
+    const int KQ = ceil_div(P.KT, CH);
+    P.KQP = ceil_div(KQ, 8) * 8;
+    P.spt = P.KQP / 8;
+    P.stages = P.ntaps * P.spt;
+
+    const int d2c = s.D2 / CH;
+    pl.vec = (s.D2 % CH == 0) && (d2c & (d2c - 1)) == 0;
+    P.d2c_shift = 0;
+    if (pl.vec)
+        while ((1 << P.d2c_shift) < d2c) ++P.d2c_shift;
+    pl.st4 = s.D3 % 4 == 0;
+
+    // tile: the largest whose grid still gives every CU a few blocks; small problems take
+    // small tiles and, if still short of blocks, split the K loop.
+    const int kCUs = 256;
+    const TileChoice choices[3] = {{256, 256}, {128, 128}, {64, 64}};
+    int pick = 2;
+    for (int i = 0; i < 3; ++i) {
+        const long long blocks = (long long)ceil_div(P.rows, choices[i].BM) *
+                                 ceil_div(P.cols, choices[i].BN) * s.D0;
+        const bool fits_cols = P.cols >= choices[i].BN / 2 || i == 2;
+        if (fits_cols && blocks >= 2 * kCUs) { pick = i; break; }
+    }
+    pl.tile = choices[pick];
+    P.row_tiles = ceil_div(P.rows, pl.tile.BM);
+    P.col_tiles = ceil_div(P.cols, pl.tile.BN);
+    P.colsp = P.col_tiles * pl.tile.BN;
+    long long blocks = (long long)P.row_tiles * P.col_tiles * s.D0;
+    int nsplit = 1;
+    if (blocks < kCUs) {
+        nsplit = ceil_div(2 * kCUs, blocks);
+        if (nsplit > P.stages) nsplit = P.stages;
+        if (nsplit > 64) nsplit = 64;
+    }
+    P.stages_per_split = ceil_div(P.stages, nsplit);
+    P.nsplit = ceil_div(P.stages, P.stages_per_split);
+    pl.blocks = blocks * P.nsplit;
+    pl.repack_bytes = (size_t)s.D0 * P.ntaps * P.KQP * P.colsp * 16;
+    pl.partial_bytes = P.nsplit > 1 ? (size_t)P.nsplit * P.out_elems * sizeof(float) : 0;
+    return pl;
+}
+
+template <typename Tag, bool VEC, bool ST4, int BM, int BN>
+hipError_t launch_tile(const Plan& pl, hipStream_t stream)
+{
+    auto kern = igemm_kernel<Tag, VEC, ST4, BM, BN, 2, 2>;
+    const size_t lds_bytes = (size_t)2 * 8 * (BM + BN) * 16;
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)lds_bytes);
+    if (err != hipSuccess) return err;
+    kern<<<dim3((unsigned)pl.blocks), dim3(256), lds_bytes, stream>>>(pl.P);
+    return hipGetLastError();
+}
+
+template <typename Tag, bool VEC, bool ST4>
+hipError_t launch_flags(const Plan& pl, hipStream_t stream)
+{
+    switch (pl.tile.BM) {
+        case 256: return launch_tile<Tag, VEC, ST4, 256, 256>(pl, stream);
+        case 128: return launch_tile<Tag, VEC, ST4, 128, 128>(pl, stream);
+        default: return launch_tile<Tag, VEC, ST4, 64, 64>(pl, stream);
+    }
+}
+
+template <typename Tag>
+hipError_t launch_typed(const Plan& pl, hipStream_t stream)
+{
+    if (pl.vec) {
+        return pl.st4 ? launch_flags<Tag, true, true>(pl, stream)
+                      : launch_flags<Tag, true, false>(pl, stream);
+    }
+    return pl.st4 ? launch_flags<Tag, false, true>(pl, stream)
+                  : launch_flags<Tag, false, false>(pl, stream);
+}
+
+bool shape_supported(const ConvShape& s)
+{
+    // 32-bit quantities inside the kernel
+    const long long cols = (long long)s.M * s.D3, kt = (long long)s.C * s.D2;
+    if (cols > (1 << 24) || kt > (1 << 24)) return false;
+    if ((long long)s.D0 * s.D1 * s.D2 > (1 << 24)) return false;
+    if ((long long)s.Ho * s.Wo > (1LL << 30)) return false;
+    return true;
+}
+
+hipError_t launch_igemm(const ConvShape& s, const void* in, const void* kernel, float* out,
+                        void* workspace, hipStream_t stream)
+{
+    Plan pl = make_plan(s);
+    if (pl.blocks <= 0 || pl.blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    char* ws = static_cast<char*>(workspace);
+    void* kp = ws;
+    float* partial = reinterpret_cast<float*>(ws + ((pl.repack_bytes + 255) & ~(size_t)255));
+    pl.P.in = in;
+    pl.P.kp = kp;
+    pl.P.out = pl.P.nsplit > 1 ? partial : out;
+
+    const size_t chunks = pl.repack_bytes / 16;
+    const unsigned rblocks = (unsigned)((chunks + 255) / 256);
+    if (s.dtype == 0) {
+        repack_kernel<float, 4><<<rblocks, 256, 0, stream>>>(
+            (const float*)kernel, (float*)kp, pl.P.ntaps, s.C, s.M, s.D0, s.D2, s.D3, pl.P.KT,
+            pl.P.KQP, pl.P.cols, pl.P.colsp, chunks);
+    } else {
+        repack_kernel<unsigned short, 8><<<rblocks, 256, 0, stream>>>(
+            (const unsigned short*)kernel, (unsigned short*)kp, pl.P.ntaps, s.C, s.M, s.D0, s.D2,
+            s.D3, pl.P.KT, pl.P.KQP, pl.P.cols, pl.P.colsp, chunks);
+    }
+    hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+
+    switch (s.dtype) {
+        case 0: err = launch_typed<f32_tag>(pl, stream); break;
+        case 1: err = launch_typed<bf16_tag>(pl, stream); break;
+        case 2: err = launch_typed<f16_tag>(pl, stream); break;
+        default: return hipErrorInvalidValue;
+    }
+    if (err != hipSuccess) return err;
+
+    if (pl.P.nsplit > 1) {
+        const unsigned blocks = (unsigned)((pl.P.out_elems + 255) / 256);
+        splitk_reduce_kernel<<<blocks, 256, 0, stream>>>(partial, out, pl.P.out_elems,
+                                                         pl.P.nsplit);
+        err = hipGetLastError();
+    }
+    return err;
+}
+
+}  // namespace
+
+bool mfma_supported(const ConvShape& s) { return shape_supported(s); }
+
+size_t mfma_workspace_bytes(const ConvShape& s)
+{
+    if (!shape_supported(s)) return 0;
+    const Plan pl = make_plan(s);
+    return ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
+}
+
+hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, float* out,
+                       void* workspace, hipStream_t stream)
+{
+    return launch_igemm(s, in, kernel, out, workspace, stream);
+}
+
+}  // namespace capscaps

@@ -1,0 +1,112 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, computes output extents, and refuses bad arguments before touching the GPU."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2104_02621_amd import capscaps as cc
+from paper_2104_02621_amd import workloads as wl
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def declared_symbols():
+    text = (ROOT / "include" / "capscaps.h").read_text()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(capscaps_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = ctypes.CDLL(str(cc.library_path()))
+    names = declared_symbols()
+    assert "capscaps_conv_fwd" in names and len(names) >= 7
+    for name in names:
+        assert hasattr(lib, name), name
+
+
+def test_binding_has_the_same_names():
+    for name in declared_symbols():
+        assert callable(getattr(cc, name)), name
+
+
+def test_out_shape_matches_paper_figures_and_configs():
+    assert cc.capscaps_out_shape(5, 5, 4, 4, 1, 0) == (cc.OK, 2, 2)       # Fig. 1 and Fig. 2
+    for w in wl.CONFIGS:
+        assert cc.capscaps_out_shape(w.H, w.W, w.kh, w.kw, w.stride, w.pad) == (cc.OK, w.Ho, w.Wo)
+    assert cc.capscaps_out_shape(7, 7, 2, 2, 3, 2)[1:] == (4, 4)
+
+
+@pytest.mark.parametrize("bad", [
+    dict(H=0), dict(W=-1), dict(kh=0), dict(stride=0), dict(pad=-1), dict(kh=6, pad=0, H=5),
+    dict(kw=8, pad=1, W=5),
+])
+def test_out_shape_rejects(bad):
+    a = dict(H=5, W=5, kh=3, kw=3, stride=1, pad=0)
+    a.update(bad)
+    assert cc.capscaps_out_shape(a["H"], a["W"], a["kh"], a["kw"], a["stride"], a["pad"])[0] \
+        == cc.EINVAL
+
+
+def _args(**over):
+    a = dict(N=2, H=6, W=6, C=3, M=4, kh=3, kw=3, stride=1, pad=1, D0=1, D1=4, D2=4, D3=4,
+             dtype=cc.FP32)
+    a.update(over)
+    return [a[k] for k in ("N", "H", "W", "C", "M", "kh", "kw", "stride", "pad", "D0", "D1", "D2",
+                           "D3", "dtype")]
+
+
+FAKE = 0x10000  # a 16-byte aligned non-null "pointer"; never dereferenced on these error paths
+
+
+@pytest.mark.parametrize("over", [dict(N=0), dict(C=-3), dict(M=0), dict(D0=0), dict(D1=0),
+                                  dict(D2=-1), dict(D3=0), dict(stride=0), dict(pad=-1),
+                                  dict(kh=9), dict(dtype=3), dict(dtype=-1)])
+def test_compute_entry_points_reject_bad_shapes(over):
+    a = _args(**over)
+    assert cc.capscaps_conv_fwd_ex(FAKE, FAKE, FAKE, *a, FAKE, 1 << 30, None) == cc.EINVAL
+    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, cc.PATH_AUTO, FAKE, 1 << 30, None) \
+        == cc.EINVAL
+    assert cc.capscaps_select_path(*a) == cc.EINVAL
+    assert cc.capscaps_conv_fwd_workspace_bytes(*a) == 0
+    if over.get("pad", 0) == 0 or "pad" not in over:
+        b = a[:8] + a[9:]
+        if "pad" not in over and "kh" not in over:
+            assert cc.capscaps_conv_fwd(FAKE, FAKE, FAKE, *b, None) == cc.EINVAL
+
+
+def test_null_and_misaligned_pointers_and_bad_path():
+    a = _args()
+    for ptrs in ((None, FAKE, FAKE), (FAKE, None, FAKE), (FAKE, FAKE, None), (FAKE + 4, FAKE, FAKE),
+                 (FAKE, FAKE + 8, FAKE), (FAKE, FAKE, FAKE + 2)):
+        assert cc.capscaps_conv_fwd_ex(*ptrs, *a, FAKE, 1 << 30, None) == cc.EINVAL
+        assert cc.capscaps_conv_fwd(*ptrs, *(a[:8] + a[9:]), None) == cc.EINVAL
+    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, 7, FAKE, 1 << 30, None) == cc.EINVAL
+    # workspace checks come before any launch
+    need = cc.capscaps_conv_fwd_workspace_bytes(*a)
+    assert need > 0
+    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, cc.PATH_MFMA, None, 0, None) \
+        == cc.EWORKSPACE
+    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, cc.PATH_MFMA, FAKE, need - 1, None) \
+        == cc.EWORKSPACE
+    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, cc.PATH_MFMA, FAKE + 4, need, None) \
+        == cc.EINVAL
+
+
+def test_path_selection_and_workspace_sizes():
+    for w in wl.CONFIGS:
+        a = (w.N, w.H, w.W, w.C, w.M, w.kh, w.kw, w.stride, w.pad, w.D0, w.D1, w.D2, w.D3, w.dtype)
+        assert cc.capscaps_select_path(*a) in (cc.PATH_DIRECT, cc.PATH_MFMA)
+        kernel_bytes = w.kh * w.kw * w.C * w.M * w.D0 * w.D2 * w.D3 * w.elem_bytes
+        assert cc.capscaps_conv_fwd_workspace_bytes(*a) >= kernel_bytes
+    # the Fig. 2 example has 3 output columns: too narrow for a matrix-core tile
+    assert cc.capscaps_select_path(1, 5, 5, 1, 1, 4, 4, 1, 0, 3, 3, 3, 3, cc.FP32) == cc.PATH_DIRECT
+    assert cc.capscaps_select_path(*_args(M=64, D3=16, D1=16, D2=16, C=64, dtype=cc.FP16)) \
+        == cc.PATH_MFMA
+
+
+def test_strerror():
+    assert cc.capscaps_strerror(cc.OK) == "success"
+    for code in (cc.EINVAL, cc.EWORKSPACE, cc.EUNSUPPORTED, cc.EHIP, -99):
+        assert cc.capscaps_strerror(code)

@@ -1,0 +1,172 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle, element by
+element on the same seeded inputs.  Needs an MI355X."""
+import dataclasses
+import functools
+
+import numpy as np
+import pytest
+
+from oracle import capsconv
+from paper_2104_02621_amd import capscaps as cc
+from paper_2104_02621_amd import workloads as wl
+from tests.gpu_util import check, run_gpu, shape_args, to_device
+
+pytestmark = pytest.mark.gpu
+
+PATHS = {"direct": cc.PATH_DIRECT, "mfma": cc.PATH_MFMA, "auto": cc.PATH_AUTO}
+
+
+def small(name, dtype, N, H, W, C, M, kh, kw, s, p, D0, D1, D2, D3, dist="normal", seed=0):
+    return wl.Workload(name, dtype, N, H, W, C, M, kh, kw, s, p, D0, D1, D2, D3, dist, dist, 1.0,
+                       3000 + seed, 4000 + seed)
+
+
+@functools.lru_cache(maxsize=4)
+def oracle_full(w):
+    """Inputs and the oracle's full result for a workload (cached across path variants)."""
+    i_st, k_st, i32, k32 = wl.generate(w)
+    ref, S = capsconv.conv_fwd(i32, k32, w.stride, w.pad, with_abs_sum=True)
+    return i_st, k_st, ref, S
+
+
+def full_compare(w, path):
+    i_st, k_st, ref, S = oracle_full(w)
+    got = run_gpu(w, to_device(i_st, w.dtype), to_device(k_st, w.dtype), path).cpu().numpy()
+    return check(w, got, ref, S, f"path={path}")
+
+
+# shapes chosen to span several tiles with ragged tails in rows, columns and K, non-square
+# capsules (D1 != D2 != D3), leading capsule dimension, strides, padding, 1x1 and wide windows
+SMALL_SHAPES = [
+    #      N  H   W   C   M  kh kw s  p D0  D1  D2  D3
+    ("sq4", 3, 9, 10, 5, 6, 3, 3, 1, 1, 1, 4, 4, 4),
+    ("d3x3", 2, 8, 7, 6, 5, 3, 3, 1, 1, 3, 3, 3, 3),
+    ("nonsq", 2, 7, 9, 3, 4, 2, 3, 2, 1, 2, 2, 3, 5),
+    ("tall", 2, 6, 6, 4, 3, 3, 2, 1, 0, 1, 5, 8, 4),
+    ("wide", 1, 12, 11, 8, 9, 3, 3, 2, 2, 1, 8, 8, 8),
+    ("d16", 1, 6, 7, 4, 5, 3, 3, 1, 1, 1, 16, 16, 16),
+    ("mix16", 2, 5, 6, 3, 7, 1, 1, 1, 0, 2, 4, 16, 8),
+    ("k1", 2, 9, 9, 16, 12, 1, 1, 3, 0, 1, 4, 4, 4),
+    ("fc", 5, 4, 3, 6, 7, 4, 3, 1, 0, 1, 4, 4, 4),
+    ("odd", 1, 10, 9, 7, 3, 5, 4, 1, 2, 1, 3, 5, 7),
+    ("manyrows", 4, 20, 20, 4, 20, 3, 3, 1, 1, 1, 8, 8, 8),
+]
+
+
+@pytest.mark.parametrize("dtype", [wl.FP32, wl.BF16, wl.FP16], ids=["fp32", "bf16", "fp16"])
+@pytest.mark.parametrize("path", ["direct", "mfma"])
+@pytest.mark.parametrize("shape", SMALL_SHAPES, ids=[s[0] for s in SMALL_SHAPES])
+def test_small_shapes_match_oracle(shape, path, dtype):
+    w = small(shape[0], dtype, *shape[1:], seed=len(shape[0]))
+    full_compare(w, PATHS[path])
+
+
+@pytest.mark.parametrize("path", ["direct", "mfma", "auto"])
+def test_paper_worked_example_on_gpu(path):
+    """Fig. 2: all-ones 5x5 input of 3x3x3 capsules, all-ones 4x4 kernel -> 2x2 of 48s."""
+    import torch
+    w = small("fig2", wl.FP32, 1, 5, 5, 1, 1, 4, 4, 1, 0, 3, 3, 3, 3)
+    I = torch.ones(w.input_shape, device="cuda")
+    K = torch.ones(w.kernel_shape, device="cuda")
+    got = run_gpu(w, I, K, PATHS[path]).cpu().numpy()
+    assert got.shape == (1, 2, 2, 1, 3, 3, 3) and np.all(got == 48.0)
+
+
+@pytest.mark.parametrize("dtype", [wl.FP32, wl.BF16, wl.FP16], ids=["fp32", "bf16", "fp16"])
+@pytest.mark.parametrize("path", ["direct", "mfma"])
+def test_small_integer_inputs_are_bit_exact(path, dtype):
+    """Integer inputs in [-3,3]: every partial sum is exact in fp32, so any summation order
+    must give exactly the oracle's result -- sharp against tile-edge, halo and split errors."""
+    for shape in (SMALL_SHAPES[0], SMALL_SHAPES[2], SMALL_SHAPES[4], SMALL_SHAPES[8]):
+        w = small(shape[0], dtype, *shape[1:], dist="int", seed=11)
+        i_st, k_st, i32, k32 = wl.generate(w)
+        ref = capsconv.conv_fwd(i32, k32, w.stride, w.pad)
+        got = run_gpu(w, to_device(i_st, dtype), to_device(k_st, dtype), PATHS[path]).cpu().numpy()
+        assert np.array_equal(got.astype(np.float64), ref), f"{w.name} {path}"
+
+
+@pytest.mark.parametrize("num", [1, 4])
+@pytest.mark.parametrize("path", ["direct", "mfma", "auto"])
+def test_benchmark_configs_full_tensor(num, path):
+    full_compare(wl.config(num), PATHS[path])
+
+
+@pytest.mark.parametrize("path", ["direct", "mfma"])
+@pytest.mark.parametrize("num,batch,hw", [(2, 2, 32), (3, 2, 28), (5, 2, 6)])
+def test_benchmark_configs_reduced_full_tensor(num, batch, hw, path):
+    """Configs 2, 3, 5 with fewer images (config 5 also with a smaller image, to keep the
+    oracle's run to seconds): every pixel, channel and border, whole tensor compared."""
+    w = wl.config(num)
+    w = dataclasses.replace(w, N=batch, H=hw, W=hw, name=f"{w.name}[N={batch},HW={hw}]")
+    full_compare(w, PATHS[path])
+
+
+@pytest.mark.parametrize("num,count", [(2, 20000), (3, 6000), (5, 2500)])
+def test_benchmark_configs_full_size_sampled(num, count):
+    """Configs 2, 3, 5 at full size, in the launch configuration the bench times: sampled
+    output capsules (a quarter of them on image borders) against the oracle, and the whole
+    tensor checked for finiteness."""
+    w = wl.config(num)
+    i_st, k_st, i32, k32 = wl.generate(w)
+    which = wl.sample_capsules(w, count, seed=77 + num)
+    ref, S = capsconv.conv_fwd_subset(i32, k32, which, w.stride, w.pad, with_abs_sum=True)
+    out = run_gpu(w, to_device(i_st, w.dtype), to_device(k_st, w.dtype), cc.PATH_AUTO)
+    import torch
+    assert bool(torch.isfinite(out).all())
+    idx = torch.from_numpy(which.astype(np.int64)).cuda()
+    got = out[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
+    check(w, got, ref, S, "sampled")
+
+
+def test_split_reduction_is_deterministic():
+    """Config 4 splits its K loop over many blocks; partial sums are reduced in a fixed order."""
+    import torch
+    w = wl.config(4)
+    i_st, k_st, _, _ = wl.generate(w)
+    I, K = to_device(i_st, w.dtype), to_device(k_st, w.dtype)
+    a = run_gpu(w, I, K, cc.PATH_MFMA)
+    b = run_gpu(w, I, K, cc.PATH_MFMA)
+    assert torch.equal(a, b)
+
+
+def test_plain_entry_point_allocates_its_own_scratch():
+    """capscaps_conv_fwd (the paper's pad-free operator, stream-ordered scratch)."""
+    import torch
+    w = wl.config(1)
+    i_st, k_st, i32, k32 = wl.generate(w)
+    I, K = to_device(i_st, w.dtype), to_device(k_st, w.dtype)
+    out = torch.full(w.out_shape, float("nan"), dtype=torch.float32, device="cuda")
+    rc = cc.capscaps_conv_fwd(I.data_ptr(), K.data_ptr(), out.data_ptr(), w.N, w.H, w.W, w.C, w.M,
+                              w.kh, w.kw, w.stride, w.D0, w.D1, w.D2, w.D3, w.dtype,
+                              torch.cuda.current_stream().cuda_stream)
+    assert rc == cc.OK
+    ref, S = capsconv.conv_fwd(i32, k32, w.stride, 0, with_abs_sum=True)
+    check(w, out.cpu().numpy(), ref, S, "plain entry point")
+
+
+def test_torch_wrapper_and_side_stream():
+    import torch
+    w = small("wrap", wl.FP16, 2, 8, 8, 8, 8, 3, 3, 1, 1, 1, 8, 8, 8)
+    i_st, k_st, i32, k32 = wl.generate(w)
+    I, K = to_device(i_st, w.dtype), to_device(k_st, w.dtype)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(s):
+        out = cc.conv_fwd(I, K, stride=1, pad=1)
+    s.synchronize()
+    ref, S = capsconv.conv_fwd(i32, k32, 1, 1, with_abs_sum=True)
+    check(w, out.cpu().numpy(), ref, S, "wrapper")
+
+
+def test_workspace_too_small_is_refused_before_any_launch():
+    import torch
+    w = wl.config(1)
+    I = torch.zeros(w.input_shape, device="cuda")
+    K = torch.zeros(w.kernel_shape, device="cuda")
+    out = torch.full(w.out_shape, 7.0, device="cuda")
+    ws = torch.empty(256, dtype=torch.uint8, device="cuda")
+    rc = cc.capscaps_conv_fwd_path(I.data_ptr(), K.data_ptr(), out.data_ptr(), *shape_args(w)[:13],
+                                   w.dtype, cc.PATH_MFMA, ws.data_ptr(), 256, None)
+    assert rc == cc.EWORKSPACE
+    torch.cuda.synchronize()
+    assert bool((out == 7.0).all())
