@@ -116,6 +116,13 @@ int capscaps_select_path(int N, int H, int W, int C, int M, int kh, int kw, int 
 /* Static, human-readable text for a status code.  Never NULL. */
 const char* capscaps_strerror(int status);
 
+/*
+ * Diagnostic for CAPSCAPS_EHIP: the HIP runtime's own text for the error the calling thread's
+ * most recent failing capscaps call ran into ("no error" if none has failed).  Thread-local;
+ * the only state the library keeps.  Never NULL.
+ */
+const char* capscaps_last_hip_error(void);
+
 #pragma GCC visibility pop
 
 #ifdef __cplusplus

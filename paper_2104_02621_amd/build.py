@@ -20,7 +20,7 @@ LIB = PKG / "libcapscaps.so"
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-fvisibility=hidden",
+    "-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
     "-Wall", "-Wno-unused-function",
     # packed-fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -21,7 +21,8 @@ _lib = None
 class CapscapsError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
-        super().__init__(f"capscaps status {status}: {capscaps_strerror(status)}")
+        detail = f" ({capscaps_last_hip_error()})" if status == EHIP else ""
+        super().__init__(f"capscaps status {status}: {capscaps_strerror(status)}{detail}")
 
 
 def library_path() -> Path:
@@ -35,6 +36,13 @@ def _load():
     if not _LIB_PATH.exists():
         raise FileNotFoundError(
             f"{_LIB_PATH} is not built; run `python -m paper_2104_02621_amd.build`")
+    # One HIP runtime per process: PyTorch ships its own libamdhip64 under the same soname as
+    # ROCm's.  Importing torch first makes the dynamic loader resolve this library's dependency
+    # to the copy torch already mapped, so streams and device pointers are shared.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(str(_LIB_PATH))
     i, p, sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
     ip = ctypes.POINTER(ctypes.c_int)
@@ -52,6 +60,8 @@ def _load():
     lib.capscaps_select_path.restype = i
     lib.capscaps_strerror.argtypes = [i]
     lib.capscaps_strerror.restype = ctypes.c_char_p
+    lib.capscaps_last_hip_error.argtypes = []
+    lib.capscaps_last_hip_error.restype = ctypes.c_char_p
     _lib = lib
     return lib
 
@@ -59,6 +69,10 @@ def _load():
 # ------------------------------------------------------------------ C ABI, same names
 def capscaps_strerror(status: int) -> str:
     return _load().capscaps_strerror(int(status)).decode()
+
+
+def capscaps_last_hip_error() -> str:
+    return _load().capscaps_last_hip_error().decode()
 
 
 def capscaps_out_shape(H, W, kh, kw, stride, pad):

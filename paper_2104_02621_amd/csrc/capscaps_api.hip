@@ -9,6 +9,16 @@ using capscaps::ConvShape;
 
 namespace {
 
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+int hip_status(hipError_t err)
+{
+    if (err == hipSuccess) return CAPSCAPS_OK;
+    g_last_hip_error = err;
+    (void)hipGetLastError();  // leave no sticky error behind for the caller's next HIP call
+    return CAPSCAPS_EHIP;
+}
+
 int fill_shape(ConvShape& s, int N, int H, int W, int C, int M, int kh, int kw, int stride, int pad,
                int D0, int D1, int D2, int D3, int dtype)
 {
@@ -59,7 +69,7 @@ int run(const void* input, const void* kernel, void* out, const ConvShape& s, in
     } else {
         return CAPSCAPS_EINVAL;
     }
-    return err == hipSuccess ? CAPSCAPS_OK : CAPSCAPS_EHIP;
+    return hip_status(err);
 }
 
 }  // namespace
@@ -134,11 +144,19 @@ int capscaps_conv_fwd(const void* input, const void* kernel, void* out, int N, i
     const int path = choose_path(s);
     const size_t need = path == CAPSCAPS_PATH_MFMA ? capscaps::mfma_workspace_bytes(s) : 0;
     void* ws = nullptr;
-    if (need > 0 && hipMallocAsync(&ws, need, st) != hipSuccess) return CAPSCAPS_EHIP;
+    if (need > 0) {
+        const hipError_t err = hipMallocAsync(&ws, need, st);
+        if (err != hipSuccess) return hip_status(err);
+    }
     const int status = run(input, kernel, out, s, path, ws, need, st);
-    if (ws != nullptr && hipFreeAsync(ws, st) != hipSuccess) return CAPSCAPS_EHIP;
+    if (ws != nullptr) {
+        const hipError_t err = hipFreeAsync(ws, st);
+        if (err != hipSuccess && status == CAPSCAPS_OK) return hip_status(err);
+    }
     return status;
 }
+
+const char* capscaps_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 const char* capscaps_strerror(int status)
 {

@@ -39,7 +39,7 @@ def run_gpu(w: wl.Workload, i_dev, k_dev, path=cc.PATH_AUTO, out=None, workspace
                                    w.W, w.C, w.M, w.kh, w.kw, w.stride, w.pad, w.D0, w.D1, w.D2,
                                    w.D3, w.dtype, path, workspace.data_ptr(), workspace.numel(),
                                    torch.cuda.current_stream().cuda_stream)
-    assert rc == cc.OK, f"{w.name}: status {rc} ({cc.capscaps_strerror(rc)})"
+    assert rc == cc.OK, f"{w.name}: status {rc} ({cc.capscaps_strerror(rc)}; {cc.capscaps_last_hip_error()})"
     return out
 
 
