@@ -59,7 +59,12 @@ extern "C" {
 /* compute paths (for capscaps_conv_fwd_path / capscaps_select_path) */
 #define CAPSCAPS_PATH_AUTO 0   /* library's choice */
 #define CAPSCAPS_PATH_DIRECT 1 /* wavefront-level small-matrix path: plain FMAs, any shape */
-#define CAPSCAPS_PATH_MFMA 2   /* LDS-staged implicit GEMM on the matrix cores */
+#define CAPSCAPS_PATH_MFMA 2   /* LDS-staged implicit GEMM on the matrix cores (library picks
+                                  the kernel variant) */
+#define CAPSCAPS_PATH_MFMA_GENERIC 3 /* ... the any-shape variant (tiles 64..256, optional split
+                                        of the K loop) */
+#define CAPSCAPS_PATH_MFMA_TUNED16 4 /* ... the 256x256-tile variant for 16-bit types with
+                                        D1 = D2 in {8, 16}; other shapes: CAPSCAPS_EUNSUPPORTED */
 
 /*
  * Output extents (Fig. 1 / Fig. 2: 5 with a 4-wide kernel at stride 1 gives 2).

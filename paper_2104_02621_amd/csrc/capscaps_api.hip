@@ -59,13 +59,21 @@ int run(const void* input, const void* kernel, void* out, const ConvShape& s, in
     hipError_t err;
     if (path == CAPSCAPS_PATH_DIRECT) {
         err = capscaps::launch_direct(s, input, kernel, static_cast<float*>(out), stream);
-    } else if (path == CAPSCAPS_PATH_MFMA) {
+    } else if (path == CAPSCAPS_PATH_MFMA || path == CAPSCAPS_PATH_MFMA_GENERIC ||
+               path == CAPSCAPS_PATH_MFMA_TUNED16) {
         if (!capscaps::mfma_supported(s)) return CAPSCAPS_EUNSUPPORTED;
+        if (path == CAPSCAPS_PATH_MFMA_TUNED16 && !capscaps::mfma_tuned16_supported(s))
+            return CAPSCAPS_EUNSUPPORTED;
+        const capscaps::MfmaKernel which =
+            path == CAPSCAPS_PATH_MFMA           ? capscaps::MfmaKernel::Auto
+            : path == CAPSCAPS_PATH_MFMA_GENERIC ? capscaps::MfmaKernel::Generic
+                                                 : capscaps::MfmaKernel::Tuned16;
         const size_t need = capscaps::mfma_workspace_bytes(s);
         if (need > 0 && (workspace == nullptr || workspace_bytes < need))
             return CAPSCAPS_EWORKSPACE;
         if (need > 0 && misaligned(workspace)) return CAPSCAPS_EINVAL;
-        err = capscaps::launch_mfma(s, input, kernel, static_cast<float*>(out), workspace, stream);
+        err = capscaps::launch_mfma(s, input, kernel, static_cast<float*>(out), workspace, stream,
+                                    which);
     } else {
         return CAPSCAPS_EINVAL;
     }
@@ -113,8 +121,7 @@ int capscaps_conv_fwd_path(const void* input, const void* kernel, void* out, int
 {
     if (input == nullptr || kernel == nullptr || out == nullptr) return CAPSCAPS_EINVAL;
     if (misaligned(input) || misaligned(kernel) || misaligned(out)) return CAPSCAPS_EINVAL;
-    if (path != CAPSCAPS_PATH_AUTO && path != CAPSCAPS_PATH_DIRECT && path != CAPSCAPS_PATH_MFMA)
-        return CAPSCAPS_EINVAL;
+    if (path < CAPSCAPS_PATH_AUTO || path > CAPSCAPS_PATH_MFMA_TUNED16) return CAPSCAPS_EINVAL;
     ConvShape s;
     const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype);
     if (rc != CAPSCAPS_OK) return rc;

@@ -1,0 +1,353 @@
+// Tuned matrix-core kernel of the capsule convolution forward pass for 16-bit element types
+// and capsule dimensions D1 = D2 in {8, 16}: the shapes where the contraction is dense enough
+// to be bound by the MFMA rate.  Same implicit GEMM as igemm_conv.hip (rows (pixel,d1),
+// columns (m,d3), K = (tap, c, d2); paper Algorithm 2), same repacked kernel layout, but
+//
+//   * global -> LDS copies are buffer loads that write LDS directly (no VGPR staging, no
+//     ds_write): one wave instruction moves 64 chunks of 16 bytes = 1 KB ("block");
+//   * all per-block addressing is wave-uniform (SGPR): a block never mixes pixels, so the
+//     window tap, the padding test and the channel offset are scalar arithmetic, and a pixel
+//     outside the image is read through an out-of-range buffer offset that returns zeros;
+//   * the K loop is one branch-free basic block in which the copies of a stage NB-1 ahead and
+//     the LDS operand reads of the next k-step are placed between the MFMAs of the current
+//     k-step (operand fragments are double-buffered in registers).
+//
+// Tile: 256 rows x 256 columns, 4 waves of 128 x 128 (4 x 4 MFMA 32x32x16 tiles, 256
+// accumulator registers).  A K stage is KCH chunks (KCH*8 elements) per row; LDS holds a ring
+// of NB stages.  One barrier per stage: it is placed before the last k-step of the stage, when
+// the wave holds that k-step's operands in registers, so the MFMAs of that k-step overlap the
+// first operand reads of the next stage.
+//
+// LDS layout of one stage
+//   input side:  4*KCH blocks.  A pixel of the tile contributes, per stage, KCH chunks for
+//                each of its D1 rows = KCH*D1/64 blocks, in global memory order
+//                [channel][d1][d2-half]; blocks are spaced 1024+APAD bytes and (D2 = 16) the
+//                two halves of a row swap places for d1 >= 8, so the 16 lanes of a quarter
+//                wave always touch 16 distinct 16-byte bank groups when reading MFMA operands.
+//   kernel side: [chunk 0..KCH-1][column 0..255][16 bytes], copied verbatim from the repacked
+//                kernel; operand reads are 512 contiguous bytes per 32 lanes.
+#include <hip/hip_runtime.h>
+
+#include "igemm_common.h"
+
+namespace capscaps {
+namespace {
+
+typedef __attribute__((address_space(3))) void lds_void;
+
+template <int D1, int D2, int KCH>
+struct ALayout {
+    static constexpr int D2C = D2 / 8;             // chunks per capsule row
+    static constexpr int G = D1 * D2C;             // chunks per (pixel, channel)
+    static constexpr int CPB = 64 / G;             // channels per block
+    static constexpr int BPP = KCH * D1 / 64;      // blocks per pixel and stage
+    static constexpr int PIX = 256 / D1;           // pixels per tile
+    static constexpr int NBLK = 4 * KCH;           // blocks per operand and stage
+    // padding between blocks so that lanes of a quarter wave that belong to different pixels
+    // fall into different bank groups
+    static constexpr int APAD = (G == 8) ? 128 : 0;
+    static constexpr int ABLK = 1024 + APAD;
+    static_assert(D1 == 8 || D1 == 16, "D1");
+    static_assert(D2 == 8 || D2 == 16, "D2");
+    static_assert(KCH == 4 || KCH == 8, "chunks per stage");
+    static_assert(BPP >= 1 && BPP * 64 == KCH * D1, "a block never mixes pixels");
+    static_assert(CPB * BPP * D2C == KCH, "blocks of a pixel cover the stage's channels");
+    // the two 16-byte halves of a 32-byte capsule row trade places for the upper rows
+    static __device__ __forceinline__ int swz(int d1)
+    {
+        return (D2C == 2 && D1 == 16) ? (d1 >> 3) & 1 : 0;
+    }
+};
+
+// KCH: chunks (of 8 K elements) per row and stage; NB: LDS stage buffers in the ring.
+template <typename Tag, int D1, int D2, int KCH, int NB>
+__global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
+{
+    typedef ALayout<D1, D2, KCH> AL;
+    constexpr int NWM = 2, NWN = 2, NW = 4;
+    constexpr int BM = 256, BN = 256;
+    constexpr int D2C = AL::D2C, G = AL::G, CPB = AL::CPB, BPP = AL::BPP, PIX = AL::PIX;
+    constexpr int ABLK = AL::ABLK, NBLK = AL::NBLK;
+    constexpr int A_BYTES = NBLK * ABLK, B_BYTES = NBLK * 1024, STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int WM = BM / NWM, WN = BN / NWN, TM = WM / 32, TN = WN / 32;
+    constexpr int KS = KCH / 2;      // MFMA k-steps (16 K elements) per stage
+    constexpr int BW = NBLK / NW;    // blocks per wave, per operand and stage
+    constexpr int PPW = BW / BPP;    // pixels whose blocks this wave loads
+    constexpr int NFRAG = TN + TM;   // operand fragments per k-step
+    static_assert(BW % BPP == 0 && PPW >= 1, "a wave loads whole pixels");
+    static_assert(TM * TN >= NFRAG && TM * TN >= 2 * BW, "side operations fit between MFMAs");
+    constexpr unsigned OOB = 0x80000000u;
+    // s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+    constexpr int KEEP = (NB - 2) * 2 * BW;  // copies that may still be in flight at a barrier
+    constexpr int VMCNT_KEEP = 0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14);
+
+    extern __shared__ char smem[];
+
+    // ---- tile (same mapping as the generic kernel: XCD-contiguous, column tiles fastest)
+    const int nb = gridDim.x;
+    int L = blockIdx.x;
+    {
+        const int per = nb / 8, full = per * 8;
+        if ((int)blockIdx.x < full) L = ((int)blockIdx.x % 8) * per + (int)blockIdx.x / 8;
+    }
+    const int col_tile = L % P.col_tiles;
+    int rest = L / P.col_tiles;
+    const int row_tile = rest % P.row_tiles;
+    const int d0 = rest / P.row_tiles;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave % NWM, wn = wave / NWM;
+    const int h = lane >> 5, lr = lane & 31;
+    const int col0 = col_tile * BN;
+
+    // ---- per-wave scalar state of the pixels whose input blocks this wave loads
+    const int hw = P.Ho * P.Wo;
+    const long long npix = P.rows / D1;
+    const long long pg0 = (long long)row_tile * PIX;
+    const long long n_first = pg0 / hw;
+    const long long img_elems = (long long)P.H * P.W * P.pixsz;
+    const unsigned short* in_base = static_cast<const unsigned short*>(P.in) + n_first * img_elems;
+    int pix_off[PPW], pix_ih0[PPW], pix_iw0[PPW], pix_ok[PPW];
+#pragma unroll
+    for (int j = 0; j < PPW; ++j) {
+        const long long pg = pg0 + wave * PPW + j;
+        pix_ok[j] = pg < npix ? 1 : 0;
+        const long long pgc = pix_ok[j] ? pg : pg0;
+        const int n_rel = (int)(pgc / hw - n_first);
+        const int rem = (int)(pgc % hw);
+        const int x = rem / P.Wo, y = rem - x * P.Wo;
+        pix_ih0[j] = x * P.stride - P.pad;
+        pix_iw0[j] = y * P.stride - P.pad;
+        // byte offset of input pixel (ih0, iw0) of that image from in_base; meaningful only
+        // together with an in-range tap
+        pix_off[j] = (int)((((long long)n_rel * P.H + pix_ih0[j]) * P.W + pix_iw0[j]) * P.pixsz * 2) +
+                     d0 * D1 * D2 * 2;
+    }
+    long long in_left = P.in_bytes - n_first * img_elems * 2;
+    if (in_left > 0x7fffffffLL) in_left = 0x7fffffffLL;
+    const __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<unsigned short*>(in_base), 0, (int)in_left, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_kp = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<void*>(P.kp), 0, (int)P.kp_records, 0x00020000);
+
+    // ---- per-lane constants
+    // input block: lane -> (channel within block, d1, row half) in LDS order
+    const int a_csub = lane / G, a_g = lane % G;
+    const int a_d1 = a_g / D2C, a_s = a_g % D2C;
+    const unsigned a_voff =
+        (unsigned)((a_csub * P.cs + a_d1 * D2 + ((a_s ^ AL::swz(a_d1)) * 8)) * 2);
+    const unsigned b_voff = (unsigned)lane * 16u;
+    // operand reads: MFMA row tile b covers rows wm*WM + b*32 + lr of the tile
+    unsigned a_rd;  // byte offset within the stage's input region, for b = 0, t = 0
+    {
+        const int r = wm * WM + lr;
+        const int pl = r / D1, d1 = r % D1;
+        // chunk kql = 2t + h  ->  channel c_l = kql / D2C, half = kql % D2C
+        const int c_l = h / D2C, half = h % D2C;
+        a_rd = (unsigned)((pl * BPP + c_l / CPB) * ABLK +
+                          ((c_l % CPB) * G + d1 * D2C + (half ^ AL::swz(d1))) * 16);
+    }
+    const unsigned b_rd = (unsigned)(A_BYTES + (h * BN + wn * WN + lr) * 16);
+
+    float16v acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    // ---- K loop state (scalar) of the next stage to copy: tap (p, q), chunk within the tap
+    int p = 0, q = 0, kq = 0, tap = 0, issued = 0;
+    const int nstages = P.ntaps * (P.KQP / KCH);
+
+    // copy number j (0 .. 2*BW-1) of the stage described by (p, q, kq, tap) into ring slot
+    auto issue_copy = [&](int slot, int j) {
+        char* stage = smem + slot * STAGE_BYTES;
+        // All selections below are mask arithmetic (0 / ~0), never ?: on a condition, so that
+        // the K loop stays one basic block.  live = 0 past the last stage: the copy still runs
+        // (the count of copies in flight stays uniform) but reads nothing and stores zeros.
+        const int live = -(int)(issued < nstages);
+        if (j < BW) {
+            const int pj = j / BPP, part = j % BPP;
+            const int ok = live & -(pix_ok[pj] & (int)((unsigned)(pix_ih0[pj] + p) < (unsigned)P.H) &
+                                    (int)((unsigned)(pix_iw0[pj] + q) < (unsigned)P.W));
+            const int tap_off = (p * P.W + q) * (int)(P.pixsz * 2);
+            const int c_off = (kq / D2C) * P.cs * 2;
+            const int soff = (pix_off[pj] + tap_off + c_off + part * CPB * P.cs * 2) & ok;
+            const unsigned voff = a_voff | (OOB & ~(unsigned)ok);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rs_in, (lds_void*)(stage + (wave * BW + j) * ABLK), 16, voff, soff, 0, 0);
+        } else {
+            const int bb = wave * BW + (j - BW);
+            const int kql = bb / 4, cg = bb % 4;
+            const int kp_off =
+                (int)((((long long)(d0 * P.ntaps + tap) * P.KQP + kq) * P.colsp + col0) * 16);
+            const int soff = (kp_off + (kql * P.colsp + cg * 64) * 16) & live;
+            const unsigned voff = b_voff | (OOB & ~(unsigned)live);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(
+                rs_kp, (lds_void*)(stage + A_BYTES + bb * 1024), 16, voff, soff, 0, 0);
+        }
+    };
+    auto advance = [&]() {
+        ++issued;
+        kq += KCH;
+        const int wrap = kq == P.KQP ? 1 : 0;
+        kq = wrap ? 0 : kq;
+        tap += wrap;
+        q += wrap;
+        const int wrapq = q == P.kw ? 1 : 0;
+        q = wrapq ? 0 : q;
+        p += wrapq;
+    };
+
+    // operand fragment f of k-step t from ring slot: f < TN kernel side, else input side
+    auto read_frag = [&](int slot, int t, int f) -> chunk_t {
+        const char* stage = smem + slot * STAGE_BYTES;
+        if (f < TN)
+            return *reinterpret_cast<const chunk_t*>(stage + b_rd + (2 * t * BN + f * 32) * 16);
+        const int b = f - TN;
+        // chunk index +2t = channel +2t/D2C (row half unchanged); rows +32b = pixels +32b/D1
+        const int c_adv = 2 * t / D2C;
+        const int blk_adv = c_adv / CPB, csub_adv = c_adv % CPB;
+        const int off = ((b * 32 / D1) * BPP + blk_adv) * ABLK + csub_adv * G * 16;
+        return *reinterpret_cast<const chunk_t*>(stage + a_rd + off);
+    };
+
+    // ---- prologue: fill NB-1 ring slots, wait for the first, fetch its first fragments
+#pragma unroll
+    for (int s0 = 0; s0 < NB - 1; ++s0) {
+#pragma unroll
+        for (int j = 0; j < 2 * BW; ++j) issue_copy(s0, j);
+        advance();
+    }
+    __builtin_amdgcn_s_waitcnt(VMCNT_KEEP);
+    __syncthreads();
+    chunk_t frag[2][NFRAG];
+#pragma unroll
+    for (int f = 0; f < NFRAG; ++f) frag[0][f] = read_frag(0, 0, f);
+
+    // ---- main loop: one ring slot per iteration.  Between consecutive MFMAs go the side
+    // operations: the copies of the stage NB-1 ahead and the fragment reads of the next k-step.
+    int slot = 0;  // ring slot being contracted
+    for (int st = 0; st < nstages; ++st) {
+        const int slot_fill = slot == 0 ? NB - 1 : slot - 1;  // consumed in the last iteration
+        const int slot_next = slot == NB - 1 ? 0 : slot + 1;
+#pragma unroll
+        for (int t = 0; t < KS; ++t) {
+            const int cur = t & 1, nxt = cur ^ 1;
+            if (t == KS - 1) {
+                // everything this wave still needs from `slot` is in registers; its copies of
+                // the next stage have landed; after the barrier that holds for all waves
+                __builtin_amdgcn_s_waitcnt(VMCNT_KEEP & 0xF0FF);  // and lgkmcnt(0)
+                __syncthreads();
+            }
+#pragma unroll
+            for (int i = 0; i < TN * TM; ++i) {
+                const int a = i / TM, b = i % TM;
+                Mma<Tag>::run(frag[cur][a], frag[cur][TN + b], acc[a][b]);
+                if (i < NFRAG)
+                    frag[nxt][i] = t == KS - 1 ? read_frag(slot_next, 0, i) : read_frag(slot, t + 1, i);
+                if (t == 0 && i < 2 * BW) issue_copy(slot_fill, i);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        advance();
+        slot = slot_next;
+    }
+
+    // ---- epilogue (lane (h, lr) of tile (a, b): registers 4g..4g+3 = columns 8g+4h+0..3)
+    float* __restrict__ out = P.out;
+    const int caps_out = P.D0 * D1 * P.D3;
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+        const int r = wm * WM + b * 32 + lr;
+        const long long pixel = pg0 + r / D1;
+        if (pixel >= npix) continue;
+        const int d1 = r % D1;
+        float* orow_ptr = out + pixel * P.M * caps_out + (long long)(d0 * D1 + d1) * P.D3;
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int j0 = col0 + wn * WN + a * 32 + 8 * g + 4 * h;
+                if (j0 < P.cols) {
+                    const int m = j0 / P.D3, d3 = j0 - m * P.D3;
+                    float4v v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
+                                 acc[a][b][4 * g + 3]};
+                    *reinterpret_cast<float4v*>(orow_ptr + (long long)m * caps_out + d3) = v;
+                }
+            }
+        }
+    }
+}
+
+template <int D1, int D2>
+struct FastConfig;  // chunks per stage and ring depth chosen per capsule size
+template <>
+struct FastConfig<16, 16> { static constexpr int KCH = 4, NB = 4; };
+template <>
+struct FastConfig<8, 8> { static constexpr int KCH = 8, NB = 2; };
+
+template <typename Tag, int D1, int D2>
+hipError_t launch_one(const IgemmParams& P, long long blocks, hipStream_t stream)
+{
+    constexpr int KCH = FastConfig<D1, D2>::KCH, NB = FastConfig<D1, D2>::NB;
+    typedef ALayout<D1, D2, KCH> AL;
+    auto kern = igemm16_fast_kernel<Tag, D1, D2, KCH, NB>;
+    const size_t lds_bytes = (size_t)NB * AL::NBLK * (AL::ABLK + 1024);
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)lds_bytes);
+    if (err != hipSuccess) return err;
+    kern<<<dim3((unsigned)blocks), dim3(256), lds_bytes, stream>>>(P);
+    return hipGetLastError();
+}
+
+template <typename Tag>
+hipError_t launch_dims(const IgemmParams& P, long long blocks, hipStream_t stream)
+{
+    if (P.D1 == 16 && P.D2 == 16) return launch_one<Tag, 16, 16>(P, blocks, stream);
+    if (P.D1 == 8 && P.D2 == 8) return launch_one<Tag, 8, 8>(P, blocks, stream);
+    return hipErrorInvalidValue;
+}
+
+}  // namespace
+
+bool igemm16_fast_eligible(const ConvShape& s)
+{
+    if (s.dtype != 1 && s.dtype != 2) return false;
+    if (!((s.D1 == 16 && s.D2 == 16) || (s.D1 == 8 && s.D2 == 8))) return false;
+    if (s.D3 % 4 != 0) return false;
+    if ((s.C * s.D2) % 64 != 0) return false;  // whole K stages per tap
+    // 31-bit byte offsets: a tile's input window spans at most the images its 256/D1 pixels
+    // touch; the repacked kernel is addressed from its start
+    const long long img_bytes = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 2;
+    const long long hw = (long long)s.Ho * s.Wo;
+    const long long pix = 256 / s.D1;
+    const long long images_spanned = (pix + hw - 2) / hw + 1;
+    if (images_spanned * img_bytes >= (1LL << 31)) return false;
+    const long long colsp = ((long long)s.M * s.D3 + 255) / 256 * 256;
+    const long long kp_bytes = (long long)s.D0 * s.kh * s.kw * (s.C * s.D2 / 8) * colsp * 16;
+    if (kp_bytes >= (1LL << 31)) return false;
+    return true;
+}
+
+bool igemm16_fast_preferred(const ConvShape& s)
+{
+    if (!igemm16_fast_eligible(s)) return false;
+    // enough 256x256 tiles to fill the chip; smaller problems use the generic kernel's tiles
+    const long long colsp = ((long long)s.M * s.D3 + 255) / 256 * 256;
+    const long long tiles = ((long long)s.pixels() * s.D1 + 255) / 256 * (colsp / 256) * s.D0;
+    return tiles >= 256;
+}
+
+hipError_t launch_igemm16_fast(const IgemmParams& P, long long blocks, int dtype,
+                               hipStream_t stream)
+{
+    return dtype == 2 ? launch_dims<f16_tag>(P, blocks, stream)
+                      : launch_dims<bf16_tag>(P, blocks, stream);
+}
+
+}  // namespace capscaps

@@ -1,0 +1,81 @@
+// Internal: types shared by the matrix-core kernels of the capsule convolution forward pass.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "conv_shape.h"
+
+namespace capscaps {
+
+typedef float float4v __attribute__((ext_vector_type(4)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
+typedef unsigned int chunk_t __attribute__((ext_vector_type(4)));  // 16 raw bytes
+
+struct f32_tag { typedef float elem; };
+struct f16_tag { typedef unsigned short elem; };
+struct bf16_tag { typedef unsigned short elem; };
+
+template <typename Tag>
+struct Mma;
+template <>
+struct Mma<f16_tag> {
+    static __device__ __forceinline__ void run(const chunk_t& a, const chunk_t& b, float16v& acc)
+    {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a),
+                                                     __builtin_bit_cast(half8v, b), acc, 0, 0, 0);
+    }
+};
+template <>
+struct Mma<bf16_tag> {
+    static __device__ __forceinline__ void run(const chunk_t& a, const chunk_t& b, float16v& acc)
+    {
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8v, a),
+                                                      __builtin_bit_cast(bf16x8v, b), acc, 0, 0, 0);
+    }
+};
+template <>
+struct Mma<f32_tag> {
+    // a chunk holds 4 K elements per lane half; element u of both halves forms the K pair of
+    // one 32x32x2 instruction
+    static __device__ __forceinline__ void run(const chunk_t& a, const chunk_t& b, float16v& acc)
+    {
+        const float4v fa = __builtin_bit_cast(float4v, a);
+        const float4v fb = __builtin_bit_cast(float4v, b);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[u], fb[u], acc, 0, 0, 0);
+    }
+};
+
+struct IgemmParams {
+    const void* in;
+    const void* kp;  // repacked kernel
+    float* out;      // final output, or split-K partial buffers [split][out_elems]
+    int H, W, C, M, stride, pad, D0, D1, D2, D3, Ho, Wo, kw;
+    long long rows;        // N*Ho*Wo*D1
+    long long out_elems;   // per split
+    long long pixsz;       // C*D0*D1*D2: elements per input pixel
+    int cs;                // D0*D1*D2: input channel stride
+    int cols, colsp;       // M*D3 and its padding to the column tile
+    int KT;                // C*D2: K extent of one tap
+    int KQP;               // chunks per tap, padded to a multiple of 8
+    int d2c_shift;         // vector loader: log2(chunks per capsule row)
+    int spt;               // stages per tap
+    int stages;            // ntaps * spt
+    int stages_per_split;  // K-loop share of one split
+    int nsplit;
+    int ntaps;
+    int row_tiles, col_tiles;
+    long long in_bytes;    // size of the input tensor
+    long long kp_records;  // size of the repacked kernel in bytes
+};
+
+// Tuned 16-bit kernel (igemm16_fast.hip): 256x256 tiles, direct-to-LDS copies.
+bool igemm16_fast_eligible(const ConvShape& s);   // the kernel can run the shape
+bool igemm16_fast_preferred(const ConvShape& s);  // ... and is the library's choice for it
+hipError_t launch_igemm16_fast(const IgemmParams& P, long long blocks, int dtype,
+                               hipStream_t stream);
+
+
+}  // namespace capscaps

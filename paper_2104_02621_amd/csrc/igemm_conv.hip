@@ -26,73 +26,10 @@
 // in the same lane order, any fixed assignment of chunk halves to lanes is a valid K order.
 #include <hip/hip_runtime.h>
 
-#include "conv_shape.h"
+#include "igemm_common.h"
 
 namespace capscaps {
 namespace {
-
-typedef float float4v __attribute__((ext_vector_type(4)));
-typedef float float16v __attribute__((ext_vector_type(16)));
-typedef _Float16 half8v __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8v __attribute__((ext_vector_type(8)));
-typedef unsigned int chunk_t __attribute__((ext_vector_type(4)));  // 16 raw bytes
-
-struct f32_tag { typedef float elem; };
-struct f16_tag { typedef unsigned short elem; };
-struct bf16_tag { typedef unsigned short elem; };
-
-template <typename Tag>
-struct Mma;
-template <>
-struct Mma<f16_tag> {
-    static __device__ __forceinline__ void run(const chunk_t& a, const chunk_t& b, float16v& acc)
-    {
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8v, a),
-                                                     __builtin_bit_cast(half8v, b), acc, 0, 0, 0);
-    }
-};
-template <>
-struct Mma<bf16_tag> {
-    static __device__ __forceinline__ void run(const chunk_t& a, const chunk_t& b, float16v& acc)
-    {
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8v, a),
-                                                      __builtin_bit_cast(bf16x8v, b), acc, 0, 0, 0);
-    }
-};
-template <>
-struct Mma<f32_tag> {
-    // a chunk holds 4 K elements per lane half; element u of both halves forms the K pair of
-    // one 32x32x2 instruction
-    static __device__ __forceinline__ void run(const chunk_t& a, const chunk_t& b, float16v& acc)
-    {
-        const float4v fa = __builtin_bit_cast(float4v, a);
-        const float4v fb = __builtin_bit_cast(float4v, b);
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[u], fb[u], acc, 0, 0, 0);
-    }
-};
-
-struct IgemmParams {
-    const void* in;
-    const void* kp;  // repacked kernel
-    float* out;      // final output, or split-K partial buffers [split][out_elems]
-    int H, W, C, M, stride, pad, D0, D1, D2, D3, Ho, Wo, kw;
-    long long rows;        // N*Ho*Wo*D1
-    long long out_elems;   // per split
-    long long pixsz;       // C*D0*D1*D2: elements per input pixel
-    int cs;                // D0*D1*D2: input channel stride
-    int cols, colsp;       // M*D3 and its padding to the column tile
-    int KT;                // C*D2: K extent of one tap
-    int KQP;               // chunks per tap, padded to a multiple of 8
-    int d2c_shift;         // vector loader: log2(chunks per capsule row)
-    int spt;               // stages per tap
-    int stages;            // ntaps * spt
-    int stages_per_split;  // K-loop share of one split
-    int nsplit;
-    int ntaps;
-    int row_tiles, col_tiles;
-};
 
 // ---------------------------------------------------------------------------------------------
 // Kernel repack: Kp[d0][tap][kq][j][e] = K[tap][c][m][d0][d2][d3] with k = kq*CH+e = c*D2+d2,
@@ -344,13 +281,14 @@ struct Plan {
     IgemmParams P;
     TileChoice tile;
     bool vec, st4;
+    bool fast;  // tuned 16-bit kernel
     size_t repack_bytes, partial_bytes;
     long long blocks;
     int CH;
 };
 
 // Tile, split and padding decisions for a shape (host side, pure arithmetic).
-Plan make_plan(const ConvShape& s)
+Plan make_plan(const ConvShape& s, MfmaKernel which)
 {
     Plan pl{};
     const int CH = s.dtype == 0 ? 4 : 8;
@@ -381,8 +319,12 @@ Plan make_plan(const ConvShape& s)
     // small tiles and, if still short of blocks, split the K loop.
     const int kCUs = 256;
     const TileChoice choices[3] = {{256, 256}, {128, 128}, {64, 64}};
+    pl.fast = which == MfmaKernel::Tuned16
+                  ? igemm16_fast_eligible(s)
+                  : which == MfmaKernel::Auto && igemm16_fast_preferred(s);
     int pick = 2;
-    for (int i = 0; i < 3; ++i) {
+    if (pl.fast) pick = 0;
+    for (int i = 0; i < 3 && !pl.fast; ++i) {
         const long long blocks = (long long)ceil_div(P.rows, choices[i].BM) *
                                  ceil_div(P.cols, choices[i].BN) * s.D0;
         const bool fits_cols = P.cols >= choices[i].BN / 2 || i == 2;
@@ -394,7 +336,7 @@ Plan make_plan(const ConvShape& s)
     P.colsp = P.col_tiles * pl.tile.BN;
     long long blocks = (long long)P.row_tiles * P.col_tiles * s.D0;
     int nsplit = 1;
-    if (blocks < kCUs) {
+    if (blocks < kCUs && !pl.fast) {
         nsplit = ceil_div(2 * kCUs, blocks);
         if (nsplit > P.stages) nsplit = P.stages;
         if (nsplit > 64) nsplit = 64;
@@ -404,6 +346,8 @@ Plan make_plan(const ConvShape& s)
     pl.blocks = blocks * P.nsplit;
     pl.repack_bytes = (size_t)s.D0 * P.ntaps * P.KQP * P.colsp * 16;
     pl.partial_bytes = P.nsplit > 1 ? (size_t)P.nsplit * P.out_elems * sizeof(float) : 0;
+    P.in_bytes = (long long)s.in_elems() * (s.dtype == 0 ? 4 : 2);
+    P.kp_records = (long long)pl.repack_bytes;
     return pl;
 }
 
@@ -452,9 +396,9 @@ bool shape_supported(const ConvShape& s)
 }
 
 hipError_t launch_igemm(const ConvShape& s, const void* in, const void* kernel, float* out,
-                        void* workspace, hipStream_t stream)
+                        void* workspace, hipStream_t stream, MfmaKernel which)
 {
-    Plan pl = make_plan(s);
+    Plan pl = make_plan(s, which);
     if (pl.blocks <= 0 || pl.blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     char* ws = static_cast<char*>(workspace);
     void* kp = ws;
@@ -476,6 +420,8 @@ hipError_t launch_igemm(const ConvShape& s, const void* in, const void* kernel, 
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
+
+    if (pl.fast) return launch_igemm16_fast(pl.P, pl.blocks, s.dtype, stream);
 
     switch (s.dtype) {
         case 0: err = launch_typed<f32_tag>(pl, stream); break;
@@ -501,14 +447,25 @@ bool mfma_supported(const ConvShape& s) { return shape_supported(s); }
 size_t mfma_workspace_bytes(const ConvShape& s)
 {
     if (!shape_supported(s)) return 0;
-    const Plan pl = make_plan(s);
-    return ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
+    size_t need = 0;
+    for (MfmaKernel which : {MfmaKernel::Generic, MfmaKernel::Tuned16}) {
+        if (which == MfmaKernel::Tuned16 && !igemm16_fast_eligible(s)) continue;
+        const Plan pl = make_plan(s, which);
+        const size_t bytes = ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
+        if (bytes > need) need = bytes;
+    }
+    return need;
+}
+
+bool mfma_tuned16_supported(const ConvShape& s)
+{
+    return shape_supported(s) && igemm16_fast_eligible(s);
 }
 
 hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, float* out,
-                       void* workspace, hipStream_t stream)
+                       void* workspace, hipStream_t stream, MfmaKernel which)
 {
-    return launch_igemm(s, in, kernel, out, workspace, stream);
+    return launch_igemm(s, in, kernel, out, workspace, stream, which);
 }
 
 }  // namespace capscaps

@@ -82,7 +82,7 @@ def test_null_and_misaligned_pointers_and_bad_path():
                  (FAKE, FAKE + 8, FAKE), (FAKE, FAKE, FAKE + 2)):
         assert cc.capscaps_conv_fwd_ex(*ptrs, *a, FAKE, 1 << 30, None) == cc.EINVAL
         assert cc.capscaps_conv_fwd(*ptrs, *(a[:8] + a[9:]), None) == cc.EINVAL
-    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, 7, FAKE, 1 << 30, None) == cc.EINVAL
+    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, 9, FAKE, 1 << 30, None) == cc.EINVAL
     # workspace checks come before any launch
     need = cc.capscaps_conv_fwd_workspace_bytes(*a)
     assert need > 0

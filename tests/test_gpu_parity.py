@@ -13,7 +13,8 @@ from tests.gpu_util import check, run_gpu, shape_args, to_device
 
 pytestmark = pytest.mark.gpu
 
-PATHS = {"direct": cc.PATH_DIRECT, "mfma": cc.PATH_MFMA, "auto": cc.PATH_AUTO}
+PATHS = {"direct": cc.PATH_DIRECT, "mfma": cc.PATH_MFMA, "auto": cc.PATH_AUTO,
+         "generic": cc.PATH_MFMA_GENERIC, "tuned16": cc.PATH_MFMA_TUNED16}
 
 
 def small(name, dtype, N, H, W, C, M, kh, kw, s, p, D0, D1, D2, D3, dist="normal", seed=0):
@@ -61,6 +62,44 @@ def test_small_shapes_match_oracle(shape, path, dtype):
     full_compare(w, PATHS[path])
 
 
+# shapes the 256x256-tile 16-bit kernel accepts (D1 = D2 in {8, 16}, C*D2 a multiple of 64):
+# ragged row tiles, tiles that straddle images, several column tiles with a ragged last one,
+# leading capsule dimension, strides, padding wider than the window reach, D3 != D1
+TUNED_SHAPES = [
+    #        N  H   W   C   M  kh kw s  p D0  D1  D2  D3
+    ("t16a", 2, 9, 7, 4, 5, 3, 3, 1, 1, 1, 16, 16, 16),
+    ("t16b", 3, 6, 5, 8, 20, 2, 3, 2, 2, 2, 16, 16, 4),
+    ("t16c", 1, 20, 20, 4, 3, 1, 1, 1, 0, 1, 16, 16, 8),
+    ("t8a", 2, 11, 9, 8, 9, 3, 3, 1, 1, 1, 8, 8, 8),
+    ("t8b", 5, 5, 4, 16, 40, 3, 2, 2, 1, 3, 8, 8, 12),
+    ("t8c", 1, 30, 30, 8, 4, 3, 3, 1, 3, 1, 8, 8, 4),
+]
+
+
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.FP16], ids=["bf16", "fp16"])
+@pytest.mark.parametrize("shape", TUNED_SHAPES, ids=[s[0] for s in TUNED_SHAPES])
+def test_tuned_16bit_kernel_matches_oracle(shape, dtype):
+    w = small(shape[0], dtype, *shape[1:], seed=len(shape[0]) + 50)
+    full_compare(w, PATHS["tuned16"])
+    wi = small(shape[0] + "_int", dtype, *shape[1:], dist="int", seed=61)
+    i_st, k_st, i32, k32 = wl.generate(wi)
+    ref = capsconv.conv_fwd(i32, k32, wi.stride, wi.pad)
+    got = run_gpu(wi, to_device(i_st, dtype), to_device(k_st, dtype), PATHS["tuned16"]).cpu().numpy()
+    assert np.array_equal(got.astype(np.float64), ref), wi.name
+
+
+def test_tuned_kernel_refuses_other_shapes():
+    import torch
+    w = small("no", wl.FP32, 1, 6, 6, 4, 4, 3, 3, 1, 1, 1, 16, 16, 16)
+    I = torch.zeros(w.input_shape, device="cuda")
+    K = torch.zeros(w.kernel_shape, device="cuda")
+    out = torch.zeros(w.out_shape, device="cuda")
+    ws = torch.empty(1 << 22, dtype=torch.uint8, device="cuda")
+    rc = cc.capscaps_conv_fwd_path(I.data_ptr(), K.data_ptr(), out.data_ptr(), *shape_args(w)[:13],
+                                   w.dtype, cc.PATH_MFMA_TUNED16, ws.data_ptr(), ws.numel(), None)
+    assert rc == cc.EUNSUPPORTED
+
+
 @pytest.mark.parametrize("path", ["direct", "mfma", "auto"])
 def test_paper_worked_example_on_gpu(path):
     """Fig. 2: all-ones 5x5 input of 3x3x3 capsules, all-ones 4x4 kernel -> 2x2 of 48s."""
@@ -91,13 +130,15 @@ def test_benchmark_configs_full_tensor(num, path):
     full_compare(wl.config(num), PATHS[path])
 
 
-@pytest.mark.parametrize("path", ["direct", "mfma"])
+@pytest.mark.parametrize("path", ["direct", "generic", "tuned16"])
 @pytest.mark.parametrize("num,batch,hw", [(2, 2, 32), (3, 2, 28), (5, 2, 6)])
 def test_benchmark_configs_reduced_full_tensor(num, batch, hw, path):
     """Configs 2, 3, 5 with fewer images (config 5 also with a smaller image, to keep the
     oracle's run to seconds): every pixel, channel and border, whole tensor compared."""
     w = wl.config(num)
     w = dataclasses.replace(w, N=batch, H=hw, W=hw, name=f"{w.name}[N={batch},HW={hw}]")
+    if path == "tuned16" and w.dtype == wl.FP32:
+        pytest.skip("the tuned kernel is for 16-bit element types")
     full_compare(w, PATHS[path])
 
 
