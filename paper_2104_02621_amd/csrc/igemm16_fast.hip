@@ -33,7 +33,33 @@
 namespace capscaps {
 namespace {
 
-typedef __attribute__((address_space(3))) void lds_void;
+typedef int rsrc_t __attribute__((ext_vector_type(4)));  // raw buffer descriptor (4 SGPRs)
+
+// Raw buffer descriptor: 48-bit base, stride 0, `bytes` addressable, dword data format.
+// Offsets at or beyond `bytes` read as zero.
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes)
+{
+    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+    rsrc_t r = {(int)(unsigned)(a & 0xffffffffu), (int)(unsigned)((a >> 32) & 0xffffu), (int)bytes,
+                0x00020000};
+    return r;
+}
+
+// One wave-wide copy global -> LDS: lane i moves the 16 bytes at base + voff_i + soff to LDS
+// byte address lds_addr + 16*i.  Asynchronous; completion is counted in vmcnt.  Written as
+// inline assembly so that the waits are exactly the s_waitcnt vmcnt(n) placed by hand below:
+// the compiler otherwise drains all such copies before any later LDS read, which would undo
+// the multi-stage prefetch.
+__device__ __forceinline__ void copy_to_lds_16B(rsrc_t rs, unsigned lds_addr, unsigned voff, int soff)
+{
+    // the scalar operands are wave-uniform by construction; readfirstlane pins them to SGPRs
+    // where the compiler computed them with vector instructions (it folds away otherwise)
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :
+                 : "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(voff), "s"(rs),
+                   "s"(__builtin_amdgcn_readfirstlane(soff))
+                 : "memory");
+}
 
 template <int D1, int D2, int KCH>
 struct ALayout {
@@ -117,19 +143,21 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         const int n_rel = (int)(pgc / hw - n_first);
         const int rem = (int)(pgc % hw);
         const int x = rem / P.Wo, y = rem - x * P.Wo;
-        pix_ih0[j] = x * P.stride - P.pad;
-        pix_iw0[j] = y * P.stride - P.pad;
+        pix_ih0[j] = __builtin_amdgcn_readfirstlane(x * P.stride - P.pad);
+        pix_iw0[j] = __builtin_amdgcn_readfirstlane(y * P.stride - P.pad);
         // byte offset of input pixel (ih0, iw0) of that image from in_base; meaningful only
         // together with an in-range tap
-        pix_off[j] = (int)((((long long)n_rel * P.H + pix_ih0[j]) * P.W + pix_iw0[j]) * P.pixsz * 2) +
-                     d0 * D1 * D2 * 2;
+        pix_off[j] = __builtin_amdgcn_readfirstlane(
+            (int)((((long long)n_rel * P.H + pix_ih0[j]) * P.W + pix_iw0[j]) * P.pixsz * 2) +
+            d0 * D1 * D2 * 2);
     }
     long long in_left = P.in_bytes - n_first * img_elems * 2;
     if (in_left > 0x7fffffffLL) in_left = 0x7fffffffLL;
-    const __amdgpu_buffer_rsrc_t rs_in = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<unsigned short*>(in_base), 0, (int)in_left, 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_kp = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<void*>(P.kp), 0, (int)P.kp_records, 0x00020000);
+    rsrc_t rs_in = make_rsrc(in_base, (unsigned)in_left);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) rs_in[i] = __builtin_amdgcn_readfirstlane(rs_in[i]);
+    const rsrc_t rs_kp = make_rsrc(P.kp, (unsigned)P.kp_records);
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
 
     // ---- per-lane constants
     // input block: lane -> (channel within block, d1, row half) in LDS order
@@ -164,7 +192,7 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
 
     // copy number j (0 .. 2*BW-1) of the stage described by (p, q, kq, tap) into ring slot
     auto issue_copy = [&](int slot, int j) {
-        char* stage = smem + slot * STAGE_BYTES;
+        const unsigned stage = lds0 + slot * STAGE_BYTES;
         // All selections below are mask arithmetic (0 / ~0), never ?: on a condition, so that
         // the K loop stays one basic block.  live = 0 past the last stage: the copy still runs
         // (the count of copies in flight stays uniform) but reads nothing and stores zeros.
@@ -177,8 +205,7 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
             const int c_off = (kq / D2C) * P.cs * 2;
             const int soff = (pix_off[pj] + tap_off + c_off + part * CPB * P.cs * 2) & ok;
             const unsigned voff = a_voff | (OOB & ~(unsigned)ok);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rs_in, (lds_void*)(stage + (wave * BW + j) * ABLK), 16, voff, soff, 0, 0);
+            copy_to_lds_16B(rs_in, stage + (wave * BW + j) * ABLK, voff, soff);
         } else {
             const int bb = wave * BW + (j - BW);
             const int kql = bb / 4, cg = bb % 4;
@@ -186,8 +213,7 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
                 (int)((((long long)(d0 * P.ntaps + tap) * P.KQP + kq) * P.colsp + col0) * 16);
             const int soff = (kp_off + (kql * P.colsp + cg * 64) * 16) & live;
             const unsigned voff = b_voff | (OOB & ~(unsigned)live);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(
-                rs_kp, (lds_void*)(stage + A_BYTES + bb * 1024), 16, voff, soff, 0, 0);
+            copy_to_lds_16B(rs_kp, stage + A_BYTES + bb * 1024, voff, soff);
         }
     };
     auto advance = [&]() {
