@@ -186,46 +186,70 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    // ---- K loop state (scalar) of the next stage to copy: tap (p, q), chunk within the tap
-    int p = 0, q = 0, kq = 0, tap = 0, issued = 0;
+    // ---- K loop state of the next stage to copy.  Scalars: tap (p, q), stages left in the tap,
+    // byte offsets of the stage's first channel and of its kernel chunks; per pixel the byte
+    // offset of the tap's input pixel.  Vectors: the lane offsets, with the out-of-range bit
+    // set where the tap falls into the padding (then the copy stores zeros).  Everything that
+    // depends on the tap is refreshed in retap(), a rarely taken uniform branch; the steady
+    // state of a copy is one scalar add for the offset and one for the LDS address.
     const int nstages = P.ntaps * (P.KQP / KCH);
+    const int nstages_pad = (nstages + NB - 1) / NB * NB;  // surplus stages contract zeros
+    const int stages_per_tap = P.KQP / KCH;
+    const int c_step = (KCH / D2C) * P.cs * 2;
+    const int kp_step = KCH * P.colsp * 16;
+    const int pix_bytes = (int)(P.pixsz * 2);
+    int p = 0, q = 0, left = stages_per_tap, issued = 0, c_off = 0;
+    int kp_off = (int)(((long long)d0 * P.ntaps * P.KQP * P.colsp + col0) * 16);
+    int b_const[BW];
+#pragma unroll
+    for (int j = 0; j < BW; ++j) {
+        const int bb = wave * BW + j;
+        b_const[j] = ((bb / 4) * P.colsp + (bb % 4) * 64) * 16;
+    }
+    int cur_off[PPW];
+    unsigned a_voff_cur[PPW], b_voff_cur;
+    auto retap = [&]() {
+        const bool live = issued < nstages;
+        const int tap_off = (p * P.W + q) * pix_bytes;
+#pragma unroll
+        for (int j = 0; j < PPW; ++j) {
+            const bool ok = live && pix_ok[j] && (unsigned)(pix_ih0[j] + p) < (unsigned)P.H &&
+                            (unsigned)(pix_iw0[j] + q) < (unsigned)P.W;
+            cur_off[j] = ok ? pix_off[j] + tap_off : 0;
+            a_voff_cur[j] = ok ? a_voff : (a_voff | OOB);
+        }
+        b_voff_cur = live ? b_voff : (b_voff | OOB);
+    };
+    retap();
 
-    // copy number j (0 .. 2*BW-1) of the stage described by (p, q, kq, tap) into ring slot
+    // copy number j (0 .. 2*BW-1) of the next stage into ring slot `slot`
     auto issue_copy = [&](int slot, int j) {
         const unsigned stage = lds0 + slot * STAGE_BYTES;
-        // All selections below are mask arithmetic (0 / ~0), never ?: on a condition, so that
-        // the K loop stays one basic block.  live = 0 past the last stage: the copy still runs
-        // (the count of copies in flight stays uniform) but reads nothing and stores zeros.
-        const int live = -(int)(issued < nstages);
         if (j < BW) {
             const int pj = j / BPP, part = j % BPP;
-            const int ok = live & -(pix_ok[pj] & (int)((unsigned)(pix_ih0[pj] + p) < (unsigned)P.H) &
-                                    (int)((unsigned)(pix_iw0[pj] + q) < (unsigned)P.W));
-            const int tap_off = (p * P.W + q) * (int)(P.pixsz * 2);
-            const int c_off = (kq / D2C) * P.cs * 2;
-            const int soff = (pix_off[pj] + tap_off + c_off + part * CPB * P.cs * 2) & ok;
-            const unsigned voff = a_voff | (OOB & ~(unsigned)ok);
-            copy_to_lds_16B(rs_in, stage + (wave * BW + j) * ABLK, voff, soff);
+            copy_to_lds_16B(rs_in, stage + (wave * BW + j) * ABLK, a_voff_cur[pj],
+                            cur_off[pj] + c_off + part * CPB * P.cs * 2);
         } else {
-            const int bb = wave * BW + (j - BW);
-            const int kql = bb / 4, cg = bb % 4;
-            const int kp_off =
-                (int)((((long long)(d0 * P.ntaps + tap) * P.KQP + kq) * P.colsp + col0) * 16);
-            const int soff = (kp_off + (kql * P.colsp + cg * 64) * 16) & live;
-            const unsigned voff = b_voff | (OOB & ~(unsigned)live);
-            copy_to_lds_16B(rs_kp, stage + A_BYTES + bb * 1024, voff, soff);
+            const int jb = j - BW;
+            copy_to_lds_16B(rs_kp, stage + A_BYTES + (wave * BW + jb) * 1024, b_voff_cur,
+                            kp_off + b_const[jb]);
         }
     };
     auto advance = [&]() {
         ++issued;
-        kq += KCH;
-        const int wrap = kq == P.KQP ? 1 : 0;
-        kq = wrap ? 0 : kq;
-        tap += wrap;
-        q += wrap;
-        const int wrapq = q == P.kw ? 1 : 0;
-        q = wrapq ? 0 : q;
-        p += wrapq;
+        --left;
+        c_off += c_step;
+        kp_off += kp_step;
+        if (__builtin_expect(left == 0 || issued == nstages, 0)) {
+            left = stages_per_tap;
+            c_off = 0;
+            ++q;
+            if (q == P.kw) {
+                q = 0;
+                ++p;
+            }
+            retap();
+        }
     };
 
     // operand fragment f of k-step t from ring slot: f < TN kernel side, else input side
@@ -254,33 +278,36 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
 #pragma unroll
     for (int f = 0; f < NFRAG; ++f) frag[0][f] = read_frag(0, 0, f);
 
-    // ---- main loop: one ring slot per iteration.  Between consecutive MFMAs go the side
-    // operations: the copies of the stage NB-1 ahead and the fragment reads of the next k-step.
-    int slot = 0;  // ring slot being contracted
-    for (int st = 0; st < nstages; ++st) {
-        const int slot_fill = slot == 0 ? NB - 1 : slot - 1;  // consumed in the last iteration
-        const int slot_next = slot == NB - 1 ? 0 : slot + 1;
+    // ---- main loop, unrolled over the ring so that slots are compile-time constants.  Between
+    // consecutive MFMAs go the side operations: the copies of the stage NB-1 ahead and the
+    // fragment reads of the next k-step.
+    for (int st = 0; st < nstages_pad; st += NB) {
 #pragma unroll
-        for (int t = 0; t < KS; ++t) {
-            const int cur = t & 1, nxt = cur ^ 1;
-            if (t == KS - 1) {
-                // everything this wave still needs from `slot` is in registers; its copies of
-                // the next stage have landed; after the barrier that holds for all waves
-                __builtin_amdgcn_s_waitcnt(VMCNT_KEEP & 0xF0FF);  // and lgkmcnt(0)
-                __syncthreads();
-            }
+        for (int slot = 0; slot < NB; ++slot) {
+            const int slot_fill = (slot + NB - 1) % NB;  // consumed in the previous stage
+            const int slot_next = (slot + 1) % NB;
 #pragma unroll
-            for (int i = 0; i < TN * TM; ++i) {
-                const int a = i / TM, b = i % TM;
-                Mma<Tag>::run(frag[cur][a], frag[cur][TN + b], acc[a][b]);
-                if (i < NFRAG)
-                    frag[nxt][i] = t == KS - 1 ? read_frag(slot_next, 0, i) : read_frag(slot, t + 1, i);
-                if (t == 0 && i < 2 * BW) issue_copy(slot_fill, i);
-                __builtin_amdgcn_sched_barrier(0);
+            for (int t = 0; t < KS; ++t) {
+                const int cur = t & 1, nxt = cur ^ 1;
+                if (t == KS - 1) {
+                    // everything this wave still needs from `slot` is in registers; its copies
+                    // of the next stage have landed; after the barrier that holds for all waves
+                    __builtin_amdgcn_s_waitcnt(VMCNT_KEEP & 0xF0FF);  // and lgkmcnt(0)
+                    __syncthreads();
+                }
+#pragma unroll
+                for (int i = 0; i < TN * TM; ++i) {
+                    const int a = i / TM, b = i % TM;
+                    Mma<Tag>::run(frag[cur][a], frag[cur][TN + b], acc[a][b]);
+                    if (i < NFRAG)
+                        frag[nxt][i] =
+                            t == KS - 1 ? read_frag(slot_next, 0, i) : read_frag(slot, t + 1, i);
+                    if (t == 0 && i < 2 * BW) issue_copy(slot_fill, i);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (t == 0) advance();
             }
         }
-        advance();
-        slot = slot_next;
     }
 
     // ---- epilogue (lane (h, lr) of tile (a, b): registers 4g..4g+3 = columns 8g+4h+0..3)
