@@ -339,7 +339,11 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
 template <int D1, int D2>
 struct FastConfig;  // chunks per stage and ring depth chosen per capsule size
 template <>
-struct FastConfig<16, 16> { static constexpr int KCH = 4, NB = 4; };
+#ifndef CAPSCAPS_KCH16
+#define CAPSCAPS_KCH16 4
+#define CAPSCAPS_NB16 4
+#endif
+struct FastConfig<16, 16> { static constexpr int KCH = CAPSCAPS_KCH16, NB = CAPSCAPS_NB16; };
 template <>
 struct FastConfig<8, 8> { static constexpr int KCH = 8, NB = 2; };
 
