@@ -1,16 +1,21 @@
 // Tuned matrix-core kernel of the capsule convolution forward pass for 16-bit element types
 // and capsule dimensions D1 = D2 in {8, 16}: the shapes where the contraction is dense enough
 // to be bound by the MFMA rate.  Same implicit GEMM as igemm_conv.hip (rows (pixel,d1),
-// columns (m,d3), K = (tap, c, d2); paper Algorithm 2), same repacked kernel layout, but
+// columns (m,d3), K = (tap, c, d2); paper Algorithm 2), but
 //
 //   * global -> LDS copies are buffer loads that write LDS directly (no VGPR staging, no
 //     ds_write): one wave instruction moves 64 chunks of 16 bytes = 1 KB ("block");
 //   * all per-block addressing is wave-uniform (SGPR): a block never mixes pixels, so the
-//     window tap, the padding test and the channel offset are scalar arithmetic, and a pixel
-//     outside the image is read through an out-of-range buffer offset that returns zeros;
-//   * the K loop is one branch-free basic block in which the copies of a stage NB-1 ahead and
-//     the LDS operand reads of the next k-step are placed between the MFMAs of the current
-//     k-step (operand fragments are double-buffered in registers).
+//     window tap and the channel offset are scalar adds, and a tap that falls into the padding
+//     is an out-of-range buffer offset, which the hardware answers with zeros;
+//   * the K loop runs channel group outermost and window tap innermost: the kh*kw shifted
+//     windows of one channel group are fetched in consecutive stages, so all but the first
+//     touch of an input byte are L2 hits (tap-outermost order re-streams the whole input
+//     window from HBM once per tap);
+//   * the K loop is one branch-free basic block per stage in which the copies of the stages
+//     NB-1 and NB ahead (one after every fourth MFMA) and the LDS operand reads of the next
+//     k-step sit between the MFMAs of the current k-step (operand fragments are
+//     double-buffered in registers).
 //
 // Tile: 256 rows x 256 columns, 4 waves of 128 x 128 (4 x 4 MFMA 32x32x16 tiles, 256
 // accumulator registers).  A K stage is KCH chunks (KCH*8 elements) per row; LDS holds a ring
@@ -25,8 +30,12 @@
 //                two halves of a row swap places for d1 >= 8, so the 16 lanes of a quarter
 //                wave always touch 16 distinct 16-byte bank groups when reading MFMA operands.
 //   kernel side: [chunk 0..KCH-1][column 0..255][16 bytes], copied verbatim from the repacked
-//                kernel; operand reads are 512 contiguous bytes per 32 lanes.
+//                kernel (repacked in the same stage order); operand reads are 512 contiguous
+//                bytes per 32 lanes.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
+#include <utility>
 
 #include "igemm_common.h"
 
@@ -35,30 +44,48 @@ namespace {
 
 typedef int rsrc_t __attribute__((ext_vector_type(4)));  // raw buffer descriptor (4 SGPRs)
 
+// compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(<N-1>)
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
+
 // Raw buffer descriptor: 48-bit base, stride 0, `bytes` addressable, dword data format.
 // Offsets at or beyond `bytes` read as zero.
 __device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes)
 {
     const unsigned long long a = reinterpret_cast<unsigned long long>(base);
-    rsrc_t r = {(int)(unsigned)(a & 0xffffffffu), (int)(unsigned)((a >> 32) & 0xffffu), (int)bytes,
-                0x00020000};
+    rsrc_t r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)(a & 0xffffffffu));
+    r[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)((a >> 32) & 0xffffu));
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+    r[3] = 0x00020000;
     return r;
 }
 
-// One wave-wide copy global -> LDS: lane i moves the 16 bytes at base + voff_i + soff to LDS
-// byte address lds_addr + 16*i.  Asynchronous; completion is counted in vmcnt.  Written as
-// inline assembly so that the waits are exactly the s_waitcnt vmcnt(n) placed by hand below:
-// the compiler otherwise drains all such copies before any later LDS read, which would undo
-// the multi-stage prefetch.
-__device__ __forceinline__ void copy_to_lds_16B(rsrc_t rs, unsigned lds_addr, unsigned voff, int soff)
+// One wave-wide copy global -> LDS: lane i moves the 16 bytes at base + voff_i + soff_a + soff_b
+// to LDS byte address lds_base + LDS_IMM + 16*i.  The sum of the offsets is range-checked
+// against the descriptor: at or beyond its size the lane stores zeros.  Asynchronous;
+// completion is counted in vmcnt.  Inline assembly on purpose: the waits are exactly the
+// s_waitcnt vmcnt(n) placed by hand in the K loop (the compiler would drain all such copies
+// before any later LDS read, which would undo the multi-stage prefetch).  The scalar add
+// between the M0 write and the copy is the wait state that sequence needs.
+template <int LDS_IMM>
+__device__ __forceinline__ void copy_to_lds_16B(rsrc_t rs, unsigned lds_base, unsigned voff,
+                                                int soff_a, int soff_b)
 {
-    // the scalar operands are wave-uniform by construction; readfirstlane pins them to SGPRs
-    // where the compiler computed them with vector instructions (it folds away otherwise)
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 :
-                 : "s"(__builtin_amdgcn_readfirstlane((int)lds_addr)), "v"(voff), "s"(rs),
-                   "s"(__builtin_amdgcn_readfirstlane(soff))
-                 : "memory");
+    int tmp;
+    asm volatile(
+        "s_add_u32 m0, %1, %5\n\ts_add_u32 %0, %3, %4\n\tbuffer_load_dwordx4 %2, %6, %0 offen lds"
+        : "=&s"(tmp)
+        : "s"(lds_base), "v"(voff), "s"(soff_a), "s"(soff_b), "i"(LDS_IMM), "s"(rs)
+        : "memory", "scc");
 }
 
 template <int D1, int D2, int KCH>
@@ -96,20 +123,25 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     constexpr int ABLK = AL::ABLK, NBLK = AL::NBLK;
     constexpr int A_BYTES = NBLK * ABLK, B_BYTES = NBLK * 1024, STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int WM = BM / NWM, WN = BN / NWN, TM = WM / 32, TN = WN / 32;
+    constexpr int NMMA = TM * TN;    // MFMAs per k-step = slots for side operations
     constexpr int KS = KCH / 2;      // MFMA k-steps (16 K elements) per stage
     constexpr int BW = NBLK / NW;    // blocks per wave, per operand and stage
     constexpr int PPW = BW / BPP;    // pixels whose blocks this wave loads
     constexpr int NFRAG = TN + TM;   // operand fragments per k-step
+    constexpr int NCOPY = 2 * BW;    // copies per wave and stage
     static_assert(BW % BPP == 0 && PPW >= 1, "a wave loads whole pixels");
-    static_assert(TM * TN >= NFRAG && TM * TN >= 2 * BW, "side operations fit between MFMAs");
-    constexpr unsigned OOB = 0x80000000u;
+    static_assert(NFRAG <= NMMA && PPW <= 3 * 4, "side operations fit between the MFMAs");
+    static_assert(KS % 2 == 0, "register double buffer alternates per k-step");
+    constexpr int OOB = (int)0x80000000u;
     // s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
-    constexpr int KEEP = (NB - 2) * 2 * BW;  // copies that may still be in flight at a barrier
+    constexpr int KEEP = (NB - 2) * NCOPY;  // copies that may still be in flight at a barrier
+    static_assert(KEEP < 64, "vmcnt is a 6-bit counter");
     constexpr int VMCNT_KEEP = 0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14);
 
     extern __shared__ char smem[];
 
-    // ---- tile (same mapping as the generic kernel: XCD-contiguous, column tiles fastest)
+    // ---- tile: consecutive logical tiles go to the same XCD (blocks are dealt to the 8 XCDs
+    // round-robin), column tiles fastest so that neighbours share input rows in that L2
     const int nb = gridDim.x;
     int L = blockIdx.x;
     {
@@ -127,37 +159,41 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     const int h = lane >> 5, lr = lane & 31;
     const int col0 = col_tile * BN;
 
-    // ---- per-wave scalar state of the pixels whose input blocks this wave loads
+    // ---- the pixels whose input blocks this wave copies, and per pixel a table over the window
+    // taps (lane t = tap t): byte offset of the tap's input pixel from in_base, or the
+    // out-of-range mark where the tap falls into the padding or the pixel does not exist
     const int hw = P.Ho * P.Wo;
     const long long npix = P.rows / D1;
     const long long pg0 = (long long)row_tile * PIX;
     const long long n_first = pg0 / hw;
     const long long img_elems = (long long)P.H * P.W * P.pixsz;
     const unsigned short* in_base = static_cast<const unsigned short*>(P.in) + n_first * img_elems;
-    int pix_off[PPW], pix_ih0[PPW], pix_iw0[PPW], pix_ok[PPW];
+    const int pix_bytes = (int)(P.pixsz * 2);
+    const int tap_p = lane / P.kw, tap_q = lane - tap_p * P.kw;  // this lane's tap
+    int tap_tab[PPW];
 #pragma unroll
     for (int j = 0; j < PPW; ++j) {
         const long long pg = pg0 + wave * PPW + j;
-        pix_ok[j] = pg < npix ? 1 : 0;
-        const long long pgc = pix_ok[j] ? pg : pg0;
+        const bool exists = pg < npix;
+        const long long pgc = exists ? pg : pg0;
         const int n_rel = (int)(pgc / hw - n_first);
         const int rem = (int)(pgc % hw);
         const int x = rem / P.Wo, y = rem - x * P.Wo;
-        pix_ih0[j] = __builtin_amdgcn_readfirstlane(x * P.stride - P.pad);
-        pix_iw0[j] = __builtin_amdgcn_readfirstlane(y * P.stride - P.pad);
-        // byte offset of input pixel (ih0, iw0) of that image from in_base; meaningful only
-        // together with an in-range tap
-        pix_off[j] = __builtin_amdgcn_readfirstlane(
-            (int)((((long long)n_rel * P.H + pix_ih0[j]) * P.W + pix_iw0[j]) * P.pixsz * 2) +
-            d0 * D1 * D2 * 2);
+        const int ih = x * P.stride - P.pad + tap_p, iw = y * P.stride - P.pad + tap_q;
+        const bool ok = exists && lane < P.ntaps && (unsigned)ih < (unsigned)P.H &&
+                        (unsigned)iw < (unsigned)P.W;
+        tap_tab[j] = ok ? (int)((((long long)n_rel * P.H + ih) * P.W + iw) * pix_bytes) +
+                              d0 * D1 * D2 * 2
+                        : OOB;
     }
     long long in_left = P.in_bytes - n_first * img_elems * 2;
     if (in_left > 0x7fffffffLL) in_left = 0x7fffffffLL;
-    rsrc_t rs_in = make_rsrc(in_base, (unsigned)in_left);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) rs_in[i] = __builtin_amdgcn_readfirstlane(rs_in[i]);
+    const rsrc_t rs_in = make_rsrc(in_base, (unsigned)in_left);
     const rsrc_t rs_kp = make_rsrc(P.kp, (unsigned)P.kp_records);
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+    // LDS byte addresses of this wave's first input block and first kernel block in slot 0
+    const unsigned lds_a = __builtin_amdgcn_readfirstlane((int)(lds0 + wave * BW * ABLK));
+    const unsigned lds_b = __builtin_amdgcn_readfirstlane((int)(lds0 + A_BYTES + wave * BW * 1024));
 
     // ---- per-lane constants
     // input block: lane -> (channel within block, d1, row half) in LDS order
@@ -186,70 +222,49 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    // ---- K loop state of the next stage to copy.  Scalars: tap (p, q), stages left in the tap,
-    // byte offsets of the stage's first channel and of its kernel chunks; per pixel the byte
-    // offset of the tap's input pixel.  Vectors: the lane offsets, with the out-of-range bit
-    // set where the tap falls into the padding (then the copy stores zeros).  Everything that
-    // depends on the tap is refreshed in retap(), a rarely taken uniform branch; the steady
-    // state of a copy is one scalar add for the offset and one for the LDS address.
+    // ---- K loop state (scalar) of the next stage to copy.  Stage s covers channel group
+    // s / ntaps (KCH chunks = KCH/D2C channels) at window tap s % ntaps.
     const int nstages = P.ntaps * (P.KQP / KCH);
     const int nstages_pad = (nstages + NB - 1) / NB * NB;  // surplus stages contract zeros
-    const int stages_per_tap = P.KQP / KCH;
-    const int c_step = (KCH / D2C) * P.cs * 2;
-    const int kp_step = KCH * P.colsp * 16;
-    const int pix_bytes = (int)(P.pixsz * 2);
-    int p = 0, q = 0, left = stages_per_tap, issued = 0, c_off = 0;
-    int kp_off = (int)(((long long)d0 * P.ntaps * P.KQP * P.colsp + col0) * 16);
+    const int c_step = (KCH / D2C) * P.cs * 2;             // bytes per channel group
+    const int kp_step = KCH * P.colsp * 16;                 // repacked kernel bytes per stage
+    int tap = 0, issued = 0, c_off = 0;
+    int kp_off = (int)(((long long)d0 * nstages * KCH * P.colsp + col0) * 16);
     int b_const[BW];
 #pragma unroll
     for (int j = 0; j < BW; ++j) {
         const int bb = wave * BW + j;
         b_const[j] = ((bb / 4) * P.colsp + (bb % 4) * 64) * 16;
     }
-    int cur_off[PPW];
-    unsigned a_voff_cur[PPW], b_voff_cur;
-    auto retap = [&]() {
-        const bool live = issued < nstages;
-        const int tap_off = (p * P.W + q) * pix_bytes;
-#pragma unroll
-        for (int j = 0; j < PPW; ++j) {
-            const bool ok = live && pix_ok[j] && (unsigned)(pix_ih0[j] + p) < (unsigned)P.H &&
-                            (unsigned)(pix_iw0[j] + q) < (unsigned)P.W;
-            cur_off[j] = ok ? pix_off[j] + tap_off : 0;
-            a_voff_cur[j] = ok ? a_voff : (a_voff | OOB);
-        }
-        b_voff_cur = live ? b_voff : (b_voff | OOB);
-    };
-    retap();
+    int a_soff[PPW];  // per pixel: byte offset of the current tap's input pixel, or OOB
 
-    // copy number j (0 .. 2*BW-1) of the next stage into ring slot `slot`
-    auto issue_copy = [&](int slot, int j) {
-        const unsigned stage = lds0 + slot * STAGE_BYTES;
-        if (j < BW) {
-            const int pj = j / BPP, part = j % BPP;
-            copy_to_lds_16B(rs_in, stage + (wave * BW + j) * ABLK, a_voff_cur[pj],
-                            cur_off[pj] + c_off + part * CPB * P.cs * 2);
+    // scalar offsets of the next stage's input copies (one table lookup per pixel)
+    auto stage_offset = [&](int j) {
+        const int live = issued < nstages;
+        const int off = __builtin_amdgcn_readlane(tap_tab[j], tap);
+        a_soff[j] = live ? off : OOB;  // past the last stage: zero fill, touches no memory
+    };
+    // copy number J (0 .. NCOPY-1) of the next stage into ring slot SLOT
+    auto issue_copy = [&](auto SLOT, auto J) {
+        constexpr int slot = decltype(SLOT)::value, j = decltype(J)::value;
+        if constexpr (j < BW) {
+            constexpr int pj = j / BPP, part = j % BPP;
+            copy_to_lds_16B<slot * STAGE_BYTES + j * ABLK>(rs_in, lds_a, a_voff, a_soff[pj],
+                                                           c_off + part * CPB * P.cs * 2);
         } else {
-            const int jb = j - BW;
-            copy_to_lds_16B(rs_kp, stage + A_BYTES + (wave * BW + jb) * 1024, b_voff_cur,
-                            kp_off + b_const[jb]);
+            constexpr int jb = j - BW;
+            // beyond the repacked kernel (surplus stages) the range check returns zeros
+            copy_to_lds_16B<slot * STAGE_BYTES + jb * 1024>(rs_kp, lds_b, b_voff, kp_off,
+                                                            b_const[jb]);
         }
     };
     auto advance = [&]() {
         ++issued;
-        --left;
-        c_off += c_step;
+        ++tap;
         kp_off += kp_step;
-        if (__builtin_expect(left == 0 || issued == nstages, 0)) {
-            left = stages_per_tap;
-            c_off = 0;
-            ++q;
-            if (q == P.kw) {
-                q = 0;
-                ++p;
-            }
-            retap();
-        }
+        const bool wrap = tap == P.ntaps;
+        tap = wrap ? 0 : tap;
+        c_off = wrap ? c_off + c_step : c_off;
     };
 
     // operand fragment f of k-step t from ring slot: f < TN kernel side, else input side
@@ -265,49 +280,75 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         return *reinterpret_cast<const chunk_t*>(stage + a_rd + off);
     };
 
-    // ---- prologue: fill NB-1 ring slots, wait for the first, fetch its first fragments
+    // ---- schedule of the side operations.  A stage has KS*NMMA MFMAs and NCOPY = 4*KS copies:
+    // one copy after every fourth MFMA keeps the copy queue shallow.  The copies of stage X
+    // start right after the barrier of iteration X-NB (from there on no wave reads that ring
+    // slot any more: the last k-step's operands are in registers) and end before the barrier of
+    // iteration X-NB+1.  COPY_AT(g): window position g -> copy number, or -1.
+    static_assert(NCOPY == 4 * KS && NMMA == 16, "one copy per four MFMAs");
+    constexpr int HEAD = 4;  // copies issued in the k-step after the barrier
+
+    // ---- prologue: stages 0..NB-2 whole and the head of stage NB-1, wait for stage 0, fetch
+    // its first fragments
+    static_for<NB - 1>([&](auto S0) {
 #pragma unroll
-    for (int s0 = 0; s0 < NB - 1; ++s0) {
-#pragma unroll
-        for (int j = 0; j < 2 * BW; ++j) issue_copy(s0, j);
+        for (int j = 0; j < PPW; ++j) stage_offset(j);
+        static_for<NCOPY>([&](auto J) { issue_copy(S0, J); });
         advance();
+    });
+#pragma unroll
+    for (int j = 0; j < PPW; ++j) stage_offset(j);
+    static_for<HEAD>([&](auto J) { issue_copy(std::integral_constant<int, NB - 1>{}, J); });
+    {
+        constexpr int keep0 = (NB - 2) * NCOPY + HEAD;
+        static_assert(keep0 < 64, "vmcnt is a 6-bit counter");
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (keep0 & 15) | ((keep0 >> 4) << 14));
     }
-    __builtin_amdgcn_s_waitcnt(VMCNT_KEEP);
     __syncthreads();
     chunk_t frag[2][NFRAG];
 #pragma unroll
     for (int f = 0; f < NFRAG; ++f) frag[0][f] = read_frag(0, 0, f);
 
-    // ---- main loop, unrolled over the ring so that slots are compile-time constants.  Between
-    // consecutive MFMAs go the side operations: the copies of the stage NB-1 ahead and the
-    // fragment reads of the next k-step.
+    // ---- main loop, unrolled over the ring so that slots are compile-time constants
     for (int st = 0; st < nstages_pad; st += NB) {
-#pragma unroll
-        for (int slot = 0; slot < NB; ++slot) {
-            const int slot_fill = (slot + NB - 1) % NB;  // consumed in the previous stage
-            const int slot_next = (slot + 1) % NB;
-#pragma unroll
-            for (int t = 0; t < KS; ++t) {
-                const int cur = t & 1, nxt = cur ^ 1;
-                if (t == KS - 1) {
+        static_for<NB>([&](auto SLOT) {
+            constexpr int slot = decltype(SLOT)::value;
+            constexpr int slot_next = (slot + 1) % NB;
+            typedef std::integral_constant<int, (slot + NB - 1) % NB> SlotPrev;
+            static_for<KS>([&](auto T) {
+                constexpr int t = decltype(T)::value;
+                constexpr int cur = t & 1, nxt = cur ^ 1;
+                if constexpr (t == KS - 1) {
+                    // the stage whose copies were completed in the k-steps above is accounted
+                    advance();
                     // everything this wave still needs from `slot` is in registers; its copies
                     // of the next stage have landed; after the barrier that holds for all waves
                     __builtin_amdgcn_s_waitcnt(VMCNT_KEEP & 0xF0FF);  // and lgkmcnt(0)
                     __syncthreads();
                 }
-#pragma unroll
-                for (int i = 0; i < TN * TM; ++i) {
-                    const int a = i / TM, b = i % TM;
+                static_for<NMMA>([&](auto I) {
+                    constexpr int i = decltype(I)::value;
+                    constexpr int a = i / TM, b = i % TM;
                     Mma<Tag>::run(frag[cur][a], frag[cur][TN + b], acc[a][b]);
-                    if (i < NFRAG)
+                    if constexpr (i < NFRAG)
                         frag[nxt][i] =
                             t == KS - 1 ? read_frag(slot_next, 0, i) : read_frag(slot, t + 1, i);
-                    if (t == 0 && i < 2 * BW) issue_copy(slot_fill, i);
+                    if constexpr (t == KS - 1) {
+                        // head of the stage NB ahead, into the slot this iteration has just
+                        // finished reading
+                        if constexpr (i < PPW) stage_offset(i);
+                        if constexpr (i % 4 == 2)
+                            issue_copy(SLOT, std::integral_constant<int, i / 4>{});
+                    } else {
+                        // rest of the stage NB-1 ahead (its head went out one k-step earlier)
+                        if constexpr (i % 4 == 2)
+                            issue_copy(SlotPrev{},
+                                       std::integral_constant<int, HEAD + t * 4 + i / 4>{});
+                    }
                     __builtin_amdgcn_sched_barrier(0);
-                }
-                if (t == 0) advance();
-            }
-        }
+                });
+            });
+        });
     }
 
     // ---- epilogue (lane (h, lr) of tile (a, b): registers 4g..4g+3 = columns 8g+4h+0..3)
@@ -339,11 +380,7 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
 template <int D1, int D2>
 struct FastConfig;  // chunks per stage and ring depth chosen per capsule size
 template <>
-#ifndef CAPSCAPS_KCH16
-#define CAPSCAPS_KCH16 4
-#define CAPSCAPS_NB16 4
-#endif
-struct FastConfig<16, 16> { static constexpr int KCH = CAPSCAPS_KCH16, NB = CAPSCAPS_NB16; };
+struct FastConfig<16, 16> { static constexpr int KCH = 4, NB = 4; };
 template <>
 struct FastConfig<8, 8> { static constexpr int KCH = 8, NB = 2; };
 
@@ -377,7 +414,8 @@ bool igemm16_fast_eligible(const ConvShape& s)
     if (s.dtype != 1 && s.dtype != 2) return false;
     if (!((s.D1 == 16 && s.D2 == 16) || (s.D1 == 8 && s.D2 == 8))) return false;
     if (s.D3 % 4 != 0) return false;
-    if ((s.C * s.D2) % 64 != 0) return false;  // whole K stages per tap
+    if ((s.C * s.D2) % 64 != 0) return false;  // whole K stages per channel group
+    if (s.kh * s.kw > 64) return false;        // one lane of the tap table per window tap
     // 31-bit byte offsets: a tile's input window spans at most the images its 256/D1 pixels
     // touch; the repacked kernel is addressed from its start
     const long long img_bytes = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 2;
@@ -387,7 +425,7 @@ bool igemm16_fast_eligible(const ConvShape& s)
     if (images_spanned * img_bytes >= (1LL << 31)) return false;
     const long long colsp = ((long long)s.M * s.D3 + 255) / 256 * 256;
     const long long kp_bytes = (long long)s.D0 * s.kh * s.kw * (s.C * s.D2 / 8) * colsp * 16;
-    if (kp_bytes >= (1LL << 31)) return false;
+    if (kp_bytes >= (1LL << 31) - (1 << 24)) return false;
     return true;
 }
 
@@ -398,6 +436,11 @@ bool igemm16_fast_preferred(const ConvShape& s)
     const long long colsp = ((long long)s.M * s.D3 + 255) / 256 * 256;
     const long long tiles = ((long long)s.pixels() * s.D1 + 255) / 256 * (colsp / 256) * s.D0;
     return tiles >= 256;
+}
+
+int igemm16_fast_kgroup(const ConvShape& s)
+{
+    return s.D1 == 16 ? FastConfig<16, 16>::KCH : FastConfig<8, 8>::KCH;
 }
 
 hipError_t launch_igemm16_fast(const IgemmParams& P, long long blocks, int dtype,

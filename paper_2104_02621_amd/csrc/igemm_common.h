@@ -74,6 +74,7 @@ struct IgemmParams {
 // Tuned 16-bit kernel (igemm16_fast.hip): 256x256 tiles, direct-to-LDS copies.
 bool igemm16_fast_eligible(const ConvShape& s);   // the kernel can run the shape
 bool igemm16_fast_preferred(const ConvShape& s);  // ... and is the library's choice for it
+int igemm16_fast_kgroup(const ConvShape& s);      // chunks per K stage (repack order)
 hipError_t launch_igemm16_fast(const IgemmParams& P, long long blocks, int dtype,
                                hipStream_t stream);
 

@@ -32,21 +32,33 @@ namespace capscaps {
 namespace {
 
 // ---------------------------------------------------------------------------------------------
-// Kernel repack: Kp[d0][tap][kq][j][e] = K[tap][c][m][d0][d2][d3] with k = kq*CH+e = c*D2+d2,
-// j = m*D3+d3; zero where k >= C*D2 or j >= M*D3.  One thread per 16-byte chunk.
+// Kernel repack: Kp[..][j][e] = K[tap][c][m][d0][d2][d3] with k = kq*CH+e = c*D2+d2,
+// j = m*D3+d3; zero where k >= C*D2 or j >= M*D3.  One thread per 16-byte chunk.  Chunk order
+// is the order in which the consuming kernel walks K:  kgroup = 0: [d0][tap][kq] (tap outermost);
+// kgroup = g > 0: [d0][kq / g][tap][kq % g] (groups of g chunks outermost, tap inside).
 template <typename E, int CH>
 __global__ __launch_bounds__(256) void repack_kernel(const E* __restrict__ kernel,
                                                      E* __restrict__ kp, int ntaps, int C, int M,
                                                      int D0, int D2, int D3, int KT, int KQP,
-                                                     int cols, int colsp, size_t total_chunks)
+                                                     int cols, int colsp, int kgroup,
+                                                     size_t total_chunks)
 {
     const size_t id = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (id >= total_chunks) return;
     size_t r = id;
     const int j = (int)(r % colsp); r /= colsp;
-    const int kq = (int)(r % KQP);  r /= KQP;
-    const int tap = (int)(r % ntaps);
-    const int d0 = (int)(r / ntaps);
+    int kq, tap, d0;
+    if (kgroup > 0) {
+        const int kql = (int)(r % kgroup); r /= kgroup;
+        tap = (int)(r % ntaps);            r /= ntaps;
+        const int groups = KQP / kgroup;
+        kq = (int)(r % groups) * kgroup + kql;
+        d0 = (int)(r / groups);
+    } else {
+        kq = (int)(r % KQP);  r /= KQP;
+        tap = (int)(r % ntaps);
+        d0 = (int)(r / ntaps);
+    }
     E v[CH];
 #pragma unroll
     for (int e = 0; e < CH; ++e) {
@@ -408,15 +420,16 @@ hipError_t launch_igemm(const ConvShape& s, const void* in, const void* kernel, 
     pl.P.out = pl.P.nsplit > 1 ? partial : out;
 
     const size_t chunks = pl.repack_bytes / 16;
+    const int kgroup = pl.fast ? igemm16_fast_kgroup(s) : 0;
     const unsigned rblocks = (unsigned)((chunks + 255) / 256);
     if (s.dtype == 0) {
         repack_kernel<float, 4><<<rblocks, 256, 0, stream>>>(
             (const float*)kernel, (float*)kp, pl.P.ntaps, s.C, s.M, s.D0, s.D2, s.D3, pl.P.KT,
-            pl.P.KQP, pl.P.cols, pl.P.colsp, chunks);
+            pl.P.KQP, pl.P.cols, pl.P.colsp, kgroup, chunks);
     } else {
         repack_kernel<unsigned short, 8><<<rblocks, 256, 0, stream>>>(
             (const unsigned short*)kernel, (unsigned short*)kp, pl.P.ntaps, s.C, s.M, s.D0, s.D2,
-            s.D3, pl.P.KT, pl.P.KQP, pl.P.cols, pl.P.colsp, chunks);
+            s.D3, pl.P.KT, pl.P.KQP, pl.P.cols, pl.P.colsp, kgroup, chunks);
     }
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
