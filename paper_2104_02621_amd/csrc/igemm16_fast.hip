@@ -88,27 +88,55 @@ __device__ __forceinline__ void copy_to_lds_16B(rsrc_t rs, unsigned lds_base, un
         : "memory", "scc");
 }
 
+// Input-side block geometry.  A block is the 64 chunks one wave-wide copy moves.  Either a
+// pixel's stage data fills one or more blocks (PPB = 1, BPP blocks per pixel, each holding CPB
+// channels as [channel][d1][d2-half]), or two pixels share a block (PPB = 2, D1 = D2 = 8 with 4
+// chunks per stage: [channel 0..3][pixel 0..1][d1 0..7], the lower half wave copies one pixel,
+// the upper half the other).
 template <int D1, int D2, int KCH>
 struct ALayout {
     static constexpr int D2C = D2 / 8;             // chunks per capsule row
     static constexpr int G = D1 * D2C;             // chunks per (pixel, channel)
-    static constexpr int CPB = 64 / G;             // channels per block
-    static constexpr int BPP = KCH * D1 / 64;      // blocks per pixel and stage
+    static constexpr int PPB = (KCH * D1 >= 64) ? 1 : 64 / (KCH * D1);  // pixels per block
+    static constexpr int BPP = (PPB == 1) ? KCH * D1 / 64 : 1;  // blocks per pixel (PPB = 1)
+    static constexpr int CPB = 64 / (G * PPB);     // channels per block
     static constexpr int PIX = 256 / D1;           // pixels per tile
     static constexpr int NBLK = 4 * KCH;           // blocks per operand and stage
     // padding between blocks so that lanes of a quarter wave that belong to different pixels
     // fall into different bank groups
-    static constexpr int APAD = (G == 8) ? 128 : 0;
+    static constexpr int APAD = (G == 8 && PPB == 1) ? 128 : 0;
     static constexpr int ABLK = 1024 + APAD;
     static_assert(D1 == 8 || D1 == 16, "D1");
     static_assert(D2 == 8 || D2 == 16, "D2");
     static_assert(KCH == 4 || KCH == 8, "chunks per stage");
-    static_assert(BPP >= 1 && BPP * 64 == KCH * D1, "a block never mixes pixels");
+    static_assert(PPB == 1 || (PPB == 2 && D2C == 1), "at most two pixels share a block");
+    static_assert(PPB * BPP * 64 == PPB * PPB * KCH * D1 || PPB == 1, "block geometry");
     static_assert(CPB * BPP * D2C == KCH, "blocks of a pixel cover the stage's channels");
     // the two 16-byte halves of a 32-byte capsule row trade places for the upper rows
     static __device__ __forceinline__ int swz(int d1)
     {
         return (D2C == 2 && D1 == 16) ? (d1 >> 3) & 1 : 0;
+    }
+    // lane of a copy -> element offset of its chunk within the pixel's stage data
+    // (cs = channel stride in elements), and which of the block's pixels it belongs to
+    static __device__ __forceinline__ int lane_elem_offset(int lane, int cs)
+    {
+        if (PPB == 1) {
+            const int csub = lane / G, g = lane % G, d1 = g / D2C, sh = g % D2C;
+            return csub * cs + d1 * D2 + ((sh ^ swz(d1)) * 8);
+        }
+        const int csub = lane / 16, d1 = lane % 8;
+        return csub * cs + d1 * D2;
+    }
+    static __device__ __forceinline__ int lane_pixel(int lane) { return PPB == 1 ? 0 : (lane >> 3) & 1; }
+    // byte position, within the stage's input region, of chunk (pixel pl of the tile, stage
+    // channel c_l, row d1, row half)
+    static __device__ __forceinline__ int chunk_pos(int pl, int c_l, int d1, int half)
+    {
+        if (PPB == 1)
+            return (pl * BPP + c_l / CPB) * ABLK +
+                   ((c_l % CPB) * G + d1 * D2C + (half ^ swz(d1))) * 16;
+        return (pl / 2) * ABLK + (c_l * 16 + (pl % 2) * 8 + d1) * 16;
     }
 };
 
@@ -119,18 +147,18 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     typedef ALayout<D1, D2, KCH> AL;
     constexpr int NWM = 2, NWN = 2, NW = 4;
     constexpr int BM = 256, BN = 256;
-    constexpr int D2C = AL::D2C, G = AL::G, CPB = AL::CPB, BPP = AL::BPP, PIX = AL::PIX;
+    constexpr int D2C = AL::D2C, CPB = AL::CPB, BPP = AL::BPP, PPB = AL::PPB, PIX = AL::PIX;
     constexpr int ABLK = AL::ABLK, NBLK = AL::NBLK;
     constexpr int A_BYTES = NBLK * ABLK, B_BYTES = NBLK * 1024, STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int WM = BM / NWM, WN = BN / NWN, TM = WM / 32, TN = WN / 32;
     constexpr int NMMA = TM * TN;    // MFMAs per k-step = slots for side operations
     constexpr int KS = KCH / 2;      // MFMA k-steps (16 K elements) per stage
     constexpr int BW = NBLK / NW;    // blocks per wave, per operand and stage
-    constexpr int PPW = BW / BPP;    // pixels whose blocks this wave loads
+    constexpr int PPW = BW * PPB / BPP;  // pixels whose blocks this wave loads
     constexpr int NFRAG = TN + TM;   // operand fragments per k-step
     constexpr int NCOPY = 2 * BW;    // copies per wave and stage
     static_assert(BW % BPP == 0 && PPW >= 1, "a wave loads whole pixels");
-    static_assert(NFRAG <= NMMA && PPW <= 3 * 4, "side operations fit between the MFMAs");
+    static_assert(NFRAG <= NMMA && PPW <= NMMA / 2, "side operations fit between the MFMAs");
     static_assert(KS % 2 == 0, "register double buffer alternates per k-step");
     constexpr int OOB = (int)0x80000000u;
     // s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
@@ -159,9 +187,11 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     const int h = lane >> 5, lr = lane & 31;
     const int col0 = col_tile * BN;
 
-    // ---- the pixels whose input blocks this wave copies, and per pixel a table over the window
-    // taps (lane t = tap t): byte offset of the tap's input pixel from in_base, or the
-    // out-of-range mark where the tap falls into the padding or the pixel does not exist
+    // ---- the pixels whose input blocks this wave copies.  Per pixel (all scalar): the byte
+    // offset of its window's first input pixel from in_base (meaningful together with an
+    // in-range tap), and a bit mask over the window taps: bit t set = tap t reads a real input
+    // pixel, clear = it falls into the padding or the output pixel does not exist.  The mask is
+    // a wave ballot: lane t evaluates tap t.
     const int hw = P.Ho * P.Wo;
     const long long npix = P.rows / D1;
     const long long pg0 = (long long)row_tile * PIX;
@@ -170,7 +200,8 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     const unsigned short* in_base = static_cast<const unsigned short*>(P.in) + n_first * img_elems;
     const int pix_bytes = (int)(P.pixsz * 2);
     const int tap_p = lane / P.kw, tap_q = lane - tap_p * P.kw;  // this lane's tap
-    int tap_tab[PPW];
+    int pix_off[PPW];
+    unsigned long long tap_ok[PPW];
 #pragma unroll
     for (int j = 0; j < PPW; ++j) {
         const long long pg = pg0 + wave * PPW + j;
@@ -179,12 +210,12 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         const int n_rel = (int)(pgc / hw - n_first);
         const int rem = (int)(pgc % hw);
         const int x = rem / P.Wo, y = rem - x * P.Wo;
-        const int ih = x * P.stride - P.pad + tap_p, iw = y * P.stride - P.pad + tap_q;
-        const bool ok = exists && lane < P.ntaps && (unsigned)ih < (unsigned)P.H &&
-                        (unsigned)iw < (unsigned)P.W;
-        tap_tab[j] = ok ? (int)((((long long)n_rel * P.H + ih) * P.W + iw) * pix_bytes) +
-                              d0 * D1 * D2 * 2
-                        : OOB;
+        const int ih0 = x * P.stride - P.pad, iw0 = y * P.stride - P.pad;
+        const bool ok = exists && lane < P.ntaps && (unsigned)(ih0 + tap_p) < (unsigned)P.H &&
+                        (unsigned)(iw0 + tap_q) < (unsigned)P.W;
+        tap_ok[j] = __builtin_amdgcn_ballot_w64(ok);
+        pix_off[j] = __builtin_amdgcn_readfirstlane(
+            (int)((((long long)n_rel * P.H + ih0) * P.W + iw0) * pix_bytes) + d0 * D1 * D2 * 2);
     }
     long long in_left = P.in_bytes - n_first * img_elems * 2;
     if (in_left > 0x7fffffffLL) in_left = 0x7fffffffLL;
@@ -196,21 +227,16 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     const unsigned lds_b = __builtin_amdgcn_readfirstlane((int)(lds0 + A_BYTES + wave * BW * 1024));
 
     // ---- per-lane constants
-    // input block: lane -> (channel within block, d1, row half) in LDS order
-    const int a_csub = lane / G, a_g = lane % G;
-    const int a_d1 = a_g / D2C, a_s = a_g % D2C;
-    const unsigned a_voff =
-        (unsigned)((a_csub * P.cs + a_d1 * D2 + ((a_s ^ AL::swz(a_d1)) * 8)) * 2);
+    // input block: byte offset of the lane's chunk within its pixel's stage data
+    const unsigned a_voff = (unsigned)(AL::lane_elem_offset(lane, P.cs) * 2);
+    const int a_hi = -AL::lane_pixel(lane);  // all ones in the lanes that copy a block's 2nd pixel
     const unsigned b_voff = (unsigned)lane * 16u;
-    // operand reads: MFMA row tile b covers rows wm*WM + b*32 + lr of the tile
+    // operand reads: MFMA row tile b covers rows wm*WM + b*32 + lr of the tile; lane half h
+    // takes chunk 2t + h of the stage: channel (2t+h)/D2C, row half (2t+h)%D2C
     unsigned a_rd;  // byte offset within the stage's input region, for b = 0, t = 0
     {
         const int r = wm * WM + lr;
-        const int pl = r / D1, d1 = r % D1;
-        // chunk kql = 2t + h  ->  channel c_l = kql / D2C, half = kql % D2C
-        const int c_l = h / D2C, half = h % D2C;
-        a_rd = (unsigned)((pl * BPP + c_l / CPB) * ABLK +
-                          ((c_l % CPB) * G + d1 * D2C + (half ^ AL::swz(d1))) * 16);
+        a_rd = (unsigned)AL::chunk_pos(r / D1, h / D2C, r % D1, h % D2C);
     }
     const unsigned b_rd = (unsigned)(A_BYTES + (h * BN + wn * WN + lr) * 16);
 
@@ -222,13 +248,16 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    // ---- K loop state (scalar) of the next stage to copy.  Stage s covers channel group
-    // s / ntaps (KCH chunks = KCH/D2C channels) at window tap s % ntaps.
+    // ---- K loop state (scalar).  Stage s covers channel group s / ntaps (KCH chunks =
+    // KCH/D2C channels) at window tap s % ntaps.  The input-side state describes the stage
+    // whose input copies go out next, the kernel-side state (one offset) the stage whose kernel
+    // copies go out next; in the steady state the input side runs one stage ahead.
     const int nstages = P.ntaps * (P.KQP / KCH);
     const int nstages_pad = (nstages + NB - 1) / NB * NB;  // surplus stages contract zeros
     const int c_step = (KCH / D2C) * P.cs * 2;             // bytes per channel group
     const int kp_step = KCH * P.colsp * 16;                 // repacked kernel bytes per stage
-    int tap = 0, issued = 0, c_off = 0;
+    const int row_skip = (P.W - P.kw + 1) * pix_bytes;     // last tap of a window row -> next row
+    int a_stage = 0, tap = 0, tap_q_cur = 0, tap_off = 0, c_off = 0;
     int kp_off = (int)(((long long)d0 * nstages * KCH * P.colsp + col0) * 16);
     int b_const[BW];
 #pragma unroll
@@ -238,33 +267,51 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     }
     int a_soff[PPW];  // per pixel: byte offset of the current tap's input pixel, or OOB
 
-    // scalar offsets of the next stage's input copies (one table lookup per pixel)
+    // All of the following is scalar arithmetic (nothing on the vector pipe that could hold up
+    // the MFMAs); the main loop deals it out in small pieces between the MFMAs.
+    // offset of the input-side stage's copies for pixel j
     auto stage_offset = [&](int j) {
-        const int live = issued < nstages;
-        const int off = __builtin_amdgcn_readlane(tap_tab[j], tap);
-        a_soff[j] = live ? off : OOB;  // past the last stage: zero fill, touches no memory
+        // past the last stage (surplus stages of the ring): zero fill, touches no memory
+        const bool ok = ((tap_ok[j] >> tap) & 1ull) != 0 && a_stage < nstages;
+        a_soff[j] = ok ? pix_off[j] + tap_off : OOB;
     };
-    // copy number J (0 .. NCOPY-1) of the next stage into ring slot SLOT
-    auto issue_copy = [&](auto SLOT, auto J) {
+    // input-side state -> next stage, in three pieces
+    auto advance_a = [&](int piece) {
+        if (piece == 0) {
+            ++a_stage;
+            ++tap;
+            ++tap_q_cur;
+        } else if (piece == 1) {
+            const bool row_end = tap_q_cur == P.kw;
+            tap_q_cur = row_end ? 0 : tap_q_cur;
+            tap_off += row_end ? row_skip : pix_bytes;
+        } else {
+            const bool wrap = tap == P.ntaps;  // window done: next channel group, first tap
+            tap = wrap ? 0 : tap;
+            tap_q_cur = wrap ? 0 : tap_q_cur;
+            tap_off = wrap ? 0 : tap_off;
+            c_off = wrap ? c_off + c_step : c_off;
+        }
+    };
+    // input copy J (0 .. BW-1) of the input-side stage / kernel copy J of the kernel-side stage
+    auto copy_a = [&](auto SLOT, auto J) {
         constexpr int slot = decltype(SLOT)::value, j = decltype(J)::value;
-        if constexpr (j < BW) {
+        if constexpr (PPB == 1) {
             constexpr int pj = j / BPP, part = j % BPP;
             copy_to_lds_16B<slot * STAGE_BYTES + j * ABLK>(rs_in, lds_a, a_voff, a_soff[pj],
                                                            c_off + part * CPB * P.cs * 2);
         } else {
-            constexpr int jb = j - BW;
-            // beyond the repacked kernel (surplus stages) the range check returns zeros
-            copy_to_lds_16B<slot * STAGE_BYTES + jb * 1024>(rs_kp, lds_b, b_voff, kp_off,
-                                                            b_const[jb]);
+            // two pixels per block: the pixel's offset travels in the lane offset (wrapping
+            // arithmetic; an out-of-range mark in either half keeps that half out of range)
+            const int lo = a_soff[2 * j], hi = a_soff[2 * j + 1];
+            const unsigned voff = a_voff + (unsigned)lo + ((unsigned)(hi - lo) & (unsigned)a_hi);
+            copy_to_lds_16B<slot * STAGE_BYTES + j * ABLK>(rs_in, lds_a, voff, c_off, 0);
         }
     };
-    auto advance = [&]() {
-        ++issued;
-        ++tap;
-        kp_off += kp_step;
-        const bool wrap = tap == P.ntaps;
-        tap = wrap ? 0 : tap;
-        c_off = wrap ? c_off + c_step : c_off;
+    auto copy_b = [&](auto SLOT, auto J) {
+        constexpr int slot = decltype(SLOT)::value, j = decltype(J)::value;
+        // beyond the repacked kernel (surplus stages) the range check returns zeros
+        copy_to_lds_16B<slot * STAGE_BYTES + j * 1024>(rs_kp, lds_b, b_voff, kp_off, b_const[j]);
     };
 
     // operand fragment f of k-step t from ring slot: f < TN kernel side, else input side
@@ -273,34 +320,41 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         if (f < TN)
             return *reinterpret_cast<const chunk_t*>(stage + b_rd + (2 * t * BN + f * 32) * 16);
         const int b = f - TN;
-        // chunk index +2t = channel +2t/D2C (row half unchanged); rows +32b = pixels +32b/D1
-        const int c_adv = 2 * t / D2C;
-        const int blk_adv = c_adv / CPB, csub_adv = c_adv % CPB;
-        const int off = ((b * 32 / D1) * BPP + blk_adv) * ABLK + csub_adv * G * 16;
+        // chunk index +2t = channel +2t/D2C (row half unchanged); rows +32b = pixels +32b/D1.
+        // The lane's own (pixel, channel, d1, half) at b = t = 0 adds no carry: positions are
+        // affine in the pixel (steps of 32/D1) and channel advance (CPB, blocks per pixel even).
+        const int off = AL::chunk_pos(b * 32 / D1, 2 * t / D2C, 0, 0) - AL::chunk_pos(0, 0, 0, 0);
         return *reinterpret_cast<const chunk_t*>(stage + a_rd + off);
     };
 
-    // ---- schedule of the side operations.  A stage has KS*NMMA MFMAs and NCOPY = 4*KS copies:
-    // one copy after every fourth MFMA keeps the copy queue shallow.  The copies of stage X
-    // start right after the barrier of iteration X-NB (from there on no wave reads that ring
-    // slot any more: the last k-step's operands are in registers) and end before the barrier of
-    // iteration X-NB+1.  COPY_AT(g): window position g -> copy number, or -1.
-    static_assert(NCOPY == 4 * KS && NMMA == 16, "one copy per four MFMAs");
-    constexpr int HEAD = 4;  // copies issued in the k-step after the barrier
+    // ---- schedule of the side operations.  A stage is two k-steps of NMMA = 16 MFMAs; per
+    // wave it needs BW = 4 input copies and 4 kernel copies: one copy after every fourth MFMA
+    // keeps the copy queue shallow.  In the k-step after the barrier of iteration s go the input
+    // copies of stage s+NB, into the ring slot that iteration has just finished reading (the
+    // last k-step's operands are in registers); in the first k-step of iteration s+1 go that
+    // stage's kernel copies, and, dealt out over the other gaps, the scalar arithmetic that
+    // moves the input-side state on by one stage.  No gap holds more than a handful of
+    // instructions, so the next MFMA is always issued before the matrix pipe runs dry.
+    static_assert(KS == 2 && BW == 4 && NMMA == 16, "the schedule below is written for this shape");
+    constexpr int LOOKUP_GAP[8] = {4, 5, 7, 8, 9, 11, 12, 13};  // gaps of k-step 0 free of copies
 
-    // ---- prologue: stages 0..NB-2 whole and the head of stage NB-1, wait for stage 0, fetch
-    // its first fragments
+    // ---- prologue: stages 0..NB-2 whole and the input side of stage NB-1, wait for stage 0,
+    // fetch its first fragments
     static_for<NB - 1>([&](auto S0) {
 #pragma unroll
         for (int j = 0; j < PPW; ++j) stage_offset(j);
-        static_for<NCOPY>([&](auto J) { issue_copy(S0, J); });
-        advance();
+        static_for<BW>([&](auto J) { copy_a(S0, J); });
+        static_for<BW>([&](auto J) { copy_b(S0, J); });
+        advance_a(0);
+        advance_a(1);
+        advance_a(2);
+        kp_off += kp_step;
     });
 #pragma unroll
     for (int j = 0; j < PPW; ++j) stage_offset(j);
-    static_for<HEAD>([&](auto J) { issue_copy(std::integral_constant<int, NB - 1>{}, J); });
+    static_for<BW>([&](auto J) { copy_a(std::integral_constant<int, NB - 1>{}, J); });
     {
-        constexpr int keep0 = (NB - 2) * NCOPY + HEAD;
+        constexpr int keep0 = (NB - 2) * NCOPY + BW;
         static_assert(keep0 < 64, "vmcnt is a 6-bit counter");
         __builtin_amdgcn_s_waitcnt(0x0F70 | (keep0 & 15) | ((keep0 >> 4) << 14));
     }
@@ -315,38 +369,32 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
             constexpr int slot = decltype(SLOT)::value;
             constexpr int slot_next = (slot + 1) % NB;
             typedef std::integral_constant<int, (slot + NB - 1) % NB> SlotPrev;
-            static_for<KS>([&](auto T) {
-                constexpr int t = decltype(T)::value;
-                constexpr int cur = t & 1, nxt = cur ^ 1;
-                if constexpr (t == KS - 1) {
-                    // the stage whose copies were completed in the k-steps above is accounted
-                    advance();
-                    // everything this wave still needs from `slot` is in registers; its copies
-                    // of the next stage have landed; after the barrier that holds for all waves
-                    __builtin_amdgcn_s_waitcnt(VMCNT_KEEP & 0xF0FF);  // and lgkmcnt(0)
-                    __syncthreads();
-                }
-                static_for<NMMA>([&](auto I) {
-                    constexpr int i = decltype(I)::value;
-                    constexpr int a = i / TM, b = i % TM;
-                    Mma<Tag>::run(frag[cur][a], frag[cur][TN + b], acc[a][b]);
-                    if constexpr (i < NFRAG)
-                        frag[nxt][i] =
-                            t == KS - 1 ? read_frag(slot_next, 0, i) : read_frag(slot, t + 1, i);
-                    if constexpr (t == KS - 1) {
-                        // head of the stage NB ahead, into the slot this iteration has just
-                        // finished reading
-                        if constexpr (i < PPW) stage_offset(i);
-                        if constexpr (i % 4 == 2)
-                            issue_copy(SLOT, std::integral_constant<int, i / 4>{});
-                    } else {
-                        // rest of the stage NB-1 ahead (its head went out one k-step earlier)
-                        if constexpr (i % 4 == 2)
-                            issue_copy(SlotPrev{},
-                                       std::integral_constant<int, HEAD + t * 4 + i / 4>{});
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                });
+            // k-step 0: kernel copies of the stage NB-1 ahead; input-side state -> stage NB ahead
+            static_for<NMMA>([&](auto I) {
+                constexpr int i = decltype(I)::value;
+                Mma<Tag>::run(frag[0][i / TM], frag[0][TN + i % TM], acc[i / TM][i % TM]);
+                if constexpr (i < NFRAG) frag[1][i] = read_frag(slot, 1, i);
+                if constexpr (i % 4 == 2) copy_b(SlotPrev{}, std::integral_constant<int, i / 4>{});
+                if constexpr (i == 0) advance_a(0);
+                if constexpr (i == 1) advance_a(1);
+                if constexpr (i == 3) advance_a(2);
+#pragma unroll
+                for (int j = 0; j < PPW; ++j)
+                    if (LOOKUP_GAP[j] == i) stage_offset(j);
+                if constexpr (i == NMMA - 1) kp_off += kp_step;
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            // everything this wave still needs from `slot` is in registers; its copies of the
+            // next stage have landed; after the barrier that holds for all waves
+            __builtin_amdgcn_s_waitcnt(VMCNT_KEEP & 0xF0FF);  // and lgkmcnt(0)
+            __syncthreads();
+            // k-step 1: input copies of the stage NB ahead into the slot just released
+            static_for<NMMA>([&](auto I) {
+                constexpr int i = decltype(I)::value;
+                Mma<Tag>::run(frag[1][i / TM], frag[1][TN + i % TM], acc[i / TM][i % TM]);
+                if constexpr (i < NFRAG) frag[0][i] = read_frag(slot_next, 0, i);
+                if constexpr (i % 4 == 2) copy_a(SLOT, std::integral_constant<int, i / 4>{});
+                __builtin_amdgcn_sched_barrier(0);
             });
         });
     }
@@ -382,7 +430,7 @@ struct FastConfig;  // chunks per stage and ring depth chosen per capsule size
 template <>
 struct FastConfig<16, 16> { static constexpr int KCH = 4, NB = 4; };
 template <>
-struct FastConfig<8, 8> { static constexpr int KCH = 8, NB = 2; };
+struct FastConfig<8, 8> { static constexpr int KCH = 4, NB = 4; };
 
 template <typename Tag, int D1, int D2>
 hipError_t launch_one(const IgemmParams& P, long long blocks, hipStream_t stream)
