@@ -27,7 +27,11 @@ PEAK_HBM_GBS = 8000.0
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs scaled by a copy kernel of known size (see profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    # profiles/igemm16_fast_hbm_traffic_configs_3_5.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB
+    5: int((7221076 * 2.0 + 4194338) * 1024),
+    3: int((1421796 * 2.0 + 401408) * 1024),
+}
 
 
 def cpu_baseline(w, i32, k32, gpu_out, target_seconds=15.0):
@@ -71,6 +75,9 @@ def main():
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--path", default="auto", choices=["auto", "mfma", "direct"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy (the known-size kernel that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build measures the capsule convolution on ONE GPU only "
@@ -107,6 +114,12 @@ def main():
         if rc != cc.OK:
             sys.exit(f"bench.py: capscaps status {rc}: {cc.capscaps_strerror(rc)}")
 
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

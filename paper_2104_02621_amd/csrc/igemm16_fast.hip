@@ -168,14 +168,13 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
 
     extern __shared__ char smem[];
 
-    // ---- tile: consecutive logical tiles go to the same XCD (blocks are dealt to the 8 XCDs
-    // round-robin), column tiles fastest so that neighbours share input rows in that L2
-    const int nb = gridDim.x;
-    int L = blockIdx.x;
-    {
-        const int per = nb / 8, full = per * 8;
-        if ((int)blockIdx.x < full) L = ((int)blockIdx.x % 8) * per + (int)blockIdx.x / 8;
-    }
+    // ---- tile: column tiles fastest in launch order.  The hardware deals consecutive
+    // workgroups to the 8 XCDs in turn, so with 4 (or 2, or 8) column tiles every XCD works on
+    // one column tile and on every other row tile: its L2 streams a single column tile of the
+    // repacked kernel for all its resident workgroups, and vertically adjacent row tiles, which
+    // share input halo rows, meet in the same L2.  Measured on config 5: 2.5x fewer L2 misses
+    // than handing each XCD a contiguous range of tiles covering all column tiles.
+    const int L = blockIdx.x;
     const int col_tile = L % P.col_tiles;
     int rest = L / P.col_tiles;
     const int row_tile = rest % P.row_tiles;
