@@ -65,6 +65,9 @@ extern "C" {
                                         of the K loop) */
 #define CAPSCAPS_PATH_MFMA_TUNED16 4 /* ... the 256x256-tile variant for 16-bit types with
                                         D1 = D2 in {8, 16}; other shapes: CAPSCAPS_EUNSUPPORTED */
+#define CAPSCAPS_PATH_MFMA_TUNED32 5 /* ... the fp32 variant with direct-to-LDS copies, for
+                                        capsule rows of 3, 4, 6, 8, 12 or 16 floats; other
+                                        shapes: CAPSCAPS_EUNSUPPORTED */
 
 /*
  * Output extents (Fig. 1 / Fig. 2: 5 with a 4-wide kernel at stride 1 gives 2).

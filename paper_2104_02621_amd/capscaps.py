@@ -12,6 +12,7 @@ from pathlib import Path
 
 FP32, BF16, FP16 = 0, 1, 2
 PATH_AUTO, PATH_DIRECT, PATH_MFMA, PATH_MFMA_GENERIC, PATH_MFMA_TUNED16 = 0, 1, 2, 3, 4
+PATH_MFMA_TUNED32 = 5
 OK, EINVAL, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
 
 _LIB_PATH = Path(__file__).resolve().parent / "libcapscaps.so"

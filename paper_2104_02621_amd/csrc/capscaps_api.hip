@@ -60,14 +60,17 @@ int run(const void* input, const void* kernel, void* out, const ConvShape& s, in
     if (path == CAPSCAPS_PATH_DIRECT) {
         err = capscaps::launch_direct(s, input, kernel, static_cast<float*>(out), stream);
     } else if (path == CAPSCAPS_PATH_MFMA || path == CAPSCAPS_PATH_MFMA_GENERIC ||
-               path == CAPSCAPS_PATH_MFMA_TUNED16) {
+               path == CAPSCAPS_PATH_MFMA_TUNED16 || path == CAPSCAPS_PATH_MFMA_TUNED32) {
         if (!capscaps::mfma_supported(s)) return CAPSCAPS_EUNSUPPORTED;
         if (path == CAPSCAPS_PATH_MFMA_TUNED16 && !capscaps::mfma_tuned16_supported(s))
+            return CAPSCAPS_EUNSUPPORTED;
+        if (path == CAPSCAPS_PATH_MFMA_TUNED32 && !capscaps::mfma_dma32_supported(s))
             return CAPSCAPS_EUNSUPPORTED;
         const capscaps::MfmaKernel which =
             path == CAPSCAPS_PATH_MFMA           ? capscaps::MfmaKernel::Auto
             : path == CAPSCAPS_PATH_MFMA_GENERIC ? capscaps::MfmaKernel::Generic
-                                                 : capscaps::MfmaKernel::Tuned16;
+            : path == CAPSCAPS_PATH_MFMA_TUNED16 ? capscaps::MfmaKernel::Tuned16
+                                                 : capscaps::MfmaKernel::Dma32;
         const size_t need = capscaps::mfma_workspace_bytes(s);
         if (need > 0 && (workspace == nullptr || workspace_bytes < need))
             return CAPSCAPS_EWORKSPACE;
@@ -121,7 +124,7 @@ int capscaps_conv_fwd_path(const void* input, const void* kernel, void* out, int
 {
     if (input == nullptr || kernel == nullptr || out == nullptr) return CAPSCAPS_EINVAL;
     if (misaligned(input) || misaligned(kernel) || misaligned(out)) return CAPSCAPS_EINVAL;
-    if (path < CAPSCAPS_PATH_AUTO || path > CAPSCAPS_PATH_MFMA_TUNED16) return CAPSCAPS_EINVAL;
+    if (path < CAPSCAPS_PATH_AUTO || path > CAPSCAPS_PATH_MFMA_TUNED32) return CAPSCAPS_EINVAL;
     ConvShape s;
     const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype);
     if (rc != CAPSCAPS_OK) return rc;

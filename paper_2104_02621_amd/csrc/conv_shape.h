@@ -25,9 +25,10 @@ hipError_t launch_direct(const ConvShape& s, const void* in, const void* kernel,
 // Matrix-core path (LDS-staged implicit GEMM).  `mfma_supported` tells whether the path can
 // run the shape; `mfma_workspace_bytes` is the scratch it needs (repacked kernel plus, for
 // small problems, split-reduction partial sums).
-enum class MfmaKernel { Auto, Generic, Tuned16 };
+enum class MfmaKernel { Auto, Generic, Tuned16, Dma32 };
 bool mfma_supported(const ConvShape& s);
 bool mfma_tuned16_supported(const ConvShape& s);
+bool mfma_dma32_supported(const ConvShape& s);
 size_t mfma_workspace_bytes(const ConvShape& s);  // enough for every MfmaKernel choice
 hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, float* out,
                        void* workspace, hipStream_t stream, MfmaKernel which = MfmaKernel::Auto);

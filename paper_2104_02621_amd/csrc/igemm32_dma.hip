@@ -1,0 +1,431 @@
+// fp32 matrix-core kernel of the capsule convolution forward pass with direct-to-LDS copies.
+// Same implicit GEMM as the other igemm kernels (rows (pixel,d1), columns (m,d3),
+// K = (tap, c, d2); paper Algorithm 2).  It serves capsule rows of 3 floats (D2 a multiple of
+// 3: the 3x3x3 capsules of the paper's Fig. 2) as well as multiples of 4.
+//
+// Unit of data movement: a 16-byte LDS slot holding CW = 3 or 4 consecutive d2 of one capsule
+// row ("chunk").  For CW = 3 the copy is a 12-byte buffer load, which the hardware places at
+// a 16-byte lane stride in LDS, so both cases read operands with one 16-byte LDS load per lane
+// and feed CW MFMA 32x32x2 instructions from it (element u of the lower and of the upper half
+// wave form the K pair of instruction u; the fourth float of a 3-float slot is never used).
+//
+// Tile: 64*NW rows x 32*TN columns; wave w copies and contracts rows 64w..64w+63 (two MFMA
+// row tiles) against all TN column tiles.  Lane i of a wave copies row 64w+i: its byte offset,
+// with the out-of-range mark where the current tap falls into the padding, sits in one VGPR
+// and is refreshed once per stage from a per-lane bit mask over the taps; everything else
+// (tap, channel group, chunk) is a scalar offset.  K runs channel group outermost, tap inside,
+// 4 chunks per stage, ring of 3 LDS stages, one barrier per stage; the K loop can be split over
+// blocks (partial sums are reduced in a fixed order by the caller's reduce kernel).
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+#include <utility>
+
+#include "igemm_common.h"
+
+namespace capscaps {
+namespace {
+
+typedef int rsrc_t __attribute__((ext_vector_type(4)));
+
+template <typename F, int... I>
+__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
+{
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
+}
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes)
+{
+    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
+    rsrc_t r;
+    r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)(a & 0xffffffffu));
+    r[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)((a >> 32) & 0xffffu));
+    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
+    r[3] = 0x00020000;
+    return r;
+}
+
+// Wave-wide copy global -> LDS of DW dwords per lane (3 or 4): lane i reads at
+// base + voff_i + soff and writes LDS byte address lds_addr + 16*i.  Offsets at or beyond the
+// descriptor's size store zeros.  Asynchronous, counted in vmcnt; inline assembly so that the
+// only waits are the hand-placed ones (see igemm16_fast.hip).
+template <int DW>
+__device__ __forceinline__ void copy_to_lds(rsrc_t rs, unsigned lds_addr, unsigned voff, int soff)
+{
+    static_assert(DW == 3 || DW == 4, "12- or 16-byte copies");
+    const int lds_s = __builtin_amdgcn_readfirstlane((int)lds_addr);
+    const int soff_s = __builtin_amdgcn_readfirstlane(soff);
+    if (DW == 3)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx3 %1, %2, %3 offen lds"
+                     :
+                     : "s"(lds_s), "v"(voff), "s"(rs), "s"(soff_s)
+                     : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :
+                     : "s"(lds_s), "v"(voff), "s"(rs), "s"(soff_s)
+                     : "memory");
+}
+
+constexpr int KCH = 4;  // chunks per row and stage
+constexpr int NB = 3;   // LDS stages in the ring
+
+template <int CW, int TN, int NW>
+__global__ __launch_bounds__(64 * NW) void igemm32_dma_kernel(const Dma32Params P)
+{
+    constexpr int BM = 64 * NW, BN = 32 * TN, BNL = (BN + 63) / 64 * 64, TM = 2;
+    constexpr int A_BYTES = KCH * BM * 16, B_BYTES = KCH * BNL * 16;
+    constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int NBC = KCH * BNL / 64;  // kernel-side copies per stage, all waves
+    constexpr int BPW = NBC / NW;        // ... per wave
+    static_assert(NBC % NW == 0, "kernel copies divide evenly over the waves");
+    constexpr int NCOPY = KCH + BPW;     // copies per wave and stage
+    constexpr int OOB = (int)0x80000000u;
+    constexpr int VMCNT_KEEP = 0x0F70 | (NCOPY & 15) | ((NCOPY >> 4) << 14);
+
+    extern __shared__ char smem[];
+
+    // ---- tile: column tiles fastest, then row tiles, leading capsule index, K split
+    const int L = blockIdx.x;
+    const int col_tile = L % P.col_tiles;
+    int rest = L / P.col_tiles;
+    const int row_tile = rest % P.row_tiles;
+    rest /= P.row_tiles;
+    const int d0 = rest % P.D0;
+    const int split = rest / P.D0;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = lane >> 5, lr = lane & 31;
+    const long long row0 = (long long)row_tile * BM;
+    const int col0 = col_tile * BN;
+
+    // ---- this lane's row: byte offset of its capsule row in the window's first input pixel,
+    // relative to the first image the tile touches, and the bit mask of taps that read a real
+    // input pixel
+    const int hw = P.Ho * P.Wo;
+    const long long n_first = (row0 / P.D1) / hw;
+    const long long img_bytes = (long long)P.H * P.W * P.pixsz * 4;
+    const int pix_bytes = (int)(P.pixsz * 4);
+    // Lane offsets must not be negative (the hardware adds lane and scalar offset without
+    // wrapping), but a window's first pixel may lie in the padding: the descriptor's base is
+    // moved back by the largest such distance and every lane offset forward by the same.
+    // Nothing is read below the tensor: only in-range taps are ever addressed.
+    const int bias = (P.pad * P.W + P.pad) * pix_bytes;
+    const char* in_base = static_cast<const char*>(P.in) + n_first * img_bytes - bias;
+    int row_off;
+    unsigned long long tap_ok = 0;
+    {
+        const long long rg = row0 + 64 * wave + lane;
+        const bool exists = rg < P.rows;
+        const long long rr = exists ? rg : row0;
+        const long long pixel = rr / P.D1;
+        const int d1 = (int)(rr % P.D1);
+        const int n_rel = (int)(pixel / hw - n_first);
+        const int rem = (int)(pixel % hw);
+        const int x = rem / P.Wo, y = rem - x * P.Wo;
+        const int ih0 = x * P.stride - P.pad, iw0 = y * P.stride - P.pad;
+        row_off = (int)((((long long)n_rel * P.H + ih0) * P.W + iw0) * pix_bytes) +
+                  (d0 * P.D1 + d1) * P.D2 * 4 + bias;
+        if (exists) {
+            int t = 0;
+            for (int p = 0; p < P.kh; ++p)
+                for (int q = 0; q < P.kw; ++q, ++t)
+                    if ((unsigned)(ih0 + p) < (unsigned)P.H && (unsigned)(iw0 + q) < (unsigned)P.W)
+                        tap_ok |= 1ull << t;
+        }
+    }
+    long long in_left = P.in_bytes - n_first * img_bytes + bias;
+    if (in_left > 0x7fffffffLL) in_left = 0x7fffffffLL;
+    const rsrc_t rs_in = make_rsrc(in_base, (unsigned)in_left);
+    rsrc_t rs_none = rs_in;  // nothing addressable: every lane stores zeros
+    rs_none[2] = 0;
+    const rsrc_t rs_kp = make_rsrc(P.kp, (unsigned)P.kp_bytes);
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+
+    // ---- K loop state of the next stage to copy (all scalar)
+    const int st_begin = split * P.stages_per_split;
+    int st_end = st_begin + P.stages_per_split;
+    if (st_end > P.nstages) st_end = P.nstages;
+    const int my_stages = st_end - st_begin;
+    const int my_stages_pad = (my_stages + NB - 1) / NB * NB;
+    const int chan_per_group = KCH / P.D2C;                  // D2C is 1, 2 or 4
+    const int g_step = chan_per_group * P.cs * 4;           // bytes per channel group
+    const int kp_step = KCH * P.colsp * 16;
+    const int row_skip = (P.W - P.kw + 1) * pix_bytes;
+    int issued = 0;
+    int tap = st_begin % P.ntaps, grp = st_begin / P.ntaps;
+    int tap_q = tap % P.kw;
+    int tap_off = ((tap / P.kw) * P.W + tap_q) * pix_bytes;
+    int g_off = grp * g_step;
+    int c0 = grp * chan_per_group;  // first channel of the group
+    int kp_off = (int)((((long long)d0 * P.nstages + st_begin) * KCH * P.colsp + col0) * 16);
+    int q_off[KCH], q_chan[KCH];
+#pragma unroll
+    for (int q = 0; q < KCH; ++q) {
+        q_chan[q] = q / P.D2C;
+        q_off[q] = (q_chan[q] * P.cs + (q % P.D2C) * CW) * 4;
+    }
+    int b_const[BPW];
+#pragma unroll
+    for (int j = 0; j < BPW; ++j) {
+        const int c = wave * BPW + j;
+        b_const[j] = ((c / (BNL / 64)) * P.colsp + (c % (BNL / 64)) * 64) * 16;
+    }
+    const unsigned b_voff = (unsigned)lane * 16u;
+
+    auto issue_stage = [&](int slot) {
+        const bool live = issued < my_stages;
+        const unsigned stage = lds0 + slot * STAGE_BYTES;
+        // input side: this lane's row, chunks 0..KCH-1 of the stage
+        const bool ok = live && ((tap_ok >> tap) & 1ull) != 0;
+        const unsigned voff = ok ? (unsigned)row_off : (unsigned)OOB;
+        const int s_base = tap_off + g_off;
+#pragma unroll
+        for (int q = 0; q < KCH; ++q) {
+            const bool chan_ok = c0 + q_chan[q] < P.C;  // last group may be partial
+            copy_to_lds<CW>(chan_ok ? rs_in : rs_none, stage + (q * BM + 64 * wave) * 16, voff,
+                            s_base + q_off[q]);
+        }
+        // kernel side: this wave's share of the stage's KCH x BNL chunks
+#pragma unroll
+        for (int j = 0; j < BPW; ++j) {
+            const int c = wave * BPW + j;
+            copy_to_lds<4>(rs_kp, stage + A_BYTES + c * 1024, b_voff,
+                           live ? kp_off + b_const[j] : OOB);
+        }
+        // next stage: next tap, after the last tap the next channel group
+        ++issued;
+        kp_off += kp_step;
+        ++tap;
+        ++tap_q;
+        const bool row_end = tap_q == P.kw;
+        tap_q = row_end ? 0 : tap_q;
+        tap_off += row_end ? row_skip : pix_bytes;
+        if (tap == P.ntaps) {
+            tap = 0;
+            tap_q = 0;
+            tap_off = 0;
+            g_off += g_step;
+            c0 += chan_per_group;
+        }
+    };
+
+    float16v acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    auto compute_stage = [&](int slot) {
+        const char* stage = smem + slot * STAGE_BYTES;
+#pragma unroll
+        for (int t = 0; t < KCH / 2; ++t) {
+            // lanes 0..31 take chunk 2t, lanes 32..63 chunk 2t+1
+            float4v ka[TN], ib[TM];
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+                ka[a] = *reinterpret_cast<const float4v*>(
+                    stage + A_BYTES + ((2 * t + h) * BNL + a * 32 + lr) * 16);
+#pragma unroll
+            for (int b = 0; b < TM; ++b)
+                ib[b] = *reinterpret_cast<const float4v*>(
+                    stage + ((2 * t + h) * BM + 64 * wave + b * 32 + lr) * 16);
+#pragma unroll
+            for (int u = 0; u < CW; ++u)
+#pragma unroll
+                for (int a = 0; a < TN; ++a)
+#pragma unroll
+                    for (int b = 0; b < TM; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(ka[a][u], ib[b][u],
+                                                                         acc[a][b], 0, 0, 0);
+        }
+    };
+
+    // ---- prologue: two stages in flight, the first one landed
+    issue_stage(0);
+    issue_stage(1);
+    __builtin_amdgcn_s_waitcnt(VMCNT_KEEP);
+    __syncthreads();
+
+    // ---- main loop: copy stage s+2 into the slot read in iteration s-1, contract stage s
+    for (int st = 0; st < my_stages_pad; st += NB) {
+        static_for<NB>([&](auto SLOT) {
+            constexpr int slot = decltype(SLOT)::value;
+            issue_stage((slot + 2) % NB);
+            compute_stage(slot);
+            // this wave's copies of the next stage have landed, its reads of this stage are
+            // done; after the barrier both hold for every wave
+            __builtin_amdgcn_s_waitcnt(VMCNT_KEEP & 0xF0FF);
+            __syncthreads();
+        });
+    }
+
+    // ---- epilogue: lane (h, lr) of tile (a, b) holds in registers 4g..4g+3 the columns
+    // 8g + 4h + 0..3 of the tile for output row lr of the tile
+    float* __restrict__ out = P.out + (long long)split * P.out_elems;
+    const int caps_out = P.D0 * P.D1 * P.D3;
+    const bool st4 = (P.D3 & 3) == 0;
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+        const long long orow = row0 + 64 * wave + b * 32 + lr;
+        if (orow >= P.rows) continue;
+        const long long pixel = orow / P.D1;
+        const int d1 = (int)(orow % P.D1);
+        float* orow_ptr = out + pixel * P.M * caps_out + (long long)(d0 * P.D1 + d1) * P.D3;
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int j0 = col0 + a * 32 + 8 * g + 4 * h;
+                if (st4) {
+                    if (j0 < P.cols) {
+                        const int m = j0 / P.D3, d3 = j0 - m * P.D3;
+                        float4v v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
+                                     acc[a][b][4 * g + 3]};
+                        *reinterpret_cast<float4v*>(orow_ptr + (long long)m * caps_out + d3) = v;
+                    }
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int j = j0 + u;
+                        if (j < P.cols) {
+                            const int m = j / P.D3, d3 = j - m * P.D3;
+                            orow_ptr[(long long)m * caps_out + d3] = acc[a][b][4 * g + u];
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+template <int CW, int TN, int NW>
+hipError_t launch_one(const Dma32Params& P, long long blocks, hipStream_t stream)
+{
+    constexpr int BM = 64 * NW, BNL = (32 * TN + 63) / 64 * 64;
+    auto kern = igemm32_dma_kernel<CW, TN, NW>;
+    const size_t lds_bytes = (size_t)NB * KCH * (BM + BNL) * 16;
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)lds_bytes);
+    if (err != hipSuccess) return err;
+    kern<<<dim3((unsigned)blocks), dim3(64 * NW), lds_bytes, stream>>>(P);
+    return hipGetLastError();
+}
+
+template <int CW, int NW>
+hipError_t launch_tn(const Dma32Params& P, int tn, long long blocks, hipStream_t stream)
+{
+    switch (tn) {
+        case 1: return launch_one<CW, 1, NW>(P, blocks, stream);
+        case 2: return launch_one<CW, 2, NW>(P, blocks, stream);
+        case 3: return launch_one<CW, 3, NW>(P, blocks, stream);
+        default: return launch_one<CW, 4, NW>(P, blocks, stream);
+    }
+}
+
+inline int ceil_div_ll(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+}  // namespace
+
+// Valid floats per 16-byte chunk: 4 or 3, such that a capsule row is 1, 2 or 4 chunks (so that
+// the 4 chunks of a stage never split a row); 0 if neither fits.
+int igemm32_dma_chunk_width(const ConvShape& s)
+{
+    for (int cw : {4, 3}) {
+        if (s.D2 % cw) continue;
+        const int d2c = s.D2 / cw;
+        if (d2c == 1 || d2c == 2 || d2c == 4) return cw;
+    }
+    return 0;
+}
+
+bool igemm32_dma_eligible(const ConvShape& s)
+{
+    if (s.dtype != 0) return false;
+    const int cw = igemm32_dma_chunk_width(s);
+    if (cw == 0) return false;
+    if (s.kh * s.kw > 64) return false;                   // one mask bit per window tap
+    const long long img_bytes = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 4;
+    const long long hw = (long long)s.Ho * s.Wo;
+    const long long pix = (256 + s.D1 - 1) / s.D1 + 1;
+    const long long images_spanned = (pix + hw - 2) / hw + 1;
+    const long long bias = ((long long)s.pad * s.W + s.pad) * s.C * s.D0 * s.D1 * s.D2 * 4;
+    if (images_spanned * img_bytes + bias >= (1LL << 31)) return false;
+    const Dma32Plan pl = igemm32_dma_plan(s);
+    if ((long long)pl.repack_bytes >= (1LL << 31) - (1 << 24)) return false;
+    return pl.blocks > 0 && pl.blocks < 0x7fffffffLL;
+}
+
+// Tile, split and padding decisions (host side, pure arithmetic).
+Dma32Plan igemm32_dma_plan(const ConvShape& s)
+{
+    Dma32Plan pl{};
+    Dma32Params& P = pl.P;
+    const int cw = igemm32_dma_chunk_width(s);
+    pl.cw = cw;
+    P.H = s.H; P.W = s.W; P.C = s.C; P.M = s.M; P.stride = s.stride; P.pad = s.pad;
+    P.D0 = s.D0; P.D1 = s.D1; P.D2 = s.D2; P.D3 = s.D3; P.Ho = s.Ho; P.Wo = s.Wo;
+    P.kh = s.kh; P.kw = s.kw; P.ntaps = s.kh * s.kw;
+    P.rows = s.pixels() * s.D1;
+    P.out_elems = (long long)s.out_elems();
+    P.pixsz = (long long)s.C * s.D0 * s.D1 * s.D2;
+    P.cs = s.D0 * s.D1 * s.D2;
+    P.cols = s.M * s.D3;
+    P.D2C = cw ? s.D2 / cw : 1;
+    const int KK = s.C * P.D2C;                 // chunks per row and tap
+    const int groups = (KK + KCH - 1) / KCH;
+    pl.kqp = groups * KCH;
+    P.nstages = groups * P.ntaps;
+    pl.tn = P.cols <= 32 ? 1 : P.cols <= 64 ? 2 : P.cols <= 96 ? 3 : 4;
+    const int BN = 32 * pl.tn;
+    P.col_tiles = (P.cols + BN - 1) / BN;
+    P.colsp = P.col_tiles * BN;
+    // four waves per block (256 rows) when that still fills the chip, else one (64 rows)
+    const long long big = (long long)ceil_div_ll(P.rows, 256) * P.col_tiles * s.D0;
+    pl.nw = big >= 256 ? 4 : 1;
+    P.row_tiles = ceil_div_ll(P.rows, 64 * pl.nw);
+    const long long tiles = (long long)P.row_tiles * P.col_tiles * s.D0;
+    int nsplit = 1;
+    if (tiles < 256) {
+        nsplit = ceil_div_ll(512, tiles);
+        if (nsplit > P.nstages) nsplit = P.nstages;
+        if (nsplit > 64) nsplit = 64;
+    }
+    P.stages_per_split = (P.nstages + nsplit - 1) / nsplit;
+    P.nsplit = (P.nstages + P.stages_per_split - 1) / P.stages_per_split;
+    pl.blocks = tiles * P.nsplit;
+    pl.repack_bytes = (size_t)s.D0 * P.nstages * KCH * P.colsp * 16;
+    pl.partial_bytes = P.nsplit > 1 ? (size_t)P.nsplit * P.out_elems * sizeof(float) : 0;
+    P.in_bytes = (long long)s.in_elems() * 4;
+    P.kp_bytes = (long long)pl.repack_bytes;
+    return pl;
+}
+
+bool igemm32_dma_preferred(const ConvShape& s)
+{
+    if (!igemm32_dma_eligible(s)) return false;
+    // measured on MI355X: 1.8x faster than the generic kernel on config 2 (many 256-row tiles);
+    // on problems so small that the K loop is split the generic kernel's 64x64 tiles win
+    const Dma32Plan pl = igemm32_dma_plan(s);
+    return pl.nw == 4 && pl.P.nsplit == 1;
+}
+
+hipError_t launch_igemm32_dma(const Dma32Plan& pl, hipStream_t stream)
+{
+    if (pl.cw == 3)
+        return pl.nw == 4 ? launch_tn<3, 4>(pl.P, pl.tn, pl.blocks, stream)
+                          : launch_tn<3, 1>(pl.P, pl.tn, pl.blocks, stream);
+    return pl.nw == 4 ? launch_tn<4, 4>(pl.P, pl.tn, pl.blocks, stream)
+                      : launch_tn<4, 1>(pl.P, pl.tn, pl.blocks, stream);
+}
+
+}  // namespace capscaps

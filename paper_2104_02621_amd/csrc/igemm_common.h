@@ -71,6 +71,39 @@ struct IgemmParams {
     long long kp_records;  // size of the repacked kernel in bytes
 };
 
+// Shared launch helpers (igemm_conv.hip).  Repack: 16-byte chunks of `cw` valid K elements
+// (zero-filled up to the slot's 4 floats / 8 halves); kgroup as documented at repack_kernel.
+hipError_t launch_repack(const ConvShape& s, const void* kernel, void* kp, int cw, int KQP,
+                         int colsp, int kgroup, size_t chunks, hipStream_t stream);
+hipError_t launch_splitk_reduce(const float* partial, float* out, long long elems, int nsplit,
+                                hipStream_t stream);
+
+// fp32 kernel with direct-to-LDS copies (igemm32_dma.hip): capsule rows of 3k or 4k floats.
+struct Dma32Params {
+    const void* in;
+    const void* kp;
+    float* out;  // final output, or split-K partial buffers [split][out_elems]
+    int H, W, C, M, stride, pad, D0, D1, D2, D3, Ho, Wo, kh, kw, ntaps;
+    long long rows, out_elems, pixsz, in_bytes, kp_bytes;
+    int cs;        // D0*D1*D2: input channel stride (elements)
+    int cols, colsp;
+    int D2C;       // chunks per capsule row
+    int nstages;   // channel groups * taps
+    int stages_per_split, nsplit;
+    int row_tiles, col_tiles;
+};
+struct Dma32Plan {
+    Dma32Params P;
+    int cw, tn, nw, kqp;
+    long long blocks;
+    size_t repack_bytes, partial_bytes;
+};
+int igemm32_dma_chunk_width(const ConvShape& s);
+Dma32Plan igemm32_dma_plan(const ConvShape& s);
+bool igemm32_dma_eligible(const ConvShape& s);   // the kernel can run the shape
+bool igemm32_dma_preferred(const ConvShape& s);  // ... and is the library's choice for it
+hipError_t launch_igemm32_dma(const Dma32Plan& pl, hipStream_t stream);
+
 // Tuned 16-bit kernel (igemm16_fast.hip): 256x256 tiles, direct-to-LDS copies.
 bool igemm16_fast_eligible(const ConvShape& s);   // the kernel can run the shape
 bool igemm16_fast_preferred(const ConvShape& s);  // ... and is the library's choice for it

@@ -40,7 +40,7 @@ template <typename E, int CH>
 __global__ __launch_bounds__(256) void repack_kernel(const E* __restrict__ kernel,
                                                      E* __restrict__ kp, int ntaps, int C, int M,
                                                      int D0, int D2, int D3, int KT, int KQP,
-                                                     int cols, int colsp, int kgroup,
+                                                     int cols, int colsp, int kgroup, int cw,
                                                      size_t total_chunks)
 {
     const size_t id = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -62,9 +62,9 @@ __global__ __launch_bounds__(256) void repack_kernel(const E* __restrict__ kerne
     E v[CH];
 #pragma unroll
     for (int e = 0; e < CH; ++e) {
-        const int k = kq * CH + e;
+        const int k = kq * cw + e;  // cw valid elements per chunk, the rest of the slot zero
         E x = 0;
-        if (k < KT && j < cols) {
+        if (e < cw && k < KT && j < cols) {
             const int c = k / D2, d2 = k % D2, m = j / D3, d3 = j % D3;
             x = kernel[(((((size_t)tap * C + c) * M + m) * D0 + d0) * D2 + d2) * D3 + d3];
         }
@@ -421,17 +421,7 @@ hipError_t launch_igemm(const ConvShape& s, const void* in, const void* kernel, 
 
     const size_t chunks = pl.repack_bytes / 16;
     const int kgroup = pl.fast ? igemm16_fast_kgroup(s) : 0;
-    const unsigned rblocks = (unsigned)((chunks + 255) / 256);
-    if (s.dtype == 0) {
-        repack_kernel<float, 4><<<rblocks, 256, 0, stream>>>(
-            (const float*)kernel, (float*)kp, pl.P.ntaps, s.C, s.M, s.D0, s.D2, s.D3, pl.P.KT,
-            pl.P.KQP, pl.P.cols, pl.P.colsp, kgroup, chunks);
-    } else {
-        repack_kernel<unsigned short, 8><<<rblocks, 256, 0, stream>>>(
-            (const unsigned short*)kernel, (unsigned short*)kp, pl.P.ntaps, s.C, s.M, s.D0, s.D2,
-            s.D3, pl.P.KT, pl.P.KQP, pl.P.cols, pl.P.colsp, kgroup, chunks);
-    }
-    hipError_t err = hipGetLastError();
+    hipError_t err = launch_repack(s, kernel, kp, pl.CH, pl.P.KQP, pl.P.colsp, kgroup, chunks, stream);
     if (err != hipSuccess) return err;
 
     if (pl.fast) return launch_igemm16_fast(pl.P, pl.blocks, s.dtype, stream);
@@ -444,16 +434,54 @@ hipError_t launch_igemm(const ConvShape& s, const void* in, const void* kernel, 
     }
     if (err != hipSuccess) return err;
 
-    if (pl.P.nsplit > 1) {
-        const unsigned blocks = (unsigned)((pl.P.out_elems + 255) / 256);
-        splitk_reduce_kernel<<<blocks, 256, 0, stream>>>(partial, out, pl.P.out_elems,
-                                                         pl.P.nsplit);
-        err = hipGetLastError();
-    }
+    if (pl.P.nsplit > 1) err = launch_splitk_reduce(partial, out, pl.P.out_elems, pl.P.nsplit, stream);
+    return err;
+}
+
+hipError_t launch_dma32(const ConvShape& s, const void* in, const void* kernel, float* out,
+                        void* workspace, hipStream_t stream)
+{
+    Dma32Plan pl = igemm32_dma_plan(s);
+    char* ws = static_cast<char*>(workspace);
+    float* partial = reinterpret_cast<float*>(ws + ((pl.repack_bytes + 255) & ~(size_t)255));
+    pl.P.in = in;
+    pl.P.kp = ws;
+    pl.P.out = pl.P.nsplit > 1 ? partial : out;
+    hipError_t err = launch_repack(s, kernel, ws, pl.cw, pl.kqp, pl.P.colsp, 4, pl.repack_bytes / 16,
+                                   stream);
+    if (err != hipSuccess) return err;
+    err = launch_igemm32_dma(pl, stream);
+    if (err != hipSuccess) return err;
+    if (pl.P.nsplit > 1) err = launch_splitk_reduce(partial, out, pl.P.out_elems, pl.P.nsplit, stream);
     return err;
 }
 
 }  // namespace
+
+hipError_t launch_repack(const ConvShape& s, const void* kernel, void* kp, int cw, int KQP,
+                         int colsp, int kgroup, size_t chunks, hipStream_t stream)
+{
+    const unsigned rblocks = (unsigned)((chunks + 255) / 256);
+    const int ntaps = s.kh * s.kw, KT = s.C * s.D2, cols = s.M * s.D3;
+    if (s.dtype == 0) {
+        repack_kernel<float, 4><<<rblocks, 256, 0, stream>>>(
+            (const float*)kernel, (float*)kp, ntaps, s.C, s.M, s.D0, s.D2, s.D3, KT, KQP, cols,
+            colsp, kgroup, cw, chunks);
+    } else {
+        repack_kernel<unsigned short, 8><<<rblocks, 256, 0, stream>>>(
+            (const unsigned short*)kernel, (unsigned short*)kp, ntaps, s.C, s.M, s.D0, s.D2, s.D3,
+            KT, KQP, cols, colsp, kgroup, cw, chunks);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_splitk_reduce(const float* partial, float* out, long long elems, int nsplit,
+                                hipStream_t stream)
+{
+    const unsigned blocks = (unsigned)((elems + 255) / 256);
+    splitk_reduce_kernel<<<blocks, 256, 0, stream>>>(partial, out, elems, nsplit);
+    return hipGetLastError();
+}
 
 bool mfma_supported(const ConvShape& s) { return shape_supported(s); }
 
@@ -467,7 +495,17 @@ size_t mfma_workspace_bytes(const ConvShape& s)
         const size_t bytes = ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
         if (bytes > need) need = bytes;
     }
+    if (igemm32_dma_eligible(s)) {
+        const Dma32Plan pl = igemm32_dma_plan(s);
+        const size_t bytes = ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
+        if (bytes > need) need = bytes;
+    }
     return need;
+}
+
+bool mfma_dma32_supported(const ConvShape& s)
+{
+    return shape_supported(s) && igemm32_dma_eligible(s);
 }
 
 bool mfma_tuned16_supported(const ConvShape& s)
@@ -478,6 +516,8 @@ bool mfma_tuned16_supported(const ConvShape& s)
 hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, float* out,
                        void* workspace, hipStream_t stream, MfmaKernel which)
 {
+    if (which == MfmaKernel::Dma32 || (which == MfmaKernel::Auto && igemm32_dma_preferred(s)))
+        return launch_dma32(s, in, kernel, out, workspace, stream);
     return launch_igemm(s, in, kernel, out, workspace, stream, which);
 }
 

@@ -14,7 +14,8 @@ from tests.gpu_util import check, run_gpu, shape_args, to_device
 pytestmark = pytest.mark.gpu
 
 PATHS = {"direct": cc.PATH_DIRECT, "mfma": cc.PATH_MFMA, "auto": cc.PATH_AUTO,
-         "generic": cc.PATH_MFMA_GENERIC, "tuned16": cc.PATH_MFMA_TUNED16}
+         "generic": cc.PATH_MFMA_GENERIC, "tuned16": cc.PATH_MFMA_TUNED16,
+         "tuned32": cc.PATH_MFMA_TUNED32}
 
 
 def small(name, dtype, N, H, W, C, M, kh, kw, s, p, D0, D1, D2, D3, dist="normal", seed=0):
@@ -55,11 +56,37 @@ SMALL_SHAPES = [
 
 
 @pytest.mark.parametrize("dtype", [wl.FP32, wl.BF16, wl.FP16], ids=["fp32", "bf16", "fp16"])
-@pytest.mark.parametrize("path", ["direct", "mfma"])
+@pytest.mark.parametrize("path", ["direct", "mfma", "generic"])
 @pytest.mark.parametrize("shape", SMALL_SHAPES, ids=[s[0] for s in SMALL_SHAPES])
 def test_small_shapes_match_oracle(shape, path, dtype):
     w = small(shape[0], dtype, *shape[1:], seed=len(shape[0]))
     full_compare(w, PATHS[path])
+
+
+# extra shapes for the fp32 kernel with direct-to-LDS copies: partial last channel group
+# (C*D2/CW not a multiple of 4), capsule rows of 6 and 12 floats, many rows (4-wave tiles),
+# wide column extents (several column tiles), padding wider than the window reach
+TUNED32_SHAPES = SMALL_SHAPES + [
+    #        N  H   W   C   M  kh kw s  p D0  D1  D2  D3
+    ("c5d3", 2, 6, 6, 5, 4, 3, 3, 1, 1, 1, 3, 3, 3),
+    ("d6", 1, 7, 6, 3, 5, 2, 2, 1, 0, 2, 4, 6, 3),
+    ("d12", 1, 5, 5, 2, 3, 3, 3, 2, 1, 1, 2, 12, 4),
+    ("rows", 6, 24, 24, 3, 40, 3, 3, 1, 1, 3, 3, 3, 3),
+    ("cols", 2, 10, 10, 4, 70, 3, 3, 1, 2, 1, 4, 4, 4),
+]
+
+
+@pytest.mark.parametrize("shape", TUNED32_SHAPES, ids=[s[0] for s in TUNED32_SHAPES])
+def test_tuned_fp32_kernel_matches_oracle(shape):
+    if shape[0] == "odd":
+        pytest.skip("capsule rows of 5 floats are served by the generic kernel")
+    w = small(shape[0], wl.FP32, *shape[1:], seed=len(shape[0]) + 70)
+    full_compare(w, PATHS["tuned32"])
+    wi = small(shape[0] + "_int", wl.FP32, *shape[1:], dist="int", seed=71)
+    i_st, k_st, i32, k32 = wl.generate(wi)
+    ref = capsconv.conv_fwd(i32, k32, wi.stride, wi.pad)
+    got = run_gpu(wi, to_device(i_st, wl.FP32), to_device(k_st, wl.FP32), PATHS["tuned32"])
+    assert np.array_equal(got.cpu().numpy().astype(np.float64), ref), wi.name
 
 
 # shapes the 256x256-tile 16-bit kernel accepts (D1 = D2 in {8, 16}, C*D2 a multiple of 64):
@@ -125,12 +152,12 @@ def test_small_integer_inputs_are_bit_exact(path, dtype):
 
 
 @pytest.mark.parametrize("num", [1, 4])
-@pytest.mark.parametrize("path", ["direct", "mfma", "auto"])
+@pytest.mark.parametrize("path", ["direct", "mfma", "auto", "generic", "tuned32"])
 def test_benchmark_configs_full_tensor(num, path):
     full_compare(wl.config(num), PATHS[path])
 
 
-@pytest.mark.parametrize("path", ["direct", "generic", "tuned16"])
+@pytest.mark.parametrize("path", ["direct", "generic", "tuned16", "tuned32"])
 @pytest.mark.parametrize("num,batch,hw", [(2, 2, 32), (3, 2, 28), (5, 2, 6)])
 def test_benchmark_configs_reduced_full_tensor(num, batch, hw, path):
     """Configs 2, 3, 5 with fewer images (config 5 also with a smaller image, to keep the
@@ -138,7 +165,9 @@ def test_benchmark_configs_reduced_full_tensor(num, batch, hw, path):
     w = wl.config(num)
     w = dataclasses.replace(w, N=batch, H=hw, W=hw, name=f"{w.name}[N={batch},HW={hw}]")
     if path == "tuned16" and w.dtype == wl.FP32:
-        pytest.skip("the tuned kernel is for 16-bit element types")
+        pytest.skip("the tuned 16-bit kernel is for 16-bit element types")
+    if path == "tuned32" and w.dtype != wl.FP32:
+        pytest.skip("the tuned fp32 kernel is for fp32")
     full_compare(w, PATHS[path])
 
 
