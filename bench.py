@@ -73,7 +73,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
-    ap.add_argument("--path", default="auto", choices=["auto", "mfma", "direct"])
+    ap.add_argument("--path", default="auto",
+                    choices=["auto", "mfma", "direct", "mfma-generic", "mfma-tuned16", "mfma-tuned32"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (the known-size kernel that "
@@ -92,7 +93,9 @@ def main():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     torch.cuda.set_device(0)
     w = wl.config(args.config)
-    path = {"auto": cc.PATH_AUTO, "mfma": cc.PATH_MFMA, "direct": cc.PATH_DIRECT}[args.path]
+    path = {"auto": cc.PATH_AUTO, "mfma": cc.PATH_MFMA, "direct": cc.PATH_DIRECT,
+            "mfma-generic": cc.PATH_MFMA_GENERIC, "mfma-tuned16": cc.PATH_MFMA_TUNED16,
+            "mfma-tuned32": cc.PATH_MFMA_TUNED32}[args.path]
     shape = (w.N, w.H, w.W, w.C, w.M, w.kh, w.kw, w.stride, w.pad, w.D0, w.D1, w.D2, w.D3, w.dtype)
 
     i_st, k_st, i32, k32 = wl.generate(w)
@@ -140,7 +143,7 @@ def main():
     value = flops_exact / (ms_per_step * 1e-3) / 1e9
     dname = wl.DTYPE_NAMES[w.dtype]
     achieved_tflops = flops_exact / (kernel_ms * 1e-3) / 1e12
-    chosen = cc.capscaps_select_path(*shape) if path == cc.PATH_AUTO else path
+    chosen = cc.capscaps_select_path(*shape) if path in (cc.PATH_AUTO, cc.PATH_MFMA) else path
     result = {
         "metric": "capsule-conv useful GFLOP/s at 1 GPU + % of MFMA roofline",
         "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -150,7 +153,9 @@ def main():
         "config": {
             "workload": f"config {args.config}: {w.name}", "N": w.N, "H": w.H, "W": w.W, "C": w.C,
             "M": w.M, "kh": w.kh, "kw": w.kw, "stride": w.stride, "pad": w.pad,
-            "capsule": [w.D0, w.D1, w.D2, w.D3], "path": {1: "direct", 2: "mfma"}[chosen],
+            "capsule": [w.D0, w.D1, w.D2, w.D3],
+            "path": {1: "direct", 2: "mfma", 3: "mfma-generic", 4: "mfma-tuned16",
+                     5: "mfma-tuned32"}[chosen],
             "flops_tap_exact": flops_exact, "flops_nominal": flops_nominal,
             "gflops_nominal": round(flops_nominal / (ms_per_step * 1e-3) / 1e9, 1),
             "compulsory_bytes": w.compulsory_bytes(),

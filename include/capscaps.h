@@ -115,8 +115,9 @@ size_t capscaps_conv_fwd_workspace_bytes(int N, int H, int W, int C, int M, int 
                                          int dtype);
 
 /*
- * Which path CAPSCAPS_PATH_AUTO resolves to for these arguments (CAPSCAPS_PATH_DIRECT or
- * CAPSCAPS_PATH_MFMA), or a negative status for invalid arguments.  Host-only.
+ * Which path CAPSCAPS_PATH_AUTO resolves to for these arguments (CAPSCAPS_PATH_DIRECT or one of
+ * the CAPSCAPS_PATH_MFMA_* kernel variants), or a negative status for invalid arguments.
+ * Host-only.
  */
 int capscaps_select_path(int N, int H, int W, int C, int M, int kh, int kw, int stride, int pad,
                          int D0, int D1, int D2, int D3, int dtype);

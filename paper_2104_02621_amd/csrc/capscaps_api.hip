@@ -47,7 +47,11 @@ int choose_path(const ConvShape& s)
     const long long cols = (long long)s.M * s.D3;
     const long long kdim = (long long)s.kh * s.kw * s.C * s.D2;
     if (cols < 16 || kdim < 32) return CAPSCAPS_PATH_DIRECT;
-    return CAPSCAPS_PATH_MFMA;
+    switch (capscaps::mfma_auto_kernel(s)) {
+        case capscaps::MfmaKernel::Tuned16: return CAPSCAPS_PATH_MFMA_TUNED16;
+        case capscaps::MfmaKernel::Dma32: return CAPSCAPS_PATH_MFMA_TUNED32;
+        default: return CAPSCAPS_PATH_MFMA_GENERIC;
+    }
 }
 
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
@@ -152,7 +156,7 @@ int capscaps_conv_fwd(const void* input, const void* kernel, void* out, int N, i
     if (rc != CAPSCAPS_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int path = choose_path(s);
-    const size_t need = path == CAPSCAPS_PATH_MFMA ? capscaps::mfma_workspace_bytes(s) : 0;
+    const size_t need = path != CAPSCAPS_PATH_DIRECT ? capscaps::mfma_workspace_bytes(s) : 0;
     void* ws = nullptr;
     if (need > 0) {
         const hipError_t err = hipMallocAsync(&ws, need, st);

@@ -27,6 +27,7 @@ hipError_t launch_direct(const ConvShape& s, const void* in, const void* kernel,
 // small problems, split-reduction partial sums).
 enum class MfmaKernel { Auto, Generic, Tuned16, Dma32 };
 bool mfma_supported(const ConvShape& s);
+MfmaKernel mfma_auto_kernel(const ConvShape& s);  // what Auto resolves to (never Auto)
 bool mfma_tuned16_supported(const ConvShape& s);
 bool mfma_dma32_supported(const ConvShape& s);
 size_t mfma_workspace_bytes(const ConvShape& s);  // enough for every MfmaKernel choice

@@ -503,6 +503,13 @@ size_t mfma_workspace_bytes(const ConvShape& s)
     return need;
 }
 
+MfmaKernel mfma_auto_kernel(const ConvShape& s)
+{
+    if (igemm32_dma_preferred(s)) return MfmaKernel::Dma32;
+    if (igemm16_fast_preferred(s)) return MfmaKernel::Tuned16;
+    return MfmaKernel::Generic;
+}
+
 bool mfma_dma32_supported(const ConvShape& s)
 {
     return shape_supported(s) && igemm32_dma_eligible(s);

@@ -97,13 +97,19 @@ def test_null_and_misaligned_pointers_and_bad_path():
 def test_path_selection_and_workspace_sizes():
     for w in wl.CONFIGS:
         a = (w.N, w.H, w.W, w.C, w.M, w.kh, w.kw, w.stride, w.pad, w.D0, w.D1, w.D2, w.D3, w.dtype)
-        assert cc.capscaps_select_path(*a) in (cc.PATH_DIRECT, cc.PATH_MFMA)
+        assert cc.capscaps_select_path(*a) in (cc.PATH_MFMA_GENERIC, cc.PATH_MFMA_TUNED16,
+                                               cc.PATH_MFMA_TUNED32)
         kernel_bytes = w.kh * w.kw * w.C * w.M * w.D0 * w.D2 * w.D3 * w.elem_bytes
         assert cc.capscaps_conv_fwd_workspace_bytes(*a) >= kernel_bytes
     # the Fig. 2 example has 3 output columns: too narrow for a matrix-core tile
     assert cc.capscaps_select_path(1, 5, 5, 1, 1, 4, 4, 1, 0, 3, 3, 3, 3, cc.FP32) == cc.PATH_DIRECT
+    # small problems take the generic kernel's small tiles; the benchmark shapes the tuned ones
     assert cc.capscaps_select_path(*_args(M=64, D3=16, D1=16, D2=16, C=64, dtype=cc.FP16)) \
-        == cc.PATH_MFMA
+        == cc.PATH_MFMA_GENERIC
+    picks = [cc.capscaps_select_path(w.N, w.H, w.W, w.C, w.M, w.kh, w.kw, w.stride, w.pad, w.D0,
+                                     w.D1, w.D2, w.D3, w.dtype) for w in wl.CONFIGS]
+    assert picks == [cc.PATH_MFMA_GENERIC, cc.PATH_MFMA_TUNED32, cc.PATH_MFMA_TUNED16,
+                     cc.PATH_MFMA_GENERIC, cc.PATH_MFMA_TUNED16]
 
 
 def test_strerror():
