@@ -192,22 +192,24 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     // pixel, clear = it falls into the padding or the output pixel does not exist.  The mask is
     // a wave ballot: lane t evaluates tap t.
     const int hw = P.Ho * P.Wo;
-    const long long npix = P.rows / D1;
-    const long long pg0 = (long long)row_tile * PIX;
-    const long long n_first = pg0 / hw;
+    // pixel indices fit 32 bits (checked by the launcher): 32-bit divisions keep the set-up short
+    const int npix = (int)(P.rows / D1);
+    const int pg0 = row_tile * PIX;
+    const int n_first = pg0 / hw;
     const long long img_elems = (long long)P.H * P.W * P.pixsz;
-    const unsigned short* in_base = static_cast<const unsigned short*>(P.in) + n_first * img_elems;
+    const unsigned short* in_base =
+        static_cast<const unsigned short*>(P.in) + (long long)n_first * img_elems;
     const int pix_bytes = (int)(P.pixsz * 2);
     const int tap_p = lane / P.kw, tap_q = lane - tap_p * P.kw;  // this lane's tap
     int pix_off[PPW];
     unsigned long long tap_ok[PPW];
 #pragma unroll
     for (int j = 0; j < PPW; ++j) {
-        const long long pg = pg0 + wave * PPW + j;
+        const int pg = pg0 + wave * PPW + j;
         const bool exists = pg < npix;
-        const long long pgc = exists ? pg : pg0;
-        const int n_rel = (int)(pgc / hw - n_first);
-        const int rem = (int)(pgc % hw);
+        const int pgc = exists ? pg : pg0;
+        const int n_rel = pgc / hw - n_first;
+        const int rem = pgc - (pgc / hw) * hw;
         const int x = rem / P.Wo, y = rem - x * P.Wo;
         const int ih0 = x * P.stride - P.pad, iw0 = y * P.stride - P.pad;
         const bool ok = exists && lane < P.ntaps && (unsigned)(ih0 + tap_p) < (unsigned)P.H &&
@@ -216,7 +218,7 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         pix_off[j] = __builtin_amdgcn_readfirstlane(
             (int)((((long long)n_rel * P.H + ih0) * P.W + iw0) * pix_bytes) + d0 * D1 * D2 * 2);
     }
-    long long in_left = P.in_bytes - n_first * img_elems * 2;
+    long long in_left = P.in_bytes - (long long)n_first * img_elems * 2;
     if (in_left > 0x7fffffffLL) in_left = 0x7fffffffLL;
     const rsrc_t rs_in = make_rsrc(in_base, (unsigned)in_left);
     const rsrc_t rs_kp = make_rsrc(P.kp, (unsigned)P.kp_records);
@@ -398,23 +400,29 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         });
     }
 
-    // ---- epilogue (lane (h, lr) of tile (a, b): registers 4g..4g+3 = columns 8g+4h+0..3)
+    // ---- epilogue: lane (h, lr) of MFMA tile (a, b) holds in registers 4g..4g+3 the columns
+    // 8g + 4h + 0..3 of that tile for its output row lr.  Columns advance in steps of 8, so
+    // (m, d3) of a column is found by shifts when D3 is a power of two, by division otherwise.
     float* __restrict__ out = P.out;
     const int caps_out = P.D0 * D1 * P.D3;
+    const bool d3_pow2 = (P.D3 & (P.D3 - 1)) == 0;
+    const int d3_shift = 31 - __builtin_clz(P.D3);
 #pragma unroll
     for (int b = 0; b < TM; ++b) {
         const int r = wm * WM + b * 32 + lr;
-        const long long pixel = pg0 + r / D1;
+        const int pixel = pg0 + r / D1;
         if (pixel >= npix) continue;
         const int d1 = r % D1;
-        float* orow_ptr = out + pixel * P.M * caps_out + (long long)(d0 * D1 + d1) * P.D3;
+        float* orow_ptr =
+            out + (long long)pixel * P.M * caps_out + (long long)(d0 * D1 + d1) * P.D3;
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int j0 = col0 + wn * WN + a * 32 + 8 * g + 4 * h;
                 if (j0 < P.cols) {
-                    const int m = j0 / P.D3, d3 = j0 - m * P.D3;
+                    const int m = d3_pow2 ? j0 >> d3_shift : j0 / P.D3;
+                    const int d3 = j0 - m * P.D3;
                     float4v v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
                                  acc[a][b][4 * g + 3]};
                     *reinterpret_cast<float4v*>(orow_ptr + (long long)m * caps_out + d3) = v;
@@ -473,6 +481,7 @@ bool igemm16_fast_eligible(const ConvShape& s)
     const long long colsp = ((long long)s.M * s.D3 + 255) / 256 * 256;
     const long long kp_bytes = (long long)s.D0 * s.kh * s.kw * (s.C * s.D2 / 8) * colsp * 16;
     if (kp_bytes >= (1LL << 31) - (1 << 24)) return false;
+    if ((long long)s.pixels() >= (1LL << 31) - 256) return false;  // 32-bit pixel indices
     return true;
 }
 
