@@ -52,6 +52,13 @@ SMALL_SHAPES = [
     ("fc", 5, 4, 3, 6, 7, 4, 3, 1, 0, 1, 4, 4, 4),
     ("odd", 1, 10, 9, 7, 3, 5, 4, 1, 2, 1, 3, 5, 7),
     ("manyrows", 4, 20, 20, 4, 20, 3, 3, 1, 1, 1, 8, 8, 8),
+    # degenerate geometries: a single pixel, a window equal to the padded input, a stride
+    # larger than the window, padding wider than the window's reach, scalar capsules
+    ("pixel", 1, 1, 1, 3, 2, 1, 1, 1, 0, 1, 2, 3, 2),
+    ("whole", 2, 2, 3, 2, 3, 4, 5, 1, 1, 2, 3, 4, 2),
+    ("jump", 1, 9, 9, 2, 2, 2, 2, 4, 0, 1, 4, 4, 4),
+    ("farpad", 1, 3, 3, 2, 2, 3, 3, 2, 3, 1, 4, 8, 4),
+    ("scalar", 2, 6, 6, 5, 7, 3, 3, 1, 1, 1, 1, 1, 1),
 ]
 
 
@@ -78,8 +85,8 @@ TUNED32_SHAPES = SMALL_SHAPES + [
 
 @pytest.mark.parametrize("shape", TUNED32_SHAPES, ids=[s[0] for s in TUNED32_SHAPES])
 def test_tuned_fp32_kernel_matches_oracle(shape):
-    if shape[0] == "odd":
-        pytest.skip("capsule rows of 5 floats are served by the generic kernel")
+    if shape[12] % 3 and shape[12] % 4:
+        pytest.skip("capsule rows of 1, 2, 5, 7 ... floats are served by the generic kernel")
     w = small(shape[0], wl.FP32, *shape[1:], seed=len(shape[0]) + 70)
     full_compare(w, PATHS["tuned32"])
     wi = small(shape[0] + "_int", wl.FP32, *shape[1:], dist="int", seed=71)
@@ -186,6 +193,37 @@ def test_benchmark_configs_full_size_sampled(num, count):
     idx = torch.from_numpy(which.astype(np.int64)).cuda()
     got = out[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
     check(w, got, ref, S, "sampled")
+
+
+def test_offsets_beyond_4GB():
+    """A config-5-like layer whose input (5.4 GB) and output (10.7 GB) exceed 32-bit byte
+    offsets: output capsules sampled from the last images, where every address is past 4 GB."""
+    import torch
+    w = dataclasses.replace(wl.config(5), N=160, name="large_caps_fp16[N=160]")
+    rng = np.random.default_rng(99)
+    # seeded inputs of the workload's distributions, drawn image by image to bound host memory
+    I = torch.empty(w.input_shape, dtype=torch.float16, device="cuda")
+    per_image = int(np.prod(w.input_shape[1:]))
+    tail = {}
+    for n in range(w.N):
+        img = rng.standard_normal(per_image, dtype=np.float32).astype(np.float16)
+        I[n] = torch.from_numpy(img).cuda().view(w.input_shape[1:])
+        if n >= w.N - 2:
+            tail[n] = img.reshape(w.input_shape[1:])
+    k16 = (rng.standard_normal(w.kernel_shape, dtype=np.float32) * np.float32(w.kernel_sigma)) \
+        .astype(np.float16)
+    K = torch.from_numpy(k16).cuda()
+    out = run_gpu(w, I, K, cc.PATH_AUTO)
+    assert bool(torch.isfinite(out[-2:]).all())
+    # oracle on the last two images only (same values, re-indexed as a 2-image problem)
+    i2 = np.stack([tail[w.N - 2], tail[w.N - 1]]).astype(np.float32)
+    w2 = dataclasses.replace(w, N=2)
+    which = wl.sample_capsules(w2, 400, seed=5)
+    ref, S = capsconv.conv_fwd_subset(i2, k16.astype(np.float32), which, w.stride, w.pad,
+                                      with_abs_sum=True)
+    idx = torch.from_numpy(which.astype(np.int64)).cuda()
+    got = out[idx[:, 0] + (w.N - 2), idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
+    check(w, got, ref, S, "last images of a >4 GB tensor")
 
 
 def test_split_reduction_is_deterministic():
