@@ -42,6 +42,10 @@ def _load():
         lib.capsconv_oracle_fwd.restype = i
         lib.capsconv_oracle_fwd_subset.argtypes = [p, p, p, p] + [i] * 13 + [p, ll]
         lib.capsconv_oracle_fwd_subset.restype = i
+        lib.capsconv_oracle_bwd_input.argtypes = [p, p, p] + [i] * 13
+        lib.capsconv_oracle_bwd_input.restype = i
+        lib.capsconv_oracle_bwd_kernel.argtypes = [p, p, p] + [i] * 13
+        lib.capsconv_oracle_bwd_kernel.restype = i
         lib.capsconv_oracle_threads.argtypes = []
         lib.capsconv_oracle_threads.restype = i
         _lib = lib
@@ -113,3 +117,39 @@ def conv_fwd_subset(I, K, which, stride=1, pad=0, with_abs_sum=False):
     if rc:
         raise ValueError(f"oracle rejected the request (rc={rc})")
     return (O, S) if with_abs_sum else O
+
+
+def conv_bwd_input(G, K, input_hw, stride=1, pad=0):
+    """dL/dI from G = dL/dO [N,H',W',M,D0,D1,D3] and K [kh,kw,C,M,D0,D2,D3]; input_hw = (H, W).
+    Returns float64 [N,H,W,C,D0,D1,D2]."""
+    G = _as_f32(G, 7, "G")
+    K = _as_f32(K, 7, "K")
+    H, W = input_hw
+    N, Ho, Wo, M, D0, D1, D3 = G.shape
+    kh, kw, C, Mk, D0k, D2, D3k = K.shape
+    if (Mk, D0k, D3k) != (M, D0, D3) or out_shape(H, W, kh, kw, stride, pad) != (Ho, Wo):
+        raise ValueError(f"G {G.shape}, K {K.shape} and input {H}x{W} do not fit together")
+    dI = np.empty((N, H, W, C, D0, D1, D2), dtype=np.float64)
+    rc = _load().capsconv_oracle_bwd_input(G.ctypes.data, K.ctypes.data, dI.ctypes.data, N, H, W, C,
+                                           M, kh, kw, stride, pad, D0, D1, D2, D3)
+    if rc:
+        raise ValueError(f"oracle rejected the dimensions (rc={rc})")
+    return dI
+
+
+def conv_bwd_kernel(I, G, kernel_hw, stride=1, pad=0):
+    """dL/dK from I [N,H,W,C,D0,D1,D2] and G = dL/dO [N,H',W',M,D0,D1,D3]; kernel_hw = (kh, kw).
+    Returns float64 [kh,kw,C,M,D0,D2,D3]."""
+    I = _as_f32(I, 7, "I")
+    G = _as_f32(G, 7, "G")
+    kh, kw = kernel_hw
+    N, H, W, C, D0, D1, D2 = I.shape
+    Ng, Ho, Wo, M, D0g, D1g, D3 = G.shape
+    if (Ng, D0g, D1g) != (N, D0, D1) or out_shape(H, W, kh, kw, stride, pad) != (Ho, Wo):
+        raise ValueError(f"I {I.shape}, G {G.shape} and window {kh}x{kw} do not fit together")
+    dK = np.empty((kh, kw, C, M, D0, D2, D3), dtype=np.float64)
+    rc = _load().capsconv_oracle_bwd_kernel(I.ctypes.data, G.ctypes.data, dK.ctypes.data, N, H, W,
+                                            C, M, kh, kw, stride, pad, D0, D1, D2, D3)
+    if rc:
+        raise ValueError(f"oracle rejected the dimensions (rc={rc})")
+    return dK

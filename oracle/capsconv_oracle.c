@@ -170,6 +170,106 @@ int capsconv_oracle_fwd_subset(const float *I, const float *K, double *O, double
     return 0;
 }
 
+/*
+ * ---------------------------------------------------------------------------------------------
+ * Backward pass (the two results of the paper's Algorithm 4: Input_diff and Kernel_diff).
+ * The printed algorithm is garbled (a one-argument batched multiply, Input_diff typed as a
+ * D1 x D3 capsule), so the definition taken here is the derivative of Algorithm 2's sum, which
+ * is what any backward pass of that operator must produce.  With G = dL/dO:
+ *
+ *   dI[n,h,w,c,d0] (D1 x D2) = sum over (x,p) with x*stride+p-pad = h, (y,q) with y*stride+q-pad = w,
+ *                              and m of   G[n,x,y,m,d0] (D1 x D3) . K[p,q,c,m,d0]^T (D3 x D2)
+ *   dK[p,q,c,m,d0] (D2 x D3) = sum over n, x, y with an in-range input pixel of
+ *                              I[n,x*stride+p-pad,y*stride+q-pad,c,d0]^T (D2 x D1) . G[n,x,y,m,d0] (D1 x D3)
+ *
+ * Both are written in gather form (one output element at a time), so there is nothing to
+ * synchronise and every sum has a fixed order.  Products and sums in double.
+ */
+static double G_at(const float *G, const capsconv_dims *g, int Ho, int Wo, int n, int x, int y,
+                   int m, int d0, int d1, int d3)
+{
+    size_t idx = ((((((size_t)n * Ho + x) * Wo + y) * g->M + m) * g->D0 + d0) * g->D1 + d1) *
+                     g->D3 + d3;
+    return (double)G[idx];
+}
+
+/* dI: N*H*W*C*D0*D1*D2 doubles.  Returns 0, or -1 on invalid dimensions. */
+int capsconv_oracle_bwd_input(const float *G, const float *K, double *dI, int N, int H, int W,
+                              int C, int M, int kh, int kw, int stride, int pad, int D0, int D1,
+                              int D2, int D3)
+{
+    capsconv_dims g = {N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3};
+    int Ho, Wo;
+    if (N <= 0 || C <= 0 || M <= 0 || D0 <= 0 || D1 <= 0 || D2 <= 0 || D3 <= 0) return -1;
+    if (capsconv_oracle_out_shape(H, W, kh, kw, stride, pad, &Ho, &Wo)) return -1;
+    const long long npix = (long long)N * H * W;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (long long pix = 0; pix < npix; ++pix) {
+        const int n = (int)(pix / ((long long)H * W));
+        const int h = (int)((pix / W) % H);
+        const int w = (int)(pix % W);
+        for (int c = 0; c < C; ++c)
+            for (int d0 = 0; d0 < D0; ++d0)
+                for (int d1 = 0; d1 < D1; ++d1)
+                    for (int d2 = 0; d2 < D2; ++d2) {
+                        double acc = 0.0;
+                        for (int p = 0; p < kh; ++p) {
+                            const int hx = h + pad - p; /* = x * stride */
+                            if (hx < 0 || hx % stride != 0 || hx / stride >= Ho) continue;
+                            for (int q = 0; q < kw; ++q) {
+                                const int wy = w + pad - q;
+                                if (wy < 0 || wy % stride != 0 || wy / stride >= Wo) continue;
+                                const int x = hx / stride, y = wy / stride;
+                                for (int m = 0; m < M; ++m)
+                                    for (int d3 = 0; d3 < D3; ++d3)
+                                        acc += G_at(G, &g, Ho, Wo, n, x, y, m, d0, d1, d3) *
+                                               K_at(K, &g, p, q, c, m, d0, d2, d3);
+                            }
+                        }
+                        dI[((((size_t)pix * C + c) * D0 + d0) * D1 + d1) * D2 + d2] = acc;
+                    }
+    }
+    return 0;
+}
+
+/* dK: kh*kw*C*M*D0*D2*D3 doubles.  Returns 0, or -1 on invalid dimensions. */
+int capsconv_oracle_bwd_kernel(const float *I, const float *G, double *dK, int N, int H, int W,
+                               int C, int M, int kh, int kw, int stride, int pad, int D0, int D1,
+                               int D2, int D3)
+{
+    capsconv_dims g = {N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3};
+    int Ho, Wo;
+    if (N <= 0 || C <= 0 || M <= 0 || D0 <= 0 || D1 <= 0 || D2 <= 0 || D3 <= 0) return -1;
+    if (capsconv_oracle_out_shape(H, W, kh, kw, stride, pad, &Ho, &Wo)) return -1;
+    const long long ncaps = (long long)kh * kw * C * M;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (long long kc = 0; kc < ncaps; ++kc) {
+        const int m = (int)(kc % M);
+        const int c = (int)((kc / M) % C);
+        const int q = (int)((kc / ((long long)M * C)) % kw);
+        const int p = (int)(kc / ((long long)M * C * kw));
+        for (int d0 = 0; d0 < D0; ++d0)
+            for (int d2 = 0; d2 < D2; ++d2)
+                for (int d3 = 0; d3 < D3; ++d3) {
+                    double acc = 0.0;
+                    for (int n = 0; n < N; ++n)
+                        for (int x = 0; x < Ho; ++x) {
+                            const int h = x * stride + p - pad;
+                            if (h < 0 || h >= H) continue;
+                            for (int y = 0; y < Wo; ++y) {
+                                const int w = y * stride + q - pad;
+                                if (w < 0 || w >= W) continue;
+                                for (int d1 = 0; d1 < D1; ++d1)
+                                    acc += I_at(I, &g, n, h, w, c, d0, d1, d2) *
+                                           G_at(G, &g, Ho, Wo, n, x, y, m, d0, d1, d3);
+                            }
+                        }
+                    dK[(((size_t)kc * D0 + d0) * D2 + d2) * D3 + d3] = acc;
+                }
+    }
+    return 0;
+}
+
 /* Number of OpenMP threads the loops above will use (for reporting). */
 #ifdef _OPENMP
 #include <omp.h>
