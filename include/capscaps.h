@@ -1,5 +1,5 @@
 /*
- * capscaps -- capsule-convolution forward pass on AMD MI355X (gfx950).  C ABI.
+ * capscaps -- capsule convolution (forward and backward pass) on AMD MI355X (gfx950).  C ABI.
  *
  * The operator (paper Sec. 1.2 and Algorithm 2, "General capsule convolution"; 3-D capsules
  * as in Fig. 2): for every image n, output pixel (x, y), output channel m and leading capsule
@@ -121,6 +121,42 @@ size_t capscaps_conv_fwd_workspace_bytes(int N, int H, int W, int C, int M, int 
  */
 int capscaps_select_path(int N, int H, int W, int C, int M, int kh, int kw, int stride, int pad,
                          int D0, int D1, int D2, int D3, int dtype);
+
+/*
+ * Backward pass (Algorithm 4, read as the derivative of Algorithm 2's sum: the printed
+ * algorithm's index expressions are garbled).  With `dout` = dL/dO, laid out like `out` but
+ * holding elements of type `dtype` (the gradient arrives in the storage type of the layer's
+ * operands), both results are fp32 and overwritten, never accumulated into:
+ *
+ *   dinput [N][H][W][C][D0][D1][D2]:
+ *     dI[n,h,w,c,d0] = sum over (x,y,p,q) with x*stride+p-pad = h, y*stride+q-pad = w, and m of
+ *                      dO[n,x,y,m,d0] (D1 x D3) . transpose(K[p,q,c,m,d0]) (D3 x D2)
+ *   dkernel [kh][kw][C][M][D0][D2][D3]:
+ *     dK[p,q,c,m,d0] = sum over n and output pixels (x,y) whose tap (p,q) lies inside the image of
+ *                      transpose(I[n,x*stride+p-pad,y*stride+q-pad,c,d0]) (D2 x D1) . dO[n,x,y,m,d0]
+ *
+ * The shape arguments are those of the forward call whose gradients are wanted.  For stride 1
+ * both gradients are themselves capsule convolutions and run on the forward kernels after a
+ * re-layout in `workspace` (dinput needs a square window for that); other strides run plain
+ * gather kernels and need no workspace.  Pointer, stream and error rules as for the forward
+ * calls; `workspace` must hold capscaps_conv_bwd_input_workspace_bytes(...) resp.
+ * capscaps_conv_bwd_kernel_workspace_bytes(...) bytes for the same arguments (0 = may be NULL).
+ */
+int capscaps_conv_bwd_input(const void* dout, const void* kernel, void* dinput, int N, int H, int W,
+                            int C, int M, int kh, int kw, int stride, int pad, int D0, int D1,
+                            int D2, int D3, int dtype, void* workspace, size_t workspace_bytes,
+                            void* stream);
+int capscaps_conv_bwd_kernel(const void* input, const void* dout, void* dkernel, int N, int H,
+                             int W, int C, int M, int kh, int kw, int stride, int pad, int D0,
+                             int D1, int D2, int D3, int dtype, void* workspace,
+                             size_t workspace_bytes, void* stream);
+/* Host-only; 0 also for invalid arguments (the compute call reports those). */
+size_t capscaps_conv_bwd_input_workspace_bytes(int N, int H, int W, int C, int M, int kh, int kw,
+                                               int stride, int pad, int D0, int D1, int D2, int D3,
+                                               int dtype);
+size_t capscaps_conv_bwd_kernel_workspace_bytes(int N, int H, int W, int C, int M, int kh, int kw,
+                                                int stride, int pad, int D0, int D1, int D2,
+                                                int D3, int dtype);
 
 /* Static, human-readable text for a status code.  Never NULL. */
 const char* capscaps_strerror(int status);

@@ -59,6 +59,11 @@ def _load():
     lib.capscaps_conv_fwd_workspace_bytes.restype = sz
     lib.capscaps_select_path.argtypes = [i] * 14
     lib.capscaps_select_path.restype = i
+    for name in ("capscaps_conv_bwd_input", "capscaps_conv_bwd_kernel"):
+        getattr(lib, name).argtypes = [p, p, p] + [i] * 14 + [p, sz, p]
+        getattr(lib, name).restype = i
+        getattr(lib, name + "_workspace_bytes").argtypes = [i] * 14
+        getattr(lib, name + "_workspace_bytes").restype = sz
     lib.capscaps_strerror.argtypes = [i]
     lib.capscaps_strerror.restype = ctypes.c_char_p
     lib.capscaps_last_hip_error.argtypes = []
@@ -114,6 +119,32 @@ def capscaps_select_path(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dty
                                             dtype))
 
 
+def capscaps_conv_bwd_input(dout, kernel, dinput, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2,
+                            D3, dtype, workspace, workspace_bytes, stream=None) -> int:
+    return _load().capscaps_conv_bwd_input(dout, kernel, dinput, N, H, W, C, M, kh, kw, stride,
+                                           pad, D0, D1, D2, D3, dtype, workspace, workspace_bytes,
+                                           stream)
+
+
+def capscaps_conv_bwd_kernel(input, dout, dkernel, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2,
+                             D3, dtype, workspace, workspace_bytes, stream=None) -> int:
+    return _load().capscaps_conv_bwd_kernel(input, dout, dkernel, N, H, W, C, M, kh, kw, stride,
+                                            pad, D0, D1, D2, D3, dtype, workspace,
+                                            workspace_bytes, stream)
+
+
+def capscaps_conv_bwd_input_workspace_bytes(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3,
+                                            dtype) -> int:
+    return int(_load().capscaps_conv_bwd_input_workspace_bytes(N, H, W, C, M, kh, kw, stride, pad,
+                                                               D0, D1, D2, D3, dtype))
+
+
+def capscaps_conv_bwd_kernel_workspace_bytes(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3,
+                                             dtype) -> int:
+    return int(_load().capscaps_conv_bwd_kernel_workspace_bytes(N, H, W, C, M, kh, kw, stride,
+                                                                pad, D0, D1, D2, D3, dtype))
+
+
 # ------------------------------------------------------------------ torch convenience
 def _torch_dtype_code(t):
     import torch
@@ -152,3 +183,64 @@ def conv_fwd(input, kernel, stride=1, pad=0, path=PATH_AUTO, out=None, workspace
     if rc != OK:
         raise CapscapsError(rc)
     return out
+
+
+def _bwd_common(a, b):
+    if not (a.is_cuda and b.is_cuda):
+        raise ValueError("capscaps runs on the GPU only: pass device tensors")
+    if a.dtype != b.dtype or a.dim() != 7 or b.dim() != 7:
+        raise ValueError("operands must be 7-D tensors of one dtype")
+    if not (a.is_contiguous() and b.is_contiguous()):
+        raise ValueError("operands must be contiguous")
+
+
+def conv_bwd_input(dout, kernel, input_hw, stride=1, pad=0):
+    """dout [N,H',W',M,D0,D1,D3], kernel [kh,kw,C,M,D0,D2,D3] (one dtype), input_hw = (H, W) of
+    the forward input -> float32 dinput [N,H,W,C,D0,D1,D2]."""
+    import torch
+    _bwd_common(dout, kernel)
+    N, Ho, Wo, M, D0, D1, D3 = dout.shape
+    kh, kw, C, Mk, D0k, D2, D3k = kernel.shape
+    H, W = input_hw
+    rc, ho, wo = capscaps_out_shape(H, W, kh, kw, stride, pad)
+    if rc != OK:
+        raise CapscapsError(rc)
+    if (Mk, D0k, D3k, ho, wo) != (M, D0, D3, Ho, Wo):
+        raise ValueError("dout, kernel and input_hw do not describe one convolution")
+    dt = _torch_dtype_code(dout)
+    shape = (N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dt)
+    need = capscaps_conv_bwd_input_workspace_bytes(*shape)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dout.device)
+    din = torch.empty((N, H, W, C, D0, D1, D2), dtype=torch.float32, device=dout.device)
+    rc = capscaps_conv_bwd_input(dout.data_ptr(), kernel.data_ptr(), din.data_ptr(), *shape,
+                                 ws.data_ptr(), ws.numel(),
+                                 torch.cuda.current_stream(dout.device).cuda_stream)
+    if rc != OK:
+        raise CapscapsError(rc)
+    return din
+
+
+def conv_bwd_kernel(input, dout, kernel_hw, stride=1, pad=0):
+    """input [N,H,W,C,D0,D1,D2], dout [N,H',W',M,D0,D1,D3] (one dtype), kernel_hw = (kh, kw)
+    -> float32 dkernel [kh,kw,C,M,D0,D2,D3]."""
+    import torch
+    _bwd_common(input, dout)
+    N, H, W, C, D0, D1, D2 = input.shape
+    Ng, Ho, Wo, M, D0g, D1g, D3 = dout.shape
+    kh, kw = kernel_hw
+    rc, ho, wo = capscaps_out_shape(H, W, kh, kw, stride, pad)
+    if rc != OK:
+        raise CapscapsError(rc)
+    if (Ng, D0g, D1g, ho, wo) != (N, D0, D1, Ho, Wo):
+        raise ValueError("input, dout and kernel_hw do not describe one convolution")
+    dt = _torch_dtype_code(input)
+    shape = (N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dt)
+    need = capscaps_conv_bwd_kernel_workspace_bytes(*shape)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=input.device)
+    dk = torch.empty((kh, kw, C, M, D0, D2, D3), dtype=torch.float32, device=input.device)
+    rc = capscaps_conv_bwd_kernel(input.data_ptr(), dout.data_ptr(), dk.data_ptr(), *shape,
+                                  ws.data_ptr(), ws.numel(),
+                                  torch.cuda.current_stream(input.device).cuda_stream)
+    if rc != OK:
+        raise CapscapsError(rc)
+    return dk

@@ -1,4 +1,4 @@
-// C ABI of the capsule-convolution forward pass: argument checking, path choice, launches.
+// C ABI of the capsule convolution (forward and backward pass): argument checking, path choice, launches.
 // Declarations and their contracts are in include/capscaps.h.
 #include <hip/hip_runtime.h>
 
@@ -89,6 +89,23 @@ int run(const void* input, const void* kernel, void* out, const ConvShape& s, in
 
 }  // namespace
 
+namespace capscaps {
+
+int status_from_hip(hipError_t err) { return hip_status(err); }
+
+size_t forward_workspace_bytes(const ConvShape& s)
+{
+    return choose_path(s) == CAPSCAPS_PATH_DIRECT ? 0 : mfma_workspace_bytes(s);
+}
+
+int forward_auto(const ConvShape& s, const void* in, const void* kernel, float* out,
+                 void* workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    return run(in, kernel, out, s, CAPSCAPS_PATH_AUTO, workspace, workspace_bytes, stream);
+}
+
+}  // namespace capscaps
+
 extern "C" {
 
 int capscaps_out_shape(int H, int W, int kh, int kw, int stride, int pad, int* Ho, int* Wo)
@@ -168,6 +185,60 @@ int capscaps_conv_fwd(const void* input, const void* kernel, void* out, int N, i
         if (err != hipSuccess && status == CAPSCAPS_OK) return hip_status(err);
     }
     return status;
+}
+
+size_t capscaps_conv_bwd_input_workspace_bytes(int N, int H, int W, int C, int M, int kh, int kw,
+                                               int stride, int pad, int D0, int D1, int D2, int D3,
+                                               int dtype)
+{
+    ConvShape s;
+    if (fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype) != CAPSCAPS_OK)
+        return 0;
+    return capscaps::bwd_input_workspace_bytes(s);
+}
+
+size_t capscaps_conv_bwd_kernel_workspace_bytes(int N, int H, int W, int C, int M, int kh, int kw,
+                                                int stride, int pad, int D0, int D1, int D2,
+                                                int D3, int dtype)
+{
+    ConvShape s;
+    if (fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype) != CAPSCAPS_OK)
+        return 0;
+    return capscaps::bwd_kernel_workspace_bytes(s);
+}
+
+int capscaps_conv_bwd_input(const void* dout, const void* kernel, void* dinput, int N, int H, int W,
+                            int C, int M, int kh, int kw, int stride, int pad, int D0, int D1,
+                            int D2, int D3, int dtype, void* workspace, size_t workspace_bytes,
+                            void* stream)
+{
+    if (dout == nullptr || kernel == nullptr || dinput == nullptr) return CAPSCAPS_EINVAL;
+    if (misaligned(dout) || misaligned(kernel) || misaligned(dinput)) return CAPSCAPS_EINVAL;
+    ConvShape s;
+    const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype);
+    if (rc != CAPSCAPS_OK) return rc;
+    const size_t need = capscaps::bwd_input_workspace_bytes(s);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return CAPSCAPS_EWORKSPACE;
+    if (need > 0 && misaligned(workspace)) return CAPSCAPS_EINVAL;
+    return capscaps::launch_bwd_input(s, dout, kernel, static_cast<float*>(dinput), workspace,
+                                      workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+int capscaps_conv_bwd_kernel(const void* input, const void* dout, void* dkernel, int N, int H,
+                             int W, int C, int M, int kh, int kw, int stride, int pad, int D0,
+                             int D1, int D2, int D3, int dtype, void* workspace,
+                             size_t workspace_bytes, void* stream)
+{
+    if (input == nullptr || dout == nullptr || dkernel == nullptr) return CAPSCAPS_EINVAL;
+    if (misaligned(input) || misaligned(dout) || misaligned(dkernel)) return CAPSCAPS_EINVAL;
+    ConvShape s;
+    const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype);
+    if (rc != CAPSCAPS_OK) return rc;
+    const size_t need = capscaps::bwd_kernel_workspace_bytes(s);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return CAPSCAPS_EWORKSPACE;
+    if (need > 0 && misaligned(workspace)) return CAPSCAPS_EINVAL;
+    return capscaps::launch_bwd_kernel(s, input, dout, static_cast<float*>(dkernel), workspace,
+                                       workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 const char* capscaps_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }

@@ -34,4 +34,22 @@ size_t mfma_workspace_bytes(const ConvShape& s);  // enough for every MfmaKernel
 hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, float* out,
                        void* workspace, hipStream_t stream, MfmaKernel which = MfmaKernel::Auto);
 
+// The forward pass with the library's own path choice, and the scratch it needs (defined next
+// to the C ABI); used by the backward pass, which for stride 1 is two forward convolutions.
+// Both return a status code of the C ABI; `status_from_hip` maps a HIP error to one and
+// records it for the ABI's diagnostic call.
+size_t forward_workspace_bytes(const ConvShape& s);
+int forward_auto(const ConvShape& s, const void* in, const void* kernel, float* out,
+                 void* workspace, size_t workspace_bytes, hipStream_t stream);
+int status_from_hip(hipError_t err);
+
+// Backward pass (backward.hip): gradients with respect to input and kernel, fp32 results.
+size_t bwd_input_workspace_bytes(const ConvShape& s);
+size_t bwd_kernel_workspace_bytes(const ConvShape& s);
+// Return a status code of the C ABI.
+int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, float* din,
+                     void* workspace, size_t workspace_bytes, hipStream_t stream);
+int launch_bwd_kernel(const ConvShape& s, const void* input, const void* dout, float* dkernel,
+                      void* workspace, size_t workspace_bytes, hipStream_t stream);
+
 }  // namespace capscaps

@@ -172,6 +172,13 @@ def generate(w: Workload):
     return i_st, k_st, i_32, k_32
 
 
+def generate_dout(w: Workload):
+    """Output gradient dL/dO for the backward pass of a workload: (storage, f32) in the
+    workload's element type, drawn like the input (its own seed)."""
+    xg = _draw(np.random.default_rng(w.seed_input + 7000), w.out_shape, w.input_dist, 1.0)
+    return to_storage(xg, w.dtype)
+
+
 def integer_variant(w: Workload) -> Workload:
     """Same shape, small-integer values: every partial sum is exact in fp32, so any correct
     implementation must reproduce the exact result bit for bit in any summation order."""

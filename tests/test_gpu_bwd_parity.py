@@ -1,0 +1,163 @@
+"""GPU parity of the backward pass: the HIP library's input and kernel gradients, called
+through the C ABI, against the CPU oracle's, element by element on the same seeded inputs.
+Needs an MI355X."""
+import dataclasses
+import functools
+
+import numpy as np
+import pytest
+
+from oracle import capsconv
+from paper_2104_02621_amd import capscaps as cc
+from paper_2104_02621_amd import workloads as wl
+from tests.gpu_util import check, shape_args, to_device
+from tests.test_gpu_parity import SMALL_SHAPES, small
+
+pytestmark = pytest.mark.gpu
+
+
+def run_bwd_input(w, g_dev, k_dev):
+    import torch
+    din = torch.full(w.input_shape, float("nan"), dtype=torch.float32, device="cuda")
+    need = cc.capscaps_conv_bwd_input_workspace_bytes(*shape_args(w))
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    rc = cc.capscaps_conv_bwd_input(g_dev.data_ptr(), k_dev.data_ptr(), din.data_ptr(),
+                                    *shape_args(w), ws.data_ptr(), ws.numel(),
+                                    torch.cuda.current_stream().cuda_stream)
+    assert rc == cc.OK, f"{w.name}: status {rc} ({cc.capscaps_strerror(rc)}; {cc.capscaps_last_hip_error()})"
+    return din
+
+
+def run_bwd_kernel(w, i_dev, g_dev):
+    import torch
+    dk = torch.full(w.kernel_shape, float("nan"), dtype=torch.float32, device="cuda")
+    need = cc.capscaps_conv_bwd_kernel_workspace_bytes(*shape_args(w))
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    rc = cc.capscaps_conv_bwd_kernel(i_dev.data_ptr(), g_dev.data_ptr(), dk.data_ptr(),
+                                     *shape_args(w), ws.data_ptr(), ws.numel(),
+                                     torch.cuda.current_stream().cuda_stream)
+    assert rc == cc.OK, f"{w.name}: status {rc} ({cc.capscaps_strerror(rc)}; {cc.capscaps_last_hip_error()})"
+    return dk
+
+
+@functools.lru_cache(maxsize=2)
+def oracle_bwd(w):
+    """Inputs, the oracle's two gradients and, as the error scale of each gradient element,
+    the same sums taken over absolute values."""
+    i_st, k_st, i32, k32 = wl.generate(w)
+    g_st, g32 = wl.generate_dout(w)
+    hw, khw = (w.H, w.W), (w.kh, w.kw)
+    dI = capsconv.conv_bwd_input(g32, k32, hw, w.stride, w.pad)
+    dK = capsconv.conv_bwd_kernel(i32, g32, khw, w.stride, w.pad)
+    SI = capsconv.conv_bwd_input(np.abs(g32), np.abs(k32), hw, w.stride, w.pad)
+    SK = capsconv.conv_bwd_kernel(np.abs(i32), np.abs(g32), khw, w.stride, w.pad)
+    return i_st, k_st, g_st, dI, dK, SI, SK
+
+
+def both_gradients(w):
+    i_st, k_st, g_st, dI, dK, SI, SK = oracle_bwd(w)
+    i_dev, k_dev, g_dev = (to_device(a, w.dtype) for a in (i_st, k_st, g_st))
+    got_i = run_bwd_input(w, g_dev, k_dev).cpu().numpy()
+    got_k = run_bwd_kernel(w, i_dev, g_dev).cpu().numpy()
+    # an input pixel no window reaches has dI = 0 and scale 0: compare those exactly
+    dead = SI == 0
+    assert (got_i[dead] == 0).all()
+    check(w, got_i, dI, np.where(dead, 1.0, SI), "dinput")
+    dead = SK == 0
+    assert (got_k[dead] == 0).all()
+    check(w, got_k, dK, np.where(dead, 1.0, SK), "dkernel")
+    return got_i, got_k, dI, dK
+
+
+# the forward pass's small shapes (strides 1..4, non-square windows and capsules, degenerate
+# geometries) plus stride-1 cases that exercise the convolution route on several tiles
+BWD_SHAPES = SMALL_SHAPES + [
+    #          N  H   W   C   M  kh kw s  p D0  D1  D2  D3
+    ("deeppad", 2, 5, 5, 3, 4, 3, 3, 1, 4, 1, 4, 4, 4),     # pad > k-1: no flipped-kernel form
+    ("s1wide", 3, 12, 12, 24, 20, 3, 3, 1, 1, 1, 8, 8, 8),
+    ("s1d16", 2, 9, 8, 16, 12, 3, 3, 1, 1, 1, 16, 16, 16),
+    ("s1nonsq", 2, 10, 7, 6, 9, 2, 2, 1, 0, 2, 3, 5, 4),
+    ("s1k5", 1, 11, 11, 8, 8, 5, 5, 1, 2, 1, 4, 4, 4),
+]
+
+
+@pytest.mark.parametrize("dtype", [wl.FP32, wl.BF16, wl.FP16], ids=["fp32", "bf16", "fp16"])
+@pytest.mark.parametrize("shape", BWD_SHAPES, ids=[s[0] for s in BWD_SHAPES])
+def test_gradients_match_oracle(shape, dtype):
+    both_gradients(small(shape[0], dtype, *shape[1:], seed=len(shape[0]) + 50))
+
+
+@pytest.mark.parametrize("dtype", [wl.FP32, wl.BF16, wl.FP16], ids=["fp32", "bf16", "fp16"])
+@pytest.mark.parametrize("shape", BWD_SHAPES, ids=[s[0] for s in BWD_SHAPES])
+def test_integer_data_is_bit_exact(shape, dtype):
+    """Small-integer operands: every partial sum is exact in fp32, so both gradients must equal
+    the oracle's bit for bit whatever the summation order."""
+    w = wl.integer_variant(small(shape[0], dtype, *shape[1:], seed=len(shape[0]) + 60))
+    got_i, got_k, dI, dK = both_gradients(w)
+    assert np.abs(dI).max() < 2 ** 24 and np.abs(dK).max() < 2 ** 24
+    assert np.array_equal(got_i.astype(np.float64), dI)
+    assert np.array_equal(got_k.astype(np.float64), dK)
+
+
+def test_fig2_example_gradients():
+    """The worked example's geometry (Fig. 2: 5x5 image of 3x3x3 capsules, 4x4 window)."""
+    w = small("fig2", wl.FP32, 1, 5, 5, 1, 1, 4, 4, 1, 0, 3, 3, 3, 3, seed=77)
+    both_gradients(w)
+
+
+@pytest.mark.parametrize("number", [1, 2, 3, 4, 5])
+def test_benchmark_configs_reduced_batch(number):
+    """The five benchmark shapes with the batch (and, for the largest, the image) cut to what
+    the oracle finishes in seconds."""
+    full = wl.config(number)
+    w = full.with_batch(2)
+    if w.flops_nominal() > 5e10:
+        w = dataclasses.replace(w, N=1, H=8, W=8)
+    both_gradients(w)
+
+
+@pytest.mark.parametrize("number", [1, 2, 3, 4, 5])
+def test_benchmark_configs_full_size_sampled(number):
+    """Full benchmark sizes.  dI[n,:,:,c] depends only on image n of the gradient and channel c
+    of the kernel, dK[:,:,c,m] only on channel c of the input and channel m of the gradient, so
+    the oracle computes sampled slices exactly from sliced operands."""
+    w = wl.config(number)
+    i_st, k_st, i32, k32 = wl.generate(w)
+    g_st, g32 = wl.generate_dout(w)
+    i_dev, k_dev, g_dev = (to_device(a, w.dtype) for a in (i_st, k_st, g_st))
+    got_i = run_bwd_input(w, g_dev, k_dev)
+    got_k = run_bwd_kernel(w, i_dev, g_dev)
+    rng = np.random.default_rng(900 + number)
+    hw, khw = (w.H, w.W), (w.kh, w.kw)
+    for _ in range(3):
+        n, c, m = int(rng.integers(w.N)), int(rng.integers(w.C)), int(rng.integers(w.M))
+        gs, ks = g32[n:n + 1], np.ascontiguousarray(k32[:, :, c:c + 1])
+        ref = capsconv.conv_bwd_input(gs, ks, hw, w.stride, w.pad)
+        S = capsconv.conv_bwd_input(np.abs(gs), np.abs(ks), hw, w.stride, w.pad)
+        sub = dataclasses.replace(w, name=f"{w.name} dI[{n},:,:,{c}]")
+        check(sub, got_i[n:n + 1, :, :, c:c + 1].cpu().numpy(), ref, np.maximum(S, 1e-30))
+        isl = np.ascontiguousarray(i32[:, :, :, c:c + 1])
+        gsl = np.ascontiguousarray(g32[:, :, :, m:m + 1])
+        ref = capsconv.conv_bwd_kernel(isl, gsl, khw, w.stride, w.pad)
+        S = capsconv.conv_bwd_kernel(np.abs(isl), np.abs(gsl), khw, w.stride, w.pad)
+        sub = dataclasses.replace(w, name=f"{w.name} dK[:,:,{c},{m}]")
+        check(sub, got_k[:, :, c:c + 1, m:m + 1].cpu().numpy(), ref, np.maximum(S, 1e-30))
+    assert bool(got_i.isfinite().all()) and bool(got_k.isfinite().all())
+
+
+def test_workspace_too_small_is_refused():
+    import torch
+    w = small("s1", wl.FP16, 2, 6, 6, 4, 4, 3, 3, 1, 1, 1, 8, 8, 8)
+    args = shape_args(w)
+    need_i = cc.capscaps_conv_bwd_input_workspace_bytes(*args)
+    need_k = cc.capscaps_conv_bwd_kernel_workspace_bytes(*args)
+    assert need_i > 0 and need_k > 0
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    p = buf.data_ptr()
+    assert cc.capscaps_conv_bwd_input(p, p, p, *args, p, need_i - 1, st) == cc.EWORKSPACE
+    assert cc.capscaps_conv_bwd_kernel(p, p, p, *args, 0, 0, st) == cc.EWORKSPACE
+    assert cc.capscaps_conv_bwd_input(0, p, p, *args, p, need_i, st) == cc.EINVAL
+    strided = small("s2", wl.FP16, 2, 6, 6, 4, 4, 3, 3, 2, 1, 1, 8, 8, 8)
+    assert cc.capscaps_conv_bwd_input_workspace_bytes(*shape_args(strided)) == 0
+    assert cc.capscaps_conv_bwd_kernel_workspace_bytes(*shape_args(strided)) == 0
