@@ -2,12 +2,15 @@
 """Benchmark of the capsule-convolution forward pass on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--path auto|mfma|direct]
+                    [--op fwd|bwd_input|bwd_kernel]
 
 A step is one pass of the whole hot path (kernel repack, window addressing, LDS staging,
 matrix-core contraction, accumulation, fp32 store) over one batch of seeded synthetic input
 that is already resident in HBM.  The default workload is benchmark configuration 5
 (fp16 in, fp32 accumulate, N=64, 32x32, C=M=64, 3x3, pad 1, 16x16 capsules), the largest one
-and the one the roofline target is stated on.  Prints ONE JSON line.
+and the one the roofline target is stated on.  `--op bwd_input` / `--op bwd_kernel` time the
+backward pass (gradient with respect to the input / the kernel) of the same workload instead.
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -67,6 +70,48 @@ def cpu_baseline(w, i32, k32, gpu_out, target_seconds=15.0):
     return rec, err
 
 
+def cpu_baseline_bwd(w, op, i32, k32, g32, gpu_grad, target_seconds=12.0):
+    """Backward counterpart: the oracle on slices it can compute exactly from sliced operands
+    (dI[n,:,:,c] from image n of the gradient and channel c of the kernel; dK[:,:,c,m] from
+    channel c of the input and channel m of the gradient)."""
+    import numpy as np
+    from oracle import capsconv
+
+    rng = np.random.default_rng(4244)
+    slices = w.N * w.C if op == "bwd_input" else w.C * w.M
+    flops_per_slice = w.flops_tap_exact() / slices
+    done, spent, err, ref_max = 0, 0.0, 0.0, 0.0
+    while done < slices and (done == 0 or spent * (done + 1) / done < target_seconds):
+        if op == "bwd_input":
+            n, c = int(rng.integers(w.N)), int(rng.integers(w.C))
+            a, b = g32[n:n + 1], np.ascontiguousarray(k32[:, :, c:c + 1])
+            t0 = time.perf_counter()
+            ref = capsconv.conv_bwd_input(a, b, (w.H, w.W), w.stride, w.pad)
+            spent += time.perf_counter() - t0
+            got = gpu_grad[n:n + 1, :, :, c:c + 1].cpu().numpy()
+        else:
+            c, m = int(rng.integers(w.C)), int(rng.integers(w.M))
+            a = np.ascontiguousarray(i32[:, :, :, c:c + 1])
+            b = np.ascontiguousarray(g32[:, :, :, m:m + 1])
+            t0 = time.perf_counter()
+            ref = capsconv.conv_bwd_kernel(a, b, (w.kh, w.kw), w.stride, w.pad)
+            spent += time.perf_counter() - t0
+            got = gpu_grad[:, :, c:c + 1, m:m + 1].cpu().numpy()
+        err = max(err, float(np.abs(got - ref).max()))
+        ref_max = max(ref_max, float(np.abs(ref).max()))
+        done += 1
+    gflops = done * flops_per_slice / spent / 1e9
+    what = "dI[n,:,:,c]" if op == "bwd_input" else "dK[:,:,c,m]"
+    rec = {
+        "value": round(gflops, 3), "unit": "GFLOP/s", "cores": capsconv.threads(),
+        "kind": "oracle",
+        "sample": (f"{done} of {slices} slices {what} of the same workload, fixed seed; "
+                   f"{spent:.1f} s; tap-exact FLOPs of the sample; full workload extrapolates "
+                   f"to {w.flops_tap_exact() / gflops / 1e9:.0f} s"),
+    }
+    return rec, err / max(ref_max, 1e-300)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -75,6 +120,7 @@ def main():
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--path", default="auto",
                     choices=["auto", "mfma", "direct", "mfma-generic", "mfma-tuned16", "mfma-tuned32"])
+    ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_input", "bwd_kernel"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (the known-size kernel that "
@@ -105,15 +151,36 @@ def main():
     else:
         I = torch.from_numpy(i_st).cuda()
         K = torch.from_numpy(k_st).cuda()
-    out = torch.empty(w.out_shape, dtype=torch.float32, device="cuda")
-    need = cc.capscaps_conv_fwd_workspace_bytes(*shape)
+    g32 = None
+    if args.op == "fwd":
+        out = torch.empty(w.out_shape, dtype=torch.float32, device="cuda")
+        need = cc.capscaps_conv_fwd_workspace_bytes(*shape)
+    else:
+        if args.path != "auto":
+            sys.exit("bench.py: --path applies to --op fwd only")
+        g_st, g32 = wl.generate_dout(w)
+        G = (torch.from_numpy(g_st.view(np.int16)).cuda().view(torch.bfloat16)
+             if w.dtype == wl.BF16 else torch.from_numpy(g_st).cuda())
+        if args.op == "bwd_input":
+            out = torch.empty(w.input_shape, dtype=torch.float32, device="cuda")
+            need = cc.capscaps_conv_bwd_input_workspace_bytes(*shape)
+        else:
+            out = torch.empty(w.kernel_shape, dtype=torch.float32, device="cuda")
+            need = cc.capscaps_conv_bwd_kernel_workspace_bytes(*shape)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
 
     def step():
-        rc = cc.capscaps_conv_fwd_path(I.data_ptr(), K.data_ptr(), out.data_ptr(), *shape[:13],
-                                       w.dtype, path, ws.data_ptr(), ws.numel(),
-                                       stream.cuda_stream)
+        if args.op == "fwd":
+            rc = cc.capscaps_conv_fwd_path(I.data_ptr(), K.data_ptr(), out.data_ptr(),
+                                           *shape[:13], w.dtype, path, ws.data_ptr(), ws.numel(),
+                                           stream.cuda_stream)
+        elif args.op == "bwd_input":
+            rc = cc.capscaps_conv_bwd_input(G.data_ptr(), K.data_ptr(), out.data_ptr(), *shape,
+                                            ws.data_ptr(), ws.numel(), stream.cuda_stream)
+        else:
+            rc = cc.capscaps_conv_bwd_kernel(I.data_ptr(), G.data_ptr(), out.data_ptr(), *shape,
+                                             ws.data_ptr(), ws.numel(), stream.cuda_stream)
         if rc != cc.OK:
             sys.exit(f"bench.py: capscaps status {rc}: {cc.capscaps_strerror(rc)}")
 
@@ -145,17 +212,18 @@ def main():
     achieved_tflops = flops_exact / (kernel_ms * 1e-3) / 1e12
     chosen = cc.capscaps_select_path(*shape) if path in (cc.PATH_AUTO, cc.PATH_MFMA) else path
     result = {
-        "metric": "capsule-conv useful GFLOP/s at 1 GPU + % of MFMA roofline",
+        "metric": ("capsule-conv useful GFLOP/s at 1 GPU + % of MFMA roofline" if args.op == "fwd"
+                   else f"capsule-conv {args.op} useful GFLOP/s at 1 GPU"),
         "value": round(value, 1), "unit": "GFLOP/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32" if w.dtype == wl.FP32 else
         f"{dname} in, f32 accumulate", "data": "synthetic",
         "config": {
-            "workload": f"config {args.config}: {w.name}", "N": w.N, "H": w.H, "W": w.W, "C": w.C,
+            "workload": f"config {args.config}: {w.name}", "op": args.op, "N": w.N, "H": w.H, "W": w.W, "C": w.C,
             "M": w.M, "kh": w.kh, "kw": w.kw, "stride": w.stride, "pad": w.pad,
             "capsule": [w.D0, w.D1, w.D2, w.D3],
             "path": {1: "direct", 2: "mfma", 3: "mfma-generic", 4: "mfma-tuned16",
-                     5: "mfma-tuned32"}[chosen],
+                     5: "mfma-tuned32"}[chosen] if args.op == "fwd" else "auto",
             "flops_tap_exact": flops_exact, "flops_nominal": flops_nominal,
             "gflops_nominal": round(flops_nominal / (ms_per_step * 1e-3) / 1e9, 1),
             "compulsory_bytes": w.compulsory_bytes(),
@@ -167,12 +235,15 @@ def main():
         "roofline": {
             "bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": PEAK_TFLOPS[dname],
             "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_TFLOPS[dname], 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if args.op == "fwd" else None,
             "kernel_ms": round(kernel_ms, 4),
         },
     }
     if not args.no_cpu_baseline:
-        rec, err = cpu_baseline(w, i32, k32, out)
+        if args.op == "fwd":
+            rec, err = cpu_baseline(w, i32, k32, out)
+        else:
+            rec, err = cpu_baseline_bwd(w, args.op, i32, k32, g32, out)
         result["cpu_baseline"] = rec
         result["config"]["max_err_vs_oracle_sample"] = err
     print(json.dumps(result), flush=True)

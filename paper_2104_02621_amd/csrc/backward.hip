@@ -11,8 +11,13 @@
 //   dK = conv_fwd(I', G'), I' = I as [C][H][W][N][D0][D2][D1] (images <-> channels, capsules
 //        transposed), G' = G as [H'][W'][N][M][D0][D1][D3] (the output gradient is the window),
 //        same padding; the result [C][kh][kw][M][D0][D2][D3] is permuted into the kernel layout.
-// The layout changes are done by one strided-gather kernel.  Other strides (and non-square
-// windows for dI) take plain gather kernels, one thread per gradient element.
+// A stride s > 1 is the same with the output gradient spread out: G is copied into a zero
+// buffer of the stride-1 output extent (H+2*pad-kh+1 rows), pixel (x,y) at (x*s, y*s).  The
+// contraction then runs over s*s times the needed terms (the zeros), but on the matrix cores.
+// The fully-connected layer's dI (one output pixel, window = image) is a 1x1 convolution whose
+// output channels are the (h,w,c) of the input.  The layout changes are done by one strided
+// copy kernel.  What these forms do not cover (dI with a non-square window or pad > kh-1)
+// takes a plain gather kernel, one thread per element of dI.
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 
@@ -21,11 +26,32 @@
 namespace capscaps {
 namespace {
 
+// Strided copy over a 7-D index space: dst[dst_base + sum c_k*dst_stride_k] =
+// src[src_base + sum c_k*src_stride_k] for every index c (last coordinate fastest).
 struct Permute7 {
-    long long dst_dim[7];     // dense destination extents, last fastest
-    long long src_stride[7];  // source stride (elements) of each destination coordinate
-    long long src_base;       // source offset of destination element 0
+    long long dim[7];
+    long long src_stride[7];
+    long long src_base;
+    long long dst_stride[7];
+    long long dst_base;
 };
+
+// dense destination of extents dim[]: element strides of a row-major array
+Permute7 gather_into_dense(const long long (&dim)[7], const long long (&src_stride)[7],
+                           long long src_base)
+{
+    Permute7 pm{};
+    long long st = 1;
+    for (int k = 6; k >= 0; --k) {
+        pm.dim[k] = dim[k];
+        pm.src_stride[k] = src_stride[k];
+        pm.dst_stride[k] = st;
+        st *= dim[k];
+    }
+    pm.src_base = src_base;
+    pm.dst_base = 0;
+    return pm;
+}
 
 template <typename T>
 __global__ __launch_bounds__(256) void permute7_kernel(const T* __restrict__ src,
@@ -34,21 +60,38 @@ __global__ __launch_bounds__(256) void permute7_kernel(const T* __restrict__ src
 {
     const long long id = (long long)blockIdx.x * 256 + threadIdx.x;
     if (id >= total) return;
-    long long r = id, off = pm.src_base;
+    long long r = id, so = pm.src_base, dofs = pm.dst_base;
 #pragma unroll
     for (int k = 6; k >= 0; --k) {
-        const long long c = r % pm.dst_dim[k];
-        r /= pm.dst_dim[k];
-        off += c * pm.src_stride[k];
+        const long long c = r % pm.dim[k];
+        r /= pm.dim[k];
+        so += c * pm.src_stride[k];
+        dofs += c * pm.dst_stride[k];
     }
-    dst[id] = src[off];
+    dst[dofs] = src[so];
+}
+
+// bytes is a multiple of 16
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint4* __restrict__ dst, size_t chunks)
+{
+    const size_t id = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (id < chunks) dst[id] = make_uint4(0u, 0u, 0u, 0u);
+}
+
+hipError_t launch_fill_zero(void* dst, size_t bytes, hipStream_t stream)
+{
+    const size_t chunks = bytes / 16, blocks = (chunks + 255) / 256;
+    if (blocks == 0) return hipSuccess;
+    if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+    fill_zero_kernel<<<(unsigned)blocks, 256, 0, stream>>>(static_cast<uint4*>(dst), chunks);
+    return hipGetLastError();
 }
 
 hipError_t launch_permute(const void* src, void* dst, const Permute7& pm, int elem_bytes,
                           hipStream_t stream)
 {
     long long total = 1;
-    for (int k = 0; k < 7; ++k) total *= pm.dst_dim[k];
+    for (int k = 0; k < 7; ++k) total *= pm.dim[k];
     const long long blocks = (total + 255) / 256;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (elem_bytes == 4)
@@ -72,7 +115,7 @@ __device__ __forceinline__ float to_f32<__hip_bfloat16>(__hip_bfloat16 v)
     return __bfloat162float(v);
 }
 
-// dI, any stride and window: one thread per element of dI, gather over taps, m and d3.
+// dI, any stride, window and padding: one thread per element of dI, gather over taps, m, d3.
 template <typename T>
 __global__ __launch_bounds__(256) void bwd_input_direct_kernel(const T* __restrict__ G,
                                                                const T* __restrict__ K,
@@ -113,43 +156,6 @@ __global__ __launch_bounds__(256) void bwd_input_direct_kernel(const T* __restri
     dI[e] = acc;
 }
 
-// dK, any stride: one thread per element of dK, gather over images, output pixels and d1.
-template <typename T>
-__global__ __launch_bounds__(256) void bwd_kernel_direct_kernel(const T* __restrict__ I,
-                                                                const T* __restrict__ G,
-                                                                float* __restrict__ dK, ConvShape s,
-                                                                size_t total)
-{
-    const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (e >= total) return;
-    size_t r = e;
-    const int d3 = (int)(r % s.D3); r /= s.D3;
-    const int d2 = (int)(r % s.D2); r /= s.D2;
-    const int d0 = (int)(r % s.D0); r /= s.D0;
-    const int m = (int)(r % s.M);   r /= s.M;
-    const int c = (int)(r % s.C);   r /= s.C;
-    const int q = (int)(r % s.kw);
-    const int p = (int)(r / s.kw);
-    const size_t i_caps = (size_t)s.D0 * s.D1 * s.D2, g_caps = (size_t)s.D0 * s.D1 * s.D3;
-    float acc = 0.f;
-    for (int n = 0; n < s.N; ++n)
-        for (int x = 0; x < s.Ho; ++x) {
-            const int h = x * s.stride + p - s.pad;
-            if (h < 0 || h >= s.H) continue;
-            for (int y = 0; y < s.Wo; ++y) {
-                const int w = y * s.stride + q - s.pad;
-                if (w < 0 || w >= s.W) continue;
-                const T* ip = I + ((((size_t)n * s.H + h) * s.W + w) * s.C + c) * i_caps +
-                              (size_t)d0 * s.D1 * s.D2 + d2;
-                const T* gp = G + ((((size_t)n * s.Ho + x) * s.Wo + y) * s.M + m) * g_caps +
-                              (size_t)d0 * s.D1 * s.D3 + d3;
-                for (int d1 = 0; d1 < s.D1; ++d1)
-                    acc = fmaf(to_f32(ip[(size_t)d1 * s.D2]), to_f32(gp[(size_t)d1 * s.D3]), acc);
-            }
-        }
-    dK[e] = acc;
-}
-
 template <typename Kern, typename... Args>
 hipError_t launch_1d(Kern kern, size_t total, hipStream_t stream, Args... args)
 {
@@ -162,23 +168,39 @@ hipError_t launch_1d(Kern kern, size_t total, hipStream_t stream, Args... args)
 size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 int elem_bytes(const ConvShape& s) { return s.dtype == 0 ? 4 : 2; }
 
-// dI as a forward convolution of G with the flipped, transposed kernel
-bool bwd_input_as_conv(const ConvShape& s)
+// extents of the output gradient spread out to stride 1
+int spread_h(const ConvShape& s) { return s.H + 2 * s.pad - s.kh + 1; }
+int spread_w(const ConvShape& s) { return s.W + 2 * s.pad - s.kw + 1; }
+size_t spread_elems(const ConvShape& s)
 {
-    return s.stride == 1 && s.kh == s.kw && s.pad <= s.kh - 1;
+    return (size_t)s.N * spread_h(s) * spread_w(s) * s.M * s.D0 * s.D1 * s.D3;
 }
+
+// fully-connected layer: one output pixel, the window is the whole unpadded image
+bool bwd_input_as_fc(const ConvShape& s)
+{
+    return s.Ho == 1 && s.Wo == 1 && s.pad == 0 && s.kh == s.H && s.kw == s.W;
+}
+ConvShape bwd_input_fc_shape(const ConvShape& s)
+{
+    // input G [N][1][1][M][D0][D1][D3], kernel [1][1][M][(h,w,c)][D0][D3][D2] -> dI [N][(h,w,c)][D0][D1][D2]
+    return ConvShape{s.N, 1, 1, s.M, s.kh * s.kw * s.C, 1, 1, 1, 0, s.D0, s.D1, s.D3, s.D2, 1, 1,
+                     s.dtype};
+}
+// dI as a forward convolution of the (spread-out) G with the flipped, transposed kernel
+bool bwd_input_as_conv(const ConvShape& s) { return s.kh == s.kw && s.pad <= s.kh - 1; }
 ConvShape bwd_input_conv_shape(const ConvShape& s)
 {
-    // input G [N][Ho][Wo][M][D0][D1][D3], kernel K' [kh][kw][M][C][D0][D3][D2] -> dI [N][H][W][C][D0][D1][D2]
-    return ConvShape{s.N, s.Ho, s.Wo, s.M, s.C, s.kh, s.kw, 1, s.kh - 1 - s.pad,
+    // input Gs [N][Hs][Ws][M][D0][D1][D3], kernel K' [kh][kw][M][C][D0][D3][D2] -> dI [N][H][W][C][D0][D1][D2]
+    return ConvShape{s.N, spread_h(s), spread_w(s), s.M, s.C, s.kh, s.kw, 1, s.kh - 1 - s.pad,
                      s.D0, s.D1, s.D3, s.D2, s.H, s.W, s.dtype};
 }
-// dK as a forward convolution of the re-laid-out input with the output gradient as the window
-bool bwd_kernel_as_conv(const ConvShape& s) { return s.stride == 1; }
+// dK as a forward convolution of the re-laid-out input with the (spread-out) output gradient
+// as the window
 ConvShape bwd_kernel_conv_shape(const ConvShape& s)
 {
-    // input I' [C][H][W][N][D0][D2][D1], kernel G' [Ho][Wo][N][M][D0][D1][D3] -> [C][kh][kw][M][D0][D2][D3]
-    return ConvShape{s.C, s.H, s.W, s.N, s.M, s.Ho, s.Wo, 1, s.pad,
+    // input I' [C][H][W][N][D0][D2][D1], kernel G' [Hs][Ws][N][M][D0][D1][D3] -> [C][kh][kw][M][D0][D2][D3]
+    return ConvShape{s.C, s.H, s.W, s.N, s.M, spread_h(s), spread_w(s), 1, s.pad,
                      s.D0, s.D2, s.D1, s.D3, s.kh, s.kw, s.dtype};
 }
 
@@ -186,15 +208,16 @@ ConvShape bwd_kernel_conv_shape(const ConvShape& s)
 
 size_t bwd_input_workspace_bytes(const ConvShape& s)
 {
+    const size_t kbytes = align256(s.kernel_elems() * elem_bytes(s));
+    if (bwd_input_as_fc(s)) return kbytes + forward_workspace_bytes(bwd_input_fc_shape(s));
     if (!bwd_input_as_conv(s)) return 0;
-    return align256(s.kernel_elems() * elem_bytes(s)) +
-           forward_workspace_bytes(bwd_input_conv_shape(s));
+    const size_t gbytes = s.stride > 1 ? align256(spread_elems(s) * elem_bytes(s)) : 0;
+    return kbytes + gbytes + forward_workspace_bytes(bwd_input_conv_shape(s));
 }
 
 size_t bwd_kernel_workspace_bytes(const ConvShape& s)
 {
-    if (!bwd_kernel_as_conv(s)) return 0;
-    return align256(s.in_elems() * elem_bytes(s)) + align256(s.out_elems() * elem_bytes(s)) +
+    return align256(s.in_elems() * elem_bytes(s)) + align256(spread_elems(s) * elem_bytes(s)) +
            align256(s.kernel_elems() * sizeof(float)) +
            forward_workspace_bytes(bwd_kernel_conv_shape(s));
 }
@@ -202,19 +225,55 @@ size_t bwd_kernel_workspace_bytes(const ConvShape& s)
 int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, float* din,
                      void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
+    const int eb = elem_bytes(s);
+    const long long sD3 = 1, sD2 = s.D3, sD0 = (long long)s.D2 * s.D3, sM = sD0 * s.D0,
+                    sC = sM * s.M, sQ = sC * s.C, sP = sQ * s.kw;
+    if (bwd_input_as_fc(s)) {
+        char* ws = static_cast<char*>(workspace);
+        const size_t used = align256(s.kernel_elems() * eb);
+        // K2[m][(h,w,c)][d0][d3][d2] = K[h][w][c][m][d0][d2][d3]; (h,w,c) is one index of stride sC
+        const Permute7 pm = gather_into_dense(
+            {1, 1, s.M, (long long)s.kh * s.kw * s.C, s.D0, s.D3, s.D2},
+            {0, 0, sM, sC, sD0, sD3, sD2}, 0);
+        hipError_t err = launch_permute(kernel, ws, pm, eb, stream);
+        if (err != hipSuccess) return status_from_hip(err);
+        return forward_auto(bwd_input_fc_shape(s), dout, ws, din, ws + used,
+                            workspace_bytes - used, stream);
+    }
     if (bwd_input_as_conv(s)) {
         char* ws = static_cast<char*>(workspace);
         void* kflip = ws;
-        const size_t used = align256(s.kernel_elems() * elem_bytes(s));
+        size_t used = align256(s.kernel_elems() * eb);
         // K'[p'][q'][m][c][d0][d3][d2] = K[kh-1-p'][kw-1-q'][c][m][d0][d2][d3]
-        const long long sD3 = 1, sD2 = s.D3, sD0 = (long long)s.D2 * s.D3, sM = sD0 * s.D0,
-                        sC = sM * s.M, sQ = sC * s.C, sP = sQ * s.kw;
-        Permute7 pm{{s.kh, s.kw, s.M, s.C, s.D0, s.D3, s.D2},
-                    {-sP, -sQ, sM, sC, sD0, sD3, sD2},
-                    (long long)(s.kh - 1) * sP + (long long)(s.kw - 1) * sQ};
-        hipError_t err = launch_permute(kernel, kflip, pm, elem_bytes(s), stream);
+        const Permute7 pm = gather_into_dense({s.kh, s.kw, s.M, s.C, s.D0, s.D3, s.D2},
+                                              {-sP, -sQ, sM, sC, sD0, sD3, sD2},
+                                              (long long)(s.kh - 1) * sP + (long long)(s.kw - 1) * sQ);
+        hipError_t err = launch_permute(kernel, kflip, pm, eb, stream);
         if (err != hipSuccess) return status_from_hip(err);
-        return forward_auto(bwd_input_conv_shape(s), dout, kflip, din, ws + used,
+        const void* g = dout;
+        if (s.stride > 1) {
+            // Gs[n][x*s][y*s] = G[n][x][y], zero elsewhere; a pixel (M capsules) moves as one run
+            void* gs = ws + used;
+            const size_t gbytes = align256(spread_elems(s) * eb);
+            used += gbytes;
+            err = launch_fill_zero(gs, gbytes, stream);
+            if (err != hipSuccess) return status_from_hip(err);
+            const long long pix = (long long)s.M * s.D0 * s.D1 * s.D3;
+            Permute7 sp{};
+            const long long dim[7] = {1, 1, 1, s.N, s.Ho, s.Wo, pix};
+            const long long ss[7] = {0, 0, 0, (long long)s.Ho * s.Wo * pix, s.Wo * pix, pix, 1};
+            const long long ds[7] = {0, 0, 0, (long long)spread_h(s) * spread_w(s) * pix,
+                                     (long long)s.stride * spread_w(s) * pix, s.stride * pix, 1};
+            for (int k = 0; k < 7; ++k) {
+                sp.dim[k] = dim[k];
+                sp.src_stride[k] = ss[k];
+                sp.dst_stride[k] = ds[k];
+            }
+            err = launch_permute(dout, gs, sp, eb, stream);
+            if (err != hipSuccess) return status_from_hip(err);
+            g = gs;
+        }
+        return forward_auto(bwd_input_conv_shape(s), g, kflip, din, ws + used,
                             workspace_bytes - used, stream);
     }
     const size_t total = s.in_elems();
@@ -234,53 +293,49 @@ int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, f
 int launch_bwd_kernel(const ConvShape& s, const void* input, const void* dout, float* dkernel,
                       void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
-    if (bwd_kernel_as_conv(s)) {
-        char* ws = static_cast<char*>(workspace);
-        void* in_t = ws;
-        size_t used = align256(s.in_elems() * elem_bytes(s));
-        void* g_t = ws + used;
-        used += align256(s.out_elems() * elem_bytes(s));
-        float* dk_t = reinterpret_cast<float*>(ws + used);
-        used += align256(s.kernel_elems() * sizeof(float));
-        // I'[c][h][w][n][d0][d2][d1] = I[n][h][w][c][d0][d1][d2]
-        {
-            const long long sD2 = 1, sD1 = s.D2, sD0 = (long long)s.D1 * s.D2, sC = sD0 * s.D0,
-                            sW = sC * s.C, sH = sW * s.W, sN = sH * s.H;
-            Permute7 pm{{s.C, s.H, s.W, s.N, s.D0, s.D2, s.D1}, {sC, sH, sW, sN, sD0, sD2, sD1}, 0};
-            hipError_t err = launch_permute(input, in_t, pm, elem_bytes(s), stream);
-            if (err != hipSuccess) return status_from_hip(err);
-        }
-        // G'[x][y][n][m][d0][d1][d3] = G[n][x][y][m][d0][d1][d3]
-        {
-            const long long caps = (long long)s.D0 * s.D1 * s.D3, sM = caps, sY = sM * s.M,
-                            sX = sY * s.Wo, sN = sX * s.Ho;
-            Permute7 pm{{s.Ho, s.Wo, s.N, s.M, s.D0, s.D1, s.D3},
-                        {sX, sY, sN, sM, (long long)s.D1 * s.D3, s.D3, 1}, 0};
-            hipError_t err = launch_permute(dout, g_t, pm, elem_bytes(s), stream);
-            if (err != hipSuccess) return status_from_hip(err);
-        }
-        const int rc = forward_auto(bwd_kernel_conv_shape(s), in_t, g_t, dk_t, ws + used,
-                                    workspace_bytes - used, stream);
-        if (rc != 0) return rc;
-        // dK[p][q][c][m][d0][d2][d3] = dK'[c][p][q][m][d0][d2][d3]
-        const long long caps = (long long)s.D0 * s.D2 * s.D3, sM = caps, sQ = sM * s.M,
-                        sP = sQ * s.kw, sC = sP * s.kh;
-        Permute7 pm{{s.kh, s.kw, s.C, s.M, s.D0, s.D2, s.D3},
-                    {sP, sQ, sC, sM, (long long)s.D2 * s.D3, s.D3, 1}, 0};
-        return status_from_hip(launch_permute(dk_t, dkernel, pm, 4, stream));
+    const int eb = elem_bytes(s);
+    char* ws = static_cast<char*>(workspace);
+    void* in_t = ws;
+    size_t used = align256(s.in_elems() * eb);
+    void* g_t = ws + used;
+    const size_t gbytes = align256(spread_elems(s) * eb);
+    used += gbytes;
+    float* dk_t = reinterpret_cast<float*>(ws + used);
+    used += align256(s.kernel_elems() * sizeof(float));
+    // I'[c][h][w][n][d0][d2][d1] = I[n][h][w][c][d0][d1][d2]
+    {
+        const long long sD2 = 1, sD1 = s.D2, sD0 = (long long)s.D1 * s.D2, sC = sD0 * s.D0,
+                        sW = sC * s.C, sH = sW * s.W, sN = sH * s.H;
+        const Permute7 pm = gather_into_dense({s.C, s.H, s.W, s.N, s.D0, s.D2, s.D1},
+                                              {sC, sH, sW, sN, sD0, sD2, sD1}, 0);
+        hipError_t err = launch_permute(input, in_t, pm, eb, stream);
+        if (err != hipSuccess) return status_from_hip(err);
     }
-    const size_t total = s.kernel_elems();
-    hipError_t err;
-    if (s.dtype == 0)
-        err = launch_1d(bwd_kernel_direct_kernel<float>, total, stream, (const float*)input,
-                        (const float*)dout, dkernel, s);
-    else if (s.dtype == 1)
-        err = launch_1d(bwd_kernel_direct_kernel<__hip_bfloat16>, total, stream,
-                        (const __hip_bfloat16*)input, (const __hip_bfloat16*)dout, dkernel, s);
-    else
-        err = launch_1d(bwd_kernel_direct_kernel<__half>, total, stream, (const __half*)input,
-                        (const __half*)dout, dkernel, s);
-    return status_from_hip(err);
+    // G'[x*s][y*s][n][m][d0][d1][d3] = G[n][x][y][m][d0][d1][d3], zero elsewhere
+    {
+        if (s.stride > 1) {
+            hipError_t err = launch_fill_zero(g_t, gbytes, stream);
+            if (err != hipSuccess) return status_from_hip(err);
+        }
+        const long long caps = (long long)s.D0 * s.D1 * s.D3, sM = caps, sY = sM * s.M,
+                        sX = sY * s.Wo, sN = sX * s.Ho;
+        Permute7 pm = gather_into_dense({s.Ho, s.Wo, s.N, s.M, s.D0, s.D1, s.D3},
+                                        {sX, sY, sN, sM, (long long)s.D1 * s.D3, s.D3, 1}, 0);
+        const long long pix = (long long)s.N * s.M * caps;  // one window tap of G'
+        pm.dst_stride[0] = (long long)s.stride * spread_w(s) * pix;
+        pm.dst_stride[1] = (long long)s.stride * pix;
+        hipError_t err = launch_permute(dout, g_t, pm, eb, stream);
+        if (err != hipSuccess) return status_from_hip(err);
+    }
+    const int rc = forward_auto(bwd_kernel_conv_shape(s), in_t, g_t, dk_t, ws + used,
+                                workspace_bytes - used, stream);
+    if (rc != 0) return rc;
+    // dK[p][q][c][m][d0][d2][d3] = dK'[c][p][q][m][d0][d2][d3]
+    const long long caps = (long long)s.D0 * s.D2 * s.D3, sM = caps, sQ = sM * s.M,
+                    sP = sQ * s.kw, sC = sP * s.kh;
+    const Permute7 pm = gather_into_dense({s.kh, s.kw, s.C, s.M, s.D0, s.D2, s.D3},
+                                          {sP, sQ, sC, sM, (long long)s.D2 * s.D3, s.D3, 1}, 0);
+    return status_from_hip(launch_permute(dk_t, dkernel, pm, 4, stream));
 }
 
 }  // namespace capscaps
