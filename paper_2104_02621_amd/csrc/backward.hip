@@ -21,7 +21,7 @@
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 
-#include "conv_shape.h"
+#include "igemm_common.h"
 
 namespace capscaps {
 namespace {
@@ -217,6 +217,7 @@ size_t bwd_input_workspace_bytes(const ConvShape& s)
 
 size_t bwd_kernel_workspace_bytes(const ConvShape& s)
 {
+    if (wgrad16_eligible(s)) return wgrad16_workspace_bytes(s);
     return align256(s.in_elems() * elem_bytes(s)) + align256(spread_elems(s) * elem_bytes(s)) +
            align256(s.kernel_elems() * sizeof(float)) +
            forward_workspace_bytes(bwd_kernel_conv_shape(s));
@@ -293,6 +294,8 @@ int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, f
 int launch_bwd_kernel(const ConvShape& s, const void* input, const void* dout, float* dkernel,
                       void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
+    if (wgrad16_eligible(s))
+        return status_from_hip(launch_wgrad16(s, input, dout, dkernel, workspace, stream));
     const int eb = elem_bytes(s);
     char* ws = static_cast<char*>(workspace);
     void* in_t = ws;

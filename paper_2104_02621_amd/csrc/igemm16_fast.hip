@@ -34,59 +34,11 @@
 //                bytes per 32 lanes.
 #include <hip/hip_runtime.h>
 
-#include <type_traits>
-#include <utility>
-
 #include "igemm_common.h"
+#include "lds_dma.h"
 
 namespace capscaps {
 namespace {
-
-typedef int rsrc_t __attribute__((ext_vector_type(4)));  // raw buffer descriptor (4 SGPRs)
-
-// compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(<N-1>)
-template <typename F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
-{
-    (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
-}
-
-// Raw buffer descriptor: 48-bit base, stride 0, `bytes` addressable, dword data format.
-// Offsets at or beyond `bytes` read as zero.
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes)
-{
-    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
-    rsrc_t r;
-    r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)(a & 0xffffffffu));
-    r[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)((a >> 32) & 0xffffu));
-    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
-    r[3] = 0x00020000;
-    return r;
-}
-
-// One wave-wide copy global -> LDS: lane i moves the 16 bytes at base + voff_i + soff_a + soff_b
-// to LDS byte address lds_base + LDS_IMM + 16*i.  The sum of the offsets is range-checked
-// against the descriptor: at or beyond its size the lane stores zeros.  Asynchronous;
-// completion is counted in vmcnt.  Inline assembly on purpose: the waits are exactly the
-// s_waitcnt vmcnt(n) placed by hand in the K loop (the compiler would drain all such copies
-// before any later LDS read, which would undo the multi-stage prefetch).  The scalar add
-// between the M0 write and the copy is the wait state that sequence needs.
-template <int LDS_IMM>
-__device__ __forceinline__ void copy_to_lds_16B(rsrc_t rs, unsigned lds_base, unsigned voff,
-                                                int soff_a, int soff_b)
-{
-    int tmp;
-    asm volatile(
-        "s_add_u32 m0, %1, %5\n\ts_add_u32 %0, %3, %4\n\tbuffer_load_dwordx4 %2, %6, %0 offen lds"
-        : "=&s"(tmp)
-        : "s"(lds_base), "v"(voff), "s"(soff_a), "s"(soff_b), "i"(LDS_IMM), "s"(rs)
-        : "memory", "scc");
-}
 
 // Input-side block geometry.  A block is the 64 chunks one wave-wide copy moves.  Either a
 // pixel's stage data fills one or more blocks (PPB = 1, BPP blocks per pixel, each holding CPB

@@ -111,5 +111,10 @@ int igemm16_fast_kgroup(const ConvShape& s);      // chunks per K stage (repack 
 hipError_t launch_igemm16_fast(const IgemmParams& P, long long blocks, int dtype,
                                hipStream_t stream);
 
+// Kernel gradient on the matrix cores for 16-bit types, D1 in {8, 16} (wgrad16.hip).
+bool wgrad16_eligible(const ConvShape& s);
+size_t wgrad16_workspace_bytes(const ConvShape& s);
+hipError_t launch_wgrad16(const ConvShape& s, const void* input, const void* dout, float* dkernel,
+                          void* workspace, hipStream_t stream);
 
 }  // namespace capscaps

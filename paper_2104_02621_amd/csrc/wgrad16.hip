@@ -1,0 +1,515 @@
+// Kernel gradient of the capsule convolution (the K_diff result of the paper's Algorithm 4,
+// taken as the derivative of Algorithm 2's sum) on the matrix cores, for 16-bit element types
+// and D1 in {8, 16}.  With G = dL/dO, per window tap (p,q) and leading capsule index d0 it is
+// one GEMM
+//
+//     rows     r = (c, d2)                                           C*D2 of them
+//     columns  j = (m, d3)                                           M*D3 of them
+//     K index  k = (n, x, y, d1)   over the output pixels whose tap (p,q) lies inside the image
+//
+//     dK[p,q,c,m,d0,d2,d3] = sum_k I[n, x*s+p-pad, y*s+q-pad, c, d0, d1, d2] * G[n, x, y, m, d0, d1, d3]
+//
+// In both tensors the contracted index d1 is the slower one of a capsule, so a pre-pass writes
+// capsule-transposed copies It[n][h][w][c][d0][d2][d1] and Gt[n][x][y][m][d0][d3][d1]: the D1
+// values a matrix instruction wants side by side are then 16 or 32 contiguous bytes, and for
+// one pixel the 256 rows (or columns) of a tile are one contiguous run (D0 = 1) of It (Gt).
+//
+// A workgroup owns one 256 x 256 tile of one tap and a range of images (the K loop is split
+// over images when the tiles alone do not fill the chip; partial sums go to scratch and are
+// added in a fixed order by a second kernel).  It walks the valid output pixels of its tap, a
+// rectangle per image, so no multiplication by padding zeros is done and any stride costs the
+// same.  A K stage is 32 contracted values = 32/D1 pixels; per stage each wave copies 64 rows
+// and 64 columns (4 x 1 KB each) straight into LDS with buffer loads whose scalar offset is
+// the pixel.  The K loop has the shape of the tuned forward kernel's: a ring of 4 LDS stages,
+// operand fragments double-buffered in registers, one barrier per stage, copies and the scalar
+// pixel walk dealt out between the MFMAs.
+//
+// LDS stage: [side: It rows, Gt columns][chunk 0..3][row 0..255][16 bytes]; chunk kc holds d1
+// values (kc % (D1/8))*8 .. +7 of pixel kc / (D1/8) of the stage.  Operand reads are 512
+// contiguous bytes per 32 lanes.
+#include <hip/hip_runtime.h>
+
+#include "igemm_common.h"
+#include "lds_dma.h"
+
+namespace capscaps {
+namespace {
+
+struct WgradParams {
+    const void* it;  // capsule-transposed input
+    const void* gt;  // capsule-transposed output gradient
+    float* out;      // dK, or partial sums [split][kernel elements]
+    int N, H, W, C, M, kw, stride, pad, D0, D2, D3, Ho, Wo;
+    int rows, cols;  // C*D2, M*D3
+    int row_tiles, col_tiles, ntaps;
+    int tiles;       // ntaps * D0 * row_tiles * col_tiles
+    int nsplit, imgs_per_split;
+    long long items;      // tiles * nsplit = workgroups
+    long long out_elems;  // elements of dK
+    long long it_img_bytes, gt_img_bytes;
+};
+
+// dst[x][b][a] = src[x][a][b] for `nmat` matrices of A x B 16-bit elements, A % 8 == 0.
+// One thread per 16 destination bytes.
+__global__ __launch_bounds__(256) void transpose_caps_kernel(const unsigned short* __restrict__ src,
+                                                             unsigned short* __restrict__ dst,
+                                                             int A, int B, size_t chunks)
+{
+    const size_t id = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= chunks) return;
+    const int a8n = A / 8;
+    const int a8 = (int)(id % a8n);
+    const size_t rest = id / a8n;
+    const int b = (int)(rest % B);
+    const size_t mat = rest / B;
+    const unsigned short* s = src + (mat * A + (size_t)a8 * 8) * B + b;
+    unsigned short v[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = s[(size_t)e * B];
+    chunk_t out;
+    __builtin_memcpy(&out, v, 16);
+    reinterpret_cast<chunk_t*>(dst)[id] = out;
+}
+
+template <typename Tag, int D1>
+__global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
+{
+    constexpr int KCH = 4, NB = 4;
+    constexpr int D1C = D1 / 8;     // chunks per pixel and row
+    constexpr int PPS = KCH / D1C;  // pixels per stage
+    constexpr int NWM = 2, NWN = 2;
+    constexpr int BM = 256, BN = 256;
+    constexpr int SIDE_BYTES = KCH * BM * 16, STAGE_BYTES = 2 * SIDE_BYTES;
+    constexpr int WM = BM / NWM, WN = BN / NWN, TM = WM / 32, TN = WN / 32;
+    constexpr int NMMA = TM * TN;
+    constexpr int NFRAG = TN + TM;
+    constexpr int NCOPY = 2 * KCH;  // copies per wave and stage
+    constexpr int OOB = (int)0x80000000u;
+    constexpr int KEEP = (NB - 2) * NCOPY;
+    static_assert(KEEP < 64, "vmcnt is a 6-bit counter");
+    constexpr int VMCNT_KEEP = 0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14);
+    static_assert(D1 == 8 || D1 == 16, "D1");
+    static_assert(NMMA == 16 && KCH == 4, "the schedule below is written for this shape");
+
+    extern __shared__ char smem[];
+
+    // ---- which item.  Consecutive workgroups go to the 8 XCDs in turn; each XCD is handed a
+    // contiguous range of items, ordered image range slowest, then tap, then tile, so the
+    // workgroups resident on one XCD at a time read the same pixels of It and Gt through its L2.
+    long long item = blockIdx.x;
+    {
+        const long long per = P.items / 8;
+        if (item < per * 8) item = (item % 8) * per + item / 8;
+    }
+    const int split = (int)(item / P.tiles);
+    int rest = (int)(item % P.tiles);
+    const int col_tile = rest % P.col_tiles;
+    rest /= P.col_tiles;
+    const int row_tile = rest % P.row_tiles;
+    rest /= P.row_tiles;
+    const int tap = rest % P.ntaps;
+    const int d0 = rest / P.ntaps;
+    const int tp = tap / P.kw, tq = tap - tp * P.kw;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int wm = wave % NWM, wn = wave / NWM;
+    const int h = lane >> 5, lr = lane & 31;
+
+    // ---- the pixels of this item: images [n0, n1), and per image the rectangle of output
+    // pixels (x, y) whose tap (tp, tq) reads a real input pixel
+    const int n0 = split * P.imgs_per_split;
+    const int n1 = n0 + P.imgs_per_split < P.N ? n0 + P.imgs_per_split : P.N;
+    const int s = P.stride;
+    int nx, ny, x_lo, y_lo;
+    {
+        const int tx = P.pad - tp, ty = P.pad - tq;  // need x*s >= tx and x*s <= H-1+tx
+        x_lo = tx > 0 ? (tx + s - 1) / s : 0;
+        y_lo = ty > 0 ? (ty + s - 1) / s : 0;
+        const int hx = P.H - 1 + tx, hy = P.W - 1 + ty;
+        int x_hi = hx >= 0 ? hx / s : -1, y_hi = hy >= 0 ? hy / s : -1;
+        if (x_hi > P.Ho - 1) x_hi = P.Ho - 1;
+        if (y_hi > P.Wo - 1) y_hi = P.Wo - 1;
+        nx = x_hi - x_lo + 1;
+        ny = y_hi - y_lo + 1;
+        if (nx <= 0 || ny <= 0) nx = ny = 0;
+    }
+    const int npix = (n1 - n0) * nx * ny;
+    const int ipix = P.C * P.D0 * P.D2 * D1 * 2;  // bytes per pixel of It / Gt
+    const int gpix = P.M * P.D0 * P.D3 * D1 * 2;
+    const int i_step = s * ipix, g_step = gpix;
+    // from the last pixel of a rectangle row to the first of the next row; from there, after
+    // the last row, on to the first row of the next image
+    const int i_rowjump = (s * P.W - (ny - 1) * s) * ipix, g_rowjump = (P.Wo - (ny - 1)) * gpix;
+    const int i_imgjump = (P.H * P.W - nx * s * P.W) * ipix, g_imgjump = (P.Ho * P.Wo - nx * P.Wo) * gpix;
+    // two walkers over the same pixel sequence, one per tensor (the It copies of a stage go out
+    // one k-step before its Gt copies, so each side keeps its own position)
+    int i_cur = ((x_lo * s - (P.pad - tp)) * P.W + (y_lo * s - (P.pad - tq))) * ipix;
+    int g_cur = (x_lo * P.Wo + y_lo) * gpix;
+    int i_left = npix, i_yl = ny, i_xl = nx;
+    int g_left = npix, g_yl = ny, g_xl = nx;
+
+    const char* it_base = static_cast<const char*>(P.it) + (long long)n0 * P.it_img_bytes;
+    const char* gt_base = static_cast<const char*>(P.gt) + (long long)n0 * P.gt_img_bytes;
+    const rsrc_t rs_it = make_rsrc(it_base, (unsigned)((n1 - n0) * P.it_img_bytes));
+    const rsrc_t rs_gt = make_rsrc(gt_base, (unsigned)((n1 - n0) * P.gt_img_bytes));
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+    // this wave copies rows (and columns) wave*64 .. +63 of the tile, all chunks
+    const unsigned lds_a = __builtin_amdgcn_readfirstlane((int)(lds0 + wave * 1024));
+    const unsigned lds_b = lds_a + SIDE_BYTES;
+
+    // ---- per-lane constants: byte offset of the lane's row (column) within a pixel, or the
+    // out-of-range mark for rows (columns) past the end: those copy zeros
+    unsigned a_voff, b_voff;
+    {
+        const int R = row_tile * BM + wave * 64 + lane;
+        const int c = R / P.D2, d2 = R - c * P.D2;
+        a_voff = R < P.rows ? (unsigned)((((c * P.D0 + d0) * P.D2 + d2) * D1) * 2) : (unsigned)OOB;
+        const int J = col_tile * BN + wave * 64 + lane;
+        const int m = J / P.D3, d3 = J - m * P.D3;
+        b_voff = J < P.cols ? (unsigned)((((m * P.D0 + d0) * P.D3 + d3) * D1) * 2) : (unsigned)OOB;
+    }
+    const unsigned a_rd = (unsigned)((h * BM + wm * WM + lr) * 16);
+    const unsigned b_rd = (unsigned)(SIDE_BYTES + (h * BN + wn * WN + lr) * 16);
+
+    float16v acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    const int nstages = (npix + PPS - 1) / PPS;
+    const int nstages_pad = (nstages + NB - 1) / NB * NB;  // surplus stages contract zeros
+
+    // Pixel offsets of the stage whose It copies go out next (a_soff) and of the stage whose
+    // Gt copies go out next (g_soff).  All scalar.
+    int a_soff[PPS], g_soff[PPS];
+    // One pixel step of a walker, in three branch-free pieces that the main loop puts into
+    // different gaps between MFMAs: (0) record the walker's pixel for slot j of the stage, or
+    // past the last pixel the out-of-range mark (zero fill, touches no memory); (1) count down
+    // the rectangle row and pick the step; (2) apply it, and at the end of an image the jump to
+    // the next one.
+    int i_inc = 0, g_inc = 0;
+    // (the empty volatile statements keep each piece's scalar arithmetic inside its gap, as
+    // for the MFMAs below)
+    auto walk_i = [&](int j, int piece) {
+        if (piece == 0) {
+            asm volatile("" : "+s"(i_left), "+s"(i_cur));
+            a_soff[j] = i_left > 0 ? i_cur : OOB;
+            --i_left;
+            asm volatile("" : "+s"(i_left), "+s"(a_soff[j]));
+        } else if (piece == 1) {
+            asm volatile("" : "+s"(i_yl), "+s"(i_xl));
+            --i_yl;
+            const bool row_end = i_yl == 0;
+            i_inc = row_end ? i_rowjump : i_step;
+            i_yl = row_end ? ny : i_yl;
+            i_xl -= row_end ? 1 : 0;
+            asm volatile("" : "+s"(i_yl), "+s"(i_xl), "+s"(i_inc));
+        } else {
+            asm volatile("" : "+s"(i_xl), "+s"(i_cur), "+s"(i_inc));
+            const bool img_end = i_xl == 0;
+            i_cur += i_inc;
+            i_cur += img_end ? i_imgjump : 0;
+            i_xl = img_end ? nx : i_xl;
+            asm volatile("" : "+s"(i_xl), "+s"(i_cur));
+        }
+    };
+    auto walk_g = [&](int j, int piece) {
+        if (piece == 0) {
+            asm volatile("" : "+s"(g_left), "+s"(g_cur));
+            g_soff[j] = g_left > 0 ? g_cur : OOB;
+            --g_left;
+            asm volatile("" : "+s"(g_left), "+s"(g_soff[j]));
+        } else if (piece == 1) {
+            asm volatile("" : "+s"(g_yl), "+s"(g_xl));
+            --g_yl;
+            const bool row_end = g_yl == 0;
+            g_inc = row_end ? g_rowjump : g_step;
+            g_yl = row_end ? ny : g_yl;
+            g_xl -= row_end ? 1 : 0;
+            asm volatile("" : "+s"(g_yl), "+s"(g_xl), "+s"(g_inc));
+        } else {
+            asm volatile("" : "+s"(g_xl), "+s"(g_cur), "+s"(g_inc));
+            const bool img_end = g_xl == 0;
+            g_cur += g_inc;
+            g_cur += img_end ? g_imgjump : 0;
+            g_xl = img_end ? nx : g_xl;
+            asm volatile("" : "+s"(g_xl), "+s"(g_cur));
+        }
+    };
+    auto copy_a = [&](auto SLOT, auto KC) {
+        constexpr int slot = decltype(SLOT)::value, kc = decltype(KC)::value;
+        copy_to_lds_16B<slot * STAGE_BYTES + kc * BM * 16>(rs_it, lds_a, a_voff, a_soff[kc / D1C],
+                                                           (kc % D1C) * 16);
+    };
+    auto copy_b = [&](auto SLOT, auto KC) {
+        constexpr int slot = decltype(SLOT)::value, kc = decltype(KC)::value;
+        copy_to_lds_16B<slot * STAGE_BYTES + kc * BN * 16>(rs_gt, lds_b, b_voff, g_soff[kc / D1C],
+                                                           (kc % D1C) * 16);
+    };
+    // operand fragment f of k-step t from ring slot: f < TN column side (Gt), else row side (It)
+    auto read_frag = [&](int slot, int t, int f) -> chunk_t {
+        const char* stage = smem + slot * STAGE_BYTES;
+        if (f < TN)
+            return *reinterpret_cast<const chunk_t*>(stage + b_rd + (2 * t * BN + f * 32) * 16);
+        return *reinterpret_cast<const chunk_t*>(stage + a_rd + (2 * t * BM + (f - TN) * 32) * 16);
+    };
+
+    // An MFMA has no side effect the compiler must order, so by itself it may drift away from
+    // the gap it is written in; the two empty volatile statements around it (which do keep their
+    // order among the copies and scheduling barriers) hold its accumulator, and so the MFMA,
+    // in place.
+    auto pinned_mma = [&](const chunk_t& ka, const chunk_t& ib, float16v& c) {
+        asm volatile("" : "+a"(c));
+        Mma<Tag>::run(ka, ib, c);
+        asm volatile("" : "+a"(c));
+    };
+
+    // ---- prologue: stages 0..NB-2 whole and the It side of stage NB-1
+    static_for<NB - 1>([&](auto S0) {
+#pragma unroll
+        for (int j = 0; j < PPS; ++j)
+#pragma unroll
+            for (int piece = 0; piece < 3; ++piece) {
+                walk_i(j, piece);
+                walk_g(j, piece);
+            }
+        static_for<KCH>([&](auto KC) { copy_a(S0, KC); });
+        static_for<KCH>([&](auto KC) { copy_b(S0, KC); });
+    });
+#pragma unroll
+    for (int j = 0; j < PPS; ++j)
+#pragma unroll
+        for (int piece = 0; piece < 3; ++piece) {
+            walk_i(j, piece);
+            walk_g(j, piece);
+        }
+    static_for<KCH>([&](auto KC) { copy_a(std::integral_constant<int, NB - 1>{}, KC); });
+    {
+        constexpr int keep0 = (NB - 2) * NCOPY + KCH;
+        static_assert(keep0 < 64, "vmcnt is a 6-bit counter");
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (keep0 & 15) | ((keep0 >> 4) << 14));
+    }
+    __syncthreads();
+    chunk_t frag[2][NFRAG];
+#pragma unroll
+    for (int f = 0; f < NFRAG; ++f) frag[0][f] = read_frag(0, 0, f);
+
+    // ---- main loop, unrolled over the ring so that slots are compile-time constants.
+    // Iteration st: k-step 0 issues the Gt copies of stage st+NB-1 (one after every fourth
+    // MFMA) and walks the It pixels of stage st+NB; after the barrier, k-step 1 issues the It
+    // copies of stage st+NB into the slot just released and walks the Gt pixels of that stage.
+    // gaps for the 3*PPS walker pieces of a k-step: those without a copy, late ones first
+    constexpr int WALK_GAP[12] = {8, 9, 11, 12, 13, 15, 0, 1, 3, 4, 5, 7};
+    constexpr int NPIECE = 3 * PPS;
+    // the pieces must run in order: sort the first NPIECE gaps
+    constexpr auto piece_gap = [](int q) {
+        int g[12] = {0};
+        for (int k = 0; k < NPIECE; ++k) g[k] = WALK_GAP[k];
+        for (int a = 0; a < NPIECE; ++a)
+            for (int b = a + 1; b < NPIECE; ++b)
+                if (g[b] < g[a]) {
+                    const int t = g[a];
+                    g[a] = g[b];
+                    g[b] = t;
+                }
+        return g[q];
+    };
+    for (int st = 0; st < nstages_pad; st += NB) {
+        static_for<NB>([&](auto SLOT) {
+            constexpr int slot = decltype(SLOT)::value;
+            constexpr int slot_next = (slot + 1) % NB;
+            typedef std::integral_constant<int, (slot + NB - 1) % NB> SlotPrev;
+            static_for<NMMA>([&](auto I) {
+                constexpr int i = decltype(I)::value;
+                pinned_mma(frag[0][i / TM], frag[0][TN + i % TM], acc[i / TM][i % TM]);
+                if constexpr (i < NFRAG) frag[1][i] = read_frag(slot, 1, i);
+                if constexpr (i % 4 == 2) copy_b(SlotPrev{}, std::integral_constant<int, i / 4>{});
+                static_for<NPIECE>([&](auto Q) {
+                    constexpr int q = decltype(Q)::value;
+                    if constexpr (piece_gap(q) == i) walk_i(q / 3, q % 3);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            __builtin_amdgcn_s_waitcnt(VMCNT_KEEP & 0xF0FF);  // and lgkmcnt(0)
+            __syncthreads();
+            static_for<NMMA>([&](auto I) {
+                constexpr int i = decltype(I)::value;
+                pinned_mma(frag[1][i / TM], frag[1][TN + i % TM], acc[i / TM][i % TM]);
+                if constexpr (i < NFRAG) frag[0][i] = read_frag(slot_next, 0, i);
+                if constexpr (i % 4 == 2) copy_a(SLOT, std::integral_constant<int, i / 4>{});
+                static_for<NPIECE>([&](auto Q) {
+                    constexpr int q = decltype(Q)::value;
+                    if constexpr (piece_gap(q) == i) walk_g(q / 3, q % 3);
+                });
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+    }
+    // the copies of the surplus stages still write (zeros) into this workgroup's LDS
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+
+    // ---- epilogue: lane (h, lr) of MFMA tile (a, b) holds in registers 4g..4g+3 the columns
+    // 8g + 4h + 0..3 of that tile for its row lr
+    float* __restrict__ out = P.out + (long long)split * P.out_elems;
+    const long long caps = (long long)P.D0 * P.D2 * P.D3;
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+        const int R = row_tile * BM + wm * WM + b * 32 + lr;
+        if (R >= P.rows) continue;
+        const int c = R / P.D2, d2 = R - c * P.D2;
+        float* orow = out + ((long long)tap * P.C + c) * P.M * caps +
+                      ((long long)d0 * P.D2 + d2) * P.D3;
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int j0 = col_tile * BN + wn * WN + a * 32 + 8 * g + 4 * h;
+                if (j0 < P.cols) {
+                    const int m = j0 / P.D3, d3 = j0 - m * P.D3;
+                    float4v v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
+                                 acc[a][b][4 * g + 3]};
+                    *reinterpret_cast<float4v*>(orow + (long long)m * caps + d3) = v;
+                }
+            }
+        }
+    }
+}
+
+struct WgradPlan {
+    WgradParams P;
+    size_t it_bytes, gt_bytes, partial_bytes;
+};
+
+int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+// Tiles and the split over images (host side, pure arithmetic).
+WgradPlan make_plan(const ConvShape& s)
+{
+    WgradPlan pl{};
+    WgradParams& P = pl.P;
+    P.N = s.N; P.H = s.H; P.W = s.W; P.C = s.C; P.M = s.M; P.kw = s.kw; P.stride = s.stride;
+    P.pad = s.pad; P.D0 = s.D0; P.D2 = s.D2; P.D3 = s.D3; P.Ho = s.Ho; P.Wo = s.Wo;
+    P.rows = s.C * s.D2;
+    P.cols = s.M * s.D3;
+    P.row_tiles = ceil_div_i(P.rows, 256);
+    P.col_tiles = ceil_div_i(P.cols, 256);
+    P.ntaps = s.kh * s.kw;
+    P.tiles = P.ntaps * s.D0 * P.row_tiles * P.col_tiles;
+    P.out_elems = (long long)s.kernel_elems();
+    P.it_img_bytes = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 2;
+    P.gt_img_bytes = (long long)s.Ho * s.Wo * s.M * s.D0 * s.D1 * s.D3 * 2;
+    pl.it_bytes = (size_t)s.N * P.it_img_bytes;
+    pl.gt_bytes = (size_t)s.N * P.gt_img_bytes;
+
+    // Images per workgroup: the cost of a choice is (rounds of 256 workgroups) x (pixels per
+    // workgroup + the fixed cost of a workgroup, about 15 us, in pixel units); byte offsets
+    // within a workgroup's images must stay below 2^31, and the partial sums below 1 GiB.
+    const long long img_max = P.it_img_bytes > P.gt_img_bytes ? P.it_img_bytes : P.gt_img_bytes;
+    long long imgs_cap = ((1LL << 31) - 1) / (img_max > 0 ? img_max : 1);
+    if (imgs_cap > s.N) imgs_cap = s.N;
+    const double pix_per_img = (double)s.Ho * s.Wo;
+    const double fixed = s.D1 == 16 ? 70.0 : 140.0;
+    double best = 0;
+    int best_imgs = (int)imgs_cap;
+    for (int imgs = (int)imgs_cap; imgs >= 1; --imgs) {
+        const int nsplit = ceil_div_i(s.N, imgs);
+        if (nsplit > 1 && (double)nsplit * P.out_elems * 4 > (double)(1 << 30)) break;
+        const long long items = (long long)nsplit * P.tiles;
+        const double rounds = (double)((items + 255) / 256);
+        const double cost = rounds * (imgs * pix_per_img + fixed);
+        if (imgs == (int)imgs_cap || cost < best * 0.98) {
+            best = cost;
+            best_imgs = imgs;
+        }
+    }
+    P.imgs_per_split = best_imgs < 1 ? 1 : best_imgs;
+    P.nsplit = ceil_div_i(s.N, P.imgs_per_split);
+    P.items = (long long)P.nsplit * P.tiles;
+    pl.partial_bytes = P.nsplit > 1 ? (size_t)P.nsplit * P.out_elems * sizeof(float) : 0;
+    return pl;
+}
+
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+hipError_t launch_transpose(const void* src, void* dst, size_t nmat, int A, int B,
+                            hipStream_t stream)
+{
+    const size_t chunks = nmat * (size_t)(A / 8) * B;
+    const size_t blocks = (chunks + 255) / 256;
+    if (blocks == 0 || blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+    transpose_caps_kernel<<<(unsigned)blocks, 256, 0, stream>>>(
+        static_cast<const unsigned short*>(src), static_cast<unsigned short*>(dst), A, B, chunks);
+    return hipGetLastError();
+}
+
+template <typename Tag, int D1>
+hipError_t launch_kernel(const WgradParams& P, hipStream_t stream)
+{
+    auto kern = wgrad16_kernel<Tag, D1>;
+    const size_t lds_bytes = (size_t)4 * 2 * 4 * 256 * 16;  // ring of 4 stages of 32 KB
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)lds_bytes);
+    if (err != hipSuccess) return err;
+    kern<<<dim3((unsigned)P.items), dim3(256), lds_bytes, stream>>>(P);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+bool wgrad16_eligible(const ConvShape& s)
+{
+    if (s.dtype != 1 && s.dtype != 2) return false;
+    if (s.D1 != 8 && s.D1 != 16) return false;
+    if (s.D3 % 4 != 0) return false;
+    // 31-bit byte offsets within one image of either tensor, 31-bit row/column/pixel counts
+    const long long it_img = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 2;
+    const long long gt_img = (long long)s.Ho * s.Wo * s.M * s.D0 * s.D1 * s.D3 * 2;
+    if (it_img >= (1LL << 31) || gt_img >= (1LL << 31)) return false;
+    if ((long long)s.stride * s.W * s.C * s.D0 * s.D1 * s.D2 * 2 >= (1LL << 30)) return false;
+    if ((long long)s.C * s.D2 >= (1 << 24) || (long long)s.M * s.D3 >= (1 << 24)) return false;
+    const long long tiles = (long long)s.kh * s.kw * s.D0 * (((long long)s.C * s.D2 + 255) / 256) *
+                            (((long long)s.M * s.D3 + 255) / 256);
+    if (tiles * s.N >= (1LL << 31)) return false;
+    return true;
+}
+
+size_t wgrad16_workspace_bytes(const ConvShape& s)
+{
+    const WgradPlan pl = make_plan(s);
+    return align256(pl.it_bytes) + align256(pl.gt_bytes) + pl.partial_bytes;
+}
+
+hipError_t launch_wgrad16(const ConvShape& s, const void* input, const void* dout, float* dkernel,
+                          void* workspace, hipStream_t stream)
+{
+    WgradPlan pl = make_plan(s);
+    char* ws = static_cast<char*>(workspace);
+    void* it = ws;
+    void* gt = ws + align256(pl.it_bytes);
+    float* partial = reinterpret_cast<float*>(ws + align256(pl.it_bytes) + align256(pl.gt_bytes));
+    hipError_t err = launch_transpose(input, it, (size_t)s.N * s.H * s.W * s.C * s.D0, s.D1, s.D2,
+                                      stream);
+    if (err != hipSuccess) return err;
+    err = launch_transpose(dout, gt, (size_t)s.N * s.Ho * s.Wo * s.M * s.D0, s.D1, s.D3, stream);
+    if (err != hipSuccess) return err;
+    pl.P.it = it;
+    pl.P.gt = gt;
+    pl.P.out = pl.P.nsplit > 1 ? partial : dkernel;
+    if (s.dtype == 2)
+        err = s.D1 == 16 ? launch_kernel<f16_tag, 16>(pl.P, stream)
+                         : launch_kernel<f16_tag, 8>(pl.P, stream);
+    else
+        err = s.D1 == 16 ? launch_kernel<bf16_tag, 16>(pl.P, stream)
+                         : launch_kernel<bf16_tag, 8>(pl.P, stream);
+    if (err != hipSuccess) return err;
+    if (pl.P.nsplit > 1)
+        err = launch_splitk_reduce(partial, dkernel, pl.P.out_elems, pl.P.nsplit, stream);
+    return err;
+}
+
+}  // namespace capscaps

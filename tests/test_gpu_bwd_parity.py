@@ -78,6 +78,13 @@ BWD_SHAPES = SMALL_SHAPES + [
     ("s1d16", 2, 9, 8, 16, 12, 3, 3, 1, 1, 1, 16, 16, 16),
     ("s1nonsq", 2, 10, 7, 6, 9, 2, 2, 1, 0, 2, 3, 5, 4),
     ("s1k5", 1, 11, 11, 8, 8, 5, 5, 1, 2, 1, 4, 4, 4),
+    # for the 16-bit kernel-gradient kernel (D1 in {8, 16}): ragged rows and columns with a
+    # leading capsule index, window taps that never meet the image, several row and column
+    # tiles at stride 3, many images (the contraction split over image ranges)
+    ("wg_rag", 3, 7, 6, 5, 3, 3, 3, 2, 1, 2, 8, 5, 4),
+    ("wg_empty", 2, 1, 1, 3, 2, 5, 5, 1, 2, 1, 8, 4, 4),
+    ("wg_d16s3", 2, 10, 9, 20, 18, 3, 3, 3, 1, 1, 16, 16, 16),
+    ("wg_many", 70, 5, 5, 4, 4, 2, 2, 1, 0, 1, 16, 8, 8),
 ]
 
 
