@@ -2,14 +2,16 @@
 """Benchmark of the capsule-convolution forward pass on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--path auto|mfma|direct]
-                    [--op fwd|bwd_input|bwd_kernel]
+                    [--op fwd|bwd_input|bwd_kernel|scheme1|scheme2|framework_conv]
 
 A step is one pass of the whole hot path (kernel repack, window addressing, LDS staging,
 matrix-core contraction, accumulation, fp32 store) over one batch of seeded synthetic input
 that is already resident in HBM.  The default workload is benchmark configuration 5
 (fp16 in, fp32 accumulate, N=64, 32x32, C=M=64, 3x3, pad 1, 16x16 capsules), the largest one
 and the one the roofline target is stated on.  `--op bwd_input` / `--op bwd_kernel` time the
-backward pass (gradient with respect to the input / the kernel) of the same workload instead.
+backward pass (gradient with respect to the input / the kernel) of the same workload instead;
+`--op scheme1|scheme2|framework_conv` time the comparison implementations of the forward pass
+(the paper's two schemes and the framework's grouped convolution) on the same inputs.
 Prints ONE JSON line.
 """
 from __future__ import annotations
@@ -120,7 +122,8 @@ def main():
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--path", default="auto",
                     choices=["auto", "mfma", "direct", "mfma-generic", "mfma-tuned16", "mfma-tuned32"])
-    ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_input", "bwd_kernel"])
+    ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_input", "bwd_kernel", "scheme1", "scheme2",
+                                                     "framework_conv"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (the known-size kernel that "
@@ -152,9 +155,23 @@ def main():
         I = torch.from_numpy(i_st).cuda()
         K = torch.from_numpy(k_st).cuda()
     g32 = None
+    comparison = args.op in ("scheme1", "scheme2", "framework_conv")
     if args.op == "fwd":
         out = torch.empty(w.out_shape, dtype=torch.float32, device="cuda")
         need = cc.capscaps_conv_fwd_workspace_bytes(*shape)
+    elif comparison:
+        if args.path != "auto":
+            sys.exit("bench.py: --path applies to --op fwd only")
+        from paper_2104_02621_amd import comparisons as cmp
+        out = torch.empty(w.out_shape, dtype=torch.float32, device="cuda")
+        need = 0
+        if args.op == "scheme1" and w.Ho * w.Wo * w.M * w.kh * w.kw * w.C * w.D0 > cmp.MAX_BMM_BATCH:
+            sys.exit("bench.py: scheme 1 is not run on this workload (too many small products per "
+                     "batched multiply; see comparisons.MAX_BMM_BATCH)")
+        if args.op == "scheme2":
+            need = cc.capscaps_scheme2_index_bytes(*shape)
+            if need == 0 or need > (64 << 30):
+                sys.exit("bench.py: scheme 2's index arrays do not fit for this workload")
     else:
         if args.path != "auto":
             sys.exit("bench.py: --path applies to --op fwd only")
@@ -169,12 +186,25 @@ def main():
             need = cc.capscaps_conv_bwd_kernel_workspace_bytes(*shape)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream()
+    if args.op == "scheme2":  # the index arrays depend on the shape only: built once, untimed
+        rc = cc.capscaps_scheme2_build_index(ws.data_ptr(), ws.numel(), *shape, stream.cuda_stream)
+        if rc != cc.OK:
+            sys.exit(f"bench.py: capscaps status {rc}: {cc.capscaps_strerror(rc)}")
 
     def step():
         if args.op == "fwd":
             rc = cc.capscaps_conv_fwd_path(I.data_ptr(), K.data_ptr(), out.data_ptr(),
                                            *shape[:13], w.dtype, path, ws.data_ptr(), ws.numel(),
                                            stream.cuda_stream)
+        elif args.op == "scheme1":
+            out.copy_(cmp.scheme1_fwd(I, K, w.stride, w.pad))
+            return
+        elif args.op == "framework_conv":
+            out.copy_(cmp.framework_conv_fwd(I, K, w.stride, w.pad, widen=False))
+            return
+        elif args.op == "scheme2":
+            rc = cc.capscaps_scheme2_fwd(I.data_ptr(), K.data_ptr(), out.data_ptr(), ws.data_ptr(),
+                                         ws.numel(), *shape, stream.cuda_stream)
         elif args.op == "bwd_input":
             rc = cc.capscaps_conv_bwd_input(G.data_ptr(), K.data_ptr(), out.data_ptr(), *shape,
                                             ws.data_ptr(), ws.numel(), stream.cuda_stream)
@@ -240,7 +270,7 @@ def main():
         },
     }
     if not args.no_cpu_baseline:
-        if args.op == "fwd":
+        if args.op == "fwd" or comparison:
             rec, err = cpu_baseline(w, i32, k32, out)
         else:
             rec, err = cpu_baseline_bwd(w, args.op, i32, k32, g32, out)

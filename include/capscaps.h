@@ -158,6 +158,28 @@ size_t capscaps_conv_bwd_kernel_workspace_bytes(int N, int H, int W, int C, int 
                                                 int stride, int pad, int D0, int D1, int D2,
                                                 int D3, int dtype);
 
+/*
+ * Comparison implementation of the paper's second scheme (Algorithm 5; Sec. 2, last paragraph):
+ * the three operand positions of every small matrix product are calculated beforehand
+ * (capscaps_scheme2_build_index, once per shape), then one flat parallel loop multiplies and
+ * accumulates each product at its output position with atomic adds.  Same operator, layouts,
+ * pointer and stream rules as capscaps_conv_fwd_ex; fp32 out, overwritten.  For measurement
+ * against the implicit-GEMM paths only: no capscaps_conv_fwd* call takes this route, and the
+ * order of the atomic additions (hence the last bits of the result) is not fixed.
+ * `index` is a device buffer of capscaps_scheme2_index_bytes(...) bytes (12 per product;
+ * 0 = shape not supported: a tensor with 2^31 or more capsules, or 2^39 or more products), written
+ * by _build_index and only read by _fwd.  Too small -> CAPSCAPS_EWORKSPACE.
+ */
+size_t capscaps_scheme2_index_bytes(int N, int H, int W, int C, int M, int kh, int kw, int stride,
+                                    int pad, int D0, int D1, int D2, int D3, int dtype);
+int capscaps_scheme2_build_index(void* index, size_t index_bytes, int N, int H, int W, int C, int M,
+                                 int kh, int kw, int stride, int pad, int D0, int D1, int D2,
+                                 int D3, int dtype, void* stream);
+int capscaps_scheme2_fwd(const void* input, const void* kernel, void* out, const void* index,
+                         size_t index_bytes, int N, int H, int W, int C, int M, int kh, int kw,
+                         int stride, int pad, int D0, int D1, int D2, int D3, int dtype,
+                         void* stream);
+
 /* Static, human-readable text for a status code.  Never NULL. */
 const char* capscaps_strerror(int status);
 

@@ -64,6 +64,12 @@ def _load():
         getattr(lib, name).restype = i
         getattr(lib, name + "_workspace_bytes").argtypes = [i] * 14
         getattr(lib, name + "_workspace_bytes").restype = sz
+    lib.capscaps_scheme2_index_bytes.argtypes = [i] * 14
+    lib.capscaps_scheme2_index_bytes.restype = sz
+    lib.capscaps_scheme2_build_index.argtypes = [p, sz] + [i] * 14 + [p]
+    lib.capscaps_scheme2_build_index.restype = i
+    lib.capscaps_scheme2_fwd.argtypes = [p, p, p, p, sz] + [i] * 14 + [p]
+    lib.capscaps_scheme2_fwd.restype = i
     lib.capscaps_strerror.argtypes = [i]
     lib.capscaps_strerror.restype = ctypes.c_char_p
     lib.capscaps_last_hip_error.argtypes = []
@@ -143,6 +149,23 @@ def capscaps_conv_bwd_kernel_workspace_bytes(N, H, W, C, M, kh, kw, stride, pad,
                                              dtype) -> int:
     return int(_load().capscaps_conv_bwd_kernel_workspace_bytes(N, H, W, C, M, kh, kw, stride,
                                                                 pad, D0, D1, D2, D3, dtype))
+
+
+def capscaps_scheme2_index_bytes(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype) -> int:
+    return int(_load().capscaps_scheme2_index_bytes(N, H, W, C, M, kh, kw, stride, pad, D0, D1,
+                                                    D2, D3, dtype))
+
+
+def capscaps_scheme2_build_index(index, index_bytes, N, H, W, C, M, kh, kw, stride, pad, D0, D1,
+                                 D2, D3, dtype, stream=None) -> int:
+    return _load().capscaps_scheme2_build_index(index, index_bytes, N, H, W, C, M, kh, kw, stride,
+                                                pad, D0, D1, D2, D3, dtype, stream)
+
+
+def capscaps_scheme2_fwd(input, kernel, out, index, index_bytes, N, H, W, C, M, kh, kw, stride,
+                         pad, D0, D1, D2, D3, dtype, stream=None) -> int:
+    return _load().capscaps_scheme2_fwd(input, kernel, out, index, index_bytes, N, H, W, C, M, kh,
+                                        kw, stride, pad, D0, D1, D2, D3, dtype, stream)
 
 
 # ------------------------------------------------------------------ torch convenience

@@ -241,6 +241,49 @@ int capscaps_conv_bwd_kernel(const void* input, const void* dout, void* dkernel,
                                        workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
+size_t capscaps_scheme2_index_bytes(int N, int H, int W, int C, int M, int kh, int kw, int stride,
+                                    int pad, int D0, int D1, int D2, int D3, int dtype)
+{
+    ConvShape s;
+    if (fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype) != CAPSCAPS_OK)
+        return 0;
+    if (!capscaps::scheme2_supported(s)) return 0;
+    return capscaps::scheme2_products(s) * 3 * sizeof(int);
+}
+
+int capscaps_scheme2_build_index(void* index, size_t index_bytes, int N, int H, int W, int C, int M,
+                                 int kh, int kw, int stride, int pad, int D0, int D1, int D2,
+                                 int D3, int dtype, void* stream)
+{
+    if (index == nullptr || misaligned(index)) return CAPSCAPS_EINVAL;
+    ConvShape s;
+    const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype);
+    if (rc != CAPSCAPS_OK) return rc;
+    if (!capscaps::scheme2_supported(s)) return CAPSCAPS_EUNSUPPORTED;
+    if (index_bytes < capscaps::scheme2_products(s) * 3 * sizeof(int)) return CAPSCAPS_EWORKSPACE;
+    return hip_status(capscaps::launch_scheme2_index(s, static_cast<int*>(index),
+                                                     static_cast<hipStream_t>(stream)));
+}
+
+int capscaps_scheme2_fwd(const void* input, const void* kernel, void* out, const void* index,
+                         size_t index_bytes, int N, int H, int W, int C, int M, int kh, int kw,
+                         int stride, int pad, int D0, int D1, int D2, int D3, int dtype,
+                         void* stream)
+{
+    if (input == nullptr || kernel == nullptr || out == nullptr || index == nullptr)
+        return CAPSCAPS_EINVAL;
+    if (misaligned(input) || misaligned(kernel) || misaligned(out) || misaligned(index))
+        return CAPSCAPS_EINVAL;
+    ConvShape s;
+    const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype);
+    if (rc != CAPSCAPS_OK) return rc;
+    if (!capscaps::scheme2_supported(s)) return CAPSCAPS_EUNSUPPORTED;
+    if (index_bytes < capscaps::scheme2_products(s) * 3 * sizeof(int)) return CAPSCAPS_EWORKSPACE;
+    return hip_status(capscaps::launch_scheme2(s, input, kernel, static_cast<float*>(out),
+                                               static_cast<const int*>(index),
+                                               static_cast<hipStream_t>(stream)));
+}
+
 const char* capscaps_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 const char* capscaps_strerror(int status)

@@ -52,4 +52,11 @@ int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, f
 int launch_bwd_kernel(const ConvShape& s, const void* input, const void* dout, float* dkernel,
                       void* workspace, size_t workspace_bytes, hipStream_t stream);
 
+// The paper's second scheme (Algorithm 5) as a comparison implementation (scheme2.hip).
+bool scheme2_supported(const ConvShape& s);
+size_t scheme2_products(const ConvShape& s);  // small matrix products = index triples
+hipError_t launch_scheme2_index(const ConvShape& s, int* index, hipStream_t stream);
+hipError_t launch_scheme2(const ConvShape& s, const void* in, const void* kernel, float* out,
+                          const int* index, hipStream_t stream);
+
 }  // namespace capscaps
