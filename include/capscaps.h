@@ -106,6 +106,23 @@ int capscaps_conv_fwd_path(const void* input, const void* kernel, void* out, int
                            size_t workspace_bytes, void* stream);
 
 /*
+ * As capscaps_conv_fwd_ex for 16-bit operands (dtype CAPSCAPS_BF16 or CAPSCAPS_FP16; fp32 ->
+ * CAPSCAPS_EINVAL), with `out` holding elements of that same type: the fp32 accumulator is
+ * rounded to nearest even once, at the store.  The output layout [N][H'][W'][M][D0][D1][D3] is the
+ * input layout of a following layer (its C = M, its D2 = D3), so layers chain (the paper's
+ * experiment is a five-layer stack, Sec. 3) without a conversion pass and with half the output
+ * traffic.  `workspace` must hold capscaps_conv_fwd_out16_workspace_bytes(...) bytes (host-only;
+ * 0 also for invalid arguments).
+ */
+size_t capscaps_conv_fwd_out16_workspace_bytes(int N, int H, int W, int C, int M, int kh, int kw,
+                                               int stride, int pad, int D0, int D1, int D2, int D3,
+                                               int dtype);
+int capscaps_conv_fwd_out16(const void* input, const void* kernel, void* out, int N, int H, int W,
+                            int C, int M, int kh, int kw, int stride, int pad, int D0, int D1,
+                            int D2, int D3, int dtype, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/*
  * Scratch bytes capscaps_conv_fwd_ex / _path need for these arguments (repacked kernel,
  * split-reduction partial sums).  Host-only.  Returns 0 also for invalid arguments (the
  * compute call reports those).

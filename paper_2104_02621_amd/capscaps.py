@@ -53,6 +53,10 @@ def _load():
     lib.capscaps_conv_fwd.restype = i
     lib.capscaps_conv_fwd_ex.argtypes = [p, p, p] + [i] * 14 + [p, sz, p]
     lib.capscaps_conv_fwd_ex.restype = i
+    lib.capscaps_conv_fwd_out16_workspace_bytes.argtypes = [i] * 14
+    lib.capscaps_conv_fwd_out16_workspace_bytes.restype = sz
+    lib.capscaps_conv_fwd_out16.argtypes = [p, p, p] + [i] * 14 + [p, sz, p]
+    lib.capscaps_conv_fwd_out16.restype = i
     lib.capscaps_conv_fwd_path.argtypes = [p, p, p] + [i] * 15 + [p, sz, p]
     lib.capscaps_conv_fwd_path.restype = i
     lib.capscaps_conv_fwd_workspace_bytes.argtypes = [i] * 14
@@ -105,6 +109,19 @@ def capscaps_conv_fwd_ex(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad,
                          dtype, workspace, workspace_bytes, stream=None) -> int:
     return _load().capscaps_conv_fwd_ex(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad,
                                         D0, D1, D2, D3, dtype, workspace, workspace_bytes, stream)
+
+
+def capscaps_conv_fwd_out16_workspace_bytes(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3,
+                                            dtype) -> int:
+    return int(_load().capscaps_conv_fwd_out16_workspace_bytes(N, H, W, C, M, kh, kw, stride, pad,
+                                                               D0, D1, D2, D3, dtype))
+
+
+def capscaps_conv_fwd_out16(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3,
+                            dtype, workspace, workspace_bytes, stream=None) -> int:
+    return _load().capscaps_conv_fwd_out16(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad,
+                                           D0, D1, D2, D3, dtype, workspace, workspace_bytes,
+                                           stream)
 
 
 def capscaps_conv_fwd_path(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2,
@@ -174,10 +191,12 @@ def _torch_dtype_code(t):
     return {torch.float32: FP32, torch.bfloat16: BF16, torch.float16: FP16}[t.dtype]
 
 
-def conv_fwd(input, kernel, stride=1, pad=0, path=PATH_AUTO, out=None, workspace=None):
+def conv_fwd(input, kernel, stride=1, pad=0, path=PATH_AUTO, out=None, workspace=None,
+             out16=False):
     """input [N,H,W,C,D0,D1,D2], kernel [kh,kw,C,M,D0,D2,D3] (contiguous device tensors of one
-    dtype: float32, bfloat16 or float16) -> float32 [N,H',W',M,D0,D1,D3].  Enqueues on torch's
-    current stream; does not synchronise."""
+    dtype: float32, bfloat16 or float16) -> float32 [N,H',W',M,D0,D1,D3] (with `out16`: of the
+    operands' 16-bit type, library's own path choice).  Enqueues on torch's current stream; does
+    not synchronise."""
     import torch
     if not (input.is_cuda and kernel.is_cuda):
         raise ValueError("capscaps runs on the GPU only: pass device tensors")
@@ -194,15 +213,23 @@ def conv_fwd(input, kernel, stride=1, pad=0, path=PATH_AUTO, out=None, workspace
     if rc != OK:
         raise CapscapsError(rc)
     if out is None:
-        out = torch.empty((N, Ho, Wo, M, D0, D1, D3), dtype=torch.float32, device=input.device)
-    need = capscaps_conv_fwd_workspace_bytes(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dt)
+        out = torch.empty((N, Ho, Wo, M, D0, D1, D3),
+                          dtype=input.dtype if out16 else torch.float32, device=input.device)
+    need = (capscaps_conv_fwd_out16_workspace_bytes if out16 else
+            capscaps_conv_fwd_workspace_bytes)(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dt)
     if workspace is None or workspace.numel() * workspace.element_size() < need:
         workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=input.device)
     stream = torch.cuda.current_stream(input.device).cuda_stream
-    rc = capscaps_conv_fwd_path(input.data_ptr(), kernel.data_ptr(), out.data_ptr(), N, H, W, C, M,
-                                kh, kw, stride, pad, D0, D1, D2, D3, dt, path,
-                                workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                                stream)
+    if out16:
+        rc = capscaps_conv_fwd_out16(input.data_ptr(), kernel.data_ptr(), out.data_ptr(), N, H, W,
+                                     C, M, kh, kw, stride, pad, D0, D1, D2, D3, dt,
+                                     workspace.data_ptr(),
+                                     workspace.numel() * workspace.element_size(), stream)
+    else:
+        rc = capscaps_conv_fwd_path(input.data_ptr(), kernel.data_ptr(), out.data_ptr(), N, H, W,
+                                    C, M, kh, kw, stride, pad, D0, D1, D2, D3, dt, path,
+                                    workspace.data_ptr(),
+                                    workspace.numel() * workspace.element_size(), stream)
     if rc != OK:
         raise CapscapsError(rc)
     return out

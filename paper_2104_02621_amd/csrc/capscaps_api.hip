@@ -162,6 +162,34 @@ int capscaps_conv_fwd_ex(const void* input, const void* kernel, void* out, int N
                                   stream);
 }
 
+size_t capscaps_conv_fwd_out16_workspace_bytes(int N, int H, int W, int C, int M, int kh, int kw,
+                                               int stride, int pad, int D0, int D1, int D2, int D3,
+                                               int dtype)
+{
+    ConvShape s;
+    if (dtype != CAPSCAPS_BF16 && dtype != CAPSCAPS_FP16) return 0;
+    if (fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype) != CAPSCAPS_OK)
+        return 0;
+    s.out16 = dtype;
+    return capscaps::forward_workspace_bytes(s);
+}
+
+int capscaps_conv_fwd_out16(const void* input, const void* kernel, void* out, int N, int H, int W,
+                            int C, int M, int kh, int kw, int stride, int pad, int D0, int D1,
+                            int D2, int D3, int dtype, void* workspace, size_t workspace_bytes,
+                            void* stream)
+{
+    if (input == nullptr || kernel == nullptr || out == nullptr) return CAPSCAPS_EINVAL;
+    if (misaligned(input) || misaligned(kernel) || misaligned(out)) return CAPSCAPS_EINVAL;
+    if (dtype != CAPSCAPS_BF16 && dtype != CAPSCAPS_FP16) return CAPSCAPS_EINVAL;
+    ConvShape s;
+    const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype);
+    if (rc != CAPSCAPS_OK) return rc;
+    s.out16 = dtype;
+    return run(input, kernel, out, s, CAPSCAPS_PATH_AUTO, workspace, workspace_bytes,
+               static_cast<hipStream_t>(stream));
+}
+
 int capscaps_conv_fwd(const void* input, const void* kernel, void* out, int N, int H, int W, int C,
                       int M, int kh, int kw, int stride, int D0, int D1, int D2, int D3, int dtype,
                       void* stream)

@@ -12,6 +12,9 @@ struct ConvShape {
     int N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3;
     int Ho, Wo;  // output extents
     int dtype;   // CAPSCAPS_FP32 / BF16 / FP16
+    // output element type: 0 = fp32 (the accumulator as it is); CAPSCAPS_BF16 / FP16 = the
+    // accumulator rounded to nearest even at the store (forward pass of 16-bit operands only)
+    int out16 = 0;
     long long pixels() const { return (long long)N * Ho * Wo; }
     size_t in_elems() const { return (size_t)N * H * W * C * D0 * D1 * D2; }
     size_t kernel_elems() const { return (size_t)kh * kw * C * M * D0 * D2 * D3; }
@@ -19,6 +22,7 @@ struct ConvShape {
 };
 
 // Wavefront-level small-matrix path: plain FMAs, any shape, any dtype.  No scratch.
+// (`out` points to fp32 or, with s.out16, to 16-bit elements; likewise for launch_mfma)
 hipError_t launch_direct(const ConvShape& s, const void* in, const void* kernel, float* out,
                          hipStream_t stream);
 
@@ -30,7 +34,8 @@ bool mfma_supported(const ConvShape& s);
 MfmaKernel mfma_auto_kernel(const ConvShape& s);  // what Auto resolves to (never Auto)
 bool mfma_tuned16_supported(const ConvShape& s);
 bool mfma_dma32_supported(const ConvShape& s);
-size_t mfma_workspace_bytes(const ConvShape& s);  // enough for every MfmaKernel choice
+size_t mfma_workspace_bytes(const ConvShape& s);  // enough for every MfmaKernel choice (with
+                                                  // s.out16: for Auto, the only choice then)
 hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, float* out,
                        void* workspace, hipStream_t stream, MfmaKernel which = MfmaKernel::Auto);
 

@@ -7,7 +7,7 @@
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 
-#include "conv_shape.h"
+#include "igemm_common.h"
 
 namespace capscaps {
 namespace {
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(256) void direct_conv_kernel(const T* __restrict__ 
             }
         }
     }
-    out[e] = acc;
+    store1(out, (long long)e, acc, s.out16);
 }
 
 }  // namespace

@@ -93,9 +93,11 @@ struct ALayout {
 };
 
 // KCH: chunks (of 8 K elements) per row and stage; NB: LDS stage buffers in the ring.
-template <typename Tag, int D1, int D2, int KCH, int NB>
+// OUT16: the output has the operands' 16-bit type (rounded at the store) instead of fp32.
+template <typename Tag, int D1, int D2, int KCH, int NB, bool OUT16>
 __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
 {
+    constexpr int OUT_KIND = !OUT16 ? 0 : std::is_same<Tag, f16_tag>::value ? 2 : 1;
     typedef ALayout<D1, D2, KCH> AL;
     constexpr int NWM = 2, NWN = 2, NW = 4;
     constexpr int BM = 256, BN = 256;
@@ -352,6 +354,9 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         });
     }
 
+    // the copies of the surplus stages still write (zeros) into this workgroup's LDS
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+
     // ---- epilogue: lane (h, lr) of MFMA tile (a, b) holds in registers 4g..4g+3 the columns
     // 8g + 4h + 0..3 of that tile for its output row lr.  Columns advance in steps of 8, so
     // (m, d3) of a column is found by shifts when D3 is a power of two, by division otherwise.
@@ -365,8 +370,8 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         const int pixel = pg0 + r / D1;
         if (pixel >= npix) continue;
         const int d1 = r % D1;
-        float* orow_ptr =
-            out + (long long)pixel * P.M * caps_out + (long long)(d0 * D1 + d1) * P.D3;
+        const long long orow_off =
+            (long long)pixel * P.M * caps_out + (long long)(d0 * D1 + d1) * P.D3;
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
 #pragma unroll
@@ -377,7 +382,7 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
                     const int d3 = j0 - m * P.D3;
                     float4v v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
                                  acc[a][b][4 * g + 3]};
-                    *reinterpret_cast<float4v*>(orow_ptr + (long long)m * caps_out + d3) = v;
+                    store4(out, orow_off + (long long)m * caps_out + d3, v, OUT_KIND);
                 }
             }
         }
@@ -396,7 +401,8 @@ hipError_t launch_one(const IgemmParams& P, long long blocks, hipStream_t stream
 {
     constexpr int KCH = FastConfig<D1, D2>::KCH, NB = FastConfig<D1, D2>::NB;
     typedef ALayout<D1, D2, KCH> AL;
-    auto kern = igemm16_fast_kernel<Tag, D1, D2, KCH, NB>;
+    auto kern = P.out16 ? igemm16_fast_kernel<Tag, D1, D2, KCH, NB, true>
+                        : igemm16_fast_kernel<Tag, D1, D2, KCH, NB, false>;
     const size_t lds_bytes = (size_t)NB * AL::NBLK * (AL::ABLK + 1024);
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize,

@@ -48,6 +48,37 @@ struct Mma<f32_tag> {
     }
 };
 
+// fp32 -> 16-bit, round to nearest even (kind: 1 = bfloat16, 2 = IEEE half)
+__device__ __forceinline__ unsigned short round_to_16(float v, int kind)
+{
+    if (kind == 2) {
+        const _Float16 hv = (_Float16)v;
+        return __builtin_bit_cast(unsigned short, hv);
+    }
+    const unsigned u = __builtin_bit_cast(unsigned, v);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (unsigned short)((u >> 16) | 0x40u);  // NaN
+    return (unsigned short)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+}
+// store 4 consecutive outputs starting at element `off` of `out`: fp32, or 16-bit if out16
+__device__ __forceinline__ void store4(float* out, long long off, const float4v& v, int out16)
+{
+    if (out16 == 0) {
+        *reinterpret_cast<float4v*>(out + off) = v;
+    } else {
+        typedef unsigned short us4 __attribute__((ext_vector_type(4)));
+        us4 r = {round_to_16(v[0], out16), round_to_16(v[1], out16), round_to_16(v[2], out16),
+                 round_to_16(v[3], out16)};
+        *reinterpret_cast<us4*>(reinterpret_cast<unsigned short*>(out) + off) = r;
+    }
+}
+__device__ __forceinline__ void store1(float* out, long long off, float v, int out16)
+{
+    if (out16 == 0)
+        out[off] = v;
+    else
+        reinterpret_cast<unsigned short*>(out)[off] = round_to_16(v, out16);
+}
+
 struct IgemmParams {
     const void* in;
     const void* kp;  // repacked kernel
@@ -69,6 +100,7 @@ struct IgemmParams {
     int row_tiles, col_tiles;
     long long in_bytes;    // size of the input tensor
     long long kp_records;  // size of the repacked kernel in bytes
+    int out16;             // element type of the final output (0 = fp32), see ConvShape
 };
 
 // Shared launch helpers (igemm_conv.hip).  Repack: 16-byte chunks of `cw` valid K elements
@@ -76,7 +108,7 @@ struct IgemmParams {
 hipError_t launch_repack(const ConvShape& s, const void* kernel, void* kp, int cw, int KQP,
                          int colsp, int kgroup, size_t chunks, hipStream_t stream);
 hipError_t launch_splitk_reduce(const float* partial, float* out, long long elems, int nsplit,
-                                hipStream_t stream);
+                                hipStream_t stream, int out16 = 0);
 
 // fp32 kernel with direct-to-LDS copies (igemm32_dma.hip): capsule rows of 3k or 4k floats.
 struct Dma32Params {

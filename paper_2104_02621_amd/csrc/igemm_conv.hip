@@ -78,13 +78,13 @@ __global__ __launch_bounds__(256) void repack_kernel(const E* __restrict__ kerne
 // Deterministic split-K reduction: out[e] = partial[0][e] + partial[1][e] + ... in that order.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial,
                                                             float* __restrict__ out,
-                                                            long long elems, int nsplit)
+                                                            long long elems, int nsplit, int out16)
 {
     const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
     if (e >= elems) return;
     float acc = partial[e];
     for (int s = 1; s < nsplit; ++s) acc += partial[(long long)s * elems + e];
-    out[e] = acc;
+    store1(out, e, acc, out16);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -294,6 +294,7 @@ struct Plan {
     TileChoice tile;
     bool vec, st4;
     bool fast;  // tuned 16-bit kernel
+    bool via_scratch;  // results go to fp32 scratch first, then through splitk_reduce_kernel
     size_t repack_bytes, partial_bytes;
     long long blocks;
     int CH;
@@ -357,9 +358,13 @@ Plan make_plan(const ConvShape& s, MfmaKernel which)
     P.nsplit = ceil_div(P.stages, P.stages_per_split);
     pl.blocks = blocks * P.nsplit;
     pl.repack_bytes = (size_t)s.D0 * P.ntaps * P.KQP * P.colsp * 16;
-    pl.partial_bytes = P.nsplit > 1 ? (size_t)P.nsplit * P.out_elems * sizeof(float) : 0;
+    // this kernel stores fp32 only: a 16-bit output goes through the fp32 scratch and the
+    // reduction kernel, which then also converts
+    pl.via_scratch = P.nsplit > 1 || (s.out16 != 0 && !pl.fast);
+    pl.partial_bytes = pl.via_scratch ? (size_t)P.nsplit * P.out_elems * sizeof(float) : 0;
     P.in_bytes = (long long)s.in_elems() * (s.dtype == 0 ? 4 : 2);
     P.kp_records = (long long)pl.repack_bytes;
+    P.out16 = s.out16;
     return pl;
 }
 
@@ -417,7 +422,7 @@ hipError_t launch_igemm(const ConvShape& s, const void* in, const void* kernel, 
     float* partial = reinterpret_cast<float*>(ws + ((pl.repack_bytes + 255) & ~(size_t)255));
     pl.P.in = in;
     pl.P.kp = kp;
-    pl.P.out = pl.P.nsplit > 1 ? partial : out;
+    pl.P.out = pl.via_scratch ? partial : out;
 
     const size_t chunks = pl.repack_bytes / 16;
     const int kgroup = pl.fast ? igemm16_fast_kgroup(s) : 0;
@@ -434,7 +439,8 @@ hipError_t launch_igemm(const ConvShape& s, const void* in, const void* kernel, 
     }
     if (err != hipSuccess) return err;
 
-    if (pl.P.nsplit > 1) err = launch_splitk_reduce(partial, out, pl.P.out_elems, pl.P.nsplit, stream);
+    if (pl.via_scratch)
+        err = launch_splitk_reduce(partial, out, pl.P.out_elems, pl.P.nsplit, stream, pl.P.out16);
     return err;
 }
 
@@ -476,10 +482,10 @@ hipError_t launch_repack(const ConvShape& s, const void* kernel, void* kp, int c
 }
 
 hipError_t launch_splitk_reduce(const float* partial, float* out, long long elems, int nsplit,
-                                hipStream_t stream)
+                                hipStream_t stream, int out16)
 {
     const unsigned blocks = (unsigned)((elems + 255) / 256);
-    splitk_reduce_kernel<<<blocks, 256, 0, stream>>>(partial, out, elems, nsplit);
+    splitk_reduce_kernel<<<blocks, 256, 0, stream>>>(partial, out, elems, nsplit, out16);
     return hipGetLastError();
 }
 
@@ -488,6 +494,13 @@ bool mfma_supported(const ConvShape& s) { return shape_supported(s); }
 size_t mfma_workspace_bytes(const ConvShape& s)
 {
     if (!shape_supported(s)) return 0;
+    if (s.out16 != 0) {
+        // 16-bit output is offered with the library's own kernel choice only
+        const MfmaKernel which = mfma_auto_kernel(s);
+        if (which == MfmaKernel::Dma32) return 0;  // fp32 operands: not a 16-bit-output shape
+        const Plan pl = make_plan(s, which);
+        return ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
+    }
     size_t need = 0;
     for (MfmaKernel which : {MfmaKernel::Generic, MfmaKernel::Tuned16}) {
         if (which == MfmaKernel::Tuned16 && !igemm16_fast_eligible(s)) continue;
