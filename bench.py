@@ -2,7 +2,7 @@
 """Benchmark of the capsule-convolution forward pass on one MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1..5] [--path auto|mfma|direct]
-                    [--op fwd|bwd_input|bwd_kernel|scheme1|scheme2|framework_conv]
+                    [--op fwd|bwd_input|bwd_kernel|scheme1|scheme2|framework_conv|net5]
 
 A step is one pass of the whole hot path (kernel repack, window addressing, LDS staging,
 matrix-core contraction, accumulation, fp32 store) over one batch of seeded synthetic input
@@ -12,7 +12,8 @@ and the one the roofline target is stated on.  `--op bwd_input` / `--op bwd_kern
 backward pass (gradient with respect to the input / the kernel) of the same workload instead;
 `--op scheme1|scheme2|framework_conv` time the comparison implementations of the forward pass
 (the paper's two schemes and the framework's grouped convolution) on the same inputs.
-Prints ONE JSON line.
+`--op net5` times a five-layer stack of bf16 capsule convolutions chained through the
+16-bit-output entry point (--config is ignored).  Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -114,6 +115,92 @@ def cpu_baseline_bwd(w, op, i32, k32, g32, gpu_grad, target_seconds=12.0):
     return rec, err / max(ref_max, 1e-300)
 
 
+def bench_net5(args):
+    """Five chained layers (workloads.net5): layers 1-4 write bf16 activations that the next layer
+    reads as they are, layer 5 writes fp32.  One step = the five calls."""
+    import numpy as np
+    import torch
+    from oracle import capsconv
+    from paper_2104_02621_amd import capscaps as cc
+    from paper_2104_02621_amd import workloads as wl
+
+    torch.cuda.set_device(0)
+    layers = wl.net5(N=64)
+    i_st, _, i32, _ = wl.generate(layers[0])
+    x0 = torch.from_numpy(i_st.view(np.int16)).cuda().view(torch.bfloat16)
+    kernels32 = [wl.generate(w)[3] for w in layers]
+    kernels = [torch.from_numpy(wl.generate(w)[1].view(np.int16)).cuda().view(torch.bfloat16)
+               for w in layers]
+    stream = torch.cuda.current_stream()
+    outs, wss, shapes = [], [], []
+    for k, w in enumerate(layers):
+        last = k + 1 == len(layers)
+        shape = (w.N, w.H, w.W, w.C, w.M, w.kh, w.kw, w.stride, w.pad, w.D0, w.D1, w.D2, w.D3,
+                 w.dtype)
+        need = (cc.capscaps_conv_fwd_workspace_bytes if last else
+                cc.capscaps_conv_fwd_out16_workspace_bytes)(*shape)
+        outs.append(torch.empty(w.out_shape, dtype=torch.float32 if last else torch.bfloat16,
+                                device="cuda"))
+        wss.append(torch.empty(max(need, 16), dtype=torch.uint8, device="cuda"))
+        shapes.append(shape)
+
+    def step():
+        x = x0
+        for k in range(len(layers)):
+            fn = cc.capscaps_conv_fwd_ex if k + 1 == len(layers) else cc.capscaps_conv_fwd_out16
+            rc = fn(x.data_ptr(), kernels[k].data_ptr(), outs[k].data_ptr(), *shapes[k],
+                    wss[k].data_ptr(), wss[k].numel(), stream.cuda_stream)
+            if rc != cc.OK:
+                sys.exit(f"bench.py: capscaps status {rc}: {cc.capscaps_strerror(rc)}")
+            x = outs[k]
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record(stream)
+    for k in range(args.steps):
+        step()
+        ev[k + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    kernel_ms = float(np.mean([ev[k].elapsed_time(ev[k + 1]) for k in range(args.steps)]))
+    flops = sum(w.flops_tap_exact() for w in layers)
+    achieved = flops / (kernel_ms * 1e-3) / 1e12
+    result = {
+        "metric": "capsule-conv net5 useful GFLOP/s at 1 GPU",
+        "value": round(flops / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 in, f32 accumulate, bf16 activations", "data": "synthetic",
+        "config": {"workload": "net5: five chained capsule convolutions, 8x8 capsules, N=64, 32x32",
+                   "op": "net5", "layers": [w.name + " " + "x".join(map(str, w.out_shape))
+                                            for w in layers],
+                   "flops_tap_exact": flops},
+        "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_TFLOPS["bf16"],
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS["bf16"], 4),
+                     "traffic": None, "kernel_ms": round(kernel_ms, 4)},
+    }
+    if not args.no_cpu_baseline:
+        # the oracle on image 0 through all five layers, activations rounded as on the GPU
+        x32 = i32[:1]
+        t0 = time.perf_counter()
+        for k, w in enumerate(layers):
+            y = capsconv.conv_fwd(x32, kernels32[k], w.stride, w.pad)
+            if k + 1 < len(layers):
+                x32 = wl.to_storage(y.astype(np.float32), w.dtype)[1]
+        dt = time.perf_counter() - t0
+        got = outs[-1][:1].cpu().numpy()
+        result["cpu_baseline"] = {
+            "value": round(flops / 64 / dt / 1e9, 3), "unit": "GFLOP/s",
+            "cores": capsconv.threads(), "kind": "oracle",
+            "sample": f"image 0 of 64 through all five layers; {dt:.1f} s"}
+        result["config"]["max_err_vs_oracle_sample"] = float(np.abs(got - y).max() / np.abs(y).max())
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -123,7 +210,7 @@ def main():
     ap.add_argument("--path", default="auto",
                     choices=["auto", "mfma", "direct", "mfma-generic", "mfma-tuned16", "mfma-tuned32"])
     ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_input", "bwd_kernel", "scheme1", "scheme2",
-                                                     "framework_conv"])
+                                                     "framework_conv", "net5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (the known-size kernel that "
@@ -140,6 +227,8 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    if args.op == "net5":
+        return bench_net5(args)
     torch.cuda.set_device(0)
     w = wl.config(args.config)
     path = {"auto": cc.PATH_AUTO, "mfma": cc.PATH_MFMA, "direct": cc.PATH_DIRECT,

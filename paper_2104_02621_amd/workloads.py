@@ -111,6 +111,25 @@ CONFIGS = (
 )
 
 
+def net5(N: int = 64, dtype: int = BF16):
+    """A five-layer stack of capsule convolutions (the paper's experiment, Sec. 3, is a
+    five-layer convolutional CapsNet; the figure with its shapes is not available, so these are
+    stand-ins of the benchmark configurations' kind): 8x8 capsules, 32x32 images, two strided
+    layers, a fully-connected last layer.  Layer k's output (in the operands' 16-bit type) is
+    layer k+1's input; kernels N(0, 1/fan-in) keep the activations at unit scale."""
+    #          HW   C   M  k  s  p
+    layers = ((32, 16, 32, 3, 1, 1),
+              (32, 32, 32, 3, 2, 1),
+              (16, 32, 64, 3, 1, 1),
+              (16, 64, 64, 3, 2, 1),
+              (8, 64, 10, 8, 1, 0))
+    D = 8
+    return tuple(
+        Workload(f"net5_layer{k + 1}", dtype, N, hw, hw, c, m, ksz, ksz, s_, p_, 1, D, D, D,
+                 "normal", "normal", 1.0 / float(np.sqrt(ksz * ksz * c * D)), 5000 + k, 6000 + k)
+        for k, (hw, c, m, ksz, s_, p_) in enumerate(layers))
+
+
 def config(number: int) -> Workload:
     """Benchmark configuration 1..5."""
     return CONFIGS[number - 1]
