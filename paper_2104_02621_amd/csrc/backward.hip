@@ -11,7 +11,11 @@
 //   dK = conv_fwd(I', G'), I' = I as [C][H][W][N][D0][D2][D1] (images <-> channels, capsules
 //        transposed), G' = G as [H'][W'][N][M][D0][D1][D3] (the output gradient is the window),
 //        same padding; the result [C][kh][kw][M][D0][D2][D3] is permuted into the kernel layout.
-// A stride s > 1 is the same with the output gradient spread out: G is copied into a zero
+// A stride s > 1 splits dI into s*s phases, the pixels with equal ((h+pad) mod s, (w+pad) mod s):
+// phase (a,b) is a stride-1 convolution of G with the window taps p = a, a+s, ..., q = b, b+s, ...
+// (flipped), whose output pixels lie s apart in dI.  For 16-bit capsules the tuned forward kernel
+// runs each phase with its own row and column padding and writes through an output stride: no
+// multiplication by zeros.  Otherwise the output gradient is spread out: G is copied into a zero
 // buffer of the stride-1 output extent (H+2*pad-kh+1 rows), pixel (x,y) at (x*s, y*s).  The
 // contraction then runs over s*s times the needed terms (the zeros), but on the matrix cores.
 // The fully-connected layer's dI (one output pixel, window = image) is a 1x1 convolution whose
@@ -176,6 +180,69 @@ size_t spread_elems(const ConvShape& s)
     return (size_t)s.N * spread_h(s) * spread_w(s) * s.M * s.D0 * s.D1 * s.D3;
 }
 
+// One dimension of a phase of the strided input gradient: the positions h with (h + pad) mod s
+// == a are h = s*U + a - pad for U in [lo, lo + count); they are reached through the `taps`
+// window taps p = a + s*i.
+struct PhaseDim {
+    int taps, lo, count;
+};
+PhaseDim phase_dim(int extent, int k, int s, int pad, int a)
+{
+    PhaseDim d;
+    d.taps = a < k ? (k - a + s - 1) / s : 0;
+    d.lo = pad - a > 0 ? (pad - a + s - 1) / s : 0;
+    const int top = extent - 1 + pad - a;  // s*U <= top
+    const int hi = top >= 0 ? top / s : -1;
+    d.count = hi - d.lo + 1 > 0 ? hi - d.lo + 1 : 0;
+    return d;
+}
+// phase (a,b) as a forward convolution for the tuned 16-bit kernel
+ConvShape bwd_input_phase_shape(const ConvShape& s, const PhaseDim& ph, const PhaseDim& pw, int a,
+                                int b)
+{
+    ConvShape f{s.N, s.Ho, s.Wo, s.M, s.C, ph.taps, pw.taps, 1, ph.taps - 1 - ph.lo,
+                s.D0, s.D1, s.D3, s.D2, ph.count, pw.count, s.dtype};
+    f.pad_w_set = true;
+    f.pad_w = pw.taps - 1 - pw.lo;
+    f.out_view = true;
+    const long long pix = (long long)s.C * s.D0 * s.D1 * s.D2;
+    f.out_sn = (long long)s.H * s.W * pix;
+    f.out_sx = (long long)s.stride * s.W * pix;
+    f.out_sy = (long long)s.stride * pix;
+    f.out_base = ((long long)(s.stride * ph.lo + a - s.pad) * s.W + (s.stride * pw.lo + b - s.pad)) * pix;
+    return f;
+}
+// every phase that has both pixels and taps must fit the tuned kernel and fill the chip
+bool bwd_input_as_phases(const ConvShape& s)
+{
+    if (s.stride == 1 || s.stride > 4 || (s.dtype != 1 && s.dtype != 2)) return false;
+    for (int a = 0; a < s.stride; ++a)
+        for (int b = 0; b < s.stride; ++b) {
+            const PhaseDim ph = phase_dim(s.H, s.kh, s.stride, s.pad, a);
+            const PhaseDim pw = phase_dim(s.W, s.kw, s.stride, s.pad, b);
+            if (ph.count == 0 || pw.count == 0 || ph.taps == 0 || pw.taps == 0) continue;
+            const ConvShape f = bwd_input_phase_shape(s, ph, pw, a, b);
+            if (!mfma_supported(f) || !mfma_tuned16_supported(f)) return false;
+            if ((long long)f.N * f.Ho * f.Wo * f.D1 < 256LL * 128) return false;
+        }
+    return true;
+}
+
+// zero the pixels (n, h0 + i*sh, w0 + j*sw), i < nh, j < nw, of an fp32 tensor [N][H][W][pix]
+__global__ __launch_bounds__(256) void zero_pixels_kernel(float* __restrict__ out, int H, int W,
+                                                          long long pix, int h0, int sh, int nh,
+                                                          int w0, int sw, int nw, size_t total)
+{
+    const size_t id = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= total) return;
+    size_t r = id;
+    const long long e = (long long)(r % pix); r /= pix;
+    const int j = (int)(r % nw); r /= nw;
+    const int i = (int)(r % nh);
+    const long long n = (long long)(r / nh);
+    out[((n * H + h0 + (long long)i * sh) * W + w0 + (long long)j * sw) * pix + e] = 0.f;
+}
+
 // fully-connected layer: one output pixel, the window is the whole unpadded image
 bool bwd_input_as_fc(const ConvShape& s)
 {
@@ -210,6 +277,18 @@ size_t bwd_input_workspace_bytes(const ConvShape& s)
 {
     const size_t kbytes = align256(s.kernel_elems() * elem_bytes(s));
     if (bwd_input_as_fc(s)) return kbytes + forward_workspace_bytes(bwd_input_fc_shape(s));
+    if (bwd_input_as_phases(s)) {
+        size_t fwd = 0;
+        for (int a = 0; a < s.stride; ++a)
+            for (int b = 0; b < s.stride; ++b) {
+                const PhaseDim ph = phase_dim(s.H, s.kh, s.stride, s.pad, a);
+                const PhaseDim pw = phase_dim(s.W, s.kw, s.stride, s.pad, b);
+                if (ph.count == 0 || pw.count == 0 || ph.taps == 0 || pw.taps == 0) continue;
+                const size_t need = mfma_workspace_bytes(bwd_input_phase_shape(s, ph, pw, a, b));
+                if (need > fwd) fwd = need;
+            }
+        return kbytes + fwd;  // the phases' sub-kernels together are one kernel tensor
+    }
     if (!bwd_input_as_conv(s)) return 0;
     const size_t gbytes = s.stride > 1 ? align256(spread_elems(s) * elem_bytes(s)) : 0;
     return kbytes + gbytes + forward_workspace_bytes(bwd_input_conv_shape(s));
@@ -240,6 +319,41 @@ int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, f
         if (err != hipSuccess) return status_from_hip(err);
         return forward_auto(bwd_input_fc_shape(s), dout, ws, din, ws + used,
                             workspace_bytes - used, stream);
+    }
+    if (bwd_input_as_phases(s)) {
+        char* ws = static_cast<char*>(workspace);
+        const size_t kbytes = align256(s.kernel_elems() * eb);
+        const long long pix = (long long)s.C * s.D0 * s.D1 * s.D2;
+        for (int a = 0; a < s.stride; ++a)
+            for (int b = 0; b < s.stride; ++b) {
+                const PhaseDim ph = phase_dim(s.H, s.kh, s.stride, s.pad, a);
+                const PhaseDim pw = phase_dim(s.W, s.kw, s.stride, s.pad, b);
+                if (ph.count == 0 || pw.count == 0) continue;  // no pixel of dI in this phase
+                const int h0 = s.stride * ph.lo + a - s.pad, w0 = s.stride * pw.lo + b - s.pad;
+                if (ph.taps == 0 || pw.taps == 0) {  // pixels no window reaches
+                    const size_t total = (size_t)s.N * ph.count * pw.count * pix;
+                    const size_t blocks = (total + 255) / 256;
+                    if (blocks > 0x7fffffffULL) return status_from_hip(hipErrorInvalidValue);
+                    zero_pixels_kernel<<<(unsigned)blocks, 256, 0, stream>>>(
+                        din, s.H, s.W, pix, h0, s.stride, ph.count, w0, s.stride, pw.count, total);
+                    const hipError_t err = hipGetLastError();
+                    if (err != hipSuccess) return status_from_hip(err);
+                    continue;
+                }
+                // Kab[i'][j'][m][c][d0][d3][d2] = K[a + s*(taps_h-1-i')][b + s*(taps_w-1-j')][c][m][d0][d2][d3]
+                const Permute7 pm = gather_into_dense(
+                    {ph.taps, pw.taps, s.M, s.C, s.D0, s.D3, s.D2},
+                    {-s.stride * sP, -s.stride * sQ, sM, sC, sD0, sD3, sD2},
+                    (long long)(a + s.stride * (ph.taps - 1)) * sP +
+                        (long long)(b + s.stride * (pw.taps - 1)) * sQ);
+                // the sub-kernels are used one after the other on one stream: one buffer
+                hipError_t err = launch_permute(kernel, ws, pm, eb, stream);
+                if (err != hipSuccess) return status_from_hip(err);
+                const int rc = forward_tuned16(bwd_input_phase_shape(s, ph, pw, a, b), dout, ws,
+                                               din, ws + kbytes, workspace_bytes - kbytes, stream);
+                if (rc != 0) return rc;
+            }
+        return 0;
     }
     if (bwd_input_as_conv(s)) {
         char* ws = static_cast<char*>(workspace);

@@ -101,7 +101,14 @@ size_t forward_workspace_bytes(const ConvShape& s)
 int forward_auto(const ConvShape& s, const void* in, const void* kernel, float* out,
                  void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
+    if (!s.plain()) return CAPSCAPS_EINVAL;
     return run(in, kernel, out, s, CAPSCAPS_PATH_AUTO, workspace, workspace_bytes, stream);
+}
+
+int forward_tuned16(const ConvShape& s, const void* in, const void* kernel, float* out,
+                    void* workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    return run(in, kernel, out, s, CAPSCAPS_PATH_MFMA_TUNED16, workspace, workspace_bytes, stream);
 }
 
 }  // namespace capscaps

@@ -15,6 +15,19 @@ struct ConvShape {
     // output element type: 0 = fp32 (the accumulator as it is); CAPSCAPS_BF16 / FP16 = the
     // accumulator rounded to nearest even at the store (forward pass of 16-bit operands only)
     int out16 = 0;
+    // Geometry overrides understood by the tuned 16-bit kernel only (launch_mfma with
+    // MfmaKernel::Tuned16; everything else must be given shapes without them).  The backward
+    // pass uses them to run a strided layer's input gradient as stride*stride convolutions
+    // whose outputs interleave.  pad_w_set: the columns' padding is pad_w instead of pad; both
+    // may then be negative (the window starts inside the image) and Ho, Wo are taken as given.
+    // out_view: output pixel (n, x, y) is written at element out_base + n*out_sn + x*out_sx +
+    // y*out_sy of `out` instead of densely.
+    bool pad_w_set = false;
+    int pad_w = 0;
+    bool out_view = false;
+    long long out_base = 0, out_sn = 0, out_sx = 0, out_sy = 0;
+    int padw() const { return pad_w_set ? pad_w : pad; }
+    bool plain() const { return !pad_w_set && !out_view; }
     long long pixels() const { return (long long)N * Ho * Wo; }
     size_t in_elems() const { return (size_t)N * H * W * C * D0 * D1 * D2; }
     size_t kernel_elems() const { return (size_t)kh * kw * C * M * D0 * D2 * D3; }
@@ -46,6 +59,9 @@ hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, f
 size_t forward_workspace_bytes(const ConvShape& s);
 int forward_auto(const ConvShape& s, const void* in, const void* kernel, float* out,
                  void* workspace, size_t workspace_bytes, hipStream_t stream);
+// the tuned 16-bit kernel, geometry overrides allowed (EUNSUPPORTED if it cannot run the shape)
+int forward_tuned16(const ConvShape& s, const void* in, const void* kernel, float* out,
+                    void* workspace, size_t workspace_bytes, hipStream_t stream);
 int status_from_hip(hipError_t err);
 
 // Backward pass (backward.hip): gradients with respect to input and kernel, fp32 results.

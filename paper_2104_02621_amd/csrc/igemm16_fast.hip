@@ -165,7 +165,7 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         const int n_rel = pgc / hw - n_first;
         const int rem = pgc - (pgc / hw) * hw;
         const int x = rem / P.Wo, y = rem - x * P.Wo;
-        const int ih0 = x * P.stride - P.pad, iw0 = y * P.stride - P.pad;
+        const int ih0 = x * P.stride - P.pad, iw0 = y * P.stride - P.pad_w;
         const bool ok = exists && lane < P.ntaps && (unsigned)(ih0 + tap_p) < (unsigned)P.H &&
                         (unsigned)(iw0 + tap_q) < (unsigned)P.W;
         tap_ok[j] = __builtin_amdgcn_ballot_w64(ok);
@@ -370,8 +370,13 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         const int pixel = pg0 + r / D1;
         if (pixel >= npix) continue;
         const int d1 = r % D1;
-        const long long orow_off =
-            (long long)pixel * P.M * caps_out + (long long)(d0 * D1 + d1) * P.D3;
+        long long orow_off = (long long)pixel * P.M * caps_out;
+        if (P.out_view) {  // the output pixels of this call interleave with other calls'
+            const int n = pixel / hw, rem = pixel - n * hw;
+            const int x = rem / P.Wo, y = rem - x * P.Wo;
+            orow_off = P.out_base + n * P.out_sn + x * P.out_sx + y * P.out_sy;
+        }
+        orow_off += (long long)(d0 * D1 + d1) * P.D3;
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
 #pragma unroll

@@ -101,6 +101,10 @@ struct IgemmParams {
     long long in_bytes;    // size of the input tensor
     long long kp_records;  // size of the repacked kernel in bytes
     int out16;             // element type of the final output (0 = fp32), see ConvShape
+    // tuned 16-bit kernel only (see ConvShape): column padding, strided output pixels
+    int pad_w;
+    int out_view;
+    long long out_base, out_sn, out_sx, out_sy;
 };
 
 // Shared launch helpers (igemm_conv.hip).  Repack: 16-byte chunks of `cw` valid K elements

@@ -365,6 +365,9 @@ Plan make_plan(const ConvShape& s, MfmaKernel which)
     P.in_bytes = (long long)s.in_elems() * (s.dtype == 0 ? 4 : 2);
     P.kp_records = (long long)pl.repack_bytes;
     P.out16 = s.out16;
+    P.pad_w = s.padw();
+    P.out_view = s.out_view ? 1 : 0;
+    P.out_base = s.out_base; P.out_sn = s.out_sn; P.out_sx = s.out_sx; P.out_sy = s.out_sy;
     return pl;
 }
 
@@ -536,6 +539,9 @@ bool mfma_tuned16_supported(const ConvShape& s)
 hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, float* out,
                        void* workspace, hipStream_t stream, MfmaKernel which)
 {
+    // geometry overrides exist in the tuned 16-bit kernel only
+    if (!s.plain() && !(which == MfmaKernel::Tuned16 && igemm16_fast_eligible(s)))
+        return hipErrorInvalidValue;
     if (which == MfmaKernel::Dma32 || (which == MfmaKernel::Auto && igemm32_dma_preferred(s)))
         return launch_dma32(s, in, kernel, out, workspace, stream);
     return launch_igemm(s, in, kernel, out, workspace, stream, which);

@@ -85,6 +85,12 @@ BWD_SHAPES = SMALL_SHAPES + [
     ("wg_empty", 2, 1, 1, 3, 2, 5, 5, 1, 2, 1, 8, 4, 4),
     ("wg_d16s3", 2, 10, 9, 20, 18, 3, 3, 3, 1, 1, 16, 16, 16),
     ("wg_many", 70, 5, 5, 4, 4, 2, 2, 1, 0, 1, 16, 8, 8),
+    # large enough for the strided input gradient to run as interleaved phase convolutions
+    # (16-bit): stride 2; stride 3 with a 2x2 window (one phase of pixels no window reaches);
+    # a non-square window with padding beyond its reach and a leading capsule index
+    ("ph_s2", 3, 80, 80, 4, 8, 3, 3, 2, 1, 1, 8, 8, 8),
+    ("ph_s3", 3, 120, 118, 4, 8, 2, 2, 3, 0, 1, 8, 4, 8),
+    ("ph_ns", 2, 90, 61, 3, 4, 4, 3, 2, 3, 2, 16, 8, 16),
 ]
 
 
