@@ -116,3 +116,44 @@ def test_strerror():
     assert cc.capscaps_strerror(cc.OK) == "success"
     for code in (cc.EINVAL, cc.EWORKSPACE, cc.EUNSUPPORTED, cc.EHIP, -99):
         assert cc.capscaps_strerror(code)
+
+
+@pytest.mark.parametrize("over", [dict(N=0), dict(M=0), dict(D2=-1), dict(stride=0), dict(pad=-1),
+                                  dict(kh=9), dict(dtype=3)])
+def test_backward_comparison_and_out16_entry_points_reject_bad_shapes(over):
+    a = _args(**over)
+    big = 1 << 30
+    assert cc.capscaps_conv_bwd_input(FAKE, FAKE, FAKE, *a, FAKE, big, None) == cc.EINVAL
+    assert cc.capscaps_conv_bwd_kernel(FAKE, FAKE, FAKE, *a, FAKE, big, None) == cc.EINVAL
+    assert cc.capscaps_conv_bwd_input_workspace_bytes(*a) == 0
+    assert cc.capscaps_conv_bwd_kernel_workspace_bytes(*a) == 0
+    assert cc.capscaps_scheme2_index_bytes(*a) == 0
+    assert cc.capscaps_scheme2_build_index(FAKE, big, *a, None) == cc.EINVAL
+    assert cc.capscaps_scheme2_fwd(FAKE, FAKE, FAKE, FAKE, big, *a, None) == cc.EINVAL
+    a16 = _args(**{**over, "dtype": over.get("dtype", cc.FP16)})
+    assert cc.capscaps_conv_fwd_out16(FAKE, FAKE, FAKE, *a16, FAKE, big, None) == cc.EINVAL
+    assert cc.capscaps_conv_fwd_out16_workspace_bytes(*a16) == 0
+
+
+def test_backward_pointer_and_workspace_checks():
+    a = _args(dtype=cc.FP16, D1=8, D2=8, D3=8)
+    need_i = cc.capscaps_conv_bwd_input_workspace_bytes(*a)
+    need_k = cc.capscaps_conv_bwd_kernel_workspace_bytes(*a)
+    assert need_i > 0 and need_k > 0 and need_i % 256 == 0
+    for fn, need in ((cc.capscaps_conv_bwd_input, need_i), (cc.capscaps_conv_bwd_kernel, need_k)):
+        assert fn(0, FAKE, FAKE, *a, FAKE, need, None) == cc.EINVAL
+        assert fn(FAKE, FAKE + 4, FAKE, *a, FAKE, need, None) == cc.EINVAL
+        assert fn(FAKE, FAKE, FAKE, *a, FAKE, need - 1, None) == cc.EWORKSPACE
+        assert fn(FAKE, FAKE, FAKE, *a, 0, 0, None) == cc.EWORKSPACE
+        assert fn(FAKE, FAKE, FAKE, *a, FAKE + 8, need, None) == cc.EINVAL
+    # 16-bit output is for 16-bit operands only
+    assert cc.capscaps_conv_fwd_out16(FAKE, FAKE, FAKE, *_args(), FAKE, 1 << 30, None) == cc.EINVAL
+    assert cc.capscaps_conv_fwd_out16_workspace_bytes(*_args()) == 0
+
+
+def test_scheme2_index_size_and_limits():
+    a = _args()
+    products = 2 * 6 * 6 * 4 * 3 * 3 * 3 * 1
+    assert cc.capscaps_scheme2_index_bytes(*a) == products * 12
+    # 2^31 or more input capsules: refused
+    assert cc.capscaps_scheme2_index_bytes(*_args(N=1 << 20, H=64, W=64, C=8)) == 0
