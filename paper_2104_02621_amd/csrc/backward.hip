@@ -297,6 +297,7 @@ size_t bwd_input_workspace_bytes(const ConvShape& s)
 size_t bwd_kernel_workspace_bytes(const ConvShape& s)
 {
     if (wgrad16_eligible(s)) return wgrad16_workspace_bytes(s);
+    if (wgrad32_eligible(s)) return wgrad32_workspace_bytes(s);
     return align256(s.in_elems() * elem_bytes(s)) + align256(spread_elems(s) * elem_bytes(s)) +
            align256(s.kernel_elems() * sizeof(float)) +
            forward_workspace_bytes(bwd_kernel_conv_shape(s));
@@ -410,6 +411,8 @@ int launch_bwd_kernel(const ConvShape& s, const void* input, const void* dout, f
 {
     if (wgrad16_eligible(s))
         return status_from_hip(launch_wgrad16(s, input, dout, dkernel, workspace, stream));
+    if (wgrad32_eligible(s))
+        return status_from_hip(launch_wgrad32(s, input, dout, dkernel, workspace, stream));
     const int eb = elem_bytes(s);
     char* ws = static_cast<char*>(workspace);
     void* in_t = ws;

@@ -152,5 +152,10 @@ bool wgrad16_eligible(const ConvShape& s);
 size_t wgrad16_workspace_bytes(const ConvShape& s);
 hipError_t launch_wgrad16(const ConvShape& s, const void* input, const void* dout, float* dkernel,
                           void* workspace, hipStream_t stream);
+// ... and for fp32, capsule heights D1 of 3, 4, 6, 8, 12 or 16 floats (wgrad32.hip).
+bool wgrad32_eligible(const ConvShape& s);
+size_t wgrad32_workspace_bytes(const ConvShape& s);
+hipError_t launch_wgrad32(const ConvShape& s, const void* input, const void* dout, float* dkernel,
+                          void* workspace, hipStream_t stream);
 
 }  // namespace capscaps

@@ -54,4 +54,25 @@ __device__ __forceinline__ void copy_to_lds_16B(rsrc_t rs, unsigned lds_base, un
         : "memory", "scc");
 }
 
+// Same with a run-time LDS address and DW = 3 or 4 dwords per lane (a 12-byte copy still lands
+// at a 16-byte lane stride in LDS and leaves the slot's fourth dword untouched).
+template <int DW>
+__device__ __forceinline__ void copy_to_lds_dwords(rsrc_t rs, unsigned lds_addr, unsigned voff,
+                                                   int soff)
+{
+    static_assert(DW == 3 || DW == 4, "12- or 16-byte copies");
+    const int lds_s = __builtin_amdgcn_readfirstlane((int)lds_addr);
+    const int soff_s = __builtin_amdgcn_readfirstlane(soff);
+    if (DW == 3)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx3 %1, %2, %3 offen lds"
+                     :
+                     : "s"(lds_s), "v"(voff), "s"(rs), "s"(soff_s)
+                     : "memory");
+    else
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                     :
+                     : "s"(lds_s), "v"(voff), "s"(rs), "s"(soff_s)
+                     : "memory");
+}
+
 }  // namespace capscaps

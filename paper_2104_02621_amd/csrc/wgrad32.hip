@@ -1,0 +1,454 @@
+// Kernel gradient of the capsule convolution for fp32 operands on the matrix cores: the same
+// per-tap GEMM as wgrad16.hip (rows (c,d2), columns (m,d3), K = (n,x,y,d1) over the output
+// pixels whose tap lies inside the image; the K_diff result of the paper's Algorithm 4 read as
+// the derivative of Algorithm 2's sum), for capsule heights D1 of 3, 4, 6, 8, 12 or 16 floats.
+//
+// A pre-pass writes capsule-transposed copies It[n][h][w][c][d0][d2][d1] and
+// Gt[n][x][y][m][d0][d3][d1], so the D1 contracted values of one (pixel, row) are contiguous.
+// Data moves in 16-byte LDS slots of CW = 3 or 4 floats ("chunks", D1 = CW * D1C): a 12-byte
+// buffer load lands at a 16-byte lane stride in LDS, so both widths read operands with one
+// 16-byte LDS load per lane and feed CW MFMA 32x32x2 instructions from it (element u of the
+// lower and of the upper half wave form the K pair of instruction u).
+//
+// fp32 layers have few rows and columns per tap (config 2: 96 x 96) and a very long K, so the
+// tile is small -- 64*NW rows x 32*TN columns, wave w owning rows 64w..64w+63 against all
+// columns -- and the K loop is split over image ranges (partial sums to scratch, added in a
+// fixed order by the shared reduction kernel).  Lane i of a wave copies row 64w+i: a fixed
+// lane offset plus the scalar offset of the pixel.  A stage is 4 chunks = 4/D1C pixels; ring of
+// 3 LDS stages, one barrier per stage, several workgroups per CU overlap copies and MFMAs.
+#include <hip/hip_runtime.h>
+
+#include "igemm_common.h"
+#include "lds_dma.h"
+
+namespace capscaps {
+namespace {
+
+constexpr int KCH = 4;  // chunks per row and stage
+constexpr int NB = 3;   // LDS stages in the ring
+
+struct Wgrad32Params {
+    const void* it;  // capsule-transposed input
+    const void* gt;  // capsule-transposed output gradient
+    float* out;      // dK, or partial sums [split][kernel elements]
+    int N, H, W, C, M, kw, stride, pad, D0, D1, D2, D3, Ho, Wo;
+    int D1C;         // chunks per capsule column: D1 = CW * D1C, D1C in {1, 2, 4}
+    int rows, cols;  // C*D2, M*D3
+    int row_tiles, col_tiles, ntaps;
+    int tiles;       // ntaps * D0 * row_tiles * col_tiles
+    int nsplit, imgs_per_split;
+    long long items;      // tiles * nsplit = workgroups
+    long long out_elems;  // elements of dK
+    long long it_img_bytes, gt_img_bytes;
+};
+
+// dst[x][b][a] = src[x][a][b] for matrices of A x B floats.  One thread per element.
+__global__ __launch_bounds__(256) void transpose_caps32_kernel(const float* __restrict__ src,
+                                                               float* __restrict__ dst, int A,
+                                                               int B, size_t total)
+{
+    const size_t id = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= total) return;
+    const int a = (int)(id % A);
+    const size_t rest = id / A;
+    const int b = (int)(rest % B);
+    const size_t mat = rest / B;
+    dst[id] = src[(mat * A + a) * B + b];
+}
+
+template <int CW, int TN, int NW>
+__global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
+{
+    constexpr int BM = 64 * NW, BN = 32 * TN, BNL = (BN + 63) / 64 * 64, TM = 2;
+    constexpr int A_BYTES = KCH * BM * 16, B_BYTES = KCH * BNL * 16;
+    constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int NBC = KCH * BNL / 64;  // column-side copies per stage, all waves
+    constexpr int BPW = NBC / NW;        // ... per wave
+    static_assert(NBC % NW == 0, "column copies divide evenly over the waves");
+    constexpr int NCOPY = KCH + BPW;     // copies per wave and stage
+    constexpr int OOB = (int)0x80000000u;
+    constexpr int VMCNT_KEEP = 0x0F70 | (NCOPY & 15) | ((NCOPY >> 4) << 14);
+
+    extern __shared__ char smem[];
+
+    // ---- which item: each XCD (workgroups are dealt to the 8 XCDs in turn) gets a contiguous
+    // range of items, image range slowest, so its resident workgroups read the same pixels
+    long long item = blockIdx.x;
+    {
+        const long long per = P.items / 8;
+        if (item < per * 8) item = (item % 8) * per + item / 8;
+    }
+    const int split = (int)(item / P.tiles);
+    int rest = (int)(item % P.tiles);
+    const int col_tile = rest % P.col_tiles;
+    rest /= P.col_tiles;
+    const int row_tile = rest % P.row_tiles;
+    rest /= P.row_tiles;
+    const int tap = rest % P.ntaps;
+    const int d0 = rest / P.ntaps;
+    const int tp = tap / P.kw, tq = tap - tp * P.kw;
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int h = lane >> 5, lr = lane & 31;
+
+    // ---- the pixels of this item: images [n0, n1), per image the rectangle of output pixels
+    // whose tap (tp, tq) reads a real input pixel
+    const int n0 = split * P.imgs_per_split;
+    const int n1 = n0 + P.imgs_per_split < P.N ? n0 + P.imgs_per_split : P.N;
+    const int s = P.stride;
+    int nx, ny, x_lo, y_lo;
+    {
+        const int tx = P.pad - tp, ty = P.pad - tq;
+        x_lo = tx > 0 ? (tx + s - 1) / s : 0;
+        y_lo = ty > 0 ? (ty + s - 1) / s : 0;
+        const int hx = P.H - 1 + tx, hy = P.W - 1 + ty;
+        int x_hi = hx >= 0 ? hx / s : -1, y_hi = hy >= 0 ? hy / s : -1;
+        if (x_hi > P.Ho - 1) x_hi = P.Ho - 1;
+        if (y_hi > P.Wo - 1) y_hi = P.Wo - 1;
+        nx = x_hi - x_lo + 1;
+        ny = y_hi - y_lo + 1;
+        if (nx <= 0 || ny <= 0) nx = ny = 0;
+    }
+    const int npix = (n1 - n0) * nx * ny;
+    const int ipix = P.C * P.D0 * P.D2 * P.D1 * 4;  // bytes per pixel of It / Gt
+    const int gpix = P.M * P.D0 * P.D3 * P.D1 * 4;
+    const int i_step = s * ipix, g_step = gpix;
+    const int i_rowjump = (s * P.W - (ny - 1) * s) * ipix, g_rowjump = (P.Wo - (ny - 1)) * gpix;
+    const int i_imgjump = (P.H * P.W - nx * s * P.W) * ipix, g_imgjump = (P.Ho * P.Wo - nx * P.Wo) * gpix;
+    int i_cur = ((x_lo * s - (P.pad - tp)) * P.W + (y_lo * s - (P.pad - tq))) * ipix;
+    int g_cur = (x_lo * P.Wo + y_lo) * gpix;
+    int left = npix, yl = ny, xl = nx;
+
+    const char* it_base = static_cast<const char*>(P.it) + (long long)n0 * P.it_img_bytes;
+    const char* gt_base = static_cast<const char*>(P.gt) + (long long)n0 * P.gt_img_bytes;
+    const rsrc_t rs_it = make_rsrc(it_base, (unsigned)((n1 - n0) * P.it_img_bytes));
+    const rsrc_t rs_gt = make_rsrc(gt_base, (unsigned)((n1 - n0) * P.gt_img_bytes));
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
+
+    // ---- per-lane constants: byte offset of the lane's row (column) within a pixel, or the
+    // out-of-range mark past the last row (column): those copy zeros
+    unsigned a_voff;
+    {
+        const int R = row_tile * BM + wave * 64 + lane;
+        const int c = R / P.D2, d2 = R - c * P.D2;
+        a_voff = R < P.rows ? (unsigned)((((c * P.D0 + d0) * P.D2 + d2) * P.D1) * 4) : (unsigned)OOB;
+    }
+    unsigned b_voff[BPW];
+#pragma unroll
+    for (int j = 0; j < BPW; ++j) {
+        const int blk = wave * BPW + j;                 // chunk blk / (BNL/64), column block blk % ..
+        const int jl = (blk % (BNL / 64)) * 64 + lane;  // column within the tile
+        const int J = col_tile * BN + jl;
+        const int m = J / P.D3, d3 = J - m * P.D3;
+        b_voff[j] = (jl < BN && J < P.cols)
+                        ? (unsigned)((((m * P.D0 + d0) * P.D3 + d3) * P.D1) * 4)
+                        : (unsigned)OOB;
+    }
+
+    const int pps = KCH / P.D1C;                     // pixels per stage
+    const int d1c_shift = P.D1C == 1 ? 0 : P.D1C == 2 ? 1 : 2;
+    const int nstages = (npix + pps - 1) / pps;
+    const int nstages_pad = (nstages + NB - 1) / NB * NB;  // surplus stages contract zeros
+
+    // copies of the next stage (scalar pixel walk: the stage's pixels, each the next valid
+    // output pixel of the tap's rectangle, image after image; past the last one zero fill)
+    auto issue_stage = [&](int slot) {
+        const unsigned stage = lds0 + slot * STAGE_BYTES;
+        int i_soff[KCH], g_soff[KCH];
+#pragma unroll
+        for (int j = 0; j < KCH; ++j) {
+            i_soff[j] = OOB;
+            g_soff[j] = OOB;
+            if (j < pps) {
+                if (left > 0) {
+                    i_soff[j] = i_cur;
+                    g_soff[j] = g_cur;
+                }
+                --left;
+                --yl;
+                if (yl != 0) {
+                    i_cur += i_step;
+                    g_cur += g_step;
+                } else {
+                    yl = ny;
+                    --xl;
+                    i_cur += i_rowjump;
+                    g_cur += g_rowjump;
+                    if (xl == 0) {
+                        xl = nx;
+                        i_cur += i_imgjump;
+                        g_cur += g_imgjump;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < KCH; ++q) {
+            const int slot_px = q >> d1c_shift, part = q - (slot_px << d1c_shift);
+            const int px = slot_px == 0 ? i_soff[0] : slot_px == 1 ? i_soff[1]
+                         : slot_px == 2 ? i_soff[2] : i_soff[3];
+            copy_to_lds_dwords<CW>(rs_it, stage + (q * BM + 64 * wave) * 16, a_voff,
+                                   px == OOB ? OOB : px + part * CW * 4);
+        }
+#pragma unroll
+        for (int j = 0; j < BPW; ++j) {
+            const int blk = wave * BPW + j;
+            const int q = blk / (BNL / 64);
+            const int slot_px = q >> d1c_shift, part = q - (slot_px << d1c_shift);
+            const int px = slot_px == 0 ? g_soff[0] : slot_px == 1 ? g_soff[1]
+                         : slot_px == 2 ? g_soff[2] : g_soff[3];
+            copy_to_lds_dwords<CW>(rs_gt, stage + A_BYTES + blk * 1024, b_voff[j],
+                                   px == OOB ? OOB : px + part * CW * 4);
+        }
+    };
+
+    float16v acc[TN][TM];
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+
+    auto compute_stage = [&](int slot) {
+        const char* stage = smem + slot * STAGE_BYTES;
+#pragma unroll
+        for (int t = 0; t < KCH / 2; ++t) {
+            // lanes 0..31 take chunk 2t, lanes 32..63 chunk 2t+1
+            float4v kb[TN], ia[TM];
+#pragma unroll
+            for (int a = 0; a < TN; ++a)
+                kb[a] = *reinterpret_cast<const float4v*>(
+                    stage + A_BYTES + ((2 * t + h) * BNL + a * 32 + lr) * 16);
+#pragma unroll
+            for (int b = 0; b < TM; ++b)
+                ia[b] = *reinterpret_cast<const float4v*>(
+                    stage + ((2 * t + h) * BM + 64 * wave + b * 32 + lr) * 16);
+#pragma unroll
+            for (int u = 0; u < CW; ++u)
+#pragma unroll
+                for (int a = 0; a < TN; ++a)
+#pragma unroll
+                    for (int b = 0; b < TM; ++b)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(kb[a][u], ia[b][u],
+                                                                         acc[a][b], 0, 0, 0);
+        }
+    };
+
+    // ---- prologue: two stages in flight, the first one landed
+    issue_stage(0);
+    issue_stage(1);
+    __builtin_amdgcn_s_waitcnt(VMCNT_KEEP);
+    __syncthreads();
+
+    // ---- main loop: copy stage s+2 into the slot read in iteration s-1, contract stage s
+    for (int st = 0; st < nstages_pad; st += NB) {
+        static_for<NB>([&](auto SLOT) {
+            constexpr int slot = decltype(SLOT)::value;
+            issue_stage((slot + 2) % NB);
+            compute_stage(slot);
+            __builtin_amdgcn_s_waitcnt(VMCNT_KEEP & 0xF0FF);
+            __syncthreads();
+        });
+    }
+    // the copies of the surplus stages still write (zeros) into this workgroup's LDS
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+
+    // ---- epilogue: lane (h, lr) of tile (a, b) holds in registers 4g..4g+3 the columns
+    // 8g + 4h + 0..3 of the tile for row lr of the tile
+    float* __restrict__ out = P.out + (long long)split * P.out_elems;
+    const long long caps = (long long)P.D0 * P.D2 * P.D3;
+    const bool st4 = (P.D3 & 3) == 0;
+#pragma unroll
+    for (int b = 0; b < TM; ++b) {
+        const int R = row_tile * BM + 64 * wave + b * 32 + lr;
+        if (R >= P.rows) continue;
+        const int c = R / P.D2, d2 = R - c * P.D2;
+        float* orow = out + ((long long)tap * P.C + c) * P.M * caps +
+                      ((long long)d0 * P.D2 + d2) * P.D3;
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int j0 = col_tile * BN + a * 32 + 8 * g + 4 * h;
+                if (st4) {
+                    if (j0 < P.cols) {
+                        const int m = j0 / P.D3, d3 = j0 - m * P.D3;
+                        float4v v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
+                                     acc[a][b][4 * g + 3]};
+                        *reinterpret_cast<float4v*>(orow + (long long)m * caps + d3) = v;
+                    }
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int j = j0 + u;
+                        if (j < P.cols) {
+                            const int m = j / P.D3, d3 = j - m * P.D3;
+                            orow[(long long)m * caps + d3] = acc[a][b][4 * g + u];
+                        }
+                    }
+                }
+            }
+        }
+    }
+}
+
+struct Wgrad32Plan {
+    Wgrad32Params P;
+    int cw, tn, nw;
+    size_t it_bytes, gt_bytes, partial_bytes;
+};
+
+int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b); }
+size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+// Valid floats per chunk: 4 or 3, such that a capsule column of D1 floats is 1, 2 or 4 chunks.
+int chunk_width(const ConvShape& s)
+{
+    for (int cw : {4, 3}) {
+        if (s.D1 % cw) continue;
+        const int d1c = s.D1 / cw;
+        if (d1c == 1 || d1c == 2 || d1c == 4) return cw;
+    }
+    return 0;
+}
+
+// Tiles and the split over images (host side, pure arithmetic).
+Wgrad32Plan make_plan(const ConvShape& s)
+{
+    Wgrad32Plan pl{};
+    Wgrad32Params& P = pl.P;
+    pl.cw = chunk_width(s);
+    P.N = s.N; P.H = s.H; P.W = s.W; P.C = s.C; P.M = s.M; P.kw = s.kw; P.stride = s.stride;
+    P.pad = s.pad; P.D0 = s.D0; P.D1 = s.D1; P.D2 = s.D2; P.D3 = s.D3; P.Ho = s.Ho; P.Wo = s.Wo;
+    P.D1C = pl.cw ? s.D1 / pl.cw : 1;
+    P.rows = s.C * s.D2;
+    P.cols = s.M * s.D3;
+    pl.tn = P.cols <= 32 ? 1 : P.cols <= 64 ? 2 : P.cols <= 96 ? 3 : 4;
+    pl.nw = P.rows <= 128 ? 2 : 4;
+    P.row_tiles = ceil_div_i(P.rows, 64 * pl.nw);
+    P.col_tiles = ceil_div_i(P.cols, 32 * pl.tn);
+    P.ntaps = s.kh * s.kw;
+    P.tiles = P.ntaps * s.D0 * P.row_tiles * P.col_tiles;
+    P.out_elems = (long long)s.kernel_elems();
+    P.it_img_bytes = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 4;
+    P.gt_img_bytes = (long long)s.Ho * s.Wo * s.M * s.D0 * s.D1 * s.D3 * 4;
+    pl.it_bytes = (size_t)s.N * P.it_img_bytes;
+    pl.gt_bytes = (size_t)s.N * P.gt_img_bytes;
+
+    // Images per workgroup: cost = (rounds of resident workgroups) x (pixels per workgroup +
+    // a fixed cost per workgroup in pixel units); byte offsets within a workgroup's images stay
+    // below 2^31 and the partial sums below 1 GiB.  About 1024 workgroups are resident.
+    const long long img_max = P.it_img_bytes > P.gt_img_bytes ? P.it_img_bytes : P.gt_img_bytes;
+    long long imgs_cap = ((1LL << 31) - 1) / (img_max > 0 ? img_max : 1);
+    if (imgs_cap > s.N) imgs_cap = s.N;
+    const double pix_per_img = (double)s.Ho * s.Wo;
+    const double fixed = 64.0;
+    double best = 0;
+    int best_imgs = (int)imgs_cap;
+    for (int imgs = (int)imgs_cap; imgs >= 1; --imgs) {
+        const int nsplit = ceil_div_i(s.N, imgs);
+        if (nsplit > 1 && (double)nsplit * P.out_elems * 4 > (double)(1 << 30)) break;
+        const long long items = (long long)nsplit * P.tiles;
+        const double rounds = (double)((items + 1023) / 1024);
+        const double cost = rounds * (imgs * pix_per_img + fixed);
+        if (imgs == (int)imgs_cap || cost < best * 0.98) {
+            best = cost;
+            best_imgs = imgs;
+        }
+    }
+    P.imgs_per_split = best_imgs < 1 ? 1 : best_imgs;
+    P.nsplit = ceil_div_i(s.N, P.imgs_per_split);
+    P.items = (long long)P.nsplit * P.tiles;
+    pl.partial_bytes = P.nsplit > 1 ? (size_t)P.nsplit * P.out_elems * sizeof(float) : 0;
+    return pl;
+}
+
+hipError_t launch_transpose32(const void* src, void* dst, size_t nmat, int A, int B,
+                              hipStream_t stream)
+{
+    const size_t total = nmat * (size_t)A * B;
+    const size_t blocks = (total + 255) / 256;
+    if (blocks == 0 || blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+    transpose_caps32_kernel<<<(unsigned)blocks, 256, 0, stream>>>(
+        static_cast<const float*>(src), static_cast<float*>(dst), A, B, total);
+    return hipGetLastError();
+}
+
+template <int CW, int TN, int NW>
+hipError_t launch_one(const Wgrad32Params& P, hipStream_t stream)
+{
+    constexpr int BM = 64 * NW, BNL = (32 * TN + 63) / 64 * 64;
+    auto kern = wgrad32_kernel<CW, TN, NW>;
+    const size_t lds_bytes = (size_t)NB * KCH * (BM + BNL) * 16;
+    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize,
+                                         (int)lds_bytes);
+    if (err != hipSuccess) return err;
+    kern<<<dim3((unsigned)P.items), dim3(64 * NW), lds_bytes, stream>>>(P);
+    return hipGetLastError();
+}
+
+template <int CW, int NW>
+hipError_t launch_tn(const Wgrad32Params& P, int tn, hipStream_t stream)
+{
+    switch (tn) {
+        case 1: return launch_one<CW, 1, NW>(P, stream);
+        case 2: return launch_one<CW, 2, NW>(P, stream);
+        case 3: return launch_one<CW, 3, NW>(P, stream);
+        default: return launch_one<CW, 4, NW>(P, stream);
+    }
+}
+
+}  // namespace
+
+bool wgrad32_eligible(const ConvShape& s)
+{
+    if (s.dtype != 0) return false;
+    if (chunk_width(s) == 0) return false;
+    // 31-bit byte offsets within one image of either tensor, 31-bit counts
+    const long long it_img = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 4;
+    const long long gt_img = (long long)s.Ho * s.Wo * s.M * s.D0 * s.D1 * s.D3 * 4;
+    if (it_img >= (1LL << 31) || gt_img >= (1LL << 31)) return false;
+    if ((long long)s.stride * s.W * s.C * s.D0 * s.D1 * s.D2 * 4 >= (1LL << 30)) return false;
+    if ((long long)s.C * s.D2 >= (1 << 24) || (long long)s.M * s.D3 >= (1 << 24)) return false;
+    const long long tiles = (long long)s.kh * s.kw * s.D0 * (((long long)s.C * s.D2 + 127) / 128) *
+                            (((long long)s.M * s.D3 + 31) / 32);
+    if (tiles * s.N >= (1LL << 31)) return false;
+    return true;
+}
+
+size_t wgrad32_workspace_bytes(const ConvShape& s)
+{
+    const Wgrad32Plan pl = make_plan(s);
+    return align256(pl.it_bytes) + align256(pl.gt_bytes) + pl.partial_bytes;
+}
+
+hipError_t launch_wgrad32(const ConvShape& s, const void* input, const void* dout, float* dkernel,
+                          void* workspace, hipStream_t stream)
+{
+    Wgrad32Plan pl = make_plan(s);
+    char* ws = static_cast<char*>(workspace);
+    void* it = ws;
+    void* gt = ws + align256(pl.it_bytes);
+    float* partial = reinterpret_cast<float*>(ws + align256(pl.it_bytes) + align256(pl.gt_bytes));
+    hipError_t err = launch_transpose32(input, it, (size_t)s.N * s.H * s.W * s.C * s.D0, s.D1, s.D2,
+                                        stream);
+    if (err != hipSuccess) return err;
+    err = launch_transpose32(dout, gt, (size_t)s.N * s.Ho * s.Wo * s.M * s.D0, s.D1, s.D3, stream);
+    if (err != hipSuccess) return err;
+    pl.P.it = it;
+    pl.P.gt = gt;
+    pl.P.out = pl.P.nsplit > 1 ? partial : dkernel;
+    if (pl.cw == 3)
+        err = pl.nw == 4 ? launch_tn<3, 4>(pl.P, pl.tn, stream) : launch_tn<3, 2>(pl.P, pl.tn, stream);
+    else
+        err = pl.nw == 4 ? launch_tn<4, 4>(pl.P, pl.tn, stream) : launch_tn<4, 2>(pl.P, pl.tn, stream);
+    if (err != hipSuccess) return err;
+    if (pl.P.nsplit > 1)
+        err = launch_splitk_reduce(partial, dkernel, pl.P.out_elems, pl.P.nsplit, stream);
+    return err;
+}
+
+}  // namespace capscaps

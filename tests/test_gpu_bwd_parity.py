@@ -85,6 +85,11 @@ BWD_SHAPES = SMALL_SHAPES + [
     ("wg_empty", 2, 1, 1, 3, 2, 5, 5, 1, 2, 1, 8, 4, 4),
     ("wg_d16s3", 2, 10, 9, 20, 18, 3, 3, 3, 1, 1, 16, 16, 16),
     ("wg_many", 70, 5, 5, 4, 4, 2, 2, 1, 0, 1, 16, 8, 8),
+    # for the fp32 kernel-gradient kernel: capsule heights of 6 and 12 floats (two and four
+    # chunks of 3), several row and column tiles with ragged ends
+    ("wg32_d6", 2, 6, 6, 3, 5, 3, 3, 1, 1, 2, 6, 4, 3),
+    ("wg32_d12", 2, 5, 5, 2, 3, 2, 2, 2, 0, 1, 12, 5, 4),
+    ("wg32_rows", 2, 6, 6, 40, 30, 3, 3, 1, 1, 1, 4, 8, 8),
     # large enough for the strided input gradient to run as interleaved phase convolutions
     # (16-bit): stride 2; stride 3 with a 2x2 window (one phase of pixels no window reaches);
     # a non-square window with padding beyond its reach and a leading capsule index
