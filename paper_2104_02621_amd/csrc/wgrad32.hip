@@ -36,7 +36,7 @@ struct Wgrad32Params {
     int rows, cols;  // C*D2, M*D3
     int row_tiles, col_tiles, ntaps;
     int tiles;       // ntaps * D0 * row_tiles * col_tiles
-    int nsplit, imgs_per_split;
+    int nsplit;           // ranges the K loop (a tap's valid output pixels) is cut into
     long long items;      // tiles * nsplit = workgroups
     long long out_elems;  // elements of dK
     long long it_img_bytes, gt_img_bytes;
@@ -92,10 +92,9 @@ __global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int h = lane >> 5, lr = lane & 31;
 
-    // ---- the pixels of this item: images [n0, n1), per image the rectangle of output pixels
-    // whose tap (tp, tq) reads a real input pixel
-    const int n0 = split * P.imgs_per_split;
-    const int n1 = n0 + P.imgs_per_split < P.N ? n0 + P.imgs_per_split : P.N;
+    // ---- the pixels of this item.  Per image the output pixels whose tap (tp, tq) reads a
+    // real input pixel form a rectangle; the rectangles of all images, image after image, row
+    // after row, are one sequence, of which this item contracts the range [t0, t1).
     const int s = P.stride;
     int nx, ny, x_lo, y_lo;
     {
@@ -110,15 +109,28 @@ __global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
         ny = y_hi - y_lo + 1;
         if (nx <= 0 || ny <= 0) nx = ny = 0;
     }
-    const int npix = (n1 - n0) * nx * ny;
+    // every tap's sequence is cut into nsplit equal ranges
+    const long long rect = (long long)nx * ny, total = rect * P.N;
+    const long long tps = (total + P.nsplit - 1) / P.nsplit;
+    long long t0 = (long long)split * tps;
+    if (t0 > total) t0 = total;
+    long long t1 = t0 + tps;
+    if (t1 > total) t1 = total;
+    const int npix = (int)(t1 - t0);
+    const int n0 = npix > 0 ? (int)(t0 / rect) : 0;
+    const int n_last = npix > 0 ? (int)((t1 - 1) / rect) : n0;
+    const int r0 = npix > 0 ? (int)(t0 - (long long)n0 * rect) : 0;  // position in image n0
+    const int xs = ny > 0 ? r0 / ny : 0, ys = ny > 0 ? r0 - xs * ny : 0;
     const int ipix = P.C * P.D0 * P.D2 * P.D1 * 4;  // bytes per pixel of It / Gt
     const int gpix = P.M * P.D0 * P.D3 * P.D1 * 4;
     const int i_step = s * ipix, g_step = gpix;
     const int i_rowjump = (s * P.W - (ny - 1) * s) * ipix, g_rowjump = (P.Wo - (ny - 1)) * gpix;
     const int i_imgjump = (P.H * P.W - nx * s * P.W) * ipix, g_imgjump = (P.Ho * P.Wo - nx * P.Wo) * gpix;
-    int i_cur = ((x_lo * s - (P.pad - tp)) * P.W + (y_lo * s - (P.pad - tq))) * ipix;
-    int g_cur = (x_lo * P.Wo + y_lo) * gpix;
-    int left = npix, yl = ny, xl = nx;
+    // offsets are relative to image n0
+    int i_cur = (((x_lo + xs) * s - (P.pad - tp)) * P.W + ((y_lo + ys) * s - (P.pad - tq))) * ipix;
+    int g_cur = ((x_lo + xs) * P.Wo + y_lo + ys) * gpix;
+    int left = npix, yl = ny - ys, xl = nx - xs;
+    const int n1 = n_last + 1;
 
     const char* it_base = static_cast<const char*>(P.it) + (long long)n0 * P.it_img_bytes;
     const char* gt_base = static_cast<const char*>(P.gt) + (long long)n0 * P.gt_img_bytes;
@@ -314,7 +326,19 @@ int chunk_width(const ConvShape& s)
     return 0;
 }
 
-// Tiles and the split over images (host side, pure arithmetic).
+// Fewest ranges such that the images one range touches (N/nsplit + 3) stay below 2^31 bytes;
+// 0 if a single image is already too large for that.
+long long split_lower_bound(const ConvShape& s)
+{
+    const long long it_img = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 4;
+    const long long gt_img = (long long)s.Ho * s.Wo * s.M * s.D0 * s.D1 * s.D3 * 4;
+    const long long img_max = it_img > gt_img ? it_img : gt_img;
+    const long long imgs_cap = ((1LL << 31) - 1) / (img_max > 0 ? img_max : 1);
+    if (imgs_cap < 4) return 0;
+    return (s.N + (imgs_cap - 3) - 1) / (imgs_cap - 3);
+}
+
+// Tiles and the split of the K loop (host side, pure arithmetic).
 Wgrad32Plan make_plan(const ConvShape& s)
 {
     Wgrad32Plan pl{};
@@ -337,29 +361,26 @@ Wgrad32Plan make_plan(const ConvShape& s)
     pl.it_bytes = (size_t)s.N * P.it_img_bytes;
     pl.gt_bytes = (size_t)s.N * P.gt_img_bytes;
 
-    // Images per workgroup: cost = (rounds of resident workgroups) x (pixels per workgroup +
-    // a fixed cost per workgroup in pixel units); byte offsets within a workgroup's images stay
-    // below 2^31 and the partial sums below 1 GiB.  About 1024 workgroups are resident.
-    const long long img_max = P.it_img_bytes > P.gt_img_bytes ? P.it_img_bytes : P.gt_img_bytes;
-    long long imgs_cap = ((1LL << 31) - 1) / (img_max > 0 ? img_max : 1);
-    if (imgs_cap > s.N) imgs_cap = s.N;
-    const double pix_per_img = (double)s.Ho * s.Wo;
-    const double fixed = 64.0;
-    double best = 0;
-    int best_imgs = (int)imgs_cap;
-    for (int imgs = (int)imgs_cap; imgs >= 1; --imgs) {
-        const int nsplit = ceil_div_i(s.N, imgs);
-        if (nsplit > 1 && (double)nsplit * P.out_elems * 4 > (double)(1 << 30)) break;
-        const long long items = (long long)nsplit * P.tiles;
-        const double rounds = (double)((items + 1023) / 1024);
-        const double cost = rounds * (imgs * pix_per_img + fixed);
-        if (imgs == (int)imgs_cap || cost < best * 0.98) {
-            best = cost;
-            best_imgs = imgs;
-        }
-    }
-    P.imgs_per_split = best_imgs < 1 ? 1 : best_imgs;
-    P.nsplit = ceil_div_i(s.N, P.imgs_per_split);
+    // Split of the K loop (a tap's valid output pixels, at most N*Ho*Wo) over workgroups.  The
+    // workgroups resident at a time are bounded by LDS and registers; the split aims at one
+    // full round of them and keeps at least 16 stages per workgroup.  A range of N*rect/nsplit
+    // pixels touches at most N/nsplit + 3 images: their bytes must stay below 2^31 (a lower
+    // bound on nsplit), and the partial sums below 1 GiB (an upper bound).
+    const size_t lds = (size_t)NB * KCH * (64 * pl.nw + (32 * pl.tn + 63) / 64 * 64) * 16;
+    long long per_cu = (long long)(160 * 1024 / lds);
+    if (per_cu > 12 / pl.nw) per_cu = 12 / pl.nw;  // three waves per SIMD by registers
+    if (per_cu < 1) per_cu = 1;
+    const long long slots = 256 * per_cu;
+    const long long full = (long long)s.N * s.Ho * s.Wo;
+    long long want = slots / P.tiles;
+    if (want < 1) want = 1;
+    const long long min_pix = 16LL * (KCH / P.D1C);
+    if (want > (full + min_pix - 1) / min_pix) want = (full + min_pix - 1) / min_pix;
+    if (want > 3072) want = 3072;
+    while (want > 1 && (double)want * P.out_elems * 4 > (double)(1 << 30)) --want;
+    const long long lo = split_lower_bound(s);
+    if (want < lo) want = lo;
+    P.nsplit = (int)want;
     P.items = (long long)P.nsplit * P.tiles;
     pl.partial_bytes = P.nsplit > 1 ? (size_t)P.nsplit * P.out_elems * sizeof(float) : 0;
     return pl;
@@ -415,7 +436,11 @@ bool wgrad32_eligible(const ConvShape& s)
     if ((long long)s.C * s.D2 >= (1 << 24) || (long long)s.M * s.D3 >= (1 << 24)) return false;
     const long long tiles = (long long)s.kh * s.kw * s.D0 * (((long long)s.C * s.D2 + 127) / 128) *
                             (((long long)s.M * s.D3 + 31) / 32);
-    if (tiles * s.N >= (1LL << 31)) return false;
+    const long long lo = split_lower_bound(s);
+    if (lo == 0 || lo > 3072) return false;
+    if ((double)lo * (double)s.kernel_elems() * 4 > (double)(1 << 30) && lo > 1) return false;
+    if (tiles * 3072 >= (1LL << 31)) return false;  // the split never exceeds 3072 ranges
+    if ((long long)s.N * s.Ho * s.Wo >= (1LL << 31)) return false;  // pixel counts are 32-bit
     return true;
 }
 
