@@ -24,8 +24,12 @@
 namespace capscaps {
 namespace {
 
-constexpr int KCH = 4;  // chunks per row and stage
-constexpr int NB = 3;   // LDS stages in the ring
+// KCH chunks per row and stage (2 for the two-wave tile unless a capsule column is 4 chunks,
+// else 4), ring of NB stages:
+// small stages keep the LDS footprint of a workgroup low, so that two or more waves share each
+// SIMD and one wave's copies and scalar work run under another's MFMAs.
+constexpr int stage_chunks(int d1c, int nw) { return d1c == 4 || nw == 4 ? 4 : 2; }
+constexpr int ring_depth(int kch) { return kch == 2 ? 4 : 3; }
 
 struct Wgrad32Params {
     const void* it;  // capsule-transposed input
@@ -56,9 +60,10 @@ __global__ __launch_bounds__(256) void transpose_caps32_kernel(const float* __re
     dst[id] = src[(mat * A + a) * B + b];
 }
 
-template <int CW, int TN, int NW>
+template <int CW, int TN, int NW, int KCH>
 __global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
 {
+    constexpr int NB = ring_depth(KCH);
     constexpr int BM = 64 * NW, BN = 32 * TN, BNL = (BN + 63) / 64 * 64, TM = 2;
     constexpr int A_BYTES = KCH * BM * 16, B_BYTES = KCH * BNL * 16;
     constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
@@ -67,7 +72,10 @@ __global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
     static_assert(NBC % NW == 0, "column copies divide evenly over the waves");
     constexpr int NCOPY = KCH + BPW;     // copies per wave and stage
     constexpr int OOB = (int)0x80000000u;
-    constexpr int VMCNT_KEEP = 0x0F70 | (NCOPY & 15) | ((NCOPY >> 4) << 14);
+    // at a barrier the copies of the NB-2 most recent stages may still be in flight
+    constexpr int KEEP = (NB - 2) * NCOPY;
+    static_assert(KEEP < 64, "vmcnt is a 6-bit counter");
+    constexpr int VMCNT_KEEP = 0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14);
 
     extern __shared__ char smem[];
 
@@ -198,8 +206,9 @@ __global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
 #pragma unroll
         for (int q = 0; q < KCH; ++q) {
             const int slot_px = q >> d1c_shift, part = q - (slot_px << d1c_shift);
-            const int px = slot_px == 0 ? i_soff[0] : slot_px == 1 ? i_soff[1]
-                         : slot_px == 2 ? i_soff[2] : i_soff[3];
+            int px = i_soff[0];
+#pragma unroll
+            for (int k = 1; k < KCH; ++k) px = slot_px == k ? i_soff[k] : px;
             copy_to_lds_dwords<CW>(rs_it, stage + (q * BM + 64 * wave) * 16, a_voff,
                                    px == OOB ? OOB : px + part * CW * 4);
         }
@@ -208,8 +217,9 @@ __global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
             const int blk = wave * BPW + j;
             const int q = blk / (BNL / 64);
             const int slot_px = q >> d1c_shift, part = q - (slot_px << d1c_shift);
-            const int px = slot_px == 0 ? g_soff[0] : slot_px == 1 ? g_soff[1]
-                         : slot_px == 2 ? g_soff[2] : g_soff[3];
+            int px = g_soff[0];
+#pragma unroll
+            for (int k = 1; k < KCH; ++k) px = slot_px == k ? g_soff[k] : px;
             copy_to_lds_dwords<CW>(rs_gt, stage + A_BYTES + blk * 1024, b_voff[j],
                                    px == OOB ? OOB : px + part * CW * 4);
         }
@@ -248,18 +258,19 @@ __global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
         }
     };
 
-    // ---- prologue: two stages in flight, the first one landed
-    issue_stage(0);
-    issue_stage(1);
+    // ---- prologue: NB-1 stages in flight, the first one landed
+    static_for<NB - 1>([&](auto S0) { issue_stage(decltype(S0)::value); });
     __builtin_amdgcn_s_waitcnt(VMCNT_KEEP);
     __syncthreads();
 
-    // ---- main loop: copy stage s+2 into the slot read in iteration s-1, contract stage s
+    // ---- main loop: copy stage s+NB-1 into the slot read in iteration s-1, contract stage s
     for (int st = 0; st < nstages_pad; st += NB) {
         static_for<NB>([&](auto SLOT) {
             constexpr int slot = decltype(SLOT)::value;
-            issue_stage((slot + 2) % NB);
+            issue_stage((slot + NB - 1) % NB);
             compute_stage(slot);
+            // this wave's copies of the next stage have landed, its reads of this stage are
+            // done; after the barrier both hold for every wave
             __builtin_amdgcn_s_waitcnt(VMCNT_KEEP & 0xF0FF);
             __syncthreads();
         });
@@ -366,7 +377,8 @@ Wgrad32Plan make_plan(const ConvShape& s)
     // full round of them and keeps at least 16 stages per workgroup.  A range of N*rect/nsplit
     // pixels touches at most N/nsplit + 3 images: their bytes must stay below 2^31 (a lower
     // bound on nsplit), and the partial sums below 1 GiB (an upper bound).
-    const size_t lds = (size_t)NB * KCH * (64 * pl.nw + (32 * pl.tn + 63) / 64 * 64) * 16;
+    const int kch = stage_chunks(P.D1C, pl.nw);
+    const size_t lds = (size_t)ring_depth(kch) * kch * (64 * pl.nw + (32 * pl.tn + 63) / 64 * 64) * 16;
     long long per_cu = (long long)(160 * 1024 / lds);
     if (per_cu > 12 / pl.nw) per_cu = 12 / pl.nw;  // three waves per SIMD by registers
     if (per_cu < 1) per_cu = 1;
@@ -374,7 +386,7 @@ Wgrad32Plan make_plan(const ConvShape& s)
     const long long full = (long long)s.N * s.Ho * s.Wo;
     long long want = slots / P.tiles;
     if (want < 1) want = 1;
-    const long long min_pix = 16LL * (KCH / P.D1C);
+    const long long min_pix = 16LL * (kch / P.D1C);
     if (want > (full + min_pix - 1) / min_pix) want = (full + min_pix - 1) / min_pix;
     if (want > 3072) want = 3072;
     while (want > 1 && (double)want * P.out_elems * 4 > (double)(1 << 30)) --want;
@@ -397,18 +409,28 @@ hipError_t launch_transpose32(const void* src, void* dst, size_t nmat, int A, in
     return hipGetLastError();
 }
 
-template <int CW, int TN, int NW>
-hipError_t launch_one(const Wgrad32Params& P, hipStream_t stream)
+template <int CW, int TN, int NW, int KCH>
+hipError_t launch_kch(const Wgrad32Params& P, hipStream_t stream)
 {
     constexpr int BM = 64 * NW, BNL = (32 * TN + 63) / 64 * 64;
-    auto kern = wgrad32_kernel<CW, TN, NW>;
-    const size_t lds_bytes = (size_t)NB * KCH * (BM + BNL) * 16;
+    auto kern = wgrad32_kernel<CW, TN, NW, KCH>;
+    const size_t lds_bytes = (size_t)ring_depth(KCH) * KCH * (BM + BNL) * 16;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize,
                                          (int)lds_bytes);
     if (err != hipSuccess) return err;
     kern<<<dim3((unsigned)P.items), dim3(64 * NW), lds_bytes, stream>>>(P);
     return hipGetLastError();
+}
+
+template <int CW, int TN, int NW>
+hipError_t launch_one(const Wgrad32Params& P, hipStream_t stream)
+{
+    if constexpr (NW == 4)
+        return launch_kch<CW, TN, NW, 4>(P, stream);
+    else
+        return P.D1C == 4 ? launch_kch<CW, TN, NW, 4>(P, stream)
+                          : launch_kch<CW, TN, NW, 2>(P, stream);
 }
 
 template <int CW, int NW>
