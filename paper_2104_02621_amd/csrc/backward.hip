@@ -210,6 +210,7 @@ ConvShape bwd_input_phase_shape(const ConvShape& s, const PhaseDim& ph, const Ph
     f.out_sx = (long long)s.stride * s.W * pix;
     f.out_sy = (long long)s.stride * pix;
     f.out_base = ((long long)(s.stride * ph.lo + a - s.pad) * s.W + (s.stride * pw.lo + b - s.pad)) * pix;
+    f.out_alloc = (long long)s.in_elems();
     return f;
 }
 // every phase that has both pixels and taps must fit the tuned kernel and fill the chip

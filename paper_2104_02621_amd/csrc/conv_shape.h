@@ -26,6 +26,7 @@ struct ConvShape {
     int pad_w = 0;
     bool out_view = false;
     long long out_base = 0, out_sn = 0, out_sx = 0, out_sy = 0;
+    long long out_alloc = 0;  // with out_view: elements of the whole tensor `out` points into
     int padw() const { return pad_w_set ? pad_w : pad; }
     bool plain() const { return !pad_w_set && !out_view; }
     long long pixels() const { return (long long)N * Ho * Wo; }

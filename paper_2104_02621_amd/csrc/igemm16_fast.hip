@@ -358,25 +358,84 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     __builtin_amdgcn_s_waitcnt(0x0F70);
 
     // ---- epilogue: lane (h, lr) of MFMA tile (a, b) holds in registers 4g..4g+3 the columns
-    // 8g + 4h + 0..3 of that tile for its output row lr.  Columns advance in steps of 8, so
-    // (m, d3) of a column is found by shifts when D3 is a power of two, by division otherwise.
+    // 8g + 4h + 0..3 of that tile for its output row lr.
     float* __restrict__ out = P.out;
     const int caps_out = P.D0 * D1 * P.D3;
-    const bool d3_pow2 = (P.D3 & (P.D3 - 1)) == 0;
     const int d3_shift = 31 - __builtin_clz(P.D3);
+    // element offset of an output pixel
+    auto pixel_offset = [&](int pixel) -> long long {
+        if (!P.out_view) return (long long)pixel * P.M * caps_out;
+        // the output pixels of this call interleave with other calls'
+        const int n = pixel / hw, rem = pixel - n * hw;
+        const int x = rem / P.Wo, y = rem - x * P.Wo;
+        return P.out_base + n * P.out_sn + x * P.out_sx + y * P.out_sy;
+    };
+    if (P.fast_store && col0 + BN <= P.cols) {
+        // Whole column tile, D3 in {4, 8, 16, 32} (the host's test): the position of a store is
+        // (lane part) + (part that depends on a and g only), without carries between the two.
+        // So each lane keeps one 32-bit byte offset per row tile b, relative to the tile's first
+        // pixel; the (a, g) part is a scalar offset of a buffer store, and rows past the last
+        // pixel carry the out-of-range mark, which the range check drops.  No per-store vector
+        // arithmetic is left (the general form below costs about 50 instructions per store).
+        constexpr int ES = OUT16 ? 2 : 4;
+        const long long tile_base = pixel_offset(pg0);
+        const int jl = col0 + wn * WN + 4 * h;
+        const int lane_col = (jl >> d3_shift) * caps_out + (jl & (P.D3 - 1));
+        unsigned voff[TM];
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+            const int r = wm * WM + b * 32 + lr;
+            const int pixel = pg0 + r / D1;
+            const int d1 = r % D1;
+            const long long rel = pixel_offset(pixel < npix ? pixel : pg0) - tile_base +
+                                  (d0 * D1 + d1) * P.D3 + lane_col;
+            voff[b] = pixel < npix ? (unsigned)(rel * ES) : 0x80000000u;
+        }
+        long long bytes_left = (P.out_alloc - tile_base) * ES;
+        if (bytes_left > 0x7fffffffLL) bytes_left = 0x7fffffffLL;
+        const unsigned long long base_addr =
+            reinterpret_cast<unsigned long long>(out) + (unsigned long long)(tile_base * ES);
+        const unsigned base_lo = __builtin_amdgcn_readfirstlane((int)(unsigned)base_addr);
+        const unsigned base_hi = __builtin_amdgcn_readfirstlane((int)(unsigned)(base_addr >> 32));
+        const __amdgpu_buffer_rsrc_t rs_out = __builtin_amdgcn_make_buffer_rsrc(
+            reinterpret_cast<void*>(((unsigned long long)base_hi << 32) | base_lo), 0,
+            __builtin_amdgcn_readfirstlane((int)bytes_left), 0x00020000);
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int delta = a * 32 + 8 * g;
+                const int soff = ((delta >> d3_shift) * caps_out + (delta & (P.D3 - 1))) * ES;
+#pragma unroll
+                for (int b = 0; b < TM; ++b) {
+                    const float4v v = {acc[a][b][4 * g], acc[a][b][4 * g + 1],
+                                       acc[a][b][4 * g + 2], acc[a][b][4 * g + 3]};
+                    if constexpr (OUT16) {
+                        typedef unsigned int u2 __attribute__((ext_vector_type(2)));
+                        const u2 w = {(unsigned)round_to_16(v[0], OUT_KIND) |
+                                          ((unsigned)round_to_16(v[1], OUT_KIND) << 16),
+                                      (unsigned)round_to_16(v[2], OUT_KIND) |
+                                          ((unsigned)round_to_16(v[3], OUT_KIND) << 16)};
+                        __builtin_amdgcn_raw_buffer_store_b64(w, rs_out, voff[b], soff, 0);
+                    } else {
+                        __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(chunk_t, v),
+                                                               rs_out, voff[b], soff, 0);
+                    }
+                }
+            }
+        }
+        return;
+    }
+    // general form: ragged column tile, other D3.  Columns advance in steps of 8, so (m, d3) of
+    // a column is found by shifts when D3 is a power of two, by division otherwise.
+    const bool d3_pow2 = (P.D3 & (P.D3 - 1)) == 0;
 #pragma unroll
     for (int b = 0; b < TM; ++b) {
         const int r = wm * WM + b * 32 + lr;
         const int pixel = pg0 + r / D1;
         if (pixel >= npix) continue;
         const int d1 = r % D1;
-        long long orow_off = (long long)pixel * P.M * caps_out;
-        if (P.out_view) {  // the output pixels of this call interleave with other calls'
-            const int n = pixel / hw, rem = pixel - n * hw;
-            const int x = rem / P.Wo, y = rem - x * P.Wo;
-            orow_off = P.out_base + n * P.out_sn + x * P.out_sx + y * P.out_sy;
-        }
-        orow_off += (long long)(d0 * D1 + d1) * P.D3;
+        const long long orow_off = pixel_offset(pixel) + (long long)(d0 * D1 + d1) * P.D3;
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
 #pragma unroll

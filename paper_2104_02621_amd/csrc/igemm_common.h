@@ -105,6 +105,11 @@ struct IgemmParams {
     int pad_w;
     int out_view;
     long long out_base, out_sn, out_sx, out_sy;
+    // its epilogue may use buffer stores with 32-bit offsets from the tile's first pixel
+    // (host-side test of D3 and of the tile's extent in the output); elements of the tensor
+    // `out` points into
+    int fast_store;
+    long long out_alloc;
 };
 
 // Shared launch helpers (igemm_conv.hip).  Repack: 16-byte chunks of `cw` valid K elements

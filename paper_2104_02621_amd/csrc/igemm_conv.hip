@@ -368,6 +368,25 @@ Plan make_plan(const ConvShape& s, MfmaKernel which)
     P.pad_w = s.padw();
     P.out_view = s.out_view ? 1 : 0;
     P.out_base = s.out_base; P.out_sn = s.out_sn; P.out_sx = s.out_sx; P.out_sy = s.out_sy;
+    P.out_alloc = s.out_view ? s.out_alloc : P.out_elems;
+    {
+        // the tuned kernel's buffer-store epilogue: byte offsets from a tile's first output
+        // pixel (a tile holds 256/D1 consecutive pixels, which may reach into following images)
+        // plus one pixel's extent must stay below 2^31
+        const long long pix_elems = (long long)s.M * s.D0 * s.D1 * s.D3;
+        const long long tile_pix = 256 / (s.D1 > 0 ? s.D1 : 1) + 1;
+        const long long hw = (long long)s.Ho * s.Wo;
+        long long span;
+        if (s.out_view) {
+            const long long images = tile_pix / (hw > 0 ? hw : 1) + 2;
+            span = images * (s.out_sn > 0 ? s.out_sn : 0) + pix_elems;
+        } else {
+            span = (tile_pix + 1) * pix_elems;
+        }
+        const bool d3_ok = s.D3 == 4 || s.D3 == 8 || s.D3 == 16 || s.D3 == 32;
+        const bool strides_ok = !s.out_view || (s.out_sn >= 0 && s.out_sx >= 0 && s.out_sy >= 0);
+        P.fast_store = d3_ok && strides_ok && span * 4 < (1LL << 31) - (1 << 20) ? 1 : 0;
+    }
     return pl;
 }
 
