@@ -195,6 +195,46 @@ def test_benchmark_configs_full_size_sampled(num, count):
     check(w, got, ref, S, "sampled")
 
 
+@pytest.mark.parametrize("num", [3, 5])
+def test_full_size_integer_data_every_output(num):
+    """Configs 3 and 5 at full size on small-integer data, where every partial sum is exact in
+    fp32: EVERY output element is compared with the generic kernel's (bit for bit) and with the
+    framework's grouped convolution (an independent implementation of the same operator, itself
+    checked against the oracle in test_gpu_comparisons.py and on the CPU), and sampled capsules
+    with the oracle, exactly.  A wrong tile edge, halo or stage anywhere in the tensor shows as
+    a difference of at least 1."""
+    import torch
+    from paper_2104_02621_amd import comparisons as cmp
+    w = wl.integer_variant(wl.config(num))
+    i_st, k_st, i32, k32 = wl.generate(w)
+    i_dev, k_dev = to_device(i_st, w.dtype), to_device(k_st, w.dtype)
+    out = run_gpu(w, i_dev, k_dev, cc.PATH_AUTO)
+    which = wl.sample_capsules(w, 1500, seed=91 + num)
+    ref = capsconv.conv_fwd_subset(i32, k32, which, w.stride, w.pad)
+    assert np.abs(ref).max() < 2 ** 24
+    idx = torch.from_numpy(which.astype(np.int64)).cuda()
+    got = out[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
+    assert np.array_equal(got.astype(np.float64), ref)
+    # a second kernel of this library with other tiles and addressing: identical everywhere
+    generic = run_gpu(w, i_dev, k_dev, cc.PATH_MFMA_GENERIC)
+    assert bool(torch.equal(out, generic))
+    del generic
+    other = cmp.framework_conv_fwd(i_dev, k_dev, w.stride, w.pad)   # fp32 arithmetic
+    assert other.shape == out.shape
+    # Where the two differ by more than rounding noise of a transform-based algorithm (the exact
+    # results are integers), the oracle decides who is right.  (Seen on MI355X: the framework's
+    # result for config 5 is off by up to 3 in a few thousand elements of the last image.)
+    differ = torch.nonzero((out - other).abs() > 0.25)
+    print(f"{w.name}: {differ.shape[0]} of {out.numel()} outputs differ from the framework's")
+    if differ.shape[0] > 0:
+        caps = np.unique(differ[:100000, :4].cpu().numpy(), axis=0)[:200].astype(np.int32)
+        ref = capsconv.conv_fwd_subset(i32, k32, caps, w.stride, w.pad)
+        cidx = torch.from_numpy(caps.astype(np.int64)).cuda()
+        mine = out[cidx[:, 0], cidx[:, 1], cidx[:, 2], cidx[:, 3]].cpu().numpy()
+        assert np.array_equal(mine.astype(np.float64), ref)
+        assert differ.shape[0] < out.numel() // 1000, "the two implementations disagree widely"
+
+
 def test_offsets_beyond_4GB():
     """A config-5-like layer whose input (5.4 GB) and output (10.7 GB) exceed 32-bit byte
     offsets: output capsules sampled from the last images, where every address is past 4 GB."""
