@@ -115,6 +115,42 @@ def cpu_baseline_bwd(w, op, i32, k32, g32, gpu_grad, target_seconds=12.0):
     return rec, err / max(ref_max, 1e-300)
 
 
+def mfma_yardstick(dtype, zero_data=False, seconds=0.05):
+    """Sustained rate (TFLOP/s) of back-to-back matrix instructions on register operands, with
+    N(0,1) operands (or zeros), 1024 workgroups.  Timed with events on torch's current stream."""
+    import numpy as np
+    import torch
+    from paper_2104_02621_amd import capscaps as cc
+    from paper_2104_02621_amd import workloads as wl
+
+    rng = np.random.default_rng(31337)
+    n_elem = 8 * 64 * (4 if dtype == wl.FP32 else 8)
+    vals = np.zeros(n_elem, dtype=np.float32) if zero_data else \
+        rng.standard_normal(n_elem).astype(np.float32)
+    st, _ = wl.to_storage(vals, dtype)
+    seed = torch.from_numpy(st.view(np.int16) if dtype == wl.BF16 else st).cuda()
+    blocks = 1024
+    sink = torch.empty(blocks * 256, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def run(iters):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        rc = cc.capscaps_mfma_yardstick(seed.data_ptr(), sink.data_ptr(), dtype, blocks, iters,
+                                        stream.cuda_stream)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        if rc != cc.OK:
+            sys.exit(f"bench.py: yardstick status {rc}")
+        return e0.elapsed_time(e1) * 1e-3
+
+    t = run(200)
+    iters = int(min(1 << 22, max(200, 200 * seconds / max(t, 1e-6))))
+    run(iters)                       # settle the clocks under load
+    t = min(run(iters) for _ in range(3))
+    return cc.capscaps_mfma_yardstick_flops(dtype, blocks, iters) / t / 1e12
+
+
 def bench_net5(args):
     """Five chained layers (workloads.net5): layers 1-4 write bf16 activations that the next layer
     reads as they are, layer 5 writes fp32.  One step = the five calls."""
@@ -212,6 +248,8 @@ def main():
     ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_input", "bwd_kernel", "scheme1", "scheme2",
                                                      "framework_conv", "net5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-yardstick", action="store_true",
+                    help="skip the register-resident MFMA loop that measures the sustained rate")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (the known-size kernel that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by)")
@@ -358,6 +396,12 @@ def main():
             "kernel_ms": round(kernel_ms, 4),
         },
     }
+    if args.op == "fwd" and not args.no_yardstick:
+        # what the matrix cores sustain on this machine, same element type, N(0,1) operands in
+        # registers: the published peak assumes 2.4 GHz, which the chip does not hold under load
+        sustained = mfma_yardstick(w.dtype)
+        result["roofline"]["mfma_sustained_tflops"] = round(sustained, 1)
+        result["roofline"]["frac_of_sustained"] = round(achieved_tflops / sustained, 4)
     if not args.no_cpu_baseline:
         if args.op == "fwd" or comparison:
             rec, err = cpu_baseline(w, i32, k32, out)

@@ -197,6 +197,20 @@ int capscaps_scheme2_fwd(const void* input, const void* kernel, void* out, const
                          int stride, int pad, int D0, int D1, int D2, int D3, int dtype,
                          void* stream);
 
+/*
+ * Measurement aid, not part of the operator: `blocks` workgroups of 4 waves each execute
+ * `iters` x 16 independent back-to-back matrix instructions (the ones the convolution kernels
+ * use for `dtype`) on register operands -- no memory traffic, no LDS, no barriers -- so that a
+ * convolution's fraction of the published peak can be read against what the chip sustains on
+ * the same kind of data at its own clocks.  `seed`: 8 KB of device memory holding the operand
+ * fragments (8 fragments x 64 lanes x 16 bytes of `dtype` elements; their values decide how
+ * many bits toggle); `sink`: blocks * 256 floats, overwritten.  _flops returns the FLOPs one
+ * such launch executes (0 for invalid arguments).  Time it with events on `stream`.
+ */
+int capscaps_mfma_yardstick(const void* seed, void* sink, int dtype, int blocks, int iters,
+                            void* stream);
+double capscaps_mfma_yardstick_flops(int dtype, int blocks, int iters);
+
 /* Static, human-readable text for a status code.  Never NULL. */
 const char* capscaps_strerror(int status);
 

@@ -74,6 +74,10 @@ def _load():
     lib.capscaps_scheme2_build_index.restype = i
     lib.capscaps_scheme2_fwd.argtypes = [p, p, p, p, sz] + [i] * 14 + [p]
     lib.capscaps_scheme2_fwd.restype = i
+    lib.capscaps_mfma_yardstick.argtypes = [p, p, i, i, i, p]
+    lib.capscaps_mfma_yardstick.restype = i
+    lib.capscaps_mfma_yardstick_flops.argtypes = [i, i, i]
+    lib.capscaps_mfma_yardstick_flops.restype = ctypes.c_double
     lib.capscaps_strerror.argtypes = [i]
     lib.capscaps_strerror.restype = ctypes.c_char_p
     lib.capscaps_last_hip_error.argtypes = []
@@ -183,6 +187,14 @@ def capscaps_scheme2_fwd(input, kernel, out, index, index_bytes, N, H, W, C, M, 
                          pad, D0, D1, D2, D3, dtype, stream=None) -> int:
     return _load().capscaps_scheme2_fwd(input, kernel, out, index, index_bytes, N, H, W, C, M, kh,
                                         kw, stride, pad, D0, D1, D2, D3, dtype, stream)
+
+
+def capscaps_mfma_yardstick(seed, sink, dtype, blocks, iters, stream=None) -> int:
+    return _load().capscaps_mfma_yardstick(seed, sink, dtype, blocks, iters, stream)
+
+
+def capscaps_mfma_yardstick_flops(dtype, blocks, iters) -> float:
+    return float(_load().capscaps_mfma_yardstick_flops(dtype, blocks, iters))
 
 
 # ------------------------------------------------------------------ torch convenience

@@ -319,6 +319,24 @@ int capscaps_scheme2_fwd(const void* input, const void* kernel, void* out, const
                                                static_cast<hipStream_t>(stream)));
 }
 
+double capscaps_mfma_yardstick_flops(int dtype, int blocks, int iters)
+{
+    if (dtype < 0 || dtype > 2 || blocks <= 0 || iters <= 0) return 0.0;
+    return capscaps::yardstick_flops(dtype, blocks, iters);
+}
+
+int capscaps_mfma_yardstick(const void* seed, void* sink, int dtype, int blocks, int iters,
+                            void* stream)
+{
+    if (seed == nullptr || sink == nullptr || misaligned(seed) || misaligned(sink))
+        return CAPSCAPS_EINVAL;
+    if (dtype < 0 || dtype > 2 || blocks <= 0 || blocks > (1 << 20) || iters <= 0 ||
+        iters > (1 << 24))
+        return CAPSCAPS_EINVAL;
+    return hip_status(capscaps::launch_yardstick(dtype, seed, static_cast<float*>(sink), blocks,
+                                                 iters, static_cast<hipStream_t>(stream)));
+}
+
 const char* capscaps_last_hip_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 const char* capscaps_strerror(int status)

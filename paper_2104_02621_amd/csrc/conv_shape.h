@@ -81,4 +81,9 @@ hipError_t launch_scheme2_index(const ConvShape& s, int* index, hipStream_t stre
 hipError_t launch_scheme2(const ConvShape& s, const void* in, const void* kernel, float* out,
                           const int* index, hipStream_t stream);
 
+// Measurement aid (yardstick.hip): back-to-back matrix instructions on register operands.
+double yardstick_flops(int dtype, int blocks, int iters);
+hipError_t launch_yardstick(int dtype, const void* seed, float* sink, int blocks, int iters,
+                            hipStream_t stream);
+
 }  // namespace capscaps

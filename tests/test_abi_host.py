@@ -157,3 +157,13 @@ def test_scheme2_index_size_and_limits():
     assert cc.capscaps_scheme2_index_bytes(*a) == products * 12
     # 2^31 or more input capsules: refused
     assert cc.capscaps_scheme2_index_bytes(*_args(N=1 << 20, H=64, W=64, C=8)) == 0
+
+
+def test_yardstick_argument_checks():
+    assert cc.capscaps_mfma_yardstick_flops(cc.FP16, 1024, 100) == 16 * 2 * 32 * 32 * 16 * 4 * 1024 * 100
+    assert cc.capscaps_mfma_yardstick_flops(cc.FP32, 2, 3) == 16 * 4 * 2 * 32 * 32 * 2 * 4 * 2 * 3
+    assert cc.capscaps_mfma_yardstick_flops(7, 1, 1) == 0
+    assert cc.capscaps_mfma_yardstick(0, FAKE, cc.FP16, 1, 1, None) == cc.EINVAL
+    assert cc.capscaps_mfma_yardstick(FAKE, FAKE, 5, 1, 1, None) == cc.EINVAL
+    assert cc.capscaps_mfma_yardstick(FAKE, FAKE, cc.FP16, 0, 1, None) == cc.EINVAL
+    assert cc.capscaps_mfma_yardstick(FAKE, FAKE, cc.FP16, 1, 0, None) == cc.EINVAL

@@ -74,3 +74,21 @@ def test_scheme2_refuses_small_index_buffer():
     assert cc.capscaps_scheme2_build_index(p, nbytes - 1, *args, st) == cc.EWORKSPACE
     assert cc.capscaps_scheme2_fwd(p, p, p, p, nbytes - 1, *args, st) == cc.EWORKSPACE
     assert cc.capscaps_scheme2_fwd(p, p, p, 0, nbytes, *args, st) == cc.EINVAL
+
+
+@pytest.mark.parametrize("dtype", [wl.FP32, wl.BF16, wl.FP16], ids=["fp32", "bf16", "fp16"])
+def test_mfma_yardstick_computes_what_it_counts(dtype):
+    """The measurement aid's arithmetic is checked too: with all-ones operands every accumulator
+    element of a wave ends at iters * (K per instruction group), so a lane's sum over its 16
+    tiles x 16 registers is known exactly."""
+    import torch
+    n_elem = 8 * 64 * (4 if dtype == wl.FP32 else 8)
+    st, _ = wl.to_storage(np.ones(n_elem, dtype=np.float32), dtype)
+    seed = to_device(st, dtype)
+    blocks, iters = 3, 5
+    sink = torch.full((blocks * 256,), float("nan"), dtype=torch.float32, device="cuda")
+    rc = cc.capscaps_mfma_yardstick(seed.data_ptr(), sink.data_ptr(), dtype, blocks, iters,
+                                    torch.cuda.current_stream().cuda_stream)
+    assert rc == cc.OK
+    k_per_iter = 8 if dtype == wl.FP32 else 16      # contracted values per accumulator and iteration
+    assert bool((sink == 256.0 * iters * k_per_iter).all())
