@@ -72,12 +72,15 @@ __device__ __forceinline__ void copy_to_lds(rsrc_t rs, unsigned lds_addr, unsign
                      : "memory");
 }
 
-constexpr int KCH = 4;  // chunks per row and stage
-constexpr int NB = 3;   // LDS stages in the ring
+// KCH chunks per row and stage, ring of NB stages.  Small stages (2 chunks, ring of 4) halve the
+// LDS footprint of a workgroup, so that three instead of two share a CU and one wave's copies
+// and waits run under the others' MFMAs; they need capsule rows of at most 2 chunks.
+constexpr int ring_depth(int kch) { return kch == 2 ? 4 : 3; }
 
-template <int CW, int TN, int NW>
+template <int CW, int TN, int NW, int KCH>
 __global__ __launch_bounds__(64 * NW) void igemm32_dma_kernel(const Dma32Params P)
 {
+    constexpr int NB = ring_depth(KCH);
     constexpr int BM = 64 * NW, BN = 32 * TN, BNL = (BN + 63) / 64 * 64, TM = 2;
     constexpr int A_BYTES = KCH * BM * 16, B_BYTES = KCH * BNL * 16;
     constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
@@ -86,7 +89,10 @@ __global__ __launch_bounds__(64 * NW) void igemm32_dma_kernel(const Dma32Params 
     static_assert(NBC % NW == 0, "kernel copies divide evenly over the waves");
     constexpr int NCOPY = KCH + BPW;     // copies per wave and stage
     constexpr int OOB = (int)0x80000000u;
-    constexpr int VMCNT_KEEP = 0x0F70 | (NCOPY & 15) | ((NCOPY >> 4) << 14);
+    // at a barrier the copies of the NB-2 most recent stages may still be in flight
+    constexpr int KEEP = (NB - 2) * NCOPY;
+    static_assert(KEEP < 64, "vmcnt is a 6-bit counter");
+    constexpr int VMCNT_KEEP = 0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14);
 
     extern __shared__ char smem[];
 
@@ -249,17 +255,16 @@ __global__ __launch_bounds__(64 * NW) void igemm32_dma_kernel(const Dma32Params 
         }
     };
 
-    // ---- prologue: two stages in flight, the first one landed
-    issue_stage(0);
-    issue_stage(1);
+    // ---- prologue: NB-1 stages in flight, the first one landed
+    static_for<NB - 1>([&](auto S0) { issue_stage(decltype(S0)::value); });
     __builtin_amdgcn_s_waitcnt(VMCNT_KEEP);
     __syncthreads();
 
-    // ---- main loop: copy stage s+2 into the slot read in iteration s-1, contract stage s
+    // ---- main loop: copy stage s+NB-1 into the slot read in iteration s-1, contract stage s
     for (int st = 0; st < my_stages_pad; st += NB) {
         static_for<NB>([&](auto SLOT) {
             constexpr int slot = decltype(SLOT)::value;
-            issue_stage((slot + 2) % NB);
+            issue_stage((slot + NB - 1) % NB);
             compute_stage(slot);
             // this wave's copies of the next stage have landed, its reads of this stage are
             // done; after the barrier both hold for every wave
@@ -307,18 +312,28 @@ __global__ __launch_bounds__(64 * NW) void igemm32_dma_kernel(const Dma32Params 
     }
 }
 
-template <int CW, int TN, int NW>
-hipError_t launch_one(const Dma32Params& P, long long blocks, hipStream_t stream)
+template <int CW, int TN, int NW, int KCH>
+hipError_t launch_kch(const Dma32Params& P, long long blocks, hipStream_t stream)
 {
     constexpr int BM = 64 * NW, BNL = (32 * TN + 63) / 64 * 64;
-    auto kern = igemm32_dma_kernel<CW, TN, NW>;
-    const size_t lds_bytes = (size_t)NB * KCH * (BM + BNL) * 16;
+    auto kern = igemm32_dma_kernel<CW, TN, NW, KCH>;
+    const size_t lds_bytes = (size_t)ring_depth(KCH) * KCH * (BM + BNL) * 16;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize,
                                          (int)lds_bytes);
     if (err != hipSuccess) return err;
     kern<<<dim3((unsigned)blocks), dim3(64 * NW), lds_bytes, stream>>>(P);
     return hipGetLastError();
+}
+
+// 2-chunk stages where the column copies still divide over the waves
+template <int CW, int TN, int NW>
+hipError_t launch_one(const Dma32Params& P, long long blocks, hipStream_t stream)
+{
+    if constexpr ((2 * ((32 * TN + 63) / 64)) % NW == 0) {
+        if (P.kch == 2) return launch_kch<CW, TN, NW, 2>(P, blocks, stream);
+    }
+    return launch_kch<CW, TN, NW, 4>(P, blocks, stream);
 }
 
 template <int CW, int NW>
@@ -382,16 +397,23 @@ Dma32Plan igemm32_dma_plan(const ConvShape& s)
     P.cols = s.M * s.D3;
     P.D2C = cw ? s.D2 / cw : 1;
     const int KK = s.C * P.D2C;                 // chunks per row and tap
+    pl.tn = P.cols <= 32 ? 1 : P.cols <= 64 ? 2 : P.cols <= 96 ? 3 : 4;
+    // four waves per block (256 rows) when that still fills the chip, else one (64 rows)
+    {
+        const int bn = 32 * pl.tn;
+        const long long big = (long long)ceil_div_ll(s.pixels() * s.D1, 256) * ((P.cols + bn - 1) / bn) * s.D0;
+        pl.nw = big >= 256 ? 4 : 1;
+    }
+    // chunks per stage: 2 for the four-wave tile with wide column tiles and short capsule rows
+    // (measured on config 2: 0.955 ms against 0.987 ms), else 4
+    const int KCH = (pl.nw == 4 && pl.tn >= 3 && P.D2C <= 2) ? 2 : 4;
+    P.kch = KCH;
     const int groups = (KK + KCH - 1) / KCH;
     pl.kqp = groups * KCH;
     P.nstages = groups * P.ntaps;
-    pl.tn = P.cols <= 32 ? 1 : P.cols <= 64 ? 2 : P.cols <= 96 ? 3 : 4;
     const int BN = 32 * pl.tn;
     P.col_tiles = (P.cols + BN - 1) / BN;
     P.colsp = P.col_tiles * BN;
-    // four waves per block (256 rows) when that still fills the chip, else one (64 rows)
-    const long long big = (long long)ceil_div_ll(P.rows, 256) * P.col_tiles * s.D0;
-    pl.nw = big >= 256 ? 4 : 1;
     P.row_tiles = ceil_div_ll(P.rows, 64 * pl.nw);
     const long long tiles = (long long)P.row_tiles * P.col_tiles * s.D0;
     int nsplit = 1;

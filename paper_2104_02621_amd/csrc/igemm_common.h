@@ -129,6 +129,7 @@ struct Dma32Params {
     int cs;        // D0*D1*D2: input channel stride (elements)
     int cols, colsp;
     int D2C;       // chunks per capsule row
+    int kch;       // chunks per row and stage: 2 or 4
     int nstages;   // channel groups * taps
     int stages_per_split, nsplit;
     int row_tiles, col_tiles;

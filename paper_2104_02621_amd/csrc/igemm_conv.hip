@@ -475,8 +475,8 @@ hipError_t launch_dma32(const ConvShape& s, const void* in, const void* kernel, 
     pl.P.in = in;
     pl.P.kp = ws;
     pl.P.out = pl.P.nsplit > 1 ? partial : out;
-    hipError_t err = launch_repack(s, kernel, ws, pl.cw, pl.kqp, pl.P.colsp, 4, pl.repack_bytes / 16,
-                                   stream);
+    hipError_t err = launch_repack(s, kernel, ws, pl.cw, pl.kqp, pl.P.colsp, pl.P.kch,
+                                   pl.repack_bytes / 16, stream);
     if (err != hipSuccess) return err;
     err = launch_igemm32_dma(pl, stream);
     if (err != hipSuccess) return err;
