@@ -248,6 +248,9 @@ def main():
     ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_input", "bwd_kernel", "scheme1", "scheme2",
                                                      "framework_conv", "net5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step (all its launches) in a HIP graph and time replays; for "
+                         "the launch-bound small configurations")
     ap.add_argument("--no-yardstick", action="store_true",
                     help="skip the register-resident MFMA loop that measures the sustained rate")
     ap.add_argument("--copy-probe", action="store_true",
@@ -350,11 +353,30 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run_step = step
+    if args.graph:
+        # the library's calls only enqueue kernels on the stream they are given (no allocation,
+        # no memset, no synchronisation), so a step can be captured and replayed as one graph
+        eager = out.clone()
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            stream = torch.cuda.current_stream()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        stream = torch.cuda.current_stream()
+        for _ in range(3):   # replays must reproduce the eager result every time
+            out.zero_()
+            graph.replay()
+            torch.cuda.synchronize()
+            if not torch.equal(out, eager):
+                sys.exit("bench.py: graph replay differs from the eager result")
+        run_step = graph.replay
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     t0 = time.perf_counter()
     ev[0].record(stream)
     for k in range(args.steps):
-        step()
+        run_step()
         ev[k + 1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -376,7 +398,8 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32" if w.dtype == wl.FP32 else
         f"{dname} in, f32 accumulate", "data": "synthetic",
         "config": {
-            "workload": f"config {args.config}: {w.name}", "op": args.op, "N": w.N, "H": w.H, "W": w.W, "C": w.C,
+            "workload": f"config {args.config}: {w.name}", "op": args.op,
+            "launch": "hip graph replay" if args.graph else "eager", "N": w.N, "H": w.H, "W": w.W, "C": w.C,
             "M": w.M, "kh": w.kh, "kw": w.kw, "stride": w.stride, "pad": w.pad,
             "capsule": [w.D0, w.D1, w.D2, w.D3],
             "path": {1: "direct", 2: "mfma", 3: "mfma-generic", 4: "mfma-tuned16",

@@ -25,7 +25,9 @@
  * `workspace` is scratch whose contents are undefined afterwards.  `stream` is a
  * hipStream_t passed as void* (NULL = the default stream).  All work is enqueued on that
  * stream; no call here synchronises, so buffers must stay valid until the stream reaches the
- * end of the enqueued work.  The library keeps no global state between calls.
+ * end of the enqueued work.  The library keeps no global state between calls.  Calls that take a
+ * `workspace` allocate nothing and enqueue only kernels, so they may be captured in a HIP graph
+ * (capscaps_conv_fwd, which obtains its scratch itself, may not).
  *
  * Errors: functions returning int return CAPSCAPS_OK (0) or a negative status; on any error
  * nothing has been launched.  Nothing is printed, nothing throws, nothing aborts.

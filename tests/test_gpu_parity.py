@@ -306,6 +306,51 @@ def test_torch_wrapper_and_side_stream():
     check(w, out.cpu().numpy(), ref, S, "wrapper")
 
 
+def test_calls_can_be_captured_in_a_graph():
+    """With caller-provided scratch the library only enqueues kernels on the stream it is given
+    (no allocation, no memset, no synchronisation), so a call can be captured in a HIP graph.
+    Replays, with eager work and synchronisations between them, must reproduce the eager
+    result every time (split-K path: repack, MFMA kernel, reduction; and both gradients)."""
+    import torch
+    w = wl.config(4)
+    i_st, k_st, _, _ = wl.generate(w)
+    g_st, _ = wl.generate_dout(w)
+    I, K, G = (to_device(a, w.dtype) for a in (i_st, k_st, g_st))
+    args = shape_args(w)
+    out = torch.zeros(w.out_shape, dtype=torch.float32, device="cuda")
+    din = torch.zeros(w.input_shape, dtype=torch.float32, device="cuda")
+    dk = torch.zeros(w.kernel_shape, dtype=torch.float32, device="cuda")
+    ws = [torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
+          for n in (cc.capscaps_conv_fwd_workspace_bytes(*args),
+                    cc.capscaps_conv_bwd_input_workspace_bytes(*args),
+                    cc.capscaps_conv_bwd_kernel_workspace_bytes(*args))]
+
+    def step(st):
+        assert cc.capscaps_conv_fwd_ex(I.data_ptr(), K.data_ptr(), out.data_ptr(), *args,
+                                       ws[0].data_ptr(), ws[0].numel(), st) == cc.OK
+        assert cc.capscaps_conv_bwd_input(G.data_ptr(), K.data_ptr(), din.data_ptr(), *args,
+                                          ws[1].data_ptr(), ws[1].numel(), st) == cc.OK
+        assert cc.capscaps_conv_bwd_kernel(I.data_ptr(), G.data_ptr(), dk.data_ptr(), *args,
+                                           ws[2].data_ptr(), ws[2].numel(), st) == cc.OK
+
+    step(torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in (out, din, dk)]
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step(side.cuda_stream)
+    for k in range(4):
+        for t in (out, din, dk):
+            t.fill_(float(k))            # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for t, e in zip((out, din, dk), eager):
+            assert torch.equal(t, e), f"replay {k}"
+
+
 def test_workspace_too_small_is_refused_before_any_launch():
     import torch
     w = wl.config(1)
