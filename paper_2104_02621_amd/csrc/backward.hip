@@ -5,6 +5,8 @@
 //   dI[n,h,w,c,d0] (D1xD2) = sum_{x*s+p-pad=h, y*s+q-pad=w, m}  G[n,x,y,m,d0] (D1xD3) . K[p,q,c,m,d0]^T
 //   dK[p,q,c,m,d0] (D2xD3) = sum_{n,x,y}  I[n,x*s+p-pad,y*s+q-pad,c,d0]^T (D2xD1) . G[n,x,y,m,d0] (D1xD3)
 //
+// dK has kernels of its own for the common capsule shapes (wgrad16.hip, wgrad32.hip: one GEMM per
+// window tap over the output pixels the tap reaches); this file holds dI and the fallback for dK.
 // For stride 1 both are capsule convolutions themselves and run on the forward kernels:
 //   dI = conv_fwd(G, K'),  K'[kh-1-p][kw-1-q][m][c][d0][d3][d2] = K[p][q][c][m][d0][d2][d3],
 //        padding kh-1-pad (square windows), channels M -> C, capsules (D1xD3).(D3xD2);
