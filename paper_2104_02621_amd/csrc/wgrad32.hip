@@ -233,6 +233,11 @@ __global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
+    // row tiles of this wave that hold at least one real row (the others would multiply zeros)
+    bool row_tile_live[TM];
+#pragma unroll
+    for (int b = 0; b < TM; ++b) row_tile_live[b] = row_tile * BM + 64 * wave + b * 32 < P.rows;
+
     auto compute_stage = [&](int slot) {
         const char* stage = smem + slot * STAGE_BYTES;
 #pragma unroll
@@ -248,13 +253,15 @@ __global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
                 ia[b] = *reinterpret_cast<const float4v*>(
                     stage + ((2 * t + h) * BM + 64 * wave + b * 32 + lr) * 16);
 #pragma unroll
-            for (int u = 0; u < CW; ++u)
+            for (int b = 0; b < TM; ++b) {
+                if (!row_tile_live[b]) continue;  // wave-uniform
 #pragma unroll
-                for (int a = 0; a < TN; ++a)
+                for (int u = 0; u < CW; ++u)
 #pragma unroll
-                    for (int b = 0; b < TM; ++b)
+                    for (int a = 0; a < TN; ++a)
                         acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(kb[a][u], ia[b][u],
                                                                          acc[a][b], 0, 0, 0);
+            }
         }
     };
 
