@@ -387,7 +387,7 @@ Wgrad32Plan make_plan(const ConvShape& s)
     const int kch = stage_chunks(P.D1C, pl.nw);
     const size_t lds = (size_t)ring_depth(kch) * kch * (64 * pl.nw + (32 * pl.tn + 63) / 64 * 64) * 16;
     long long per_cu = (long long)(160 * 1024 / lds);
-    if (per_cu > 12 / pl.nw) per_cu = 12 / pl.nw;  // three waves per SIMD by registers
+    if (per_cu > 8 / pl.nw) per_cu = 8 / pl.nw;  // two waves per SIMD by registers
     if (per_cu < 1) per_cu = 1;
     const long long slots = 256 * per_cu;
     const long long full = (long long)s.N * s.Ho * s.Wo;
