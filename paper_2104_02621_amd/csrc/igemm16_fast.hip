@@ -172,6 +172,34 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         pix_off[j] = __builtin_amdgcn_readfirstlane(
             (int)((((long long)n_rel * P.H + ih0) * P.W + iw0) * pix_bytes) + d0 * D1 * D2 * 2);
     }
+    // Window rows that no pixel of the whole tile can use (the tile lies on the image's first
+    // or last rows and the window row falls into the padding) are left out of the K loop: the
+    // tile then runs taps [tap_lo, tap_hi) only.  The tap masks of the four waves are combined
+    // through LDS (free until the first copy is issued).
+    int tap_lo = 0, tap_hi = P.ntaps;
+    {
+        unsigned long long mine = 0;
+#pragma unroll
+        for (int j = 0; j < PPW; ++j) mine |= tap_ok[j];
+        unsigned long long* share = reinterpret_cast<unsigned long long*>(smem);
+        if (lane == 0) share[wave] = mine;
+        __syncthreads();
+        unsigned long long all = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) all |= share[w];
+        const unsigned all_lo = __builtin_amdgcn_readfirstlane((int)(unsigned)all);
+        const unsigned all_hi = __builtin_amdgcn_readfirstlane((int)(unsigned)(all >> 32));
+        const unsigned long long live = ((unsigned long long)all_hi << 32) | all_lo;
+        __syncthreads();  // everyone has read before any copy may land here
+        if (live != 0) {
+            const unsigned long long row_bits = P.kw >= 64 ? ~0ull : (1ull << P.kw) - 1;
+            int p_lo = 0, p_hi = P.ntaps / P.kw;
+            while (p_lo < p_hi - 1 && ((live >> (p_lo * P.kw)) & row_bits) == 0) ++p_lo;
+            while (p_hi - 1 > p_lo && ((live >> ((p_hi - 1) * P.kw)) & row_bits) == 0) --p_hi;
+            tap_lo = p_lo * P.kw;
+            tap_hi = p_hi * P.kw;
+        }
+    }
     long long in_left = P.in_bytes - (long long)n_first * img_elems * 2;
     if (in_left > 0x7fffffffLL) in_left = 0x7fffffffLL;
     const rsrc_t rs_in = make_rsrc(in_base, (unsigned)in_left);
@@ -207,13 +235,31 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     // KCH/D2C channels) at window tap s % ntaps.  The input-side state describes the stage
     // whose input copies go out next, the kernel-side state (one offset) the stage whose kernel
     // copies go out next; in the steady state the input side runs one stage ahead.
-    const int nstages = P.ntaps * (P.KQP / KCH);
+    const int groups = P.KQP / KCH;
+    const int nlive = tap_hi - tap_lo;                      // taps per channel group that run
+    const int nstages = nlive * groups;
     const int nstages_pad = (nstages + NB - 1) / NB * NB;  // surplus stages contract zeros
     const int c_step = (KCH / D2C) * P.cs * 2;             // bytes per channel group
     const int kp_step = KCH * P.colsp * 16;                 // repacked kernel bytes per stage
+    const int kp_wrap = (P.ntaps - nlive + 1) * kp_step;    // last live tap -> first of next group
     const int row_skip = (P.W - P.kw + 1) * pix_bytes;     // last tap of a window row -> next row
-    int a_stage = 0, tap = 0, tap_q_cur = 0, tap_off = 0, c_off = 0;
-    int kp_off = (int)(((long long)d0 * nstages * KCH * P.colsp + col0) * 16);
+    const int tap_off0 = (tap_lo / P.kw) * P.W * pix_bytes;
+    int a_stage = 0, tap = tap_lo, tap_q_cur = 0, tap_off = tap_off0, c_off = 0;
+    int kp_off = (int)((((long long)d0 * groups * P.ntaps + tap_lo) * KCH * P.colsp + col0) * 16);
+    int kp_left = nlive;  // kernel-side stages until the next channel group
+    // kernel-side state -> next stage
+    // (Scalar arithmetic has no side effect the compiler must order, so by itself it may drift
+    // out of the gap between MFMAs it is written in; the empty volatile statements, which do
+    // keep their order among the copies and scheduling barriers, hold its inputs and results in
+    // place.)
+    auto advance_b = [&]() {
+        asm volatile("" : "+s"(kp_left), "+s"(kp_off));
+        --kp_left;
+        const bool wrap = kp_left == 0;
+        kp_off += wrap ? kp_wrap : kp_step;
+        kp_left = wrap ? nlive : kp_left;
+        asm volatile("" : "+s"(kp_left), "+s"(kp_off));
+    };
     int b_const[BW];
 #pragma unroll
     for (int j = 0; j < BW; ++j) {
@@ -227,11 +273,14 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     // offset of the input-side stage's copies for pixel j
     auto stage_offset = [&](int j) {
         // past the last stage (surplus stages of the ring): zero fill, touches no memory
+        asm volatile("" : "+s"(tap), "+s"(tap_off), "+s"(a_stage));
         const bool ok = ((tap_ok[j] >> tap) & 1ull) != 0 && a_stage < nstages;
         a_soff[j] = ok ? pix_off[j] + tap_off : OOB;
+        asm volatile("" : "+s"(a_soff[j]));
     };
     // input-side state -> next stage, in three pieces
     auto advance_a = [&](int piece) {
+        asm volatile("" : "+s"(a_stage), "+s"(tap), "+s"(tap_q_cur), "+s"(tap_off), "+s"(c_off));
         if (piece == 0) {
             ++a_stage;
             ++tap;
@@ -241,12 +290,13 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
             tap_q_cur = row_end ? 0 : tap_q_cur;
             tap_off += row_end ? row_skip : pix_bytes;
         } else {
-            const bool wrap = tap == P.ntaps;  // window done: next channel group, first tap
-            tap = wrap ? 0 : tap;
+            const bool wrap = tap == tap_hi;  // window done: next channel group, first live tap
+            tap = wrap ? tap_lo : tap;
             tap_q_cur = wrap ? 0 : tap_q_cur;
-            tap_off = wrap ? 0 : tap_off;
+            tap_off = wrap ? tap_off0 : tap_off;
             c_off = wrap ? c_off + c_step : c_off;
         }
+        asm volatile("" : "+s"(a_stage), "+s"(tap), "+s"(tap_q_cur), "+s"(tap_off), "+s"(c_off));
     };
     // input copy J (0 .. BW-1) of the input-side stage / kernel copy J of the kernel-side stage
     auto copy_a = [&](auto SLOT, auto J) {
@@ -303,7 +353,7 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         advance_a(0);
         advance_a(1);
         advance_a(2);
-        kp_off += kp_step;
+        advance_b();
     });
 #pragma unroll
     for (int j = 0; j < PPW; ++j) stage_offset(j);
@@ -336,7 +386,7 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
 #pragma unroll
                 for (int j = 0; j < PPW; ++j)
                     if (LOOKUP_GAP[j] == i) stage_offset(j);
-                if constexpr (i == NMMA - 1) kp_off += kp_step;
+                if constexpr (i == NMMA - 1) advance_b();
                 __builtin_amdgcn_sched_barrier(0);
             });
             // everything this wave still needs from `slot` is in registers; its copies of the
