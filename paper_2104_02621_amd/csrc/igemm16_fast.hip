@@ -128,11 +128,26 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     // repacked kernel for all its resident workgroups, and vertically adjacent row tiles, which
     // share input halo rows, meet in the same L2.  Measured on config 5: 2.5x fewer L2 misses
     // than handing each XCD a contiguous range of tiles covering all column tiles.
+    // Longest tiles first: the row tiles on an image's first and last rows, whose K loop is
+    // shorter (see tap_lo / tap_hi below), are launched after all others, so that they fill the
+    // last round of tiles instead of leaving CUs idle at the end (the host's plan says how many
+    // such tiles an image has; 0 = launch order is tile order).
     const int L = blockIdx.x;
     const int col_tile = L % P.col_tiles;
     int rest = L / P.col_tiles;
-    const int row_tile = rest % P.row_tiles;
+    int row_tile = rest % P.row_tiles;
     const int d0 = rest / P.row_tiles;
+    if (P.lpt_timg > 0) {
+        const int ab = P.lpt_a + P.lpt_b, mid = P.lpt_timg - ab;
+        const int full = (P.row_tiles / P.lpt_timg) * mid;
+        if (row_tile < full) {
+            const int n = row_tile / mid;
+            row_tile = n * P.lpt_timg + P.lpt_a + (row_tile - n * mid);
+        } else {
+            const int r2 = row_tile - full, n = r2 / ab, u = r2 - n * ab;
+            row_tile = n * P.lpt_timg + (u < P.lpt_a ? u : P.lpt_timg - ab + u);
+        }
+    }
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);

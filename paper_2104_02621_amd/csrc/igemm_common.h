@@ -110,6 +110,9 @@ struct IgemmParams {
     // `out` points into
     int fast_store;
     long long out_alloc;
+    // its launch order: tiles per image (0 = plain order), and how many of an image's first and
+    // last row tiles have a shortened K loop (they are launched last)
+    int lpt_timg, lpt_a, lpt_b;
 };
 
 // Shared launch helpers (igemm_conv.hip).  Repack: 16-byte chunks of `cw` valid K elements

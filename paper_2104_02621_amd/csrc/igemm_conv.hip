@@ -369,6 +369,25 @@ Plan make_plan(const ConvShape& s, MfmaKernel which)
     P.out_view = s.out_view ? 1 : 0;
     P.out_base = s.out_base; P.out_sn = s.out_sn; P.out_sx = s.out_sx; P.out_sy = s.out_sy;
     P.out_alloc = s.out_view ? s.out_alloc : P.out_elems;
+    P.lpt_timg = P.lpt_a = P.lpt_b = 0;
+    if (pl.fast && s.D0 == 1 && s.D1 > 0 && 256 % s.D1 == 0) {
+        // tiles of the tuned kernel hold 256/D1 consecutive pixels; when they do not straddle
+        // images, count an image's leading (trailing) tiles all of whose pixels have a window
+        // row above (below) the image
+        const long long pix = 256 / s.D1, hw = (long long)s.Ho * s.Wo;
+        if (hw % pix == 0 && hw / pix < (1 << 20)) {
+            const int timg = (int)(hw / pix);
+            int a = 0, b = 0;
+            while (a < timg && (((a + 1) * pix - 1) / s.Wo) * s.stride - s.pad < 0) ++a;
+            while (b < timg - a &&
+                   (((timg - 1 - b) * pix) / s.Wo) * s.stride - s.pad + s.kh - 1 >= s.H) ++b;
+            if (a + b > 0 && a + b < timg) {
+                P.lpt_timg = timg;
+                P.lpt_a = a;
+                P.lpt_b = b;
+            }
+        }
+    }
     {
         // the tuned kernel's buffer-store epilogue: byte offsets from a tile's first output
         // pixel (a tile holds 256/D1 consecutive pixels, which may reach into following images)
