@@ -45,15 +45,15 @@ namespace {
 // channels as [channel][d1][d2-half]), or two pixels share a block (PPB = 2, D1 = D2 = 8 with 4
 // chunks per stage: [channel 0..3][pixel 0..1][d1 0..7], the lower half wave copies one pixel,
 // the upper half the other).
-template <int D1, int D2, int KCH>
+template <int D1, int D2, int KCH, int BM>
 struct ALayout {
     static constexpr int D2C = D2 / 8;             // chunks per capsule row
     static constexpr int G = D1 * D2C;             // chunks per (pixel, channel)
     static constexpr int PPB = (KCH * D1 >= 64) ? 1 : 64 / (KCH * D1);  // pixels per block
     static constexpr int BPP = (PPB == 1) ? KCH * D1 / 64 : 1;  // blocks per pixel (PPB = 1)
     static constexpr int CPB = 64 / (G * PPB);     // channels per block
-    static constexpr int PIX = 256 / D1;           // pixels per tile
-    static constexpr int NBLK = 4 * KCH;           // blocks per operand and stage
+    static constexpr int PIX = BM / D1;            // pixels per tile
+    static constexpr int NBLK = BM * KCH / 64;     // input-side blocks per stage
     // padding between blocks so that lanes of a quarter wave that belong to different pixels
     // fall into different bank groups
     static constexpr int APAD = (G == 8 && PPB == 1) ? 128 : 0;
@@ -94,24 +94,29 @@ struct ALayout {
 
 // KCH: chunks (of 8 K elements) per row and stage; NB: LDS stage buffers in the ring.
 // OUT16: the output has the operands' 16-bit type (rounded at the store) instead of fp32.
-template <typename Tag, int D1, int D2, int KCH, int NB, bool OUT16>
-__global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
+// BM: rows of the tile, 256 (one workgroup per CU, 128 x 128 per wave) or 128 (64 x 128 per wave,
+// half the registers and LDS, so that two workgroups share a CU and one's set-up, epilogue and
+// waits run under the other's MFMAs).
+template <typename Tag, int D1, int D2, int KCH, int NB, bool OUT16, int BM>
+__global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(const IgemmParams P)
 {
     constexpr int OUT_KIND = !OUT16 ? 0 : std::is_same<Tag, f16_tag>::value ? 2 : 1;
-    typedef ALayout<D1, D2, KCH> AL;
+    typedef ALayout<D1, D2, KCH, BM> AL;
     constexpr int NWM = 2, NWN = 2, NW = 4;
-    constexpr int BM = 256, BN = 256;
+    constexpr int BN = 256;
     constexpr int D2C = AL::D2C, CPB = AL::CPB, BPP = AL::BPP, PPB = AL::PPB, PIX = AL::PIX;
-    constexpr int ABLK = AL::ABLK, NBLK = AL::NBLK;
-    constexpr int A_BYTES = NBLK * ABLK, B_BYTES = NBLK * 1024, STAGE_BYTES = A_BYTES + B_BYTES;
+    constexpr int ABLK = AL::ABLK, NBLK = AL::NBLK, NBLK_B = BN * KCH / 64;
+    constexpr int A_BYTES = NBLK * ABLK, B_BYTES = NBLK_B * 1024, STAGE_BYTES = A_BYTES + B_BYTES;
     constexpr int WM = BM / NWM, WN = BN / NWN, TM = WM / 32, TN = WN / 32;
     constexpr int NMMA = TM * TN;    // MFMAs per k-step = slots for side operations
     constexpr int KS = KCH / 2;      // MFMA k-steps (16 K elements) per stage
-    constexpr int BW = NBLK / NW;    // blocks per wave, per operand and stage
-    constexpr int PPW = BW * PPB / BPP;  // pixels whose blocks this wave loads
+    constexpr int BWA = NBLK / NW;   // input-side blocks per wave and stage
+    constexpr int BWB = NBLK_B / NW; // kernel-side blocks per wave and stage
+    constexpr int PPW = BWA * PPB / BPP;  // pixels whose blocks this wave loads
     constexpr int NFRAG = TN + TM;   // operand fragments per k-step
-    constexpr int NCOPY = 2 * BW;    // copies per wave and stage
-    static_assert(BW % BPP == 0 && PPW >= 1, "a wave loads whole pixels");
+    constexpr int NCOPY = BWA + BWB; // copies per wave and stage
+    static_assert(BM == 256 || BM == 128, "tile rows");
+    static_assert(BWA % BPP == 0 && PPW >= 1, "a wave loads whole pixels");
     static_assert(NFRAG <= NMMA && PPW <= NMMA / 2, "side operations fit between the MFMAs");
     static_assert(KS % 2 == 0, "register double buffer alternates per k-step");
     constexpr int OOB = (int)0x80000000u;
@@ -221,8 +226,8 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     const rsrc_t rs_kp = make_rsrc(P.kp, (unsigned)P.kp_records);
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
     // LDS byte addresses of this wave's first input block and first kernel block in slot 0
-    const unsigned lds_a = __builtin_amdgcn_readfirstlane((int)(lds0 + wave * BW * ABLK));
-    const unsigned lds_b = __builtin_amdgcn_readfirstlane((int)(lds0 + A_BYTES + wave * BW * 1024));
+    const unsigned lds_a = __builtin_amdgcn_readfirstlane((int)(lds0 + wave * BWA * ABLK));
+    const unsigned lds_b = __builtin_amdgcn_readfirstlane((int)(lds0 + A_BYTES + wave * BWB * 1024));
 
     // ---- per-lane constants
     // input block: byte offset of the lane's chunk within its pixel's stage data
@@ -275,10 +280,10 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         kp_left = wrap ? nlive : kp_left;
         asm volatile("" : "+s"(kp_left), "+s"(kp_off));
     };
-    int b_const[BW];
+    int b_const[BWB];
 #pragma unroll
-    for (int j = 0; j < BW; ++j) {
-        const int bb = wave * BW + j;
+    for (int j = 0; j < BWB; ++j) {
+        const int bb = wave * BWB + j;
         b_const[j] = ((bb / 4) * P.colsp + (bb % 4) * 64) * 16;
     }
     int a_soff[PPW];  // per pixel: byte offset of the current tap's input pixel, or OOB
@@ -313,7 +318,7 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
         }
         asm volatile("" : "+s"(a_stage), "+s"(tap), "+s"(tap_q_cur), "+s"(tap_off), "+s"(c_off));
     };
-    // input copy J (0 .. BW-1) of the input-side stage / kernel copy J of the kernel-side stage
+    // input copy J (0 .. BWA-1) of the input-side stage / kernel copy J of the kernel-side stage
     auto copy_a = [&](auto SLOT, auto J) {
         constexpr int slot = decltype(SLOT)::value, j = decltype(J)::value;
         if constexpr (PPB == 1) {
@@ -348,23 +353,40 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     };
 
     // ---- schedule of the side operations.  A stage is two k-steps of NMMA = 16 MFMAs; per
-    // wave it needs BW = 4 input copies and 4 kernel copies: one copy after every fourth MFMA
+    // wave it needs 4 input copies and 4 kernel copies: one copy after every fourth MFMA
     // keeps the copy queue shallow.  In the k-step after the barrier of iteration s go the input
     // copies of stage s+NB, into the ring slot that iteration has just finished reading (the
     // last k-step's operands are in registers); in the first k-step of iteration s+1 go that
     // stage's kernel copies, and, dealt out over the other gaps, the scalar arithmetic that
     // moves the input-side state on by one stage.  No gap holds more than a handful of
     // instructions, so the next MFMA is always issued before the matrix pipe runs dry.
-    static_assert(KS == 2 && BW == 4 && NMMA == 16, "the schedule below is written for this shape");
-    constexpr int LOOKUP_GAP[8] = {4, 5, 7, 8, 9, 11, 12, 13};  // gaps of k-step 0 free of copies
+    // With the 128-row tile a k-step has 8 MFMAs and a wave 2 input copies; two workgroups share
+    // the CU then, so a fuller gap in one wave is covered by the other wave of the SIMD.
+    static_assert(KS == 2 && BWB == 4 && (NMMA == 16 || NMMA == 8), "the schedule is written for these shapes");
+    // gap (index of the MFMA it follows) of: kernel copy j (k-step 0), input copy j (k-step 1),
+    // piece of the input-side advance, tap lookup of pixel j (k-step 0, after the advance)
+    constexpr auto copy_b_gap = [](int j) { return NMMA == 16 ? 4 * j + 2 : 2 * j + 1; };
+    constexpr auto copy_a_gap = [](int j) { return NMMA == 16 ? 4 * j + 2 : 4 * j + 3; };
+    constexpr auto advance_gap = [](int piece) { return NMMA == 16 && piece == 2 ? 3 : piece; };
+    constexpr auto lookup_gap = [](int j) {
+        constexpr int wide[8] = {4, 5, 7, 8, 9, 11, 12, 13};  // free of copies
+        return NMMA == 16 ? wide[j] : 4 + j;
+    };
+    // with two waves per SIMD the MFMAs are held in their gaps explicitly (a pure instruction
+    // may otherwise drift across the scheduling barriers)
+    auto mma = [&](const chunk_t& ka, const chunk_t& ib, float16v& c) {
+        if constexpr (BM == 128) asm volatile("" : "+a"(c));
+        Mma<Tag>::run(ka, ib, c);
+        if constexpr (BM == 128) asm volatile("" : "+a"(c));
+    };
 
     // ---- prologue: stages 0..NB-2 whole and the input side of stage NB-1, wait for stage 0,
     // fetch its first fragments
     static_for<NB - 1>([&](auto S0) {
 #pragma unroll
         for (int j = 0; j < PPW; ++j) stage_offset(j);
-        static_for<BW>([&](auto J) { copy_a(S0, J); });
-        static_for<BW>([&](auto J) { copy_b(S0, J); });
+        static_for<BWA>([&](auto J) { copy_a(S0, J); });
+        static_for<BWB>([&](auto J) { copy_b(S0, J); });
         advance_a(0);
         advance_a(1);
         advance_a(2);
@@ -372,9 +394,9 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
     });
 #pragma unroll
     for (int j = 0; j < PPW; ++j) stage_offset(j);
-    static_for<BW>([&](auto J) { copy_a(std::integral_constant<int, NB - 1>{}, J); });
+    static_for<BWA>([&](auto J) { copy_a(std::integral_constant<int, NB - 1>{}, J); });
     {
-        constexpr int keep0 = (NB - 2) * NCOPY + BW;
+        constexpr int keep0 = (NB - 2) * NCOPY + BWA;
         static_assert(keep0 < 64, "vmcnt is a 6-bit counter");
         __builtin_amdgcn_s_waitcnt(0x0F70 | (keep0 & 15) | ((keep0 >> 4) << 14));
     }
@@ -392,15 +414,17 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
             // k-step 0: kernel copies of the stage NB-1 ahead; input-side state -> stage NB ahead
             static_for<NMMA>([&](auto I) {
                 constexpr int i = decltype(I)::value;
-                Mma<Tag>::run(frag[0][i / TM], frag[0][TN + i % TM], acc[i / TM][i % TM]);
+                mma(frag[0][i / TM], frag[0][TN + i % TM], acc[i / TM][i % TM]);
                 if constexpr (i < NFRAG) frag[1][i] = read_frag(slot, 1, i);
-                if constexpr (i % 4 == 2) copy_b(SlotPrev{}, std::integral_constant<int, i / 4>{});
-                if constexpr (i == 0) advance_a(0);
-                if constexpr (i == 1) advance_a(1);
-                if constexpr (i == 3) advance_a(2);
-#pragma unroll
-                for (int j = 0; j < PPW; ++j)
-                    if (LOOKUP_GAP[j] == i) stage_offset(j);
+                static_for<BWB>([&](auto J) {
+                    if constexpr (copy_b_gap(decltype(J)::value) == i) copy_b(SlotPrev{}, J);
+                });
+                static_for<3>([&](auto PC) {
+                    if constexpr (advance_gap(decltype(PC)::value) == i) advance_a(decltype(PC)::value);
+                });
+                static_for<PPW>([&](auto J) {
+                    if constexpr (lookup_gap(decltype(J)::value) == i) stage_offset(decltype(J)::value);
+                });
                 if constexpr (i == NMMA - 1) advance_b();
                 __builtin_amdgcn_sched_barrier(0);
             });
@@ -411,9 +435,11 @@ __global__ __launch_bounds__(256) void igemm16_fast_kernel(const IgemmParams P)
             // k-step 1: input copies of the stage NB ahead into the slot just released
             static_for<NMMA>([&](auto I) {
                 constexpr int i = decltype(I)::value;
-                Mma<Tag>::run(frag[1][i / TM], frag[1][TN + i % TM], acc[i / TM][i % TM]);
+                mma(frag[1][i / TM], frag[1][TN + i % TM], acc[i / TM][i % TM]);
                 if constexpr (i < NFRAG) frag[0][i] = read_frag(slot_next, 0, i);
-                if constexpr (i % 4 == 2) copy_a(SLOT, std::integral_constant<int, i / 4>{});
+                static_for<BWA>([&](auto J) {
+                    if constexpr (copy_a_gap(decltype(J)::value) == i) copy_a(SLOT, J);
+                });
                 __builtin_amdgcn_sched_barrier(0);
             });
         });
@@ -528,10 +554,25 @@ struct FastConfig<8, 8> { static constexpr int KCH = 4, NB = 4; };
 template <typename Tag, int D1, int D2>
 hipError_t launch_one(const IgemmParams& P, long long blocks, hipStream_t stream)
 {
-    constexpr int KCH = FastConfig<D1, D2>::KCH, NB = FastConfig<D1, D2>::NB;
-    typedef ALayout<D1, D2, KCH> AL;
-    auto kern = P.out16 ? igemm16_fast_kernel<Tag, D1, D2, KCH, NB, true>
-                        : igemm16_fast_kernel<Tag, D1, D2, KCH, NB, false>;
+    constexpr int KCH = FastConfig<D1, D2>::KCH;
+    if (P.bm == 128) {
+        // two workgroups per CU: a ring of 3 stages of 24..25.6 KB each
+        constexpr int NB = 3;
+        typedef ALayout<D1, D2, KCH, 128> AL;
+        auto kern = P.out16 ? igemm16_fast_kernel<Tag, D1, D2, KCH, NB, true, 128>
+                            : igemm16_fast_kernel<Tag, D1, D2, KCH, NB, false, 128>;
+        const size_t lds_bytes = (size_t)NB * (AL::NBLK * AL::ABLK + 256 * KCH * 16);
+        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                             (int)lds_bytes);
+        if (err != hipSuccess) return err;
+        kern<<<dim3((unsigned)blocks), dim3(256), lds_bytes, stream>>>(P);
+        return hipGetLastError();
+    }
+    constexpr int NB = FastConfig<D1, D2>::NB;
+    typedef ALayout<D1, D2, KCH, 256> AL;
+    auto kern = P.out16 ? igemm16_fast_kernel<Tag, D1, D2, KCH, NB, true, 256>
+                        : igemm16_fast_kernel<Tag, D1, D2, KCH, NB, false, 256>;
     const size_t lds_bytes = (size_t)NB * AL::NBLK * (AL::ABLK + 1024);
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -572,14 +613,21 @@ bool igemm16_fast_eligible(const ConvShape& s)
     return true;
 }
 
-bool igemm16_fast_preferred(const ConvShape& s)
+// Tile height the kernel would use: 256 rows when that gives every CU a tile, else 128 rows
+// (half the work per tile, two workgroups per CU; 6 % slower per FLOP on config 5, so only
+// when the larger tile cannot fill the chip), 0 when even those are too few: such problems
+// use the generic kernel's small tiles and split K loop.
+int igemm16_fast_tile_rows(const ConvShape& s)
 {
-    if (!igemm16_fast_eligible(s)) return false;
-    // enough 256x256 tiles to fill the chip; smaller problems use the generic kernel's tiles
+    if (!igemm16_fast_eligible(s)) return 0;
     const long long colsp = ((long long)s.M * s.D3 + 255) / 256 * 256;
-    const long long tiles = ((long long)s.pixels() * s.D1 + 255) / 256 * (colsp / 256) * s.D0;
-    return tiles >= 256;
+    const long long rows = (long long)s.pixels() * s.D1;
+    if ((rows + 255) / 256 * (colsp / 256) * s.D0 >= 256) return 256;
+    if ((rows + 127) / 128 * (colsp / 256) * s.D0 >= 256) return 128;
+    return 0;
 }
+
+bool igemm16_fast_preferred(const ConvShape& s) { return igemm16_fast_tile_rows(s) != 0; }
 
 int igemm16_fast_kgroup(const ConvShape& s)
 {

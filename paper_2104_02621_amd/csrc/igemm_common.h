@@ -113,6 +113,7 @@ struct IgemmParams {
     // its launch order: tiles per image (0 = plain order), and how many of an image's first and
     // last row tiles have a shortened K loop (they are launched last)
     int lpt_timg, lpt_a, lpt_b;
+    int bm;  // its tile height: 256 or 128 rows
 };
 
 // Shared launch helpers (igemm_conv.hip).  Repack: 16-byte chunks of `cw` valid K elements
@@ -152,6 +153,7 @@ hipError_t launch_igemm32_dma(const Dma32Plan& pl, hipStream_t stream);
 // Tuned 16-bit kernel (igemm16_fast.hip): 256x256 tiles, direct-to-LDS copies.
 bool igemm16_fast_eligible(const ConvShape& s);   // the kernel can run the shape
 bool igemm16_fast_preferred(const ConvShape& s);  // ... and is the library's choice for it
+int igemm16_fast_tile_rows(const ConvShape& s);   // 256, 128, or 0 if not preferred
 int igemm16_fast_kgroup(const ConvShape& s);      // chunks per K stage (repack order)
 hipError_t launch_igemm16_fast(const IgemmParams& P, long long blocks, int dtype,
                                hipStream_t stream);

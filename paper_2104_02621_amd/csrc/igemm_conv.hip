@@ -344,6 +344,12 @@ Plan make_plan(const ConvShape& s, MfmaKernel which)
         if (fits_cols && blocks >= 2 * kCUs) { pick = i; break; }
     }
     pl.tile = choices[pick];
+    // tuned 16-bit kernel: 128-row tiles (two workgroups per CU) or 256-row tiles
+    P.bm = 256;
+    if (pl.fast && igemm16_fast_tile_rows(s) == 128) {
+        P.bm = 128;
+        pl.tile.BM = 128;
+    }
     P.row_tiles = ceil_div(P.rows, pl.tile.BM);
     P.col_tiles = ceil_div(P.cols, pl.tile.BN);
     P.colsp = P.col_tiles * pl.tile.BN;
@@ -370,11 +376,11 @@ Plan make_plan(const ConvShape& s, MfmaKernel which)
     P.out_base = s.out_base; P.out_sn = s.out_sn; P.out_sx = s.out_sx; P.out_sy = s.out_sy;
     P.out_alloc = s.out_view ? s.out_alloc : P.out_elems;
     P.lpt_timg = P.lpt_a = P.lpt_b = 0;
-    if (pl.fast && s.D0 == 1 && s.D1 > 0 && 256 % s.D1 == 0) {
+    if (pl.fast && s.D0 == 1 && s.D1 > 0 && P.bm % s.D1 == 0) {
         // tiles of the tuned kernel hold 256/D1 consecutive pixels; when they do not straddle
         // images, count an image's leading (trailing) tiles all of whose pixels have a window
         // row above (below) the image
-        const long long pix = 256 / s.D1, hw = (long long)s.Ho * s.Wo;
+        const long long pix = P.bm / s.D1, hw = (long long)s.Ho * s.Wo;
         if (hw % pix == 0 && hw / pix < (1 << 20)) {
             const int timg = (int)(hw / pix);
             int a = 0, b = 0;

@@ -122,6 +122,27 @@ def test_tuned_16bit_kernel_matches_oracle(shape, dtype):
     assert np.array_equal(got.astype(np.float64), ref), wi.name
 
 
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.FP16], ids=["bf16", "fp16"])
+@pytest.mark.parametrize("shape", [
+    #        N   H   W   C   M  kh kw s  p D0  D1  D2  D3
+    ("h16", 3, 30, 30, 4, 16, 3, 3, 1, 1, 1, 16, 16, 16),   # 169 tiles of 256 rows, 338 of 128
+    ("h8", 5, 61, 59, 8, 20, 3, 3, 2, 2, 1, 8, 8, 12),      # ragged last tile and columns
+], ids=["h16", "h8"])
+def test_tuned_16bit_kernel_half_height_tiles(shape, dtype):
+    """Problems that fill the chip with 128-row tiles but not with 256-row ones take the tuned
+    kernel's half-height variant (two workgroups per CU) on the library's own choice."""
+    w = small(shape[0], dtype, *shape[1:], seed=len(shape[0]) + 70)
+    assert cc.capscaps_select_path(*shape_args(w)) == cc.PATH_MFMA_TUNED16
+    rows = w.N * w.Ho * w.Wo * w.D1
+    assert (rows + 255) // 256 * ((w.M * w.D3 + 255) // 256) < 256 <= (rows + 127) // 128 * ((w.M * w.D3 + 255) // 256)
+    full_compare(w, cc.PATH_AUTO)
+    wi = small(shape[0] + "_int", dtype, *shape[1:], dist="int", seed=71)
+    i_st, k_st, i32, k32 = wl.generate(wi)
+    ref = capsconv.conv_fwd(i32, k32, wi.stride, wi.pad)
+    got = run_gpu(wi, to_device(i_st, dtype), to_device(k_st, dtype), cc.PATH_AUTO).cpu().numpy()
+    assert np.array_equal(got.astype(np.float64), ref), wi.name
+
+
 def test_tuned_kernel_refuses_other_shapes():
     import torch
     w = small("no", wl.FP32, 1, 6, 6, 4, 4, 3, 3, 1, 1, 1, 16, 16, 16)
