@@ -49,26 +49,33 @@ struct WgradParams {
     long long it_img_bytes, gt_img_bytes;
 };
 
-// dst[x][b][a] = src[x][a][b] for `nmat` matrices of A x B 16-bit elements, A % 8 == 0.
-// One thread per 16 destination bytes.
-__global__ __launch_bounds__(256) void transpose_caps_kernel(const unsigned short* __restrict__ src,
-                                                             unsigned short* __restrict__ dst,
-                                                             int A, int B, size_t chunks)
+// dst[x][b][a] = src[x][a][b] for `nmat` matrices of A x B 16-bit elements, A % 8 == 0 (so a
+// matrix is a whole number of 16-byte chunks).  A workgroup moves `mpb` whole matrices through
+// LDS: 16-byte loads and stores, both contiguous across the lanes; the transposition is the
+// 2-byte gather from LDS in between.  cpm = chunks per matrix = (A/8)*B <= 256.
+__global__ __launch_bounds__(256) void transpose_caps_kernel(const chunk_t* __restrict__ src,
+                                                             chunk_t* __restrict__ dst, int A,
+                                                             int B, int cpm, int mpb,
+                                                             size_t chunks)
 {
-    const size_t id = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (id >= chunks) return;
+    __shared__ chunk_t tile[256];
+    const size_t base = (size_t)blockIdx.x * mpb * cpm;
+    const int t = threadIdx.x;
+    const bool mine = t < mpb * cpm && base + t < chunks;
+    if (mine) tile[t] = src[base + t];
+    __syncthreads();
+    if (!mine) return;
     const int a8n = A / 8;
-    const int a8 = (int)(id % a8n);
-    const size_t rest = id / a8n;
-    const int b = (int)(rest % B);
-    const size_t mat = rest / B;
-    const unsigned short* s = src + (mat * A + (size_t)a8 * 8) * B + b;
+    const int a8 = t % a8n;
+    const int rest = t / a8n;
+    const int b = rest % B, mat = rest / B;
+    const unsigned short* m = reinterpret_cast<const unsigned short*>(tile) + mat * A * B;
     unsigned short v[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) v[e] = s[(size_t)e * B];
+    for (int e = 0; e < 8; ++e) v[e] = m[(a8 * 8 + e) * B + b];
     chunk_t out;
     __builtin_memcpy(&out, v, 16);
-    reinterpret_cast<chunk_t*>(dst)[id] = out;
+    dst[base + t] = out;
 }
 
 template <typename Tag, int D1>
@@ -438,11 +445,13 @@ size_t align256(size_t b) { return (b + 255) & ~(size_t)255; }
 hipError_t launch_transpose(const void* src, void* dst, size_t nmat, int A, int B,
                             hipStream_t stream)
 {
-    const size_t chunks = nmat * (size_t)(A / 8) * B;
-    const size_t blocks = (chunks + 255) / 256;
+    const int cpm = (A / 8) * B;  // <= 256: checked by wgrad16_eligible
+    const int mpb = 256 / cpm;
+    const size_t chunks = nmat * (size_t)cpm;
+    const size_t blocks = (nmat + mpb - 1) / mpb;
     if (blocks == 0 || blocks > 0x7fffffffULL) return hipErrorInvalidValue;
     transpose_caps_kernel<<<(unsigned)blocks, 256, 0, stream>>>(
-        static_cast<const unsigned short*>(src), static_cast<unsigned short*>(dst), A, B, chunks);
+        static_cast<const chunk_t*>(src), static_cast<chunk_t*>(dst), A, B, cpm, mpb, chunks);
     return hipGetLastError();
 }
 
@@ -466,6 +475,7 @@ bool wgrad16_eligible(const ConvShape& s)
     if (s.dtype != 1 && s.dtype != 2) return false;
     if (s.D1 != 8 && s.D1 != 16) return false;
     if (s.D3 % 4 != 0) return false;
+    if ((s.D1 / 8) * s.D2 > 256 || (s.D1 / 8) * s.D3 > 256) return false;  // the transpose's tile
     // 31-bit byte offsets within one image of either tensor, 31-bit row/column/pixel counts
     const long long it_img = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 2;
     const long long gt_img = (long long)s.Ho * s.Wo * s.M * s.D0 * s.D1 * s.D3 * 2;
