@@ -137,7 +137,14 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
     // shorter (see tap_lo / tap_hi below), are launched after all others, so that they fill the
     // last round of tiles instead of leaving CUs idle at the end (the host's plan says how many
     // such tiles an image has; 0 = launch order is tile order).
-    const int L = blockIdx.x;
+    // Work items past tail_first are pieces of the last tiles: tile and piece of its K loop.
+    int L = blockIdx.x;
+    int tail_piece = -1;
+    if (P.tail_split > 0 && L >= P.tail_first) {
+        const int k = L - P.tail_first;
+        L = P.tail_first + k / P.tail_split;
+        tail_piece = k - (k / P.tail_split) * P.tail_split;
+    }
     const int col_tile = L % P.col_tiles;
     int rest = L / P.col_tiles;
     int row_tile = rest % P.row_tiles;
@@ -256,16 +263,24 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
     // whose input copies go out next, the kernel-side state (one offset) the stage whose kernel
     // copies go out next; in the steady state the input side runs one stage ahead.
     const int groups = P.KQP / KCH;
+    // channel groups of this work item: all, or one piece of a tile of the last round
+    int g_first = 0, g_count = groups;
+    if (tail_piece >= 0) {
+        const int per = (groups + P.tail_split - 1) / P.tail_split;
+        g_first = tail_piece * per;
+        g_count = g_first >= groups ? 0 : (groups - g_first < per ? groups - g_first : per);
+    }
     const int nlive = tap_hi - tap_lo;                      // taps per channel group that run
-    const int nstages = nlive * groups;
+    const int nstages = nlive * g_count;
     const int nstages_pad = (nstages + NB - 1) / NB * NB;  // surplus stages contract zeros
     const int c_step = (KCH / D2C) * P.cs * 2;             // bytes per channel group
     const int kp_step = KCH * P.colsp * 16;                 // repacked kernel bytes per stage
     const int kp_wrap = (P.ntaps - nlive + 1) * kp_step;    // last live tap -> first of next group
     const int row_skip = (P.W - P.kw + 1) * pix_bytes;     // last tap of a window row -> next row
     const int tap_off0 = (tap_lo / P.kw) * P.W * pix_bytes;
-    int a_stage = 0, tap = tap_lo, tap_q_cur = 0, tap_off = tap_off0, c_off = 0;
-    int kp_off = (int)((((long long)d0 * groups * P.ntaps + tap_lo) * KCH * P.colsp + col0) * 16);
+    int a_stage = 0, tap = tap_lo, tap_q_cur = 0, tap_off = tap_off0, c_off = g_first * c_step;
+    int kp_off = (int)(((((long long)d0 * groups + g_first) * P.ntaps + tap_lo) * KCH * P.colsp +
+                        col0) * 16);
     int kp_left = nlive;  // kernel-side stages until the next channel group
     // kernel-side state -> next stage
     // (Scalar arithmetic has no side effect the compiler must order, so by itself it may drift
@@ -450,8 +465,12 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
 
     // ---- epilogue: lane (h, lr) of MFMA tile (a, b) holds in registers 4g..4g+3 the columns
     // 8g + 4h + 0..3 of that tile for its output row lr.
-    float* __restrict__ out = P.out;
     const int caps_out = P.D0 * D1 * P.D3;
+    // a piece of a tile writes into its own copy of the output's last pixels
+    const long long tail_shift = (long long)P.tail_pix0 * P.M * caps_out;
+    float* __restrict__ out =
+        tail_piece < 0 ? P.out : P.tail_partial + (long long)tail_piece * P.tail_elems - tail_shift;
+    const long long out_alloc = tail_piece < 0 ? P.out_alloc : tail_shift + P.tail_elems;
     const int d3_shift = 31 - __builtin_clz(P.D3);
     // element offset of an output pixel
     auto pixel_offset = [&](int pixel) -> long long {
@@ -482,7 +501,7 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
                                   (d0 * D1 + d1) * P.D3 + lane_col;
             voff[b] = pixel < npix ? (unsigned)(rel * ES) : 0x80000000u;
         }
-        long long bytes_left = (P.out_alloc - tile_base) * ES;
+        long long bytes_left = (out_alloc - tile_base) * ES;
         if (bytes_left > 0x7fffffffLL) bytes_left = 0x7fffffffLL;
         const unsigned long long base_addr =
             reinterpret_cast<unsigned long long>(out) + (unsigned long long)(tile_base * ES);

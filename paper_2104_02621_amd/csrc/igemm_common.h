@@ -114,6 +114,13 @@ struct IgemmParams {
     // last row tiles have a shortened K loop (they are launched last)
     int lpt_timg, lpt_a, lpt_b;
     int bm;  // its tile height: 256 or 128 rows
+    // its last, partial round of tiles: tiles tail_first.. are each cut into tail_split work
+    // items over the channel groups of the K loop, which write fp32 partial results into
+    // tail_partial [tail_split][tail_elems] (the output's last tail_elems elements, from pixel
+    // tail_pix0 on); the caller adds them up.  tail_split = 0: off.
+    int tail_first, tail_split, tail_pix0;
+    long long tail_elems;
+    float* tail_partial;
 };
 
 // Shared launch helpers (igemm_conv.hip).  Repack: 16-byte chunks of `cw` valid K elements

@@ -295,6 +295,7 @@ struct Plan {
     bool vec, st4;
     bool fast;  // tuned 16-bit kernel
     bool via_scratch;  // results go to fp32 scratch first, then through splitk_reduce_kernel
+    size_t tail_bytes;  // tuned kernel: scratch for the partial results of its last round
     size_t repack_bytes, partial_bytes;
     long long blocks;
     int CH;
@@ -412,6 +413,40 @@ Plan make_plan(const ConvShape& s, MfmaKernel which)
         const bool strides_ok = !s.out_view || (s.out_sn >= 0 && s.out_sx >= 0 && s.out_sy >= 0);
         P.fast_store = d3_ok && strides_ok && span * 4 < (1LL << 31) - (1 << 20) ? 1 : 0;
     }
+    // Tuned kernel, last round of tiles.  With T tiles on 256 CUs the last T % 256 tiles run
+    // alone while the other CUs idle; when they are few, each is cut into several work items
+    // over the channel groups of its K loop, so that the last round takes a fraction of a
+    // tile's time; a reduction over the output's last pixels follows.  Only where the last
+    // tiles in launch order are the output's last pixels (dense fp32 output, one leading
+    // capsule index, plain launch order).
+    P.tail_first = P.tail_split = P.tail_pix0 = 0;
+    P.tail_elems = 0;
+    P.tail_partial = nullptr;
+    pl.tail_bytes = 0;
+    if (pl.fast && s.D0 == 1 && !s.out_view && s.out16 == 0 && P.lpt_timg == 0 && P.nsplit == 1) {
+        const long long T = (long long)P.row_tiles * P.col_tiles;
+        const int R = (int)(T % kCUs);
+        const int groups = P.KQP / igemm16_fast_kgroup(s);
+        if (T > kCUs && R > 0 && R <= kCUs / 2 && R % P.col_tiles == 0 && groups >= 2) {
+            int split = kCUs / R;
+            if (split > groups) split = groups;
+            if (split > 16) split = 16;
+            const long long pix_per_tile = P.bm / s.D1;
+            const long long pix0 = ((long long)P.row_tiles - R / P.col_tiles) * pix_per_tile;
+            const long long pix_elems = (long long)s.M * s.D0 * s.D1 * s.D3;
+            const long long elems = (s.pixels() - pix0) * pix_elems;
+            if (split >= 2 && pix0 > 0 && pix0 < (1LL << 31) && elems > 0 &&
+                (double)split * elems * 4 < (double)(1 << 30)) {
+                P.tail_first = (int)(T - R);
+                P.tail_split = split;
+                P.tail_pix0 = (int)pix0;
+                P.tail_elems = elems;
+                pl.tail_bytes = (size_t)split * elems * sizeof(float);
+                pl.blocks = (T - R) + (long long)R * split;
+            }
+        }
+    }
+    if (pl.tail_bytes > pl.partial_bytes) pl.partial_bytes = pl.tail_bytes;
     return pl;
 }
 
@@ -476,7 +511,14 @@ hipError_t launch_igemm(const ConvShape& s, const void* in, const void* kernel, 
     hipError_t err = launch_repack(s, kernel, kp, pl.CH, pl.P.KQP, pl.P.colsp, kgroup, chunks, stream);
     if (err != hipSuccess) return err;
 
-    if (pl.fast) return launch_igemm16_fast(pl.P, pl.blocks, s.dtype, stream);
+    if (pl.fast) {
+        pl.P.tail_partial = partial;
+        err = launch_igemm16_fast(pl.P, pl.blocks, s.dtype, stream);
+        if (err != hipSuccess || pl.P.tail_split == 0) return err;
+        const long long pix_elems = (long long)s.M * s.D0 * s.D1 * s.D3;
+        return launch_splitk_reduce(partial, out + (long long)pl.P.tail_pix0 * pix_elems,
+                                    pl.P.tail_elems, pl.P.tail_split, stream);
+    }
 
     switch (s.dtype) {
         case 0: err = launch_typed<f32_tag>(pl, stream); break;
