@@ -1,7 +1,8 @@
 """GPU parity of the forward pass with 16-bit output (capscaps_conv_fwd_out16): the fp32
 accumulator rounded to nearest even once, at the store.  Two checks: against the same library's
-fp32 output rounded on the host (must agree bit for bit: same kernel, same summation order, one
-rounding), and against the CPU oracle within half a 16-bit unit plus the fp32 summation error."""
+fp32 output rounded on the host (bit for bit where both calls sum in the same order: same kernel,
+one rounding), and against the CPU oracle within half a 16-bit unit plus the fp32 summation
+error."""
 import numpy as np
 import pytest
 
@@ -47,13 +48,24 @@ def bits_to_f64(bits, dtype):
     return bits.view(np.float16).astype(np.float64)
 
 
-def check_out16(w, ref=None, S=None, sample=None):
+def check_out16(w, ref=None, S=None, sample=None, exact_order=True):
     i_st, k_st, i32, k32 = wl.generate(w)
     i_dev, k_dev = to_device(i_st, w.dtype), to_device(k_st, w.dtype)
     got_bits = to_bits(run_out16(w, i_dev, k_dev))
-    # (1) one rounding of the very same fp32 result
+    # (1) one rounding of the very same fp32 result.  On large problems the fp32 call may add
+    # up the last tiles' K loop in pieces (another summation order, last bits differ): there a
+    # few values near a rounding tie may land on the neighbouring 16-bit number.
     out32 = run_gpu(w, i_dev, k_dev, cc.PATH_AUTO).cpu().numpy()
-    assert np.array_equal(got_bits, round_on_host(out32, w.dtype)), w.name
+    same = got_bits == round_on_host(out32, w.dtype)
+    if not exact_order:
+        off = ~same
+        assert off.mean() < 1e-3, w.name
+        g = bits_to_f64(got_bits[off], w.dtype)
+        # half a 16-bit unit, plus what two fp32 summation orders can differ by
+        noise = 1e-6 * np.abs(out32).max()
+        assert (np.abs(g - out32[off]) <= 0.51 * ULP16[w.dtype] * np.abs(out32[off]) + noise).all()
+    else:
+        assert same.all(), w.name
     # (2) the oracle: half a unit of the 16-bit type, the fp32 summation error, and the
     # absolute spacing of the type's smallest numbers
     got = bits_to_f64(got_bits, w.dtype)
@@ -83,7 +95,7 @@ def test_benchmark_configs_full_size_sampled(number):
     """Full size, the tuned kernel's 16-bit-output variant; the oracle on sampled capsules."""
     w = wl.config(number)
     assert cc.capscaps_select_path(*shape_args(w)) == cc.PATH_MFMA_TUNED16
-    check_out16(w, sample=wl.sample_capsules(w, 1500, seed=77 + number))
+    check_out16(w, sample=wl.sample_capsules(w, 1500, seed=77 + number), exact_order=False)
 
 
 def test_fp32_operands_are_refused():
