@@ -145,6 +145,7 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
         L = P.tail_first + k / P.tail_split;
         tail_piece = k - (k / P.tail_split) * P.tail_split;
     }
+    if (L < P.xcd_span) L = (L & 7) * (P.xcd_span >> 3) + (L >> 3);
     const int col_tile = L % P.col_tiles;
     int rest = L / P.col_tiles;
     int row_tile = rest % P.row_tiles;
@@ -279,6 +280,8 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
     const int row_skip = (P.W - P.kw + 1) * pix_bytes;     // last tap of a window row -> next row
     const int tap_off0 = (tap_lo / P.kw) * P.W * pix_bytes;
     int a_stage = 0, tap = tap_lo, tap_q_cur = 0, tap_off = tap_off0, c_off = g_first * c_step;
+    constexpr int DEAD_TAP = 63;  // no window has a 64th tap (checked by the launcher)
+    int tap_sel = nstages > 0 ? tap_lo : DEAD_TAP;
     int kp_off = (int)(((((long long)d0 * groups + g_first) * P.ntaps + tap_lo) * KCH * P.colsp +
                         col0) * 16);
     int kp_left = nlive;  // kernel-side stages until the next channel group
@@ -306,14 +309,18 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
     // All of the following is scalar arithmetic (nothing on the vector pipe that could hold up
     // the MFMAs); the main loop deals it out in small pieces between the MFMAs.
     // offset of the input-side stage's copies for pixel j
+    // (three scalar instructions, written out: bit tap_sel of the pixel's tap mask picks the
+    // address or the out-of-range mark; tap_sel is the input-side stage's tap, or the always
+    // clear bit 63 past the last stage, whose copies then fill zeros and touch no memory)
     auto stage_offset = [&](int j) {
-        // past the last stage (surplus stages of the ring): zero fill, touches no memory
-        asm volatile("" : "+s"(tap), "+s"(tap_off), "+s"(a_stage));
-        const bool ok = ((tap_ok[j] >> tap) & 1ull) != 0 && a_stage < nstages;
-        a_soff[j] = ok ? pix_off[j] + tap_off : OOB;
-        asm volatile("" : "+s"(a_soff[j]));
+        asm volatile("s_add_i32 %0, %3, %4\n\t"
+                     "s_bitcmp1_b64 %1, %2\n\t"
+                     "s_cselect_b32 %0, %0, 0x80000000"
+                     : "=&s"(a_soff[j])
+                     : "s"(tap_ok[j]), "s"(tap_sel), "s"(pix_off[j]), "s"(tap_off)
+                     : "scc");
     };
-    // input-side state -> next stage, in three pieces
+    // input-side state -> next stage, in four pieces (0, 1, 2, then 3)
     auto advance_a = [&](int piece) {
         asm volatile("" : "+s"(a_stage), "+s"(tap), "+s"(tap_q_cur), "+s"(tap_off), "+s"(c_off));
         if (piece == 0) {
@@ -324,14 +331,24 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
             const bool row_end = tap_q_cur == P.kw;
             tap_q_cur = row_end ? 0 : tap_q_cur;
             tap_off += row_end ? row_skip : pix_bytes;
+        } else if (piece == 3) {
+            tap_sel = a_stage < nstages ? tap : DEAD_TAP;
         } else {
-            const bool wrap = tap == tap_hi;  // window done: next channel group, first live tap
-            tap = wrap ? tap_lo : tap;
-            tap_q_cur = wrap ? 0 : tap_q_cur;
-            tap_off = wrap ? tap_off0 : tap_off;
-            c_off = wrap ? c_off + c_step : c_off;
+            // window done (tap == tap_hi): next channel group, first live tap.  Written out
+            // so that it stays four selects (the compiler makes a branch of it in some slots).
+            int step;
+            asm volatile("s_cmp_eq_u32 %0, %5\n\t"
+                         "s_cselect_b32 %0, %6, %0\n\t"
+                         "s_cselect_b32 %1, 0, %1\n\t"
+                         "s_cselect_b32 %2, %7, %2\n\t"
+                         "s_cselect_b32 %4, %8, 0\n\t"
+                         "s_add_i32 %3, %3, %4"
+                         : "+s"(tap), "+s"(tap_q_cur), "+s"(tap_off), "+s"(c_off), "=&s"(step)
+                         : "s"(tap_hi), "s"(tap_lo), "s"(tap_off0), "s"(c_step)
+                         : "scc");
         }
-        asm volatile("" : "+s"(a_stage), "+s"(tap), "+s"(tap_q_cur), "+s"(tap_off), "+s"(c_off));
+        asm volatile("" : "+s"(a_stage), "+s"(tap), "+s"(tap_q_cur), "+s"(tap_off), "+s"(c_off),
+                     "+s"(tap_sel));
     };
     // input copy J (0 .. BWA-1) of the input-side stage / kernel copy J of the kernel-side stage
     auto copy_a = [&](auto SLOT, auto J) {
@@ -382,9 +399,12 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
     // piece of the input-side advance, tap lookup of pixel j (k-step 0, after the advance)
     constexpr auto copy_b_gap = [](int j) { return NMMA == 16 ? 4 * j + 2 : 2 * j + 1; };
     constexpr auto copy_a_gap = [](int j) { return NMMA == 16 ? 4 * j + 2 : 4 * j + 3; };
-    constexpr auto advance_gap = [](int piece) { return NMMA == 16 && piece == 2 ? 3 : piece; };
+    constexpr auto advance_gap = [](int piece) {
+        constexpr int wide[4] = {0, 1, 3, 4}, narrow[4] = {0, 1, 2, 3};
+        return NMMA == 16 ? wide[piece] : narrow[piece];
+    };
     constexpr auto lookup_gap = [](int j) {
-        constexpr int wide[8] = {4, 5, 7, 8, 9, 11, 12, 13};  // free of copies
+        constexpr int wide[8] = {5, 7, 8, 9, 11, 12, 13, 10};
         return NMMA == 16 ? wide[j] : 4 + j;
     };
     // with two waves per SIMD the MFMAs are held in their gaps explicitly (a pure instruction
@@ -405,6 +425,7 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
         advance_a(0);
         advance_a(1);
         advance_a(2);
+        advance_a(3);
         advance_b();
     });
 #pragma unroll
@@ -434,7 +455,7 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
                 static_for<BWB>([&](auto J) {
                     if constexpr (copy_b_gap(decltype(J)::value) == i) copy_b(SlotPrev{}, J);
                 });
-                static_for<3>([&](auto PC) {
+                static_for<4>([&](auto PC) {
                     if constexpr (advance_gap(decltype(PC)::value) == i) advance_a(decltype(PC)::value);
                 });
                 static_for<PPW>([&](auto J) {
@@ -617,7 +638,7 @@ bool igemm16_fast_eligible(const ConvShape& s)
     if (!((s.D1 == 16 && s.D2 == 16) || (s.D1 == 8 && s.D2 == 8))) return false;
     if (s.D3 % 4 != 0) return false;
     if ((s.C * s.D2) % 64 != 0) return false;  // whole K stages per channel group
-    if (s.kh * s.kw > 64) return false;        // one lane of the tap table per window tap
+    if (s.kh * s.kw > 63) return false;        // one bit of the tap masks per window tap, bit 63 kept clear
     // 31-bit byte offsets: a tile's input window spans at most the images its 256/D1 pixels
     // touch; the repacked kernel is addressed from its start
     const long long img_bytes = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 2;

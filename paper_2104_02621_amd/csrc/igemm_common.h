@@ -119,6 +119,11 @@ struct IgemmParams {
     // tail_partial [tail_split][tail_elems] (the output's last tail_elems elements, from pixel
     // tail_pix0 on); the caller adds them up.  tail_split = 0: off.
     int tail_first, tail_split, tail_pix0;
+    // Launch order of the tuned kernel's first xcd_span work items (a multiple of 8 column-tile
+    // groups; 0 = off): the hardware deals consecutive workgroups to the 8 XCDs in turn, and
+    // with this set XCD j takes the j-th contiguous eighth of those tiles, so that all column
+    // tiles of a row tile and its neighbouring row tiles read their input through one L2.
+    int xcd_span;
     long long tail_elems;
     float* tail_partial;
 };
