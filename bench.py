@@ -35,8 +35,8 @@ PEAK_HBM_GBS = 8000.0
 # runs scaled by a copy kernel of known size (see profiles/); None until measured.
 MEASURED_TRAFFIC_BYTES = {
     # profiles/igemm16_fast_hbm_traffic_configs_3_5.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB
-    5: int((7221076 * 2.0 + 4194338) * 1024),
-    3: int((1421796 * 2.0 + 401408) * 1024),
+    5: int((8270338 * 2.0 + 4295766) * 1024),
+    3: int((521525 * 2.0 + 458752) * 1024),
 }
 
 

@@ -431,6 +431,12 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
 #pragma unroll
     for (int j = 0; j < PPW; ++j) stage_offset(j);
     static_for<BWA>([&](auto J) { copy_a(std::integral_constant<int, NB - 1>{}, J); });
+    // the accumulators are cleared here, while the first copies are on their way (left to
+    // itself the compiler clears them after the wait)
+#pragma unroll
+    for (int a = 0; a < TN; ++a)
+#pragma unroll
+        for (int b = 0; b < TM; ++b) asm volatile("" : "+a"(acc[a][b]));
     {
         constexpr int keep0 = (NB - 2) * NCOPY + BWA;
         static_assert(keep0 < 64, "vmcnt is a 6-bit counter");
