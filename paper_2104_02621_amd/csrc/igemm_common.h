@@ -149,6 +149,11 @@ struct Dma32Params {
     int nstages;   // channel groups * taps
     int stages_per_split, nsplit;
     int row_tiles, col_tiles;
+    // launch order: 0 = column tiles fastest, then row tiles, leading capsule index, K split;
+    // > 0 = leading capsule index fastest, then column tiles, row tiles, and the first
+    // xcd_span workgroups (a multiple of 8) permuted so that XCD j takes the j-th contiguous
+    // eighth of the tiles (the hardware deals consecutive workgroups to the 8 XCDs in turn)
+    int xcd_span;
 };
 struct Dma32Plan {
     Dma32Params P;
