@@ -40,6 +40,7 @@ struct Wgrad32Params {
     int rows, cols;  // C*D2, M*D3
     int row_tiles, col_tiles, ntaps;
     int tiles;       // ntaps * D0 * row_tiles * col_tiles
+    int natural;          // 1: it / gt are the input and the output gradient themselves
     int nsplit;           // ranges the K loop (a tap's valid output pixels) is cut into
     long long items;      // tiles * nsplit = workgroups
     long long out_elems;  // elements of dK
@@ -60,7 +61,12 @@ __global__ __launch_bounds__(256) void transpose_caps32_kernel(const float* __re
     dst[id] = src[(mat * A + a) * B + b];
 }
 
-template <int CW, int TN, int NW, int KCH>
+// NAT: the operands are the tensors themselves (square capsules, D1 = D2 = D3) instead of the
+// capsule-transposed copies.  The copies are the same -- lane i then brings row (c, d1) with its
+// d2 values where the transposed tensor has row (c, d2) with its d1 values, at the same byte
+// offsets -- and the MFMA operands, single floats, are picked out of the slots one by one:
+// row (c, d2) at K index (pixel, d1) is element d2 of slot (pixel, c, d1).
+template <int CW, int TN, int NW, int KCH, bool NAT>
 __global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
 {
     constexpr int NB = ring_depth(KCH);
@@ -238,8 +244,57 @@ __global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
 #pragma unroll
     for (int b = 0; b < TM; ++b) row_tile_live[b] = row_tile * BM + 64 * wave + b * 32 < P.rows;
 
+    // NAT: byte offsets of this lane's operands.  MFMA k-pair j takes K index 2j (lower half
+    // wave) and 2j+1 (upper half) of the stage's KCH*CW indices (pixel, d1).
+    constexpr int NPAIR = KCH * CW / 2;
+    int na_base[TM], nb_base[TN], na_k[NPAIR], nb_k[NPAIR];
+    if constexpr (NAT) {
+#pragma unroll
+        for (int b = 0; b < TM; ++b) {
+            const int rl = 64 * wave + 32 * b + lr;  // row within the tile
+            const int c_l = rl / P.D2, d2 = rl - c_l * P.D2;
+            const bool real = row_tile * BM + rl < P.rows;
+            na_base[b] = real ? ((d2 / CW) * BM + c_l * P.D1) * 16 + (d2 % CW) * 4 : 0;
+        }
+#pragma unroll
+        for (int a = 0; a < TN; ++a) {
+            const int jl = a * 32 + lr;  // column within the tile
+            const int m_l = jl / P.D3, d3 = jl - m_l * P.D3;
+            const bool real = col_tile * BN + jl < P.cols;
+            nb_base[a] = A_BYTES + (real ? ((d3 / CW) * BNL + m_l * P.D1) * 16 + (d3 % CW) * 4 : 0);
+        }
+#pragma unroll
+        for (int j = 0; j < NPAIR; ++j) {
+            const int k = 2 * j + h;
+            const int p = k / P.D1, d1 = k - p * P.D1;
+            na_k[j] = (p * P.D1C * BM + d1) * 16;
+            nb_k[j] = (p * P.D1C * BNL + d1) * 16;
+        }
+    }
+
     auto compute_stage = [&](int slot) {
         const char* stage = smem + slot * STAGE_BYTES;
+        if constexpr (NAT) {
+#pragma unroll
+            for (int j = 0; j < NPAIR; ++j) {
+                float kb[TN], ia[TM];
+#pragma unroll
+                for (int a = 0; a < TN; ++a)
+                    kb[a] = *reinterpret_cast<const float*>(stage + nb_base[a] + nb_k[j]);
+#pragma unroll
+                for (int b = 0; b < TM; ++b)
+                    ia[b] = *reinterpret_cast<const float*>(stage + na_base[b] + na_k[j]);
+#pragma unroll
+                for (int b = 0; b < TM; ++b) {
+                    if (!row_tile_live[b]) continue;  // wave-uniform
+#pragma unroll
+                    for (int a = 0; a < TN; ++a)
+                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(kb[a], ia[b], acc[a][b],
+                                                                         0, 0, 0);
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int t = 0; t < KCH / 2; ++t) {
             // lanes 0..31 take chunk 2t, lanes 32..63 chunk 2t+1
@@ -376,8 +431,12 @@ Wgrad32Plan make_plan(const ConvShape& s)
     P.out_elems = (long long)s.kernel_elems();
     P.it_img_bytes = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 4;
     P.gt_img_bytes = (long long)s.Ho * s.Wo * s.M * s.D0 * s.D1 * s.D3 * 4;
-    pl.it_bytes = (size_t)s.N * P.it_img_bytes;
-    pl.gt_bytes = (size_t)s.N * P.gt_img_bytes;
+    // square capsules whose tiles begin at whole channels need no transposed copies
+    P.natural = s.D1 == s.D2 && s.D1 == s.D3 &&
+                (P.row_tiles == 1 || (64 * pl.nw) % s.D2 == 0) &&
+                (P.col_tiles == 1 || (32 * pl.tn) % s.D3 == 0);
+    pl.it_bytes = P.natural ? 0 : (size_t)s.N * P.it_img_bytes;
+    pl.gt_bytes = P.natural ? 0 : (size_t)s.N * P.gt_img_bytes;
 
     // Split of the K loop (a tap's valid output pixels, at most N*Ho*Wo) over workgroups.  The
     // workgroups resident at a time are bounded by LDS and registers; the split aims at one
@@ -416,11 +475,11 @@ hipError_t launch_transpose32(const void* src, void* dst, size_t nmat, int A, in
     return hipGetLastError();
 }
 
-template <int CW, int TN, int NW, int KCH>
-hipError_t launch_kch(const Wgrad32Params& P, hipStream_t stream)
+template <int CW, int TN, int NW, int KCH, bool NAT>
+hipError_t launch_nat(const Wgrad32Params& P, hipStream_t stream)
 {
     constexpr int BM = 64 * NW, BNL = (32 * TN + 63) / 64 * 64;
-    auto kern = wgrad32_kernel<CW, TN, NW, KCH>;
+    auto kern = wgrad32_kernel<CW, TN, NW, KCH, NAT>;
     const size_t lds_bytes = (size_t)ring_depth(KCH) * KCH * (BM + BNL) * 16;
     hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                          hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -428,6 +487,13 @@ hipError_t launch_kch(const Wgrad32Params& P, hipStream_t stream)
     if (err != hipSuccess) return err;
     kern<<<dim3((unsigned)P.items), dim3(64 * NW), lds_bytes, stream>>>(P);
     return hipGetLastError();
+}
+
+template <int CW, int TN, int NW, int KCH>
+hipError_t launch_kch(const Wgrad32Params& P, hipStream_t stream)
+{
+    return P.natural ? launch_nat<CW, TN, NW, KCH, true>(P, stream)
+                     : launch_nat<CW, TN, NW, KCH, false>(P, stream);
 }
 
 template <int CW, int TN, int NW>
@@ -487,13 +553,18 @@ hipError_t launch_wgrad32(const ConvShape& s, const void* input, const void* dou
     void* it = ws;
     void* gt = ws + align256(pl.it_bytes);
     float* partial = reinterpret_cast<float*>(ws + align256(pl.it_bytes) + align256(pl.gt_bytes));
-    hipError_t err = launch_transpose32(input, it, (size_t)s.N * s.H * s.W * s.C * s.D0, s.D1, s.D2,
-                                        stream);
-    if (err != hipSuccess) return err;
-    err = launch_transpose32(dout, gt, (size_t)s.N * s.Ho * s.Wo * s.M * s.D0, s.D1, s.D3, stream);
-    if (err != hipSuccess) return err;
-    pl.P.it = it;
-    pl.P.gt = gt;
+    hipError_t err = hipSuccess;
+    if (pl.P.natural) {
+        pl.P.it = input;
+        pl.P.gt = dout;
+    } else {
+        err = launch_transpose32(input, it, (size_t)s.N * s.H * s.W * s.C * s.D0, s.D1, s.D2, stream);
+        if (err != hipSuccess) return err;
+        err = launch_transpose32(dout, gt, (size_t)s.N * s.Ho * s.Wo * s.M * s.D0, s.D1, s.D3, stream);
+        if (err != hipSuccess) return err;
+        pl.P.it = it;
+        pl.P.gt = gt;
+    }
     pl.P.out = pl.P.nsplit > 1 ? partial : dkernel;
     if (pl.cw == 3)
         err = pl.nw == 4 ? launch_tn<3, 4>(pl.P, pl.tn, stream) : launch_tn<3, 2>(pl.P, pl.tn, stream);

@@ -90,6 +90,15 @@ BWD_SHAPES = SMALL_SHAPES + [
     ("wg32_d6", 2, 6, 6, 3, 5, 3, 3, 1, 1, 2, 6, 4, 3),
     ("wg32_d12", 2, 5, 5, 2, 3, 2, 2, 2, 0, 1, 12, 5, 4),
     ("wg32_rows", 2, 6, 6, 40, 30, 3, 3, 1, 1, 1, 4, 8, 8),
+    # ... and square capsules, which that kernel reads without transposed copies: 3x3x3 with a
+    # leading capsule index (config 2's kind), several row and column tiles of 4x4 capsules,
+    # heights of two and four chunks of 3, and 3x3 capsules on more columns than one tile
+    # (which go the transposed way again)
+    ("wg32n_d3", 3, 7, 6, 10, 9, 3, 3, 1, 1, 3, 3, 3, 3),
+    ("wg32n_d4t", 2, 6, 6, 70, 40, 3, 3, 1, 1, 1, 4, 4, 4),
+    ("wg32n_d6", 2, 6, 6, 5, 7, 3, 3, 1, 1, 2, 6, 6, 6),
+    ("wg32n_d12", 2, 5, 5, 3, 3, 2, 2, 2, 0, 1, 12, 12, 12),
+    ("wg32n_d3t", 2, 6, 6, 20, 50, 3, 3, 2, 1, 1, 3, 3, 3),
     # large enough for the strided input gradient to run as interleaved phase convolutions
     # (16-bit): stride 2; stride 3 with a 2x2 window (one phase of pixels no window reaches);
     # a non-square window with padding beyond its reach and a leading capsule index
