@@ -659,16 +659,21 @@ bool igemm16_fast_eligible(const ConvShape& s)
     return true;
 }
 
-// Tile height the kernel would use: 256 rows when that gives every CU a tile, else 128 rows
-// (half the work per tile, two workgroups per CU; 6 % slower per FLOP on config 5, so only
-// when the larger tile cannot fill the chip), 0 when even those are too few: such problems
-// use the generic kernel's small tiles and split K loop.
+// Tile height the kernel would use: 256 rows when that gives every CU a tile and the K loop is
+// long, else 128 rows (half the work per tile, two workgroups per CU; 6 % slower per FLOP on
+// config 5), 0 when even those are too few: such problems use the generic kernel's small tiles
+// and split K loop.
 int igemm16_fast_tile_rows(const ConvShape& s)
 {
     if (!igemm16_fast_eligible(s)) return 0;
     const long long colsp = ((long long)s.M * s.D3 + 255) / 256 * 256;
     const long long rows = (long long)s.pixels() * s.D1;
-    if ((rows + 255) / 256 * (colsp / 256) * s.D0 >= 256) return 256;
+    // short K loops (measured on 36 .. 144 stages of 32 K elements): up to 72 stages the
+    // half-height tile is 2 .. 6 % faster, because the other workgroup on the CU covers a
+    // tile's set-up and stores; at 144 stages the full tile is 4 % faster
+    const long long stages = (long long)s.kh * s.kw * s.C * s.D2 / 32;
+    const bool short_k = stages <= 96 && (rows + 127) / 128 * (colsp / 256) * s.D0 >= 512;
+    if (!short_k && (rows + 255) / 256 * (colsp / 256) * s.D0 >= 256) return 256;
     if ((rows + 127) / 128 * (colsp / 256) * s.D0 >= 256) return 128;
     return 0;
 }
