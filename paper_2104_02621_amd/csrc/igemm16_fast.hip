@@ -119,7 +119,6 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
     static_assert(BWA % BPP == 0 && PPW >= 1, "a wave loads whole pixels");
     static_assert(NFRAG <= NMMA && PPW <= NMMA / 2, "side operations fit between the MFMAs");
     static_assert(KS % 2 == 0, "register double buffer alternates per k-step");
-    constexpr int OOB = (int)0x80000000u;
     // s_waitcnt vmcnt(n), other counters untouched (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
     constexpr int KEEP = (NB - 2) * NCOPY;  // copies that may still be in flight at a barrier
     static_assert(KEEP < 64, "vmcnt is a 6-bit counter");
