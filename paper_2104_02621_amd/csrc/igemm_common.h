@@ -154,6 +154,7 @@ struct Dma32Params {
     // xcd_span workgroups (a multiple of 8) permuted so that XCD j takes the j-th contiguous
     // eighth of the tiles (the hardware deals consecutive workgroups to the 8 XCDs in turn)
     int xcd_span;
+    unsigned d3_magic;  // ceil(2^32 / D3): column index / D3 as a multiplication; 0 = divide
 };
 struct Dma32Plan {
     Dma32Params P;

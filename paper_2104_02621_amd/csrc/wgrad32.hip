@@ -41,6 +41,7 @@ struct Wgrad32Params {
     int row_tiles, col_tiles, ntaps;
     int tiles;       // ntaps * D0 * row_tiles * col_tiles
     int natural;          // 1: it / gt are the input and the output gradient themselves
+    unsigned d3_magic;    // ceil(2^32 / D3): column index / D3 as a multiplication; 0 = divide
     int nsplit;           // ranges the K loop (a tap's valid output pixels) is cut into
     long long items;      // tiles * nsplit = workgroups
     long long out_elems;  // elements of dK
@@ -369,7 +370,9 @@ __global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
                     for (int u = 0; u < 4; ++u) {
                         const int j = j0 + u;
                         if (j < P.cols) {
-                            const int m = j / P.D3, d3 = j - m * P.D3;
+                            // j / D3 by multiplication (exact while j * D3 < 2^32, which the host has checked)
+                            const int m = P.d3_magic ? (int)__umulhi((unsigned)j, P.d3_magic) : j / P.D3;
+                            const int d3 = j - m * P.D3;
                             orow[(long long)m * caps + d3] = acc[a][b][4 * g + u];
                         }
                     }
@@ -429,6 +432,9 @@ Wgrad32Plan make_plan(const ConvShape& s)
     P.ntaps = s.kh * s.kw;
     P.tiles = P.ntaps * s.D0 * P.row_tiles * P.col_tiles;
     P.out_elems = (long long)s.kernel_elems();
+    P.d3_magic = s.D3 > 1 && (long long)s.M * s.D3 * s.D3 < (1LL << 32)
+                     ? (unsigned)(((1ULL << 32) + s.D3 - 1) / s.D3)
+                     : 0u;  // 0: divide
     P.it_img_bytes = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 4;
     P.gt_img_bytes = (long long)s.Ho * s.Wo * s.M * s.D0 * s.D1 * s.D3 * 4;
     // square capsules whose tiles begin at whole channels need no transposed copies
