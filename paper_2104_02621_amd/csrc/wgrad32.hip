@@ -3,8 +3,9 @@
 // pixels whose tap lies inside the image; the K_diff result of the paper's Algorithm 4 read as
 // the derivative of Algorithm 2's sum), for capsule heights D1 of 3, 4, 6, 8, 12 or 16 floats.
 //
-// A pre-pass writes capsule-transposed copies It[n][h][w][c][d0][d2][d1] and
-// Gt[n][x][y][m][d0][d3][d1], so the D1 contracted values of one (pixel, row) are contiguous.
+// Unless the capsules are square (see NAT below), a pre-pass writes capsule-transposed copies
+// It[n][h][w][c][d0][d2][d1] and Gt[n][x][y][m][d0][d3][d1], so the D1 contracted values of one
+// (pixel, row) are contiguous.
 // Data moves in 16-byte LDS slots of CW = 3 or 4 floats ("chunks", D1 = CW * D1C): a 12-byte
 // buffer load lands at a 16-byte lane stride in LDS, so both widths read operands with one
 // 16-byte LDS load per lane and feed CW MFMA 32x32x2 instructions from it (element u of the
