@@ -143,6 +143,44 @@ def test_tuned_16bit_kernel_half_height_tiles(shape, dtype):
     assert np.array_equal(got.astype(np.float64), ref), wi.name
 
 
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.FP16], ids=["bf16", "fp16"])
+def test_tuned_16bit_kernel_short_k_loop(dtype):
+    """A K loop of few stages takes the half-height tiles even where 256-row tiles would fill the
+    chip (18 stages here); each XCD then works on a contiguous range of tiles."""
+    shape = ("hk", 8, 32, 32, 8, 32, 3, 3, 1, 1, 1, 8, 8, 8)
+    w = small(shape[0], dtype, *shape[1:], seed=77)
+    assert cc.capscaps_select_path(*shape_args(w)) == cc.PATH_MFMA_TUNED16
+    rows = w.N * w.Ho * w.Wo * w.D1
+    assert rows // 256 >= 256 and w.kh * w.kw * w.C * w.D2 // 32 <= 96
+    full_compare(w, cc.PATH_AUTO)
+    wi = small(shape[0] + "_int", dtype, *shape[1:], dist="int", seed=78)
+    i_st, k_st, i32, k32 = wl.generate(wi)
+    ref = capsconv.conv_fwd(i32, k32, wi.stride, wi.pad)
+    got = run_gpu(wi, to_device(i_st, dtype), to_device(k_st, dtype), cc.PATH_AUTO).cpu().numpy()
+    assert np.array_equal(got.astype(np.float64), ref), wi.name
+
+
+def test_window_of_64_taps_leaves_the_tuned_kernel():
+    """The tuned 16-bit kernel keeps one bit of a 64-bit mask per window tap and one bit free:
+    63 taps run on it, 64 go to the generic kernel."""
+    import torch
+    for kh, kw, tuned in ((7, 9, True), (8, 8, False)):
+        w = small(f"taps{kh * kw}", wl.BF16, 64, 15, 16, 8, 4, kh, kw, 1, 0, 1, 8, 8, 8, seed=79)
+        assert (cc.capscaps_select_path(*shape_args(w)) == cc.PATH_MFMA_TUNED16) == tuned, w.name
+        if tuned:
+            full_compare(w, cc.PATH_AUTO)
+            continue
+        I = torch.zeros(w.input_shape, dtype=torch.bfloat16, device="cuda")
+        K = torch.zeros(w.kernel_shape, dtype=torch.bfloat16, device="cuda")
+        out = torch.zeros(w.out_shape, device="cuda")
+        ws = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
+        rc = cc.capscaps_conv_fwd_path(I.data_ptr(), K.data_ptr(), out.data_ptr(),
+                                       *shape_args(w)[:13], w.dtype, cc.PATH_MFMA_TUNED16,
+                                       ws.data_ptr(), ws.numel(), None)
+        assert rc == cc.EUNSUPPORTED
+        full_compare(w, cc.PATH_AUTO)
+
+
 def test_tuned_kernel_refuses_other_shapes():
     import torch
     w = small("no", wl.FP32, 1, 6, 6, 4, 4, 3, 3, 1, 1, 1, 16, 16, 16)
