@@ -34,9 +34,10 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs scaled by a copy kernel of known size (see profiles/); None until measured.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/igemm16_fast_hbm_traffic_configs_3_5.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB
+    # profiles/hbm_traffic_configs_2_3_5.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB
     5: int((8270338 * 2.0 + 4295766) * 1024),
     3: int((521525 * 2.0 + 458752) * 1024),
+    2: int((150600 * 2.0 + 290010) * 1024),
 }
 
 
