@@ -18,59 +18,11 @@
 // blocks (partial sums are reduced in a fixed order by the caller's reduce kernel).
 #include <hip/hip_runtime.h>
 
-#include <type_traits>
-#include <utility>
-
 #include "igemm_common.h"
+#include "lds_dma.h"
 
 namespace capscaps {
 namespace {
-
-typedef int rsrc_t __attribute__((ext_vector_type(4)));
-
-template <typename F, int... I>
-__device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>)
-{
-    (f(std::integral_constant<int, I>{}), ...);
-}
-template <int N, typename F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    static_for_impl(static_cast<F&&>(f), std::make_integer_sequence<int, N>{});
-}
-
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base, unsigned bytes)
-{
-    const unsigned long long a = reinterpret_cast<unsigned long long>(base);
-    rsrc_t r;
-    r[0] = __builtin_amdgcn_readfirstlane((int)(unsigned)(a & 0xffffffffu));
-    r[1] = __builtin_amdgcn_readfirstlane((int)(unsigned)((a >> 32) & 0xffffu));
-    r[2] = __builtin_amdgcn_readfirstlane((int)bytes);
-    r[3] = 0x00020000;
-    return r;
-}
-
-// Wave-wide copy global -> LDS of DW dwords per lane (3 or 4): lane i reads at
-// base + voff_i + soff and writes LDS byte address lds_addr + 16*i.  Offsets at or beyond the
-// descriptor's size store zeros.  Asynchronous, counted in vmcnt; inline assembly so that the
-// only waits are the hand-placed ones (see igemm16_fast.hip).
-template <int DW>
-__device__ __forceinline__ void copy_to_lds(rsrc_t rs, unsigned lds_addr, unsigned voff, int soff)
-{
-    static_assert(DW == 3 || DW == 4, "12- or 16-byte copies");
-    const int lds_s = __builtin_amdgcn_readfirstlane((int)lds_addr);
-    const int soff_s = __builtin_amdgcn_readfirstlane(soff);
-    if (DW == 3)
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx3 %1, %2, %3 offen lds"
-                     :
-                     : "s"(lds_s), "v"(voff), "s"(rs), "s"(soff_s)
-                     : "memory");
-    else
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                     :
-                     : "s"(lds_s), "v"(voff), "s"(rs), "s"(soff_s)
-                     : "memory");
-}
 
 // KCH chunks per row and stage, ring of NB stages.  Small stages (2 chunks, ring of 4) halve the
 // LDS footprint of a workgroup, so that three instead of two share a CU and one wave's copies
@@ -208,14 +160,14 @@ __global__ __launch_bounds__(64 * NW) void igemm32_dma_kernel(const Dma32Params 
 #pragma unroll
         for (int q = 0; q < KCH; ++q) {
             const bool chan_ok = c0 + q_chan[q] < P.C;  // last group may be partial
-            copy_to_lds<CW>(chan_ok ? rs_in : rs_none, stage + (q * BM + 64 * wave) * 16, voff,
+            copy_to_lds_dwords<CW>(chan_ok ? rs_in : rs_none, stage + (q * BM + 64 * wave) * 16, voff,
                             s_base + q_off[q]);
         }
         // kernel side: this wave's share of the stage's KCH x BNL chunks
 #pragma unroll
         for (int j = 0; j < BPW; ++j) {
             const int c = wave * BPW + j;
-            copy_to_lds<4>(rs_kp, stage + A_BYTES + c * 1024, b_voff,
+            copy_to_lds_dwords<4>(rs_kp, stage + A_BYTES + c * 1024, b_voff,
                            live ? kp_off + b_const[j] : OOB);
         }
         // next stage: next tap, after the last tap the next channel group
