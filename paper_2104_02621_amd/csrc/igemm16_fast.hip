@@ -319,7 +319,7 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
                      : "s"(tap_ok[j]), "s"(tap_sel), "s"(pix_off[j]), "s"(tap_off)
                      : "scc");
     };
-    // input-side state -> next stage, in four pieces (0, 1, 2, then 3)
+    // input-side state -> next stage, in five pieces (0 .. 4 in this order)
     auto advance_a = [&](int piece) {
         asm volatile("" : "+s"(a_stage), "+s"(tap), "+s"(tap_q_cur), "+s"(tap_off), "+s"(c_off));
         if (piece == 0) {
@@ -330,25 +330,34 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
             const bool row_end = tap_q_cur == P.kw;
             tap_q_cur = row_end ? 0 : tap_q_cur;
             tap_off += row_end ? row_skip : pix_bytes;
-        } else if (piece == 3) {
+        } else if (piece == 4) {
             tap_sel = a_stage < nstages ? tap : DEAD_TAP;
-        } else {
-            // window done (tap == tap_hi): next channel group, first live tap.  Written out
-            // so that it stays four selects (the compiler makes a branch of it in some slots).
+        } else if (piece == 2) {
+            // window done (tap == tap_hi): next channel group ... (pieces 2 and 3 are written
+            // out so that they stay selects: the compiler makes a branch of them in some slots)
             int step;
-            asm volatile("s_cmp_eq_u32 %0, %5\n\t"
-                         "s_cselect_b32 %0, %6, %0\n\t"
+            asm volatile("s_cmp_eq_u32 %2, %3\n\t"
+                         "s_cselect_b32 %1, %4, 0\n\t"
+                         "s_add_i32 %0, %0, %1"
+                         : "+s"(c_off), "=&s"(step)
+                         : "s"(tap), "s"(tap_hi), "s"(c_step)
+                         : "scc");
+        } else {
+            // ... first live tap (piece 3)
+            asm volatile("s_cmp_eq_u32 %0, %3\n\t"
+                         "s_cselect_b32 %0, %4, %0\n\t"
                          "s_cselect_b32 %1, 0, %1\n\t"
-                         "s_cselect_b32 %2, %7, %2\n\t"
-                         "s_cselect_b32 %4, %8, 0\n\t"
-                         "s_add_i32 %3, %3, %4"
-                         : "+s"(tap), "+s"(tap_q_cur), "+s"(tap_off), "+s"(c_off), "=&s"(step)
-                         : "s"(tap_hi), "s"(tap_lo), "s"(tap_off0), "s"(c_step)
+                         "s_cselect_b32 %2, %5, %2"
+                         : "+s"(tap), "+s"(tap_q_cur), "+s"(tap_off)
+                         : "s"(tap_hi), "s"(tap_lo), "s"(tap_off0)
                          : "scc");
         }
         asm volatile("" : "+s"(a_stage), "+s"(tap), "+s"(tap_q_cur), "+s"(tap_off), "+s"(c_off),
                      "+s"(tap_sel));
     };
+    // (two pixels per block) the lane offsets of the next input copy, set by prepare_a in the
+    // gap before the copy's own
+    unsigned a_voff2 = 0;
     // input copy J (0 .. BWA-1) of the input-side stage / kernel copy J of the kernel-side stage
     auto copy_a = [&](auto SLOT, auto J) {
         constexpr int slot = decltype(SLOT)::value, j = decltype(J)::value;
@@ -359,10 +368,14 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
         } else {
             // two pixels per block: the pixel's offset travels in the lane offset (wrapping
             // arithmetic; an out-of-range mark in either half keeps that half out of range)
-            const int lo = a_soff[2 * j], hi = a_soff[2 * j + 1];
-            const unsigned voff = a_voff + (unsigned)lo + ((unsigned)(hi - lo) & (unsigned)a_hi);
-            copy_to_lds_16B<slot * STAGE_BYTES + j * ABLK>(rs_in, lds_a, voff, c_off, 0);
+            copy_to_lds_16B<slot * STAGE_BYTES + j * ABLK>(rs_in, lds_a, a_voff2, c_off, 0);
         }
+    };
+    auto prepare_a = [&](int j) {
+        asm volatile("" : "+s"(a_soff[2 * j]), "+s"(a_soff[2 * j + 1]));
+        const int lo = a_soff[2 * j], hi = a_soff[2 * j + 1];
+        a_voff2 = a_voff + (unsigned)lo + ((unsigned)(hi - lo) & (unsigned)a_hi);
+        asm volatile("" : "+v"(a_voff2));
     };
     auto copy_b = [&](auto SLOT, auto J) {
         constexpr int slot = decltype(SLOT)::value, j = decltype(J)::value;
@@ -398,12 +411,14 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
     // piece of the input-side advance, tap lookup of pixel j (k-step 0, after the advance)
     constexpr auto copy_b_gap = [](int j) { return NMMA == 16 ? 4 * j + 2 : 2 * j + 1; };
     constexpr auto copy_a_gap = [](int j) { return NMMA == 16 ? 4 * j + 2 : 4 * j + 3; };
+    // (the seventh and eighth lookup go into k-step 1 -- NMMA + g: its gap g, before the copy
+    // that uses the pixel)
     constexpr auto advance_gap = [](int piece) {
-        constexpr int wide[4] = {0, 1, 3, 4}, narrow[4] = {0, 1, 2, 3};
+        constexpr int wide[5] = {0, 1, 3, 4, 5}, narrow[5] = {0, 1, 2, 2, 3};
         return NMMA == 16 ? wide[piece] : narrow[piece];
     };
     constexpr auto lookup_gap = [](int j) {
-        constexpr int wide[8] = {5, 7, 8, 9, 11, 12, 13, 10};
+        constexpr int wide[8] = {7, 8, 9, 11, 12, 13, NMMA + 7, NMMA + 8};
         return NMMA == 16 ? wide[j] : 4 + j;
     };
     // with two waves per SIMD the MFMAs are held in their gaps explicitly (a pure instruction
@@ -419,17 +434,24 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
     static_for<NB - 1>([&](auto S0) {
 #pragma unroll
         for (int j = 0; j < PPW; ++j) stage_offset(j);
-        static_for<BWA>([&](auto J) { copy_a(S0, J); });
+        static_for<BWA>([&](auto J) {
+            if constexpr (PPB == 2) prepare_a(decltype(J)::value);
+            copy_a(S0, J);
+        });
         static_for<BWB>([&](auto J) { copy_b(S0, J); });
         advance_a(0);
         advance_a(1);
         advance_a(2);
         advance_a(3);
+        advance_a(4);
         advance_b();
     });
 #pragma unroll
     for (int j = 0; j < PPW; ++j) stage_offset(j);
-    static_for<BWA>([&](auto J) { copy_a(std::integral_constant<int, NB - 1>{}, J); });
+    static_for<BWA>([&](auto J) {
+        if constexpr (PPB == 2) prepare_a(decltype(J)::value);
+        copy_a(std::integral_constant<int, NB - 1>{}, J);
+    });
     // the accumulators are cleared here, while the first copies are on their way (left to
     // itself the compiler clears them after the wait)
 #pragma unroll
@@ -460,7 +482,7 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
                 static_for<BWB>([&](auto J) {
                     if constexpr (copy_b_gap(decltype(J)::value) == i) copy_b(SlotPrev{}, J);
                 });
-                static_for<4>([&](auto PC) {
+                static_for<5>([&](auto PC) {
                     if constexpr (advance_gap(decltype(PC)::value) == i) advance_a(decltype(PC)::value);
                 });
                 static_for<PPW>([&](auto J) {
@@ -478,7 +500,13 @@ __global__ __launch_bounds__(256, BM == 256 ? 1 : 2) void igemm16_fast_kernel(co
                 constexpr int i = decltype(I)::value;
                 mma(frag[1][i / TM], frag[1][TN + i % TM], acc[i / TM][i % TM]);
                 if constexpr (i < NFRAG) frag[0][i] = read_frag(slot_next, 0, i);
+                static_for<PPW>([&](auto J) {
+                    if constexpr (lookup_gap(decltype(J)::value) == NMMA + i)
+                        stage_offset(decltype(J)::value);
+                });
                 static_for<BWA>([&](auto J) {
+                    if constexpr (PPB == 2 && copy_a_gap(decltype(J)::value) - 1 == i)
+                        prepare_a(decltype(J)::value);
                     if constexpr (copy_a_gap(decltype(J)::value) == i) copy_a(SLOT, J);
                 });
                 __builtin_amdgcn_sched_barrier(0);
