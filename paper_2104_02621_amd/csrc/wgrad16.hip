@@ -199,53 +199,45 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     // the rectangle row and pick the step; (2) apply it, and at the end of an image the jump to
     // the next one.
     int i_inc = 0, g_inc = 0;
-    // (the empty volatile statements keep each piece's scalar arithmetic inside its gap, as
-    // for the MFMAs below)
-    auto walk_i = [&](int j, int piece) {
+    // (Written out instruction by instruction: the compiler's code for these selects was two to
+    // three times as long, and a volatile statement also stays in the gap it is written in.)
+    auto walk = [&](int& soff, int& left, int& cur, int& yl, int& xl, int& inc, int step,
+                    int rowjump, int imgjump, int piece) {
         if (piece == 0) {
-            asm volatile("" : "+s"(i_left), "+s"(i_cur));
-            a_soff[j] = i_left > 0 ? i_cur : OOB;
-            --i_left;
-            asm volatile("" : "+s"(i_left), "+s"(a_soff[j]));
+            asm volatile("s_cmp_gt_i32 %1, 0\n\t"
+                         "s_cselect_b32 %0, %2, 0x80000000\n\t"
+                         "s_add_i32 %1, %1, -1"
+                         : "=&s"(soff), "+s"(left)
+                         : "s"(cur)
+                         : "scc");
         } else if (piece == 1) {
-            asm volatile("" : "+s"(i_yl), "+s"(i_xl));
-            --i_yl;
-            const bool row_end = i_yl == 0;
-            i_inc = row_end ? i_rowjump : i_step;
-            i_yl = row_end ? ny : i_yl;
-            i_xl -= row_end ? 1 : 0;
-            asm volatile("" : "+s"(i_yl), "+s"(i_xl), "+s"(i_inc));
+            // next pixel of the rectangle row, or (row done) first pixel of the next row
+            asm volatile("s_add_i32 %0, %0, -1\n\t"
+                         "s_cmp_eq_u32 %0, 0\n\t"
+                         "s_cselect_b32 %2, %4, %3\n\t"
+                         "s_cselect_b32 %0, %5, %0\n\t"
+                         "s_subb_u32 %1, %1, 0"
+                         : "+s"(yl), "+s"(xl), "=&s"(inc)
+                         : "s"(step), "s"(rowjump), "s"(ny)
+                         : "scc");
         } else {
-            asm volatile("" : "+s"(i_xl), "+s"(i_cur), "+s"(i_inc));
-            const bool img_end = i_xl == 0;
-            i_cur += i_inc;
-            i_cur += img_end ? i_imgjump : 0;
-            i_xl = img_end ? nx : i_xl;
-            asm volatile("" : "+s"(i_xl), "+s"(i_cur));
+            // apply the step; rectangle done: on to the next image
+            int jump;
+            asm volatile("s_add_i32 %1, %1, %3\n\t"
+                         "s_cmp_eq_u32 %0, 0\n\t"
+                         "s_cselect_b32 %2, %4, 0\n\t"
+                         "s_cselect_b32 %0, %5, %0\n\t"
+                         "s_add_i32 %1, %1, %2"
+                         : "+s"(xl), "+s"(cur), "=&s"(jump)
+                         : "s"(inc), "s"(imgjump), "s"(nx)
+                         : "scc");
         }
     };
+    auto walk_i = [&](int j, int piece) {
+        walk(a_soff[j], i_left, i_cur, i_yl, i_xl, i_inc, i_step, i_rowjump, i_imgjump, piece);
+    };
     auto walk_g = [&](int j, int piece) {
-        if (piece == 0) {
-            asm volatile("" : "+s"(g_left), "+s"(g_cur));
-            g_soff[j] = g_left > 0 ? g_cur : OOB;
-            --g_left;
-            asm volatile("" : "+s"(g_left), "+s"(g_soff[j]));
-        } else if (piece == 1) {
-            asm volatile("" : "+s"(g_yl), "+s"(g_xl));
-            --g_yl;
-            const bool row_end = g_yl == 0;
-            g_inc = row_end ? g_rowjump : g_step;
-            g_yl = row_end ? ny : g_yl;
-            g_xl -= row_end ? 1 : 0;
-            asm volatile("" : "+s"(g_yl), "+s"(g_xl), "+s"(g_inc));
-        } else {
-            asm volatile("" : "+s"(g_xl), "+s"(g_cur), "+s"(g_inc));
-            const bool img_end = g_xl == 0;
-            g_cur += g_inc;
-            g_cur += img_end ? g_imgjump : 0;
-            g_xl = img_end ? nx : g_xl;
-            asm volatile("" : "+s"(g_xl), "+s"(g_cur));
-        }
+        walk(g_soff[j], g_left, g_cur, g_yl, g_xl, g_inc, g_step, g_rowjump, g_imgjump, piece);
     };
     auto copy_a = [&](auto SLOT, auto KC) {
         constexpr int slot = decltype(SLOT)::value, kc = decltype(KC)::value;
