@@ -149,12 +149,10 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     // the last row, on to the first row of the next image
     const int i_rowjump = (s * P.W - (ny - 1) * s) * ipix, g_rowjump = (P.Wo - (ny - 1)) * gpix;
     const int i_imgjump = (P.H * P.W - nx * s * P.W) * ipix, g_imgjump = (P.Ho * P.Wo - nx * P.Wo) * gpix;
-    // two walkers over the same pixel sequence, one per tensor (the It copies of a stage go out
-    // one k-step before its Gt copies, so each side keeps its own position)
+    // one walker over the pixel sequence with a position in either tensor
     int i_cur = ((x_lo * s - (P.pad - tp)) * P.W + (y_lo * s - (P.pad - tq))) * ipix;
     int g_cur = (x_lo * P.Wo + y_lo) * gpix;
-    int i_left = npix, i_yl = ny, i_xl = nx;
-    int g_left = npix, g_yl = ny, g_xl = nx;
+    int w_left = npix, w_yl = ny, w_xl = nx;
 
     const char* it_base = static_cast<const char*>(P.it) + (long long)n0 * P.it_img_bytes;
     const char* gt_base = static_cast<const char*>(P.gt) + (long long)n0 * P.gt_img_bytes;
@@ -191,53 +189,56 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     const int nstages_pad = (nstages + NB - 1) / NB * NB;  // surplus stages contract zeros
 
     // Pixel offsets of the stage whose It copies go out next (a_soff) and of the stage whose
-    // Gt copies go out next (g_soff).  All scalar.
+    // Gt copies go out next (g_soff): the same stage, the Gt copies follow one k-step later.
+    // All scalar.
     int a_soff[PPS], g_soff[PPS];
-    // One pixel step of a walker, in three branch-free pieces that the main loop puts into
-    // different gaps between MFMAs: (0) record the walker's pixel for slot j of the stage, or
+    // One pixel step of the walker, in four branch-free pieces that the main loop puts into
+    // different gaps between MFMAs: (0) record the pixel's offsets for slot j of the stage, or
     // past the last pixel the out-of-range mark (zero fill, touches no memory); (1) count down
-    // the rectangle row and pick the step; (2) apply it, and at the end of an image the jump to
-    // the next one.
+    // the rectangle row and pick the steps; (2) apply them; (3) at the end of an image jump to
+    // the next one.  Written out instruction by instruction: the compiler's code for these
+    // selects was two to three times as long, and a volatile statement also stays in the gap
+    // it is written in.
     int i_inc = 0, g_inc = 0;
-    // (Written out instruction by instruction: the compiler's code for these selects was two to
-    // three times as long, and a volatile statement also stays in the gap it is written in.)
-    auto walk = [&](int& soff, int& left, int& cur, int& yl, int& xl, int& inc, int step,
-                    int rowjump, int imgjump, int piece) {
+    auto walk = [&](int j, int piece) {
         if (piece == 0) {
-            asm volatile("s_cmp_gt_i32 %1, 0\n\t"
-                         "s_cselect_b32 %0, %2, 0x80000000\n\t"
-                         "s_add_i32 %1, %1, -1"
-                         : "=&s"(soff), "+s"(left)
-                         : "s"(cur)
+            asm volatile("s_cmp_gt_i32 %2, 0\n\t"
+                         "s_cselect_b32 %0, %3, 0x80000000\n\t"
+                         "s_cselect_b32 %1, %4, 0x80000000\n\t"
+                         "s_add_i32 %2, %2, -1"
+                         : "=&s"(a_soff[j]), "=&s"(g_soff[j]), "+s"(w_left)
+                         : "s"(i_cur), "s"(g_cur)
                          : "scc");
         } else if (piece == 1) {
             // next pixel of the rectangle row, or (row done) first pixel of the next row
             asm volatile("s_add_i32 %0, %0, -1\n\t"
                          "s_cmp_eq_u32 %0, 0\n\t"
-                         "s_cselect_b32 %2, %4, %3\n\t"
-                         "s_cselect_b32 %0, %5, %0\n\t"
+                         "s_cselect_b32 %2, %5, %4\n\t"
+                         "s_cselect_b32 %3, %7, %6\n\t"
+                         "s_cselect_b32 %0, %8, %0\n\t"
                          "s_subb_u32 %1, %1, 0"
-                         : "+s"(yl), "+s"(xl), "=&s"(inc)
-                         : "s"(step), "s"(rowjump), "s"(ny)
+                         : "+s"(w_yl), "+s"(w_xl), "=&s"(i_inc), "=&s"(g_inc)
+                         : "s"(i_step), "s"(i_rowjump), "s"(g_step), "s"(g_rowjump), "s"(ny)
+                         : "scc");
+        } else if (piece == 2) {
+            asm volatile("s_add_i32 %0, %0, %2\n\t"
+                         "s_add_i32 %1, %1, %3"
+                         : "+s"(i_cur), "+s"(g_cur)
+                         : "s"(i_inc), "s"(g_inc)
                          : "scc");
         } else {
-            // apply the step; rectangle done: on to the next image
-            int jump;
-            asm volatile("s_add_i32 %1, %1, %3\n\t"
-                         "s_cmp_eq_u32 %0, 0\n\t"
-                         "s_cselect_b32 %2, %4, 0\n\t"
-                         "s_cselect_b32 %0, %5, %0\n\t"
-                         "s_add_i32 %1, %1, %2"
-                         : "+s"(xl), "+s"(cur), "=&s"(jump)
-                         : "s"(inc), "s"(imgjump), "s"(nx)
+            // rectangle done: on to the next image
+            int ji, jg;
+            asm volatile("s_cmp_eq_u32 %0, 0\n\t"
+                         "s_cselect_b32 %3, %5, 0\n\t"
+                         "s_cselect_b32 %4, %6, 0\n\t"
+                         "s_cselect_b32 %0, %7, %0\n\t"
+                         "s_add_i32 %1, %1, %3\n\t"
+                         "s_add_i32 %2, %2, %4"
+                         : "+s"(w_xl), "+s"(i_cur), "+s"(g_cur), "=&s"(ji), "=&s"(jg)
+                         : "s"(i_imgjump), "s"(g_imgjump), "s"(nx)
                          : "scc");
         }
-    };
-    auto walk_i = [&](int j, int piece) {
-        walk(a_soff[j], i_left, i_cur, i_yl, i_xl, i_inc, i_step, i_rowjump, i_imgjump, piece);
-    };
-    auto walk_g = [&](int j, int piece) {
-        walk(g_soff[j], g_left, g_cur, g_yl, g_xl, g_inc, g_step, g_rowjump, g_imgjump, piece);
     };
     auto copy_a = [&](auto SLOT, auto KC) {
         constexpr int slot = decltype(SLOT)::value, kc = decltype(KC)::value;
@@ -272,20 +273,14 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
 #pragma unroll
         for (int j = 0; j < PPS; ++j)
 #pragma unroll
-            for (int piece = 0; piece < 3; ++piece) {
-                walk_i(j, piece);
-                walk_g(j, piece);
-            }
+            for (int piece = 0; piece < 4; ++piece) walk(j, piece);
         static_for<KCH>([&](auto KC) { copy_a(S0, KC); });
         static_for<KCH>([&](auto KC) { copy_b(S0, KC); });
     });
 #pragma unroll
     for (int j = 0; j < PPS; ++j)
 #pragma unroll
-        for (int piece = 0; piece < 3; ++piece) {
-            walk_i(j, piece);
-            walk_g(j, piece);
-        }
+        for (int piece = 0; piece < 4; ++piece) walk(j, piece);
     static_for<KCH>([&](auto KC) { copy_a(std::integral_constant<int, NB - 1>{}, KC); });
     {
         constexpr int keep0 = (NB - 2) * NCOPY + KCH;
@@ -299,24 +294,18 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
 
     // ---- main loop, unrolled over the ring so that slots are compile-time constants.
     // Iteration st: k-step 0 issues the Gt copies of stage st+NB-1 (one after every fourth
-    // MFMA) and walks the It pixels of stage st+NB; after the barrier, k-step 1 issues the It
-    // copies of stage st+NB into the slot just released and walks the Gt pixels of that stage.
-    // gaps for the 3*PPS walker pieces of a k-step: those without a copy, late ones first
-    constexpr int WALK_GAP[12] = {8, 9, 11, 12, 13, 15, 0, 1, 3, 4, 5, 7};
-    constexpr int NPIECE = 3 * PPS;
-    // the pieces must run in order: sort the first NPIECE gaps
+    // MFMA); after the barrier, k-step 1 issues the It copies of stage st+NB into the slot just
+    // released.  The walk over the pixels of stage st+NB runs through both k-steps, in gaps
+    // without a copy: pixel j's first piece after the last Gt copy that still reads the previous
+    // stage's offset of slot j (k-step 0) and before the first It copy that reads the new one
+    // (k-step 1).  Gaps 0..15 are k-step 0's, 16..31 k-step 1's.
+    constexpr int NPIECE = 4 * PPS;
     constexpr auto piece_gap = [](int q) {
-        int g[12] = {0};
-        for (int k = 0; k < NPIECE; ++k) g[k] = WALK_GAP[k];
-        for (int a = 0; a < NPIECE; ++a)
-            for (int b = a + 1; b < NPIECE; ++b)
-                if (g[b] < g[a]) {
-                    const int t = g[a];
-                    g[a] = g[b];
-                    g[b] = t;
-                }
-        return g[q];
+        constexpr int four[16] = {3, 4, 5, 7, 8, 9, 11, 12, 13, 15, 16, 17, 19, 20, 21, 23};
+        constexpr int two[8] = {7, 8, 9, 11, 15, 16, 17, 19};
+        return PPS == 4 ? four[q] : two[q];
     };
+    static_assert(PPS == 4 || PPS == 2, "the walk's schedule is written for these stage shapes");
     for (int st = 0; st < nstages_pad; st += NB) {
         static_for<NB>([&](auto SLOT) {
             constexpr int slot = decltype(SLOT)::value;
@@ -329,7 +318,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
                 if constexpr (i % 4 == 2) copy_b(SlotPrev{}, std::integral_constant<int, i / 4>{});
                 static_for<NPIECE>([&](auto Q) {
                     constexpr int q = decltype(Q)::value;
-                    if constexpr (piece_gap(q) == i) walk_i(q / 3, q % 3);
+                    if constexpr (piece_gap(q) == i) walk(q / 4, q % 4);
                 });
                 __builtin_amdgcn_sched_barrier(0);
             });
@@ -342,7 +331,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
                 if constexpr (i % 4 == 2) copy_a(SLOT, std::integral_constant<int, i / 4>{});
                 static_for<NPIECE>([&](auto Q) {
                     constexpr int q = decltype(Q)::value;
-                    if constexpr (piece_gap(q) == i) walk_g(q / 3, q % 3);
+                    if constexpr (piece_gap(q) == NMMA + i) walk(q / 4, q % 4);
                 });
                 __builtin_amdgcn_sched_barrier(0);
             });
