@@ -316,13 +316,22 @@ int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, f
         char* ws = static_cast<char*>(workspace);
         const size_t used = align256(s.kernel_elems() * eb);
         // K2[m][(h,w,c)][d0][d3][d2] = K[h][w][c][m][d0][d2][d3]; (h,w,c) is one index of stride sC
+        ConvShape f = bwd_input_fc_shape(s);
+        if (forward_auto_repacks_kernel(f)) {  // read in place, through the repack pass
+            f.kernel_view = true;
+            f.k_sc = sM;
+            f.k_sm = sC;
+            f.k_sd0 = sD0;
+            f.k_sd2 = sD3;
+            f.k_sd3 = sD2;
+            return forward_auto(f, dout, kernel, din, ws + used, workspace_bytes - used, stream);
+        }
         const Permute7 pm = gather_into_dense(
             {1, 1, s.M, (long long)s.kh * s.kw * s.C, s.D0, s.D3, s.D2},
             {0, 0, sM, sC, sD0, sD3, sD2}, 0);
         hipError_t err = launch_permute(kernel, ws, pm, eb, stream);
         if (err != hipSuccess) return status_from_hip(err);
-        return forward_auto(bwd_input_fc_shape(s), dout, ws, din, ws + used,
-                            workspace_bytes - used, stream);
+        return forward_auto(f, dout, ws, din, ws + used, workspace_bytes - used, stream);
     }
     if (bwd_input_as_phases(s)) {
         char* ws = static_cast<char*>(workspace);
@@ -344,31 +353,51 @@ int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, f
                     if (err != hipSuccess) return status_from_hip(err);
                     continue;
                 }
-                // Kab[i'][j'][m][c][d0][d3][d2] = K[a + s*(taps_h-1-i')][b + s*(taps_w-1-j')][c][m][d0][d2][d3]
-                const Permute7 pm = gather_into_dense(
-                    {ph.taps, pw.taps, s.M, s.C, s.D0, s.D3, s.D2},
-                    {-s.stride * sP, -s.stride * sQ, sM, sC, sD0, sD3, sD2},
-                    (long long)(a + s.stride * (ph.taps - 1)) * sP +
-                        (long long)(b + s.stride * (pw.taps - 1)) * sQ);
-                // the sub-kernels are used one after the other on one stream: one buffer
-                hipError_t err = launch_permute(kernel, ws, pm, eb, stream);
-                if (err != hipSuccess) return status_from_hip(err);
-                const int rc = forward_tuned16(bwd_input_phase_shape(s, ph, pw, a, b), dout, ws,
-                                               din, ws + kbytes, workspace_bytes - kbytes, stream);
+                // the phase's kernel Kab[i'][j'][m][c][d0][d3][d2] =
+                // K[a + s*(taps_h-1-i')][b + s*(taps_w-1-j')][c][m][d0][d2][d3] is read in place:
+                // the repack pass of the convolution takes it through strides
+                ConvShape f = bwd_input_phase_shape(s, ph, pw, a, b);
+                f.kernel_view = true;
+                f.k_base = (long long)(a + s.stride * (ph.taps - 1)) * sP +
+                           (long long)(b + s.stride * (pw.taps - 1)) * sQ;
+                f.k_sp = -s.stride * sP;
+                f.k_sq = -s.stride * sQ;
+                f.k_sc = sM;   // the convolution's input channels are the layer's output channels
+                f.k_sm = sC;
+                f.k_sd0 = sD0;
+                f.k_sd2 = sD3;  // ... and its contracted capsule index the layer's d3
+                f.k_sd3 = sD2;
+                const int rc = forward_tuned16(f, dout, kernel, din, ws + kbytes,
+                                               workspace_bytes - kbytes, stream);
                 if (rc != 0) return rc;
             }
         return 0;
     }
     if (bwd_input_as_conv(s)) {
         char* ws = static_cast<char*>(workspace);
-        void* kflip = ws;
+        const void* kflip = ws;
         size_t used = align256(s.kernel_elems() * eb);
         // K'[p'][q'][m][c][d0][d3][d2] = K[kh-1-p'][kw-1-q'][c][m][d0][d2][d3]
-        const Permute7 pm = gather_into_dense({s.kh, s.kw, s.M, s.C, s.D0, s.D3, s.D2},
-                                              {-sP, -sQ, sM, sC, sD0, sD3, sD2},
-                                              (long long)(s.kh - 1) * sP + (long long)(s.kw - 1) * sQ);
-        hipError_t err = launch_permute(kernel, kflip, pm, eb, stream);
-        if (err != hipSuccess) return status_from_hip(err);
+        ConvShape f = bwd_input_conv_shape(s);
+        hipError_t err = hipSuccess;
+        if (forward_auto_repacks_kernel(f)) {  // read in place, through the repack pass
+            f.kernel_view = true;
+            f.k_base = (long long)(s.kh - 1) * sP + (long long)(s.kw - 1) * sQ;
+            f.k_sp = -sP;
+            f.k_sq = -sQ;
+            f.k_sc = sM;
+            f.k_sm = sC;
+            f.k_sd0 = sD0;
+            f.k_sd2 = sD3;
+            f.k_sd3 = sD2;
+            kflip = kernel;
+        } else {
+            const Permute7 pm = gather_into_dense({s.kh, s.kw, s.M, s.C, s.D0, s.D3, s.D2},
+                                                  {-sP, -sQ, sM, sC, sD0, sD3, sD2},
+                                                  (long long)(s.kh - 1) * sP + (long long)(s.kw - 1) * sQ);
+            err = launch_permute(kernel, ws, pm, eb, stream);
+            if (err != hipSuccess) return status_from_hip(err);
+        }
         const void* g = dout;
         if (s.stride > 1) {
             // Gs[n][x*s][y*s] = G[n][x][y], zero elsewhere; a pixel (M capsules) moves as one run
@@ -392,8 +421,7 @@ int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, f
             if (err != hipSuccess) return status_from_hip(err);
             g = gs;
         }
-        return forward_auto(bwd_input_conv_shape(s), g, kflip, din, ws + used,
-                            workspace_bytes - used, stream);
+        return forward_auto(f, g, kflip, din, ws + used, workspace_bytes - used, stream);
     }
     const size_t total = s.in_elems();
     hipError_t err;

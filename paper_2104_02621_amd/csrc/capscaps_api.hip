@@ -98,10 +98,13 @@ size_t forward_workspace_bytes(const ConvShape& s)
     return choose_path(s) == CAPSCAPS_PATH_DIRECT ? 0 : mfma_workspace_bytes(s);
 }
 
+bool forward_auto_repacks_kernel(const ConvShape& s) { return choose_path(s) != CAPSCAPS_PATH_DIRECT; }
+
 int forward_auto(const ConvShape& s, const void* in, const void* kernel, float* out,
                  void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
-    if (!s.plain()) return CAPSCAPS_EINVAL;
+    if (s.pad_w_set || s.out_view) return CAPSCAPS_EINVAL;
+    if (s.kernel_view && !forward_auto_repacks_kernel(s)) return CAPSCAPS_EINVAL;
     return run(in, kernel, out, s, CAPSCAPS_PATH_AUTO, workspace, workspace_bytes, stream);
 }
 

@@ -27,8 +27,14 @@ struct ConvShape {
     bool out_view = false;
     long long out_base = 0, out_sn = 0, out_sx = 0, out_sy = 0;
     long long out_alloc = 0;  // with out_view: elements of the whole tensor `out` points into
+    // kernel_view (matrix-core paths only, honoured where the kernel tensor is repacked): kernel
+    // element (p, q, c, m, d0, d2, d3) is read at element k_base + p*k_sp + q*k_sq + c*k_sc +
+    // m*k_sm + d0*k_sd0 + d2*k_sd2 + d3*k_sd3 of `kernel` instead of densely (strides may be
+    // negative: a flipped window).
+    bool kernel_view = false;
+    long long k_base = 0, k_sp = 0, k_sq = 0, k_sc = 0, k_sm = 0, k_sd0 = 0, k_sd2 = 0, k_sd3 = 0;
     int padw() const { return pad_w_set ? pad_w : pad; }
-    bool plain() const { return !pad_w_set && !out_view; }
+    bool plain() const { return !pad_w_set && !out_view && !kernel_view; }
     long long pixels() const { return (long long)N * Ho * Wo; }
     size_t in_elems() const { return (size_t)N * H * W * C * D0 * D1 * D2; }
     size_t kernel_elems() const { return (size_t)kh * kw * C * M * D0 * D2 * D3; }
@@ -60,6 +66,9 @@ hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, f
 size_t forward_workspace_bytes(const ConvShape& s);
 int forward_auto(const ConvShape& s, const void* in, const void* kernel, float* out,
                  void* workspace, size_t workspace_bytes, hipStream_t stream);
+// whether that choice is a matrix-core kernel, which takes the kernel tensor through a repack
+// pass and therefore accepts s.kernel_view (the wavefront-level path reads it densely)
+bool forward_auto_repacks_kernel(const ConvShape& s);
 // the tuned 16-bit kernel, geometry overrides allowed (EUNSUPPORTED if it cannot run the shape)
 int forward_tuned16(const ConvShape& s, const void* in, const void* kernel, float* out,
                     void* workspace, size_t workspace_bytes, hipStream_t stream);

@@ -36,11 +36,15 @@ namespace {
 // j = m*D3+d3; zero where k >= C*D2 or j >= M*D3.  One thread per 16-byte chunk.  Chunk order
 // is the order in which the consuming kernel walks K:  kgroup = 0: [d0][tap][kq] (tap outermost);
 // kgroup = g > 0: [d0][kq / g][tap][kq % g] (groups of g chunks outermost, tap inside).
+// Where kernel element (p, q, c, m, d0, d2, d3) lies in the tensor handed to the call (elements).
+struct KernelStrides {
+    long long base, sp, sq, sc, sm, sd0, sd2, sd3;
+};
 template <typename E, int CH>
 __global__ __launch_bounds__(256) void repack_kernel(const E* __restrict__ kernel,
-                                                     E* __restrict__ kp, int ntaps, int C, int M,
-                                                     int D0, int D2, int D3, int KT, int KQP,
-                                                     int cols, int colsp, int kgroup, int cw,
+                                                     E* __restrict__ kp, int ntaps, int kw, int D2,
+                                                     int D3, int KT, int KQP, int cols, int colsp,
+                                                     int kgroup, int cw, KernelStrides ks,
                                                      size_t total_chunks)
 {
     const size_t id = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -66,7 +70,9 @@ __global__ __launch_bounds__(256) void repack_kernel(const E* __restrict__ kerne
         E x = 0;
         if (e < cw && k < KT && j < cols) {
             const int c = k / D2, d2 = k % D2, m = j / D3, d3 = j % D3;
-            x = kernel[(((((size_t)tap * C + c) * M + m) * D0 + d0) * D2 + d2) * D3 + d3];
+            const int p = tap / kw, q = tap - p * kw;
+            x = kernel[ks.base + p * ks.sp + q * ks.sq + c * ks.sc + m * ks.sm + d0 * ks.sd0 +
+                       d2 * ks.sd2 + d3 * ks.sd3];
         }
         v[e] = x;
     }
@@ -573,14 +579,27 @@ hipError_t launch_repack(const ConvShape& s, const void* kernel, void* kp, int c
 {
     const unsigned rblocks = (unsigned)((chunks + 255) / 256);
     const int ntaps = s.kh * s.kw, KT = s.C * s.D2, cols = s.M * s.D3;
+    KernelStrides ks;
+    if (s.kernel_view) {
+        ks = {s.k_base, s.k_sp, s.k_sq, s.k_sc, s.k_sm, s.k_sd0, s.k_sd2, s.k_sd3};
+    } else {  // dense [kh][kw][C][M][D0][D2][D3]
+        ks.base = 0;
+        ks.sd3 = 1;
+        ks.sd2 = s.D3;
+        ks.sd0 = (long long)s.D2 * s.D3;
+        ks.sm = ks.sd0 * s.D0;
+        ks.sc = ks.sm * s.M;
+        ks.sq = ks.sc * s.C;
+        ks.sp = ks.sq * s.kw;
+    }
     if (s.dtype == 0) {
         repack_kernel<float, 4><<<rblocks, 256, 0, stream>>>(
-            (const float*)kernel, (float*)kp, ntaps, s.C, s.M, s.D0, s.D2, s.D3, KT, KQP, cols,
-            colsp, kgroup, cw, chunks);
+            (const float*)kernel, (float*)kp, ntaps, s.kw, s.D2, s.D3, KT, KQP, cols, colsp,
+            kgroup, cw, ks, chunks);
     } else {
         repack_kernel<unsigned short, 8><<<rblocks, 256, 0, stream>>>(
-            (const unsigned short*)kernel, (unsigned short*)kp, ntaps, s.C, s.M, s.D0, s.D2, s.D3,
-            KT, KQP, cols, colsp, kgroup, cw, chunks);
+            (const unsigned short*)kernel, (unsigned short*)kp, ntaps, s.kw, s.D2, s.D3, KT, KQP,
+            cols, colsp, kgroup, cw, ks, chunks);
     }
     return hipGetLastError();
 }
@@ -640,8 +659,9 @@ bool mfma_tuned16_supported(const ConvShape& s)
 hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, float* out,
                        void* workspace, hipStream_t stream, MfmaKernel which)
 {
-    // geometry overrides exist in the tuned 16-bit kernel only
-    if (!s.plain() && !(which == MfmaKernel::Tuned16 && igemm16_fast_eligible(s)))
+    // geometry overrides exist in the tuned 16-bit kernel only (a kernel view in all: it is the
+    // repack pass that reads the kernel tensor)
+    if ((s.pad_w_set || s.out_view) && !(which == MfmaKernel::Tuned16 && igemm16_fast_eligible(s)))
         return hipErrorInvalidValue;
     if (which == MfmaKernel::Dma32 || (which == MfmaKernel::Auto && igemm32_dma_preferred(s)))
         return launch_dma32(s, in, kernel, out, workspace, stream);
