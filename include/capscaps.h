@@ -29,8 +29,15 @@
  * `workspace` allocate nothing and enqueue only kernels, so they may be captured in a HIP graph
  * (capscaps_conv_fwd, which obtains its scratch itself, may not).
  *
- * Errors: functions returning int return CAPSCAPS_OK (0) or a negative status; on any error
- * nothing has been launched.  Nothing is printed, nothing throws, nothing aborts.
+ * Errors: functions returning int return CAPSCAPS_OK (0) or a negative status.  Arguments, the
+ * workspace size and whether a path supports the shape are checked before the first launch: on
+ * CAPSCAPS_EINVAL, CAPSCAPS_EWORKSPACE and CAPSCAPS_EUNSUPPORTED nothing has
+ * been enqueued and no buffer has been touched.  CAPSCAPS_EHIP reports a failing HIP call; a call
+ * is a short sequence of launches (kernel repack, main kernel, fixed-order reduction; the backward
+ * pass has a few more), so earlier launches of the sequence may already be enqueued: `out` and
+ * `workspace` are undefined then.  Nothing is printed, nothing throws, nothing aborts.
+ * The *_workspace_bytes queries return 0 both for "no scratch needed" and for invalid arguments;
+ * capscaps_select_path (or the compute call itself) tells the two apart.
  */
 #ifndef CAPSCAPS_H
 #define CAPSCAPS_H
@@ -55,7 +62,8 @@ extern "C" {
                                       window larger than the padded input, unknown dtype/path,
                                       misaligned pointer */
 #define CAPSCAPS_EWORKSPACE (-2)   /* workspace missing or smaller than required */
-#define CAPSCAPS_EUNSUPPORTED (-3) /* the forced path cannot run this shape/dtype */
+#define CAPSCAPS_EUNSUPPORTED (-3) /* the forced path cannot run this shape/dtype; a window of
+                                      more than 2^24 taps */
 #define CAPSCAPS_EHIP (-4)         /* a HIP call (launch, allocation) failed */
 
 /* compute paths (for capscaps_conv_fwd_path / capscaps_select_path) */
@@ -154,10 +162,14 @@ int capscaps_select_path(int N, int H, int W, int C, int M, int kh, int kw, int 
  *     dK[p,q,c,m,d0] = sum over n and output pixels (x,y) whose tap (p,q) lies inside the image of
  *                      transpose(I[n,x*stride+p-pad,y*stride+q-pad,c,d0]) (D2 x D1) . dO[n,x,y,m,d0]
  *
- * The shape arguments are those of the forward call whose gradients are wanted.  For stride 1
- * both gradients are themselves capsule convolutions and run on the forward kernels after a
- * re-layout in `workspace` (dinput needs a square window for that); other strides run plain
- * gather kernels and need no workspace.  Pointer, stream and error rules as for the forward
+ * The shape arguments are those of the forward call whose gradients are wanted.  The input
+ * gradient is itself a capsule convolution of `dout` with the flipped, transposed kernel and runs
+ * on the forward kernels (a stride s > 1 as s*s interleaved stride-1 convolutions for 16-bit
+ * capsules of 8 or 16 rows, else on `dout` spread out to stride 1 in `workspace`); the kernel
+ * gradient runs on dedicated matrix-core kernels for 16-bit capsules of 8 or 16 rows and fp32
+ * capsules of 3, 4, 6, 8, 12 or 16 rows, else as a convolution with images and channels
+ * exchanged.  Shapes none of these forms cover (a non-square window with pad > kh-1, ...) take
+ * plain gather kernels, which need no workspace.  Pointer, stream and error rules as for the forward
  * calls; `workspace` must hold capscaps_conv_bwd_input_workspace_bytes(...) resp.
  * capscaps_conv_bwd_kernel_workspace_bytes(...) bytes for the same arguments (0 = may be NULL).
  */

@@ -29,6 +29,9 @@ int fill_shape(ConvShape& s, int N, int H, int W, int C, int M, int kh, int kw, 
     int Ho = 0, Wo = 0;
     const int rc = capscaps_out_shape(H, W, kh, kw, stride, pad, &Ho, &Wo);
     if (rc != CAPSCAPS_OK) return rc;
+    // window taps are counted in 32 bits throughout (a window over a whole large scalar image,
+    // 46341 x 46341 and up, would wrap)
+    if ((long long)kh * kw > (1LL << 24)) return CAPSCAPS_EUNSUPPORTED;
     s = ConvShape{N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, Ho, Wo, dtype};
     // element counts must stay well inside 63 bits
     const long double big = (long double)N * H * W * C * D0 * D1 * D2;
@@ -59,6 +62,9 @@ bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) !
 int run(const void* input, const void* kernel, void* out, const ConvShape& s, int path,
         void* workspace, size_t workspace_bytes, hipStream_t stream)
 {
+    // the library's own choice needs scratch for the kernel it picks only; a forced path is
+    // held to the size that covers every kernel (what the size query reports)
+    const bool own_choice = path == CAPSCAPS_PATH_AUTO || path == CAPSCAPS_PATH_MFMA;
     if (path == CAPSCAPS_PATH_AUTO) path = choose_path(s);
     hipError_t err;
     if (path == CAPSCAPS_PATH_DIRECT) {
@@ -75,7 +81,8 @@ int run(const void* input, const void* kernel, void* out, const ConvShape& s, in
             : path == CAPSCAPS_PATH_MFMA_GENERIC ? capscaps::MfmaKernel::Generic
             : path == CAPSCAPS_PATH_MFMA_TUNED16 ? capscaps::MfmaKernel::Tuned16
                                                  : capscaps::MfmaKernel::Dma32;
-        const size_t need = capscaps::mfma_workspace_bytes(s);
+        const size_t need = own_choice ? capscaps::mfma_auto_workspace_bytes(s)
+                                       : capscaps::mfma_workspace_bytes(s);
         if (need > 0 && (workspace == nullptr || workspace_bytes < need))
             return CAPSCAPS_EWORKSPACE;
         if (need > 0 && misaligned(workspace)) return CAPSCAPS_EINVAL;
@@ -95,7 +102,7 @@ int status_from_hip(hipError_t err) { return hip_status(err); }
 
 size_t forward_workspace_bytes(const ConvShape& s)
 {
-    return choose_path(s) == CAPSCAPS_PATH_DIRECT ? 0 : mfma_workspace_bytes(s);
+    return choose_path(s) == CAPSCAPS_PATH_DIRECT ? 0 : mfma_auto_workspace_bytes(s);
 }
 
 bool forward_auto_repacks_kernel(const ConvShape& s) { return choose_path(s) != CAPSCAPS_PATH_DIRECT; }

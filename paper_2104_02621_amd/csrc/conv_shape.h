@@ -6,7 +6,26 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <atomic>
+
 namespace capscaps {
+
+// Raises a kernel's dynamic-LDS limit to `bytes` the first time the kernel is launched on a
+// device (the attribute stays set for the process), not on every launch: the call costs host
+// time on exactly the launch-bound problems.  `done` is the caller's record for that kernel, one
+// bit per device.
+inline hipError_t set_dynamic_lds_once(const void* kern, int bytes,
+                                       std::atomic<unsigned long long>& done)
+{
+    int dev = 0;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return err;
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (dev < 64 && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    err = hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (err == hipSuccess && dev < 64) done.fetch_or(bit, std::memory_order_release);
+    return err;
+}
 
 struct ConvShape {
     int N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3;
@@ -56,6 +75,7 @@ bool mfma_tuned16_supported(const ConvShape& s);
 bool mfma_dma32_supported(const ConvShape& s);
 size_t mfma_workspace_bytes(const ConvShape& s);  // enough for every MfmaKernel choice (with
                                                   // s.out16: for Auto, the only choice then)
+size_t mfma_auto_workspace_bytes(const ConvShape& s);  // for the kernel Auto resolves to only
 hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, float* out,
                        void* workspace, hipStream_t stream, MfmaKernel which = MfmaKernel::Auto);
 

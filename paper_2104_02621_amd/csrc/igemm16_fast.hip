@@ -635,9 +635,9 @@ hipError_t launch_one(const IgemmParams& P, long long blocks, hipStream_t stream
         auto kern = P.out16 ? igemm16_fast_kernel<Tag, D1, D2, KCH, NB, true, 128>
                             : igemm16_fast_kernel<Tag, D1, D2, KCH, NB, false, 128>;
         const size_t lds_bytes = (size_t)NB * (AL::NBLK * AL::ABLK + 256 * KCH * 16);
-        hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                             (int)lds_bytes);
+        static std::atomic<unsigned long long> lds_set[2] = {{0}, {0}};
+        hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes,
+                                              lds_set[P.out16 ? 1 : 0]);
         if (err != hipSuccess) return err;
         kern<<<dim3((unsigned)blocks), dim3(256), lds_bytes, stream>>>(P);
         return hipGetLastError();
@@ -647,9 +647,9 @@ hipError_t launch_one(const IgemmParams& P, long long blocks, hipStream_t stream
     auto kern = P.out16 ? igemm16_fast_kernel<Tag, D1, D2, KCH, NB, true, 256>
                         : igemm16_fast_kernel<Tag, D1, D2, KCH, NB, false, 256>;
     const size_t lds_bytes = (size_t)NB * AL::NBLK * (AL::ABLK + 1024);
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)lds_bytes);
+    static std::atomic<unsigned long long> lds_set[2] = {{0}, {0}};
+    hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes,
+                                          lds_set[P.out16 ? 1 : 0]);
     if (err != hipSuccess) return err;
     kern<<<dim3((unsigned)blocks), dim3(256), lds_bytes, stream>>>(P);
     return hipGetLastError();

@@ -285,9 +285,8 @@ hipError_t launch_kch(const Dma32Params& P, long long blocks, hipStream_t stream
     constexpr int BM = 64 * NW, BNL = (32 * TN + 63) / 64 * 64;
     auto kern = igemm32_dma_kernel<CW, TN, NW, KCH>;
     const size_t lds_bytes = (size_t)ring_depth(KCH) * KCH * (BM + BNL) * 16;
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)lds_bytes);
+    static std::atomic<unsigned long long> lds_set{0};
+    hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes, lds_set);
     if (err != hipSuccess) return err;
     kern<<<dim3((unsigned)blocks), dim3(64 * NW), lds_bytes, stream>>>(P);
     return hipGetLastError();

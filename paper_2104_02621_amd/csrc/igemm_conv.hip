@@ -476,9 +476,8 @@ hipError_t launch_tile(const Plan& pl, hipStream_t stream)
 {
     auto kern = igemm_kernel<Tag, VEC, ST4, BM, BN, 2, 2>;
     const size_t lds_bytes = (size_t)2 * 8 * (BM + BN) * 16;
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)lds_bytes);
+    static std::atomic<unsigned long long> lds_set{0};
+    hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes, lds_set);
     if (err != hipSuccess) return err;
     kern<<<dim3((unsigned)pl.blocks), dim3(256), lds_bytes, stream>>>(pl.P);
     return hipGetLastError();
@@ -637,6 +636,19 @@ size_t mfma_workspace_bytes(const ConvShape& s)
         if (bytes > need) need = bytes;
     }
     return need;
+}
+
+size_t mfma_auto_workspace_bytes(const ConvShape& s)
+{
+    if (!shape_supported(s)) return 0;
+    const MfmaKernel which = mfma_auto_kernel(s);
+    if (which == MfmaKernel::Dma32) {
+        if (s.out16 != 0) return 0;
+        const Dma32Plan pl = igemm32_dma_plan(s);
+        return ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
+    }
+    const Plan pl = make_plan(s, which);
+    return ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
 }
 
 MfmaKernel mfma_auto_kernel(const ConvShape& s)

@@ -441,9 +441,8 @@ hipError_t launch_kernel(const WgradParams& P, hipStream_t stream)
 {
     auto kern = wgrad16_kernel<Tag, D1>;
     const size_t lds_bytes = (size_t)4 * 2 * 4 * 256 * 16;  // ring of 4 stages of 32 KB
-    hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize,
-                                         (int)lds_bytes);
+    static std::atomic<unsigned long long> lds_set{0};
+    hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes, lds_set);
     if (err != hipSuccess) return err;
     kern<<<dim3((unsigned)P.items), dim3(256), lds_bytes, stream>>>(P);
     return hipGetLastError();

@@ -167,3 +167,15 @@ def test_yardstick_argument_checks():
     assert cc.capscaps_mfma_yardstick(FAKE, FAKE, 5, 1, 1, None) == cc.EINVAL
     assert cc.capscaps_mfma_yardstick(FAKE, FAKE, cc.FP16, 0, 1, None) == cc.EINVAL
     assert cc.capscaps_mfma_yardstick(FAKE, FAKE, cc.FP16, 1, 0, None) == cc.EINVAL
+
+
+def test_huge_window_is_refused_not_wrapped():
+    # a window over a whole large scalar image: kh*kw passes 2^31 and would wrap in 32 bits
+    a = _args(N=1, H=46341, W=46341, C=1, M=1, kh=46341, kw=46341, pad=0, D1=1, D2=1, D3=1)
+    assert cc.capscaps_select_path(*a) == cc.EUNSUPPORTED
+    assert cc.capscaps_conv_fwd_ex(FAKE, FAKE, FAKE, *a, FAKE, 1 << 30, None) == cc.EUNSUPPORTED
+    assert cc.capscaps_conv_fwd_workspace_bytes(*a) == 0
+    assert cc.capscaps_conv_bwd_input(FAKE, FAKE, FAKE, *a, FAKE, 1 << 30, None) == cc.EUNSUPPORTED
+    # 4096 x 4096 taps is the largest window taken
+    b = _args(N=1, H=4096, W=4096, C=1, M=1, kh=4096, kw=4096, pad=0, D1=1, D2=1, D3=1)
+    assert cc.capscaps_select_path(*b) > 0
