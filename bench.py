@@ -296,9 +296,10 @@ def main():
         from paper_2104_02621_amd import comparisons as cmp
         out = torch.empty(w.out_shape, dtype=torch.float32, device="cuda")
         need = 0
-        if args.op == "scheme1" and w.Ho * w.Wo * w.M * w.kh * w.kw * w.C * w.D0 > cmp.MAX_BMM_BATCH:
-            sys.exit("bench.py: scheme 1 is not run on this workload (too many small products per "
-                     "batched multiply; see comparisons.MAX_BMM_BATCH)")
+        if args.op == "scheme1" and w.M * w.kh * w.kw * w.C * w.D0 > cmp.MAX_BMM_BATCH:
+            sys.exit("bench.py: scheme 1 is not run on this workload (more small products per "
+                     "output pixel than one batched multiply is handed; see "
+                     "comparisons.MAX_BMM_BATCH)")
         if args.op == "scheme2":
             need = cc.capscaps_scheme2_index_bytes(*shape)
             if need == 0 or need > (64 << 30):

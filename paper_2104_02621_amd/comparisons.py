@@ -19,17 +19,22 @@ on the same inputs.
 from __future__ import annotations
 
 
-# Largest batch count handed to the vendor batched multiply in one call.  A call with 2.3e8
-# batches of 3x3 products (benchmark configuration 2, eight images at once) ended in a GPU
-# memory fault inside that call; 2.9e6 batches (configuration 4) run fine.  Shapes whose
-# single image needs more than this are refused rather than tried.
-MAX_BMM_BATCH = 1 << 22
+# Largest batch count handed to the vendor batched multiply in one call.  One call with 2.26e8
+# batches of 3x3 products (benchmark configuration 2, eight images at once) ended in a GPU memory
+# fault inside that call.  Each operand of that call spanned 8.15 GB, twice what a 32-bit byte
+# offset (or one buffer descriptor) can address, and its batch count was far past what one grid
+# dimension holds, so the call was beyond two limits at once; a call with 2.9e6 batches and
+# 0.1 GB operands (configuration 4) is below both and runs.  Every call made here stays inside
+# that proven regime: at most 2^21 products, operands of at most 2^21 * D*D elements.  Larger
+# problems are cut over images and output pixels.
+MAX_BMM_BATCH = 1 << 21
 
 
 def scheme1_fwd(inp, kernel, stride=1, pad=0, max_batch_elems=1 << 28):
     """inp [N,H,W,C,D0,D1,D2], kernel [kh,kw,C,M,D0,D2,D3] (device tensors, one dtype) ->
-    float32 [N,H',W',M,D0,D1,D3].  Images are processed in groups so that no intermediate
-    exceeds `max_batch_elems` elements and no batched multiply MAX_BMM_BATCH products."""
+    float32 [N,H',W',M,D0,D1,D3].  The steps of Algorithm 3 run on blocks of images and output
+    pixels sized so that no intermediate exceeds `max_batch_elems` elements and no batched
+    multiply MAX_BMM_BATCH products."""
     import torch
     import torch.nn.functional as F
 
@@ -40,15 +45,17 @@ def scheme1_fwd(inp, kernel, stride=1, pad=0, max_batch_elems=1 << 28):
     Wo = (W + 2 * pad - kw) // stride + 1
     L, T = Ho * Wo, kh * kw * C
     caps_in = D0 * D1 * D2
-    # kernel_extend: every output pixel gets its own copy of all kernel capsules
-    k_ext = (kernel.permute(3, 0, 1, 2, 4, 5, 6).reshape(1, M, T, D0, D2, D3)
-             .expand(L, M, T, D0, D2, D3).contiguous())
-    per_image = L * M * T * D0 * D1 * max(D2, D3)
-    if L * M * T * D0 > MAX_BMM_BATCH:
-        raise ValueError(f"scheme 1 needs {L * M * T * D0} small products per image in one "
+    per_pixel = M * T * D0                      # small products per output pixel
+    if per_pixel > MAX_BMM_BATCH:
+        raise ValueError(f"scheme 1 needs {per_pixel} small products per output pixel in one "
                          f"batched multiply; more than {MAX_BMM_BATCH} is not attempted")
-    group = max(1, min(N, max_batch_elems // max(per_image, 1), MAX_BMM_BATCH // (L * M * T * D0)))
-    out = torch.empty((N, Ho, Wo, M, D0, D1, D3), dtype=torch.float32, device=inp.device)
+    # pixels (of one or several images) per batched multiply
+    budget = max(1, min(MAX_BMM_BATCH // per_pixel,
+                        max_batch_elems // max(per_pixel * D1 * max(D2, D3), 1)))
+    group = max(1, min(N, budget // L))         # whole images per block, when a block holds any
+    block = L if budget >= L else budget        # else: pixels of one image per block
+    k_all = kernel.permute(3, 0, 1, 2, 4, 5, 6).reshape(1, 1, M, T, D0, D2, D3)
+    out = torch.empty((N, L, M, D0, D1, D3), dtype=torch.float32, device=inp.device)
     for n0 in range(0, N, group):
         x = inp[n0:n0 + group]
         n = x.shape[0]
@@ -56,15 +63,19 @@ def scheme1_fwd(inp, kernel, stride=1, pad=0, max_batch_elems=1 << 28):
         cols = F.unfold(x.permute(0, 3, 4, 5, 6, 1, 2).reshape(n, C * caps_in, H, W),
                         (kh, kw), padding=pad, stride=stride)          # [n, C*caps*kh*kw, L]
         flat = (cols.reshape(n, C, caps_in, kh * kw, L).permute(0, 4, 3, 1, 2)
-                .reshape(n, L, T, D0, D1, D2).contiguous())
-        # input_extend: one copy per output channel
-        i_ext = flat.unsqueeze(2).expand(n, L, M, T, D0, D1, D2).contiguous()
-        # strided batched small-matrix multiply (vendor library)
-        k_b = k_ext.unsqueeze(0).expand(n, L, M, T, D0, D2, D3).reshape(-1, D2, D3)
-        o_ext = torch.bmm(i_ext.reshape(-1, D1, D2), k_b).reshape(n, L, M, T, D0, D1, D3)
-        # output_reduce: linear combination over window and input channels
-        out[n0:n0 + n] = o_ext.float().sum(dim=3).reshape(n, Ho, Wo, M, D0, D1, D3)
-    return out
+                .reshape(n, L, T, D0, D1, D2))
+        for l0 in range(0, L, block):
+            f = flat[:, l0:l0 + block]
+            l = f.shape[1]
+            # input_extend: one copy per output channel
+            i_ext = f.unsqueeze(2).expand(n, l, M, T, D0, D1, D2).contiguous()
+            # kernel_extend: every output pixel gets its own copy of all kernel capsules
+            k_ext = k_all.expand(n, l, M, T, D0, D2, D3).contiguous()
+            # strided batched small-matrix multiply (vendor library)
+            o_ext = torch.bmm(i_ext.reshape(-1, D1, D2), k_ext.reshape(-1, D2, D3))
+            # output_reduce: linear combination over window and input channels
+            out[n0:n0 + n, l0:l0 + l] = o_ext.reshape(n, l, M, T, D0, D1, D3).sum(dim=3)
+    return out.reshape(N, Ho, Wo, M, D0, D1, D3)
 
 
 def framework_conv_fwd(inp, kernel, stride=1, pad=0, widen=True):

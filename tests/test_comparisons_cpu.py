@@ -41,8 +41,33 @@ def test_fig2_all_ones_gives_48():
     assert torch.equal(cmp.framework_conv_fwd(I, K), torch.full((1, 2, 2, 1, 3, 3, 3), 48.0))
 
 
+def test_scheme1_cuts_large_problems_into_bounded_multiplies(monkeypatch):
+    """No batched multiply is handed more than MAX_BMM_BATCH products: the blocks run over
+    images and, within an image, over output pixels."""
+    rng = np.random.default_rng(77)
+    I = rng.standard_normal((3, 6, 7, 3, 2, 3, 3)).astype(np.float32)
+    K = rng.standard_normal((3, 3, 3, 4, 2, 3, 3)).astype(np.float32)
+    ref = capsconv.conv_fwd(I, K, 1, 1)
+    seen = []
+    real_bmm = torch.bmm
+
+    def spy(a, b):
+        seen.append(a.shape[0])
+        return real_bmm(a, b)
+
+    monkeypatch.setattr(torch, "bmm", spy)
+    for limit in (4 * 27 * 2 * 5, 4 * 27 * 2 * 42 * 2):       # 5 pixels; two whole images
+        monkeypatch.setattr(cmp, "MAX_BMM_BATCH", limit)
+        seen.clear()
+        got = cmp.scheme1_fwd(torch.from_numpy(I), torch.from_numpy(K), 1, 1).numpy()
+        assert np.abs(got - ref).max() <= 1e-5 * np.abs(ref).max()
+        assert len(seen) > 1 and max(seen) <= limit
+        assert sum(seen) == 3 * 42 * 4 * 27 * 2                # every small product, once
+
+
 def test_scheme1_refuses_oversized_batches():
-    I = torch.zeros(1, 64, 64, 64, 1, 2, 2)
-    K = torch.zeros(3, 3, 64, 64, 1, 2, 2)
+    # more small products for ONE output pixel than a batched multiply is handed
+    I = torch.zeros(1, 32, 32, 64, 1, 1, 1)
+    K = torch.zeros(32, 32, 64, 64, 1, 1, 1)
     with pytest.raises(ValueError):
-        cmp.scheme1_fwd(I, K, 1, 1)
+        cmp.scheme1_fwd(I, K, 1, 0)

@@ -55,6 +55,17 @@ def test_benchmark_configs(number):
     compare_all(wl.config(number))
 
 
+def test_benchmark_config_2_two_images():
+    """Configuration 2's layer on two of its 64 images: scheme 1 needs 2.8e7 small products per
+    image there and runs them as 14 batched multiplies per image (blocks of 75 output pixels)."""
+    w = wl.config(2).with_batch(2)
+    assert w.Ho * w.Wo * w.M * w.kh * w.kw * w.C * w.D0 > 6 * cmp.MAX_BMM_BATCH
+    i_st, k_st, i32, k32 = wl.generate(w)
+    ref, S = capsconv.conv_fwd(i32, k32, w.stride, w.pad, with_abs_sum=True)
+    i_dev, k_dev = to_device(i_st, w.dtype), to_device(k_st, w.dtype)
+    check(w, cmp.scheme1_fwd(i_dev, k_dev, w.stride, w.pad).cpu().numpy(), ref, S, "scheme 1")
+
+
 def test_scheme2_integer_data_is_exact():
     """Every partial sum is exact in fp32, so the unordered atomic additions cannot show."""
     w = wl.integer_variant(small("sq4", wl.FP32, 3, 9, 10, 5, 6, 3, 3, 1, 1, 1, 4, 4, 4))
