@@ -31,7 +31,7 @@
  *
  * Errors: functions returning int return CAPSCAPS_OK (0) or a negative status.  Arguments, the
  * workspace size and whether a path supports the shape are checked before the first launch: on
- * CAPSCAPS_EINVAL, CAPSCAPS_EWORKSPACE and CAPSCAPS_EUNSUPPORTED nothing has
+ * CAPSCAPS_EINVAL, CAPSCAPS_EWORKSPACE, CAPSCAPS_EUNSUPPORTED and CAPSCAPS_ESCRATCH nothing has
  * been enqueued and no buffer has been touched.  CAPSCAPS_EHIP reports a failing HIP call; a call
  * is a short sequence of launches (kernel repack, main kernel, fixed-order reduction; the backward
  * pass has a few more), so earlier launches of the sequence may already be enqueued: `out` and
@@ -65,6 +65,8 @@ extern "C" {
 #define CAPSCAPS_EUNSUPPORTED (-3) /* the forced path cannot run this shape/dtype; a window of
                                       more than 2^24 taps */
 #define CAPSCAPS_EHIP (-4)         /* a HIP call (launch, allocation) failed */
+#define CAPSCAPS_ESCRATCH (-5)     /* capscaps_conv_fwd_static: the problem needs more scratch than
+                                      CAPSCAPS_STATIC_SCRATCH_BYTES */
 
 /* compute paths (for capscaps_conv_fwd_path / capscaps_select_path) */
 #define CAPSCAPS_PATH_AUTO 0   /* library's choice */
@@ -131,6 +133,26 @@ int capscaps_conv_fwd_out16(const void* input, const void* kernel, void* out, in
                             int C, int M, int kh, int kw, int stride, int pad, int D0, int D1,
                             int D2, int D3, int dtype, void* workspace, size_t workspace_bytes,
                             void* stream);
+
+/*
+ * capscaps_conv_fwd_ex for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid allocation.  Same
+ * operator, arguments, layouts, kernels and results as capscaps_conv_fwd_ex, but the scratch
+ * (repacked kernel, partial sums of split reductions) is a fixed array of
+ * CAPSCAPS_STATIC_SCRATCH_BYTES in each GPU's memory that exists from the moment the library's
+ * code is loaded on that GPU until the process ends.  The call allocates and frees nothing and
+ * calls no allocating routine; a problem whose scratch does not fit returns CAPSCAPS_ESCRATCH
+ * before anything is launched (all five benchmark configurations fit).  The device that holds the
+ * buffers must be the current device.  The first call on a device looks up the array's address
+ * there (make that call outside a graph capture).  All calls on one GPU share that GPU's array:
+ * calls that may overlap on one GPU (different streams, or graphs replayed concurrently) race on
+ * it and must be serialised by the caller; nothing in it needs to start at zero, every call
+ * overwrites what it reads.
+ */
+#define CAPSCAPS_STATIC_SCRATCH_BYTES (80u << 20)
+int capscaps_conv_fwd_static(const void* input, const void* kernel, void* out, int N, int H, int W,
+                             int C, int M, int kh, int kw, int stride, int pad, int D0, int D1,
+                             int D2, int D3, int dtype, void* stream);
 
 /*
  * Scratch bytes capscaps_conv_fwd_ex / _path need for these arguments (repacked kernel,

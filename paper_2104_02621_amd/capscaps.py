@@ -13,7 +13,8 @@ from pathlib import Path
 FP32, BF16, FP16 = 0, 1, 2
 PATH_AUTO, PATH_DIRECT, PATH_MFMA, PATH_MFMA_GENERIC, PATH_MFMA_TUNED16 = 0, 1, 2, 3, 4
 PATH_MFMA_TUNED32 = 5
-OK, EINVAL, EWORKSPACE, EUNSUPPORTED, EHIP = 0, -1, -2, -3, -4
+OK, EINVAL, EWORKSPACE, EUNSUPPORTED, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5
+STATIC_SCRATCH_BYTES = 80 << 20
 
 _LIB_PATH = Path(__file__).resolve().parent / "libcapscaps.so"
 _lib = None
@@ -53,6 +54,8 @@ def _load():
     lib.capscaps_conv_fwd.restype = i
     lib.capscaps_conv_fwd_ex.argtypes = [p, p, p] + [i] * 14 + [p, sz, p]
     lib.capscaps_conv_fwd_ex.restype = i
+    lib.capscaps_conv_fwd_static.argtypes = [p, p, p] + [i] * 14 + [p]
+    lib.capscaps_conv_fwd_static.restype = i
     lib.capscaps_conv_fwd_out16_workspace_bytes.argtypes = [i] * 14
     lib.capscaps_conv_fwd_out16_workspace_bytes.restype = sz
     lib.capscaps_conv_fwd_out16.argtypes = [p, p, p] + [i] * 14 + [p, sz, p]
@@ -113,6 +116,12 @@ def capscaps_conv_fwd_ex(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad,
                          dtype, workspace, workspace_bytes, stream=None) -> int:
     return _load().capscaps_conv_fwd_ex(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad,
                                         D0, D1, D2, D3, dtype, workspace, workspace_bytes, stream)
+
+
+def capscaps_conv_fwd_static(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3,
+                             dtype, stream=None) -> int:
+    return _load().capscaps_conv_fwd_static(input, kernel, out, N, H, W, C, M, kh, kw, stride, pad,
+                                            D0, D1, D2, D3, dtype, stream)
 
 
 def capscaps_conv_fwd_out16_workspace_bytes(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3,

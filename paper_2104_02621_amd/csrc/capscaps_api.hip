@@ -2,6 +2,8 @@
 // Declarations and their contracts are in include/capscaps.h.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "../../include/capscaps.h"
 #include "conv_shape.h"
 
@@ -58,6 +60,34 @@ int choose_path(const ConvShape& s)
 }
 
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Scratch of the entry point that allocates nothing (capscaps_conv_fwd_static): a fixed array in
+// every GPU's memory, there from the moment the library's code is loaded on that GPU until the
+// process ends.  In host code the array's name stands for the symbol, not for a device address:
+// the address on the current device is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[CAPSCAPS_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int scratch_of_current_device(void** ptr)
+{
+    int dev = -1;
+    hipError_t err = hipGetDevice(&dev);
+    if (err != hipSuccess) return hip_status(err);
+    if (dev < 0 || dev >= kMaxDevices) return CAPSCAPS_EUNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        err = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (err != hipSuccess) return hip_status(err);
+        if (p == nullptr) return CAPSCAPS_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return CAPSCAPS_OK;
+}
 
 int run(const void* input, const void* kernel, void* out, const ConvShape& s, int path,
         void* workspace, size_t workspace_bytes, hipStream_t stream)
@@ -232,6 +262,25 @@ int capscaps_conv_fwd(const void* input, const void* kernel, void* out, int N, i
     return status;
 }
 
+int capscaps_conv_fwd_static(const void* input, const void* kernel, void* out, int N, int H, int W,
+                             int C, int M, int kh, int kw, int stride, int pad, int D0, int D1,
+                             int D2, int D3, int dtype, void* stream)
+{
+    if (input == nullptr || kernel == nullptr || out == nullptr) return CAPSCAPS_EINVAL;
+    if (misaligned(input) || misaligned(kernel) || misaligned(out)) return CAPSCAPS_EINVAL;
+    ConvShape s;
+    const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype);
+    if (rc != CAPSCAPS_OK) return rc;
+    // the scratch the library's own kernel choice needs must fit the fixed array
+    if (capscaps::forward_workspace_bytes(s) > (size_t)CAPSCAPS_STATIC_SCRATCH_BYTES)
+        return CAPSCAPS_ESCRATCH;
+    void* ws = nullptr;
+    const int rs = scratch_of_current_device(&ws);
+    if (rs != CAPSCAPS_OK) return rs;
+    return run(input, kernel, out, s, CAPSCAPS_PATH_AUTO, ws, (size_t)CAPSCAPS_STATIC_SCRATCH_BYTES,
+               static_cast<hipStream_t>(stream));
+}
+
 size_t capscaps_conv_bwd_input_workspace_bytes(int N, int H, int W, int C, int M, int kh, int kw,
                                                int stride, int pad, int D0, int D1, int D2, int D3,
                                                int dtype)
@@ -357,6 +406,9 @@ const char* capscaps_strerror(int status)
         case CAPSCAPS_EWORKSPACE: return "workspace missing or too small";
         case CAPSCAPS_EUNSUPPORTED: return "path does not support this shape";
         case CAPSCAPS_EHIP: return "HIP runtime error";
+        case CAPSCAPS_ESCRATCH:
+            return "problem needs more scratch than the fixed buffer of the entry point that "
+                   "allocates nothing";
         default: return "unknown status";
     }
 }

@@ -179,3 +179,14 @@ def test_huge_window_is_refused_not_wrapped():
     # 4096 x 4096 taps is the largest window taken
     b = _args(N=1, H=4096, W=4096, C=1, M=1, kh=4096, kw=4096, pad=0, D1=1, D2=1, D3=1)
     assert cc.capscaps_select_path(*b) > 0
+
+
+def test_static_scratch_entry_point_checks_before_touching_the_gpu():
+    a = _args()
+    assert cc.capscaps_conv_fwd_static(None, FAKE, FAKE, *a, None) == cc.EINVAL
+    assert cc.capscaps_conv_fwd_static(FAKE, FAKE + 4, FAKE, *a, None) == cc.EINVAL
+    assert cc.capscaps_conv_fwd_static(FAKE, FAKE, FAKE, *_args(M=0), None) == cc.EINVAL
+    # a repacked kernel larger than the fixed array
+    big = _args(N=1, H=34, W=34, C=160, M=160, D1=16, D2=16, D3=16, dtype=cc.FP16)
+    assert cc.capscaps_conv_fwd_static(FAKE, FAKE, FAKE, *big, None) == cc.ESCRATCH
+    assert "scratch" in cc.capscaps_strerror(cc.ESCRATCH)
