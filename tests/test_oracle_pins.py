@@ -337,6 +337,32 @@ def test_subset_matches_full_and_abs_sum():
     assert np.all(S + 1e-12 >= np.abs(O))
 
 
+@pytest.mark.parametrize("stride,pad", [(1, 0), (1, 1), (2, 2)])
+def test_abs_sum_closed_form(stride, pad):
+    """The error scale S = sum |I*K| pinned without the oracle on both sides: input all a < 0,
+    kernel all b > 0, with alternating signs laid over both so that O cancels but S cannot:
+    S = |a*b| * C * D2 * (in-range taps at that pixel) everywhere, and O = 0 where the number of
+    terms is even."""
+    N, H, W, C, M, kh, kw, D0, D1, D2, D3 = 2, 6, 5, 3, 2, 3, 2, 2, 3, 4, 5
+    a, b = -0.75, 1.5
+    I = np.full((N, H, W, C, D0, D1, D2), a, np.float32)
+    K = np.full((kh, kw, C, M, D0, D2, D3), b, np.float32)
+    K[..., 1::2, :] *= -1                       # sign alternates along the contracted index d2
+    O, S = capsconv.conv_fwd(I, K, stride=stride, pad=pad, with_abs_sum=True)
+    Ho = (H + 2 * pad - kh) // stride + 1
+    Wo = (W + 2 * pad - kw) // stride + 1
+    for x in range(Ho):
+        rows = sum(0 <= x * stride - pad + p < H for p in range(kh))
+        for y in range(Wo):
+            cols = sum(0 <= y * stride - pad + q < W for q in range(kw))
+            assert np.all(S[:, x, y] == abs(a * b) * C * D2 * rows * cols), (x, y)
+    assert np.all(O == 0.0)                     # D2 is even: every capsule product cancels
+    which = np.array([[1, Ho - 1, 0, 1], [0, 0, Wo - 1, 0]], np.int32)
+    Os, Ss = capsconv.conv_fwd_subset(I, K, which, stride, pad, with_abs_sum=True)
+    assert np.array_equal(Ss[0], S[1, Ho - 1, 0, 1]) and np.array_equal(Ss[1], S[0, 0, Wo - 1, 0])
+    assert np.all(Os == 0.0)
+
+
 def test_rejects_bad_requests():
     I, K = _case(91)
     with pytest.raises(ValueError):
