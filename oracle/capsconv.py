@@ -15,7 +15,12 @@ import numpy as np
 
 _HERE = Path(__file__).resolve().parent
 _SRC = _HERE / "capsconv_oracle.c"
-_LIB = _HERE / "libcapsconv_oracle.so"
+# CAPSCAPS_SANITIZE=1: a second build with AddressSanitizer and UndefinedBehaviorSanitizer (clang,
+# shared runtime), for running the CPU tests under the sanitizers; the process must then preload
+# clang's libclang_rt.asan-x86_64.so.
+_SANITIZE = os.environ.get("CAPSCAPS_SANITIZE") == "1"
+_LIB = _HERE / ("libcapsconv_oracle.san.so" if _SANITIZE else "libcapsconv_oracle.so")
+_CLANG = os.environ.get("CAPSCAPS_CLANG", "/opt/rocm/lib/llvm/bin/clang")
 _lib = None
 
 
@@ -25,6 +30,10 @@ def build(force: bool = False) -> Path:
         tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
         cmd = ["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall", "-Wextra",
                "-o", str(tmp), str(_SRC)]
+        if _SANITIZE:
+            cmd = [_CLANG, "-O1", "-g", "-fopenmp", "-fPIC", "-shared", "-std=c99", "-Wall",
+                   "-Wextra", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+                   "-fno-omit-frame-pointer", "-shared-libsan", "-o", str(tmp), str(_SRC)]
         subprocess.run(cmd, check=True)
         os.replace(tmp, _LIB)
     return _LIB

@@ -15,8 +15,13 @@ from pathlib import Path
 
 PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
-OBJ = PKG / "_build"
-LIB = PKG / "libcapscaps.so"
+# CAPSCAPS_SANITIZE=1: a second build whose HOST code (argument checks, plans, launch logic) is
+# instrumented with AddressSanitizer and UndefinedBehaviorSanitizer, for running the CPU tests
+# under the sanitizers (GPU code is never instrumented).  The process that loads it must preload
+# clang's libclang_rt.asan-x86_64.so.
+SANITIZE = os.environ.get("CAPSCAPS_SANITIZE") == "1"
+OBJ = PKG / ("_build_san" if SANITIZE else "_build")
+LIB = PKG / ("libcapscaps.san.so" if SANITIZE else "libcapscaps.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -25,6 +30,10 @@ FLAGS = [
     # packed-fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
 ]
+if SANITIZE:
+    FLAGS += ["-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+              "-Xarch_host", "-fno-sanitize-recover=undefined", "-Xarch_host",
+              "-fno-omit-frame-pointer"]
 
 
 def sources():
@@ -54,6 +63,8 @@ def build(force: bool = False, jobs: int = 4) -> Path:
     if force or not LIB.exists() or any(o.stat().st_mtime > LIB.stat().st_mtime for o in objs):
         tmp = LIB.with_name(f".libcapscaps.{os.getpid()}.so")
         cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", str(tmp)] + [str(o) for o in objs]
+        if SANITIZE:
+            cmd += ["-fno-gpu-sanitize", "-fsanitize=address,undefined", "-shared-libsan"]
         r = subprocess.run(cmd, capture_output=True, text=True)
         if r.returncode != 0:
             raise RuntimeError(f"link failed:\n{r.stderr}")
