@@ -245,7 +245,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, choices=[1, 2, 3, 4, 5])
     ap.add_argument("--path", default="auto",
-                    choices=["auto", "mfma", "direct", "mfma-generic", "mfma-tuned16", "mfma-tuned32"])
+                    choices=["auto", "mfma", "direct", "mfma-generic", "mfma-tuned16", "mfma-tuned32",
+                             "mfma-small"])
     ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_input", "bwd_kernel", "scheme1", "scheme2",
                                                      "framework_conv", "net5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -275,7 +276,7 @@ def main():
     w = wl.config(args.config)
     path = {"auto": cc.PATH_AUTO, "mfma": cc.PATH_MFMA, "direct": cc.PATH_DIRECT,
             "mfma-generic": cc.PATH_MFMA_GENERIC, "mfma-tuned16": cc.PATH_MFMA_TUNED16,
-            "mfma-tuned32": cc.PATH_MFMA_TUNED32}[args.path]
+            "mfma-tuned32": cc.PATH_MFMA_TUNED32, "mfma-small": cc.PATH_MFMA_SMALL}[args.path]
     shape = (w.N, w.H, w.W, w.C, w.M, w.kh, w.kw, w.stride, w.pad, w.D0, w.D1, w.D2, w.D3, w.dtype)
 
     i_st, k_st, i32, k32 = wl.generate(w)
@@ -405,7 +406,7 @@ def main():
             "M": w.M, "kh": w.kh, "kw": w.kw, "stride": w.stride, "pad": w.pad,
             "capsule": [w.D0, w.D1, w.D2, w.D3],
             "path": {1: "direct", 2: "mfma", 3: "mfma-generic", 4: "mfma-tuned16",
-                     5: "mfma-tuned32"}[chosen] if args.op == "fwd" else "auto",
+                     5: "mfma-tuned32", 6: "mfma-small"}[chosen] if args.op == "fwd" else "auto",
             "flops_tap_exact": flops_exact, "flops_nominal": flops_nominal,
             "gflops_nominal": round(flops_nominal / (ms_per_step * 1e-3) / 1e9, 1),
             "compulsory_bytes": w.compulsory_bytes(),

@@ -80,6 +80,10 @@ extern "C" {
 #define CAPSCAPS_PATH_MFMA_TUNED32 5 /* ... the fp32 variant with direct-to-LDS copies, for
                                         capsule rows of 3, 4, 6, 8, 12 or 16 floats; other
                                         shapes: CAPSCAPS_EUNSUPPORTED */
+#define CAPSCAPS_PATH_MFMA_SMALL 6   /* ... the variant for small problems (a few thousand output
+                                        rows, the fully-connected layer): one launch, kernel
+                                        tensor read in place, 16-column tiles, fp32 matrix
+                                        instructions for every element type */
 
 /*
  * Output extents (Fig. 1 / Fig. 2: 5 with a 4-wide kernel at stride 1 gives 2).

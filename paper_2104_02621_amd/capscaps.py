@@ -8,15 +8,19 @@ library is missing or no GPU is present, calls fail.
 from __future__ import annotations
 
 import ctypes
+import os
 from pathlib import Path
 
 FP32, BF16, FP16 = 0, 1, 2
 PATH_AUTO, PATH_DIRECT, PATH_MFMA, PATH_MFMA_GENERIC, PATH_MFMA_TUNED16 = 0, 1, 2, 3, 4
 PATH_MFMA_TUNED32 = 5
+PATH_MFMA_SMALL = 6
 OK, EINVAL, EWORKSPACE, EUNSUPPORTED, EHIP, ESCRATCH = 0, -1, -2, -3, -4, -5
 STATIC_SCRATCH_BYTES = 80 << 20
 
-_LIB_PATH = Path(__file__).resolve().parent / "libcapscaps.so"
+# CAPSCAPS_SANITIZE=1 selects the build whose host code is instrumented (see build.py)
+_LIB_PATH = Path(__file__).resolve().parent / (
+    "libcapscaps.san.so" if os.environ.get("CAPSCAPS_SANITIZE") == "1" else "libcapscaps.so")
 _lib = None
 
 

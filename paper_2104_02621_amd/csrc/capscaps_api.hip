@@ -55,6 +55,7 @@ int choose_path(const ConvShape& s)
     switch (capscaps::mfma_auto_kernel(s)) {
         case capscaps::MfmaKernel::Tuned16: return CAPSCAPS_PATH_MFMA_TUNED16;
         case capscaps::MfmaKernel::Dma32: return CAPSCAPS_PATH_MFMA_TUNED32;
+        case capscaps::MfmaKernel::Small: return CAPSCAPS_PATH_MFMA_SMALL;
         default: return CAPSCAPS_PATH_MFMA_GENERIC;
     }
 }
@@ -100,16 +101,20 @@ int run(const void* input, const void* kernel, void* out, const ConvShape& s, in
     if (path == CAPSCAPS_PATH_DIRECT) {
         err = capscaps::launch_direct(s, input, kernel, static_cast<float*>(out), stream);
     } else if (path == CAPSCAPS_PATH_MFMA || path == CAPSCAPS_PATH_MFMA_GENERIC ||
-               path == CAPSCAPS_PATH_MFMA_TUNED16 || path == CAPSCAPS_PATH_MFMA_TUNED32) {
+               path == CAPSCAPS_PATH_MFMA_TUNED16 || path == CAPSCAPS_PATH_MFMA_TUNED32 ||
+               path == CAPSCAPS_PATH_MFMA_SMALL) {
         if (!capscaps::mfma_supported(s)) return CAPSCAPS_EUNSUPPORTED;
         if (path == CAPSCAPS_PATH_MFMA_TUNED16 && !capscaps::mfma_tuned16_supported(s))
             return CAPSCAPS_EUNSUPPORTED;
         if (path == CAPSCAPS_PATH_MFMA_TUNED32 && !capscaps::mfma_dma32_supported(s))
             return CAPSCAPS_EUNSUPPORTED;
+        if (path == CAPSCAPS_PATH_MFMA_SMALL && !capscaps::mfma_small_supported(s))
+            return CAPSCAPS_EUNSUPPORTED;
         const capscaps::MfmaKernel which =
             path == CAPSCAPS_PATH_MFMA           ? capscaps::MfmaKernel::Auto
             : path == CAPSCAPS_PATH_MFMA_GENERIC ? capscaps::MfmaKernel::Generic
             : path == CAPSCAPS_PATH_MFMA_TUNED16 ? capscaps::MfmaKernel::Tuned16
+            : path == CAPSCAPS_PATH_MFMA_SMALL   ? capscaps::MfmaKernel::Small
                                                  : capscaps::MfmaKernel::Dma32;
         const size_t need = own_choice ? capscaps::mfma_auto_workspace_bytes(s)
                                        : capscaps::mfma_workspace_bytes(s);
@@ -192,7 +197,7 @@ int capscaps_conv_fwd_path(const void* input, const void* kernel, void* out, int
 {
     if (input == nullptr || kernel == nullptr || out == nullptr) return CAPSCAPS_EINVAL;
     if (misaligned(input) || misaligned(kernel) || misaligned(out)) return CAPSCAPS_EINVAL;
-    if (path < CAPSCAPS_PATH_AUTO || path > CAPSCAPS_PATH_MFMA_TUNED32) return CAPSCAPS_EINVAL;
+    if (path < CAPSCAPS_PATH_AUTO || path > CAPSCAPS_PATH_MFMA_SMALL) return CAPSCAPS_EINVAL;
     ConvShape s;
     const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype);
     if (rc != CAPSCAPS_OK) return rc;

@@ -68,11 +68,12 @@ hipError_t launch_direct(const ConvShape& s, const void* in, const void* kernel,
 // Matrix-core path (LDS-staged implicit GEMM).  `mfma_supported` tells whether the path can
 // run the shape; `mfma_workspace_bytes` is the scratch it needs (repacked kernel plus, for
 // small problems, split-reduction partial sums).
-enum class MfmaKernel { Auto, Generic, Tuned16, Dma32 };
+enum class MfmaKernel { Auto, Generic, Tuned16, Dma32, Small };
 bool mfma_supported(const ConvShape& s);
 MfmaKernel mfma_auto_kernel(const ConvShape& s);  // what Auto resolves to (never Auto)
 bool mfma_tuned16_supported(const ConvShape& s);
 bool mfma_dma32_supported(const ConvShape& s);
+bool mfma_small_supported(const ConvShape& s);
 size_t mfma_workspace_bytes(const ConvShape& s);  // enough for every MfmaKernel choice (with
                                                   // s.out16: for Auto, the only choice then)
 size_t mfma_auto_workspace_bytes(const ConvShape& s);  // for the kernel Auto resolves to only

@@ -176,6 +176,14 @@ int igemm16_fast_kgroup(const ConvShape& s);      // chunks per K stage (repack 
 hipError_t launch_igemm16_fast(const IgemmParams& P, long long blocks, int dtype,
                                hipStream_t stream);
 
+// Small-problem kernel (igemm_small.hip): one launch, kernel tensor read in place, 16-column
+// tiles, K loop shared by the waves of a workgroup; honours ConvShape::kernel_view.
+bool igemm_small_eligible(const ConvShape& s);   // the kernel can run the shape
+bool igemm_small_preferred(const ConvShape& s);  // ... and is the library's choice for it
+size_t igemm_small_workspace_bytes(const ConvShape& s);
+hipError_t launch_igemm_small(const ConvShape& s, const void* in, const void* kernel, float* out,
+                              void* workspace, hipStream_t stream);
+
 // Kernel gradient on the matrix cores for 16-bit types, D1 in {8, 16} (wgrad16.hip).
 bool wgrad16_eligible(const ConvShape& s);
 size_t wgrad16_workspace_bytes(const ConvShape& s);

@@ -92,6 +92,26 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
     for (int s = 1; s < nsplit; ++s) acc += partial[(long long)s * elems + e];
     store1(out, e, acc, out16);
 }
+// The same for element counts that are a multiple of 4: 16-byte loads, and the loads of 8 partial
+// results in flight before their additions (which keep the order above).
+__global__ __launch_bounds__(256) void splitk_reduce4_kernel(const float4v* __restrict__ partial,
+                                                             float* __restrict__ out,
+                                                             long long quads, int nsplit, int out16)
+{
+    const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (e >= quads) return;
+    float4v acc = partial[e];
+    int s = 1;
+    for (; s + 8 <= nsplit; s += 8) {
+        float4v v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = partial[(long long)(s + u) * quads + e];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    for (; s < nsplit; ++s) acc += partial[(long long)s * quads + e];
+    store4(out, 4 * e, acc, out16);
+}
 
 // ---------------------------------------------------------------------------------------------
 // VEC: a chunk never straddles a capsule row (D2 % CH == 0, D2/CH a power of two) -> one
@@ -606,8 +626,16 @@ hipError_t launch_repack(const ConvShape& s, const void* kernel, void* kp, int c
 hipError_t launch_splitk_reduce(const float* partial, float* out, long long elems, int nsplit,
                                 hipStream_t stream, int out16)
 {
-    const unsigned blocks = (unsigned)((elems + 255) / 256);
-    splitk_reduce_kernel<<<blocks, 256, 0, stream>>>(partial, out, elems, nsplit, out16);
+    const bool quads = elems % 4 == 0 && (reinterpret_cast<uintptr_t>(partial) & 15u) == 0 &&
+                       (reinterpret_cast<uintptr_t>(out) & 15u) == 0;
+    if (quads) {
+        const unsigned blocks = (unsigned)((elems / 4 + 255) / 256);
+        splitk_reduce4_kernel<<<blocks, 256, 0, stream>>>(
+            reinterpret_cast<const float4v*>(partial), out, elems / 4, nsplit, out16);
+    } else {
+        const unsigned blocks = (unsigned)((elems + 255) / 256);
+        splitk_reduce_kernel<<<blocks, 256, 0, stream>>>(partial, out, elems, nsplit, out16);
+    }
     return hipGetLastError();
 }
 
@@ -620,6 +648,7 @@ size_t mfma_workspace_bytes(const ConvShape& s)
         // 16-bit output is offered with the library's own kernel choice only
         const MfmaKernel which = mfma_auto_kernel(s);
         if (which == MfmaKernel::Dma32) return 0;  // fp32 operands: not a 16-bit-output shape
+        if (which == MfmaKernel::Small) return igemm_small_workspace_bytes(s);
         const Plan pl = make_plan(s, which);
         return ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
     }
@@ -635,6 +664,7 @@ size_t mfma_workspace_bytes(const ConvShape& s)
         const size_t bytes = ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
         if (bytes > need) need = bytes;
     }
+    if (igemm_small_workspace_bytes(s) > need) need = igemm_small_workspace_bytes(s);
     return need;
 }
 
@@ -642,6 +672,7 @@ size_t mfma_auto_workspace_bytes(const ConvShape& s)
 {
     if (!shape_supported(s)) return 0;
     const MfmaKernel which = mfma_auto_kernel(s);
+    if (which == MfmaKernel::Small) return igemm_small_workspace_bytes(s);
     if (which == MfmaKernel::Dma32) {
         if (s.out16 != 0) return 0;
         const Dma32Plan pl = igemm32_dma_plan(s);
@@ -655,12 +686,18 @@ MfmaKernel mfma_auto_kernel(const ConvShape& s)
 {
     if (igemm32_dma_preferred(s)) return MfmaKernel::Dma32;
     if (igemm16_fast_preferred(s)) return MfmaKernel::Tuned16;
+    if (igemm_small_preferred(s)) return MfmaKernel::Small;
     return MfmaKernel::Generic;
 }
 
 bool mfma_dma32_supported(const ConvShape& s)
 {
     return shape_supported(s) && igemm32_dma_eligible(s);
+}
+
+bool mfma_small_supported(const ConvShape& s)
+{
+    return shape_supported(s) && igemm_small_eligible(s);
 }
 
 bool mfma_tuned16_supported(const ConvShape& s)
@@ -677,6 +714,9 @@ hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, f
         return hipErrorInvalidValue;
     if (which == MfmaKernel::Dma32 || (which == MfmaKernel::Auto && igemm32_dma_preferred(s)))
         return launch_dma32(s, in, kernel, out, workspace, stream);
+    if (which == MfmaKernel::Small ||
+        (which == MfmaKernel::Auto && mfma_auto_kernel(s) == MfmaKernel::Small))
+        return launch_igemm_small(s, in, kernel, out, workspace, stream);
     return launch_igemm(s, in, kernel, out, workspace, stream, which);
 }
 

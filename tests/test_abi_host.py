@@ -86,30 +86,38 @@ def test_null_and_misaligned_pointers_and_bad_path():
     # workspace checks come before any launch
     need = cc.capscaps_conv_fwd_workspace_bytes(*a)
     assert need > 0
-    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, cc.PATH_MFMA, None, 0, None) \
+    generic = cc.PATH_MFMA_GENERIC   # a forced kernel is held to the size the query reports
+    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, generic, None, 0, None) \
         == cc.EWORKSPACE
-    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, cc.PATH_MFMA, FAKE, need - 1, None) \
+    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, generic, FAKE, need - 1, None) \
         == cc.EWORKSPACE
-    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, cc.PATH_MFMA, FAKE + 4, need, None) \
+    assert cc.capscaps_conv_fwd_path(FAKE, FAKE, FAKE, *a, generic, FAKE + 4, need, None) \
         == cc.EINVAL
 
 
 def test_path_selection_and_workspace_sizes():
     for w in wl.CONFIGS:
         a = (w.N, w.H, w.W, w.C, w.M, w.kh, w.kw, w.stride, w.pad, w.D0, w.D1, w.D2, w.D3, w.dtype)
-        assert cc.capscaps_select_path(*a) in (cc.PATH_MFMA_GENERIC, cc.PATH_MFMA_TUNED16,
+        assert cc.capscaps_select_path(*a) in (cc.PATH_MFMA_SMALL, cc.PATH_MFMA_TUNED16,
                                                cc.PATH_MFMA_TUNED32)
         kernel_bytes = w.kh * w.kw * w.C * w.M * w.D0 * w.D2 * w.D3 * w.elem_bytes
         assert cc.capscaps_conv_fwd_workspace_bytes(*a) >= kernel_bytes
     # the Fig. 2 example has 3 output columns: too narrow for a matrix-core tile
     assert cc.capscaps_select_path(1, 5, 5, 1, 1, 4, 4, 1, 0, 3, 3, 3, 3, cc.FP32) == cc.PATH_DIRECT
-    # small problems take the generic kernel's small tiles; the benchmark shapes the tuned ones
+    # problems too small to fill the chip with the tuned kernels' tiles take the generic kernel's
+    # small tiles, the smallest ones the single-launch small-problem kernel
     assert cc.capscaps_select_path(*_args(M=64, D3=16, D1=16, D2=16, C=64, dtype=cc.FP16)) \
         == cc.PATH_MFMA_GENERIC
+    assert cc.capscaps_select_path(*_args(M=8, C=8, dtype=cc.FP16)) == cc.PATH_MFMA_SMALL
     picks = [cc.capscaps_select_path(w.N, w.H, w.W, w.C, w.M, w.kh, w.kw, w.stride, w.pad, w.D0,
                                      w.D1, w.D2, w.D3, w.dtype) for w in wl.CONFIGS]
-    assert picks == [cc.PATH_MFMA_GENERIC, cc.PATH_MFMA_TUNED32, cc.PATH_MFMA_TUNED16,
-                     cc.PATH_MFMA_GENERIC, cc.PATH_MFMA_TUNED16]
+    assert picks == [cc.PATH_MFMA_SMALL, cc.PATH_MFMA_TUNED32, cc.PATH_MFMA_TUNED16,
+                     cc.PATH_MFMA_SMALL, cc.PATH_MFMA_TUNED16]
+    # the small-problem kernel reads the kernel tensor in place: configuration 1 needs no scratch
+    # on the library's own choice (the size query covers every forced path)
+    w = wl.CONFIGS[0]
+    a = (w.N, w.H, w.W, w.C, w.M, w.kh, w.kw, w.stride, w.pad, w.D0, w.D1, w.D2, w.D3, w.dtype)
+    assert cc.capscaps_conv_fwd_ex(None, FAKE, FAKE, *a, None, 0, None) == cc.EINVAL
 
 
 def test_strerror():
@@ -167,6 +175,16 @@ def test_yardstick_argument_checks():
     assert cc.capscaps_mfma_yardstick(FAKE, FAKE, 5, 1, 1, None) == cc.EINVAL
     assert cc.capscaps_mfma_yardstick(FAKE, FAKE, cc.FP16, 0, 1, None) == cc.EINVAL
     assert cc.capscaps_mfma_yardstick(FAKE, FAKE, cc.FP16, 1, 0, None) == cc.EINVAL
+
+
+def test_small_problem_kernel_is_left_for_larger_problems():
+    for w in (wl.CONFIGS[1], wl.CONFIGS[2], wl.CONFIGS[4]):
+        a = (w.N, w.H, w.W, w.C, w.M, w.kh, w.kw, w.stride, w.pad, w.D0, w.D1, w.D2, w.D3, w.dtype)
+        assert cc.capscaps_select_path(*a) != cc.PATH_MFMA_SMALL
+    # 16-bit problems leave earlier than fp32 ones (the kernel computes at the fp32 rate)
+    mid = dict(N=4, H=16, W=16, C=16, M=16, D1=8, D2=8, D3=8)
+    assert cc.capscaps_select_path(*_args(**mid)) == cc.PATH_MFMA_SMALL
+    assert cc.capscaps_select_path(*_args(**mid, dtype=cc.BF16)) != cc.PATH_MFMA_SMALL
 
 
 def test_huge_window_is_refused_not_wrapped():

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 PATHS = {"direct": cc.PATH_DIRECT, "mfma": cc.PATH_MFMA, "auto": cc.PATH_AUTO,
          "generic": cc.PATH_MFMA_GENERIC, "tuned16": cc.PATH_MFMA_TUNED16,
-         "tuned32": cc.PATH_MFMA_TUNED32}
+         "tuned32": cc.PATH_MFMA_TUNED32, "small": cc.PATH_MFMA_SMALL}
 
 
 def small(name, dtype, N, H, W, C, M, kh, kw, s, p, D0, D1, D2, D3, dist="normal", seed=0):
@@ -63,7 +63,7 @@ SMALL_SHAPES = [
 
 
 @pytest.mark.parametrize("dtype", [wl.FP32, wl.BF16, wl.FP16], ids=["fp32", "bf16", "fp16"])
-@pytest.mark.parametrize("path", ["direct", "mfma", "generic"])
+@pytest.mark.parametrize("path", ["direct", "mfma", "generic", "small"])
 @pytest.mark.parametrize("shape", SMALL_SHAPES, ids=[s[0] for s in SMALL_SHAPES])
 def test_small_shapes_match_oracle(shape, path, dtype):
     w = small(shape[0], dtype, *shape[1:], seed=len(shape[0]))
@@ -205,7 +205,7 @@ def test_paper_worked_example_on_gpu(path):
 
 
 @pytest.mark.parametrize("dtype", [wl.FP32, wl.BF16, wl.FP16], ids=["fp32", "bf16", "fp16"])
-@pytest.mark.parametrize("path", ["direct", "mfma"])
+@pytest.mark.parametrize("path", ["direct", "mfma", "generic", "small"])
 def test_small_integer_inputs_are_bit_exact(path, dtype):
     """Integer inputs in [-3,3]: every partial sum is exact in fp32, so any summation order
     must give exactly the oracle's result -- sharp against tile-edge, halo and split errors."""
@@ -218,7 +218,7 @@ def test_small_integer_inputs_are_bit_exact(path, dtype):
 
 
 @pytest.mark.parametrize("num", [1, 4])
-@pytest.mark.parametrize("path", ["direct", "mfma", "auto", "generic", "tuned32"])
+@pytest.mark.parametrize("path", ["direct", "mfma", "auto", "generic", "tuned32", "small"])
 def test_benchmark_configs_full_tensor(num, path):
     full_compare(wl.config(num), PATHS[path])
 
@@ -331,9 +331,10 @@ def test_split_reduction_is_deterministic():
     w = wl.config(4)
     i_st, k_st, _, _ = wl.generate(w)
     I, K = to_device(i_st, w.dtype), to_device(k_st, w.dtype)
-    a = run_gpu(w, I, K, cc.PATH_MFMA)
-    b = run_gpu(w, I, K, cc.PATH_MFMA)
-    assert torch.equal(a, b)
+    for path in (cc.PATH_MFMA, cc.PATH_MFMA_GENERIC, cc.PATH_MFMA_SMALL):
+        a = run_gpu(w, I, K, path)
+        b = run_gpu(w, I, K, path)
+        assert torch.equal(a, b), path
 
 
 def test_plain_entry_point_allocates_its_own_scratch():
@@ -418,7 +419,7 @@ def test_workspace_too_small_is_refused_before_any_launch():
     out = torch.full(w.out_shape, 7.0, device="cuda")
     ws = torch.empty(256, dtype=torch.uint8, device="cuda")
     rc = cc.capscaps_conv_fwd_path(I.data_ptr(), K.data_ptr(), out.data_ptr(), *shape_args(w)[:13],
-                                   w.dtype, cc.PATH_MFMA, ws.data_ptr(), 256, None)
+                                   w.dtype, cc.PATH_MFMA_GENERIC, ws.data_ptr(), 256, None)
     assert rc == cc.EWORKSPACE
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
