@@ -30,6 +30,7 @@ if ROOT not in sys.path:
 # MI355X published dense peaks (TFLOP/s) and HBM bandwidth
 PEAK_TFLOPS = {"fp32": 157.3, "bf16": 2516.6, "fp16": 2516.6}
 PEAK_HBM_GBS = 8000.0
+PEAK_ALU_TFLOPS = 78.6   # fp32 FMAs on the vector ALUs without the packed forms
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs scaled by a copy kernel of known size (see profiles/); None until measured.
@@ -249,6 +250,11 @@ def main():
                              "mfma-small"])
     ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_input", "bwd_kernel", "scheme1", "scheme2",
                                                      "framework_conv", "net5"])
+    ap.add_argument("--shape", default=None,
+                    help="N,H,W,C,M,kh,kw,stride,pad,D0,D1,D2,D3: time this layer instead of a "
+                         "benchmark configuration (inputs N(0,1), kernel N(0, 1/fan-in); --dtype)")
+    ap.add_argument("--dtype", default="fp32", choices=["fp32", "bf16", "fp16"],
+                    help="element type for --shape")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (all its launches) in a HIP graph and time replays; for "
@@ -274,6 +280,15 @@ def main():
         return bench_net5(args)
     torch.cuda.set_device(0)
     w = wl.config(args.config)
+    if args.shape:
+        dims = [int(v) for v in args.shape.split(",")]
+        if len(dims) != 13:
+            sys.exit("bench.py: --shape takes 13 comma-separated integers")
+        N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3 = dims
+        dt = {"fp32": wl.FP32, "bf16": wl.BF16, "fp16": wl.FP16}[args.dtype]
+        w = wl.Workload("shape_" + args.shape.replace(",", "_"), dt, N, H, W, C, M, kh, kw, stride,
+                        pad, D0, D1, D2, D3, "normal", "normal",
+                        1.0 / float(np.sqrt(kh * kw * C * D2)), 7001, 7002)
     path = {"auto": cc.PATH_AUTO, "mfma": cc.PATH_MFMA, "direct": cc.PATH_DIRECT,
             "mfma-generic": cc.PATH_MFMA_GENERIC, "mfma-tuned16": cc.PATH_MFMA_TUNED16,
             "mfma-tuned32": cc.PATH_MFMA_TUNED32, "mfma-small": cc.PATH_MFMA_SMALL}[args.path]
@@ -401,7 +416,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": "f32" if w.dtype == wl.FP32 else
         f"{dname} in, f32 accumulate", "data": "synthetic",
         "config": {
-            "workload": f"config {args.config}: {w.name}", "op": args.op,
+            "workload": w.name if args.shape else f"config {args.config}: {w.name}", "op": args.op,
             "launch": "hip graph replay" if args.graph else "eager", "N": w.N, "H": w.H, "W": w.W, "C": w.C,
             "M": w.M, "kh": w.kh, "kw": w.kw, "stride": w.stride, "pad": w.pad,
             "capsule": [w.D0, w.D1, w.D2, w.D3],
@@ -416,9 +431,16 @@ def main():
             "ms_median": round(float(np.median(per_step_ms)), 4),
         },
         "roofline": {
-            "bound": "mfma", "achieved": round(achieved_tflops, 2), "peak": PEAK_TFLOPS[dname],
-            "unit": "TFLOP/s", "frac": round(achieved_tflops / PEAK_TFLOPS[dname], 4),
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config) if args.op == "fwd" else None,
+            # the wavefront-level path is plain fp32 FMAs on the vector ALUs: 256 CUs x 4 SIMDs x
+            # 16 lanes x 2 FLOP x 2.4 GHz (packed-fp32 forms are not used)
+            "bound": "alu" if chosen == cc.PATH_DIRECT and args.op == "fwd" else "mfma",
+            "achieved": round(achieved_tflops, 2),
+            "peak": PEAK_ALU_TFLOPS if chosen == cc.PATH_DIRECT and args.op == "fwd" else PEAK_TFLOPS[dname],
+            "unit": "TFLOP/s",
+            "frac": round(achieved_tflops / (PEAK_ALU_TFLOPS if chosen == cc.PATH_DIRECT and
+                                             args.op == "fwd" else PEAK_TFLOPS[dname]), 4),
+            "traffic": (MEASURED_TRAFFIC_BYTES.get(args.config)
+                        if args.op == "fwd" and not args.shape else None),
             "kernel_ms": round(kernel_ms, 4),
         },
     }

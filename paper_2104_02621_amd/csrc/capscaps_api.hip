@@ -43,15 +43,28 @@ int fill_shape(ConvShape& s, int N, int H, int W, int C, int M, int kh, int kw, 
     return CAPSCAPS_OK;
 }
 
-// The matrix-core path pays off once the (m,d3) extent fills a good part of a 32-wide MFMA
-// tile and there is enough work to amortise the kernel repack; below that the wavefront-level
-// path wins (measured on MI355X on the five benchmark shapes and the Fig. 2 example).
+// Measured on MI355X (fp32 and bf16 layers with 3 .. 32 output columns (m, d3) and K from 4 to
+// 288, the worked example of Fig. 2 among them): with 16-column tiles the matrix cores win even
+// at 4 columns (12 of 16 columns of every tile are padding there, and they still finish first:
+// the wavefront-level path spends more instructions staging an input value in LDS than
+// multiplying it when few output columns use it).  The wavefront-level path wins
+//   * where the contraction is so short (K up to 16 measured: a 1x1 or 2x2 window over one
+//     channel of 4-element capsule rows) that a matrix-core tile's 64-value K slab is mostly
+//     padding, and
+//   * on layers of at most 8 output columns whose capsule rows are not multiples of 4 elements
+//     (Fig. 2's 3x3x3 capsules: the matrix-core kernel then gathers element by element), once
+//     the layer is large enough for throughput to count (a tiny one is latency-bound, and the
+//     single-stage matrix-core kernel has the shorter latency);
+// it also serves what the matrix-core path cannot address.
 int choose_path(const ConvShape& s)
 {
     if (!capscaps::mfma_supported(s)) return CAPSCAPS_PATH_DIRECT;
-    const long long cols = (long long)s.M * s.D3;
     const long long kdim = (long long)s.kh * s.kw * s.C * s.D2;
-    if (cols < 16 || kdim < 32) return CAPSCAPS_PATH_DIRECT;
+    const long long cols = (long long)s.M * s.D3;
+    if (kdim <= 24) return CAPSCAPS_PATH_DIRECT;
+    const double flops = 2.0 * (double)s.out_elems() * (double)kdim;
+    if (cols <= 8 && (s.D2 % 4 != 0 || s.D3 % 4 != 0) && flops >= 5e7 && capscaps::wave_conv_eligible(s))
+        return CAPSCAPS_PATH_DIRECT;
     switch (capscaps::mfma_auto_kernel(s)) {
         case capscaps::MfmaKernel::Tuned16: return CAPSCAPS_PATH_MFMA_TUNED16;
         case capscaps::MfmaKernel::Dma32: return CAPSCAPS_PATH_MFMA_TUNED32;

@@ -62,8 +62,13 @@ struct ConvShape {
 
 // Wavefront-level small-matrix path: plain FMAs, any shape, any dtype.  No scratch.
 // (`out` points to fp32 or, with s.out16, to 16-bit elements; likewise for launch_mfma)
+// launch_direct takes the LDS-staged wave kernel (wave_conv.hip) where it can stage the shape,
+// else a thread-per-element kernel.
 hipError_t launch_direct(const ConvShape& s, const void* in, const void* kernel, float* out,
                          hipStream_t stream);
+bool wave_conv_eligible(const ConvShape& s);
+hipError_t launch_wave_conv(const ConvShape& s, const void* in, const void* kernel, float* out,
+                            hipStream_t stream);
 
 // Matrix-core path (LDS-staged implicit GEMM).  `mfma_supported` tells whether the path can
 // run the shape; `mfma_workspace_bytes` is the scratch it needs (repacked kernel plus, for

@@ -1,9 +1,8 @@
-// Wavefront-level small-matrix path of the capsule convolution forward pass
-// (paper Algorithm 2): every thread owns one output element O[n,x,y,m,d0,d1,d3] and walks the
-// window taps, the input channels and the contracted capsule index d2 with plain fp32 FMAs.
-// Lanes of a wavefront cover consecutive d3 (then d1, d0, m), so kernel-capsule reads are
-// contiguous across lanes and input-capsule reads are broadcasts.  It runs any shape and any
-// element type; it is the path for shapes whose (m,d3) extent cannot fill a matrix-core tile.
+// Last-resort kernel of the capsule convolution forward pass (paper Algorithm 2): every thread
+// owns one output element O[n,x,y,m,d0,d1,d3] and walks the window taps, the input channels and
+// the contracted capsule index d2 with plain fp32 FMAs, reading global memory directly.  It runs
+// any shape and any element type and serves what the wavefront-level path (wave_conv.hip) cannot
+// stage in LDS (capsules of more than 64 row x column-quad pieces, windows too wide for LDS).
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
 
@@ -73,6 +72,7 @@ __global__ __launch_bounds__(256) void direct_conv_kernel(const T* __restrict__ 
 hipError_t launch_direct(const ConvShape& s, const void* in, const void* kernel, float* out,
                          hipStream_t stream)
 {
+    if (wave_conv_eligible(s)) return launch_wave_conv(s, in, kernel, out, stream);
     const size_t total = s.out_elems();
     const size_t blocks = (total + 255) / 256;
     if (blocks > 0x7fffffffULL) return hipErrorInvalidValue;

@@ -102,8 +102,14 @@ def test_path_selection_and_workspace_sizes():
                                                cc.PATH_MFMA_TUNED32)
         kernel_bytes = w.kh * w.kw * w.C * w.M * w.D0 * w.D2 * w.D3 * w.elem_bytes
         assert cc.capscaps_conv_fwd_workspace_bytes(*a) >= kernel_bytes
-    # the Fig. 2 example has 3 output columns: too narrow for a matrix-core tile
-    assert cc.capscaps_select_path(1, 5, 5, 1, 1, 4, 4, 1, 0, 3, 3, 3, 3, cc.FP32) == cc.PATH_DIRECT
+    # the Fig. 2 example has 3 output columns and K = 48: measured, 16-column matrix-core tiles
+    # still finish before the wavefront-level path; that path takes contractions of up to 24 values
+    assert cc.capscaps_select_path(1, 5, 5, 1, 1, 4, 4, 1, 0, 3, 3, 3, 3, cc.FP32) == cc.PATH_MFMA_SMALL
+    # ... the same layer on 256 images of 20x20: throughput counts, 3-element rows: wavefront-level
+    assert cc.capscaps_select_path(256, 20, 20, 1, 1, 4, 4, 1, 0, 3, 3, 3, 3, cc.FP32) == cc.PATH_DIRECT
+    assert cc.capscaps_select_path(256, 20, 20, 2, 4, 4, 4, 1, 0, 3, 3, 3, 3, cc.FP32) != cc.PATH_DIRECT
+    assert cc.capscaps_select_path(64, 32, 32, 1, 8, 2, 2, 1, 0, 1, 4, 4, 4, cc.FP32) == cc.PATH_DIRECT
+    assert cc.capscaps_select_path(2, 6, 6, 5, 7, 1, 1, 1, 0, 1, 1, 1, 1, cc.FP32) == cc.PATH_DIRECT
     # problems too small to fill the chip with the tuned kernels' tiles take the generic kernel's
     # small tiles, the smallest ones the single-launch small-problem kernel
     assert cc.capscaps_select_path(*_args(M=64, D3=16, D1=16, D2=16, C=64, dtype=cc.FP16)) \
