@@ -32,14 +32,95 @@ PEAK_TFLOPS = {"fp32": 157.3, "bf16": 2516.6, "fp16": 2516.6}
 PEAK_HBM_GBS = 8000.0
 PEAK_ALU_TFLOPS = 78.6   # fp32 FMAs on the vector ALUs without the packed forms
 
-# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs scaled by a copy kernel of known size (see profiles/); None until measured.
-MEASURED_TRAFFIC_BYTES = {
-    # profiles/hbm_traffic_configs_2_3_5.txt: (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000) KiB
-    5: int((8270338 * 2.0 + 4295766) * 1024),
-    3: int((521525 * 2.0 + 458752) * 1024),
-    2: int((150600 * 2.0 + 290010) * 1024),
+# HBM-side bytes per launch of the dominant kernel come from profiles/hbm_traffic.json: rocprofv3
+# --pmc FETCH_SIZE / WRITE_SIZE readings, scaled by a plain device copy of known size in the same
+# process, recorded together with hashes of the kernel sources they were taken with.  A reading
+# whose sources have changed since is not reported (null).
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+KERNEL_SOURCES = {  # what the dominant kernel of each benchmark configuration is built from
+    1: ["igemm_small.hip", "igemm_common.h", "conv_shape.h"],
+    2: ["igemm32_dma.hip", "igemm_conv.hip", "igemm_common.h", "lds_dma.h", "conv_shape.h"],
+    3: ["igemm16_fast.hip", "igemm_conv.hip", "igemm_common.h", "lds_dma.h", "conv_shape.h"],
+    4: ["igemm_small.hip", "igemm_common.h", "conv_shape.h"],
+    5: ["igemm16_fast.hip", "igemm_conv.hip", "igemm_common.h", "lds_dma.h", "conv_shape.h"],
 }
+
+
+def source_hashes(config):
+    import hashlib
+    csrc = os.path.join(ROOT, "paper_2104_02621_amd", "csrc")
+    return {name: hashlib.sha256(open(os.path.join(csrc, name), "rb").read()).hexdigest()[:16]
+            for name in KERNEL_SOURCES[config]}
+
+
+def measured_traffic_bytes(config):
+    """Bytes past the L2s per launch of the configuration's dominant kernel, or None when no
+    reading exists for the kernel sources as they are now."""
+    try:
+        entries = json.load(open(TRAFFIC_FILE))["entries"]
+    except (OSError, ValueError, KeyError):
+        return None
+    for e in entries:
+        if e.get("config") == config and e.get("sources") == source_hashes(config):
+            return int((e["fetch_kib"] * e["fetch_scale"] + e["write_kib"] * e["write_scale"]) * 1024)
+    return None
+
+
+def record_traffic(config, fetch_dir, write_dir):
+    """Reads the counter_collection.csv files of two rocprofv3 --pmc runs of
+    `bench.py --config N --copy-probe` (FETCH_SIZE in one, WRITE_SIZE in the other) and writes
+    the configuration's entry of profiles/hbm_traffic.json."""
+    import csv
+    import glob
+    import subprocess
+
+    def read(directory, counter):
+        files = glob.glob(os.path.join(directory, "**", "*counter_collection.csv"), recursive=True)
+        if not files:
+            sys.exit(f"bench.py: no counter_collection.csv under {directory}")
+        per_kernel = {}
+        for row in csv.DictReader(open(files[0])):
+            if row["Counter_Name"] == counter:
+                per_kernel.setdefault(row["Kernel_Name"], []).append(float(row["Counter_Value"]))
+        copies = [v for k, vs in per_kernel.items() if "copyBuffer" in k for v in vs]
+        ours = {k: sum(vs) / len(vs) for k, vs in per_kernel.items() if "capscaps" in k}
+        if not copies or not ours:
+            sys.exit(f"bench.py: {directory} holds no copy kernel or no capscaps kernel")
+        return max(copies), ours
+
+    fetch_copy, fetch = read(fetch_dir, "FETCH_SIZE")
+    write_copy, write = read(write_dir, "WRITE_SIZE")
+    kernel = max(fetch, key=lambda k: fetch[k] + write.get(k, 0.0))
+    # --copy-probe copies 1 GiB; the runtime may cut it into equal dispatches, so the largest
+    # dispatch's WRITE_SIZE tells its size, and FETCH_SIZE of the same dispatch reads that size
+    probe_kib = float(1 << 20)
+    pieces = max(1, round(probe_kib / write_copy))
+    entry = {
+        "config": config, "kernel": kernel.split("(")[0][-60:],
+        "fetch_kib": round(fetch[kernel], 1), "write_kib": round(write.get(kernel, 0.0), 1),
+        "fetch_scale": round(probe_kib / pieces / fetch_copy, 4),
+        "write_scale": round(probe_kib / pieces / write_copy, 4),
+        "sources": source_hashes(config),
+        "command": (f"rocprofv3 --pmc FETCH_SIZE|WRITE_SIZE --output-format csv -d <dir> -o r -- python3 "
+                    f"bench.py --config {config} --steps 3 --warmup 1 --no-cpu-baseline --no-yardstick "
+                    f"--copy-probe; python3 bench.py --config {config} --record-traffic <fetch dir> <write dir>"),
+    }
+    try:
+        entry["commit"] = subprocess.run(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"],
+                                         capture_output=True, text=True).stdout.strip() or None
+    except OSError:
+        entry["commit"] = None
+    try:
+        data = json.load(open(TRAFFIC_FILE))
+    except (OSError, ValueError):
+        data = {"what": "HBM-side bytes per launch of each configuration's dominant kernel "
+                        "(rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, KiB per dispatch, scaled by a "
+                        "1 GiB device copy in the same process); read by bench.py",
+                "entries": []}
+    data["entries"] = [e for e in data["entries"] if e.get("config") != config] + [entry]
+    data["entries"].sort(key=lambda e: e["config"])
+    json.dump(data, open(TRAFFIC_FILE, "w"), indent=1)
+    print(json.dumps(entry))
 
 
 def cpu_baseline(w, i32, k32, gpu_out, target_seconds=15.0):
@@ -255,6 +336,10 @@ def main():
                          "benchmark configuration (inputs N(0,1), kernel N(0, 1/fan-in); --dtype)")
     ap.add_argument("--dtype", default="fp32", choices=["fp32", "bf16", "fp16"],
                     help="element type for --shape")
+    ap.add_argument("--record-traffic", nargs=2, metavar=("FETCH_DIR", "WRITE_DIR"), default=None,
+                    help="no GPU work: read two rocprofv3 --pmc outputs (FETCH_SIZE, WRITE_SIZE) of "
+                         "`bench.py --config N --copy-probe` and write N's entry of "
+                         "profiles/hbm_traffic.json")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step (all its launches) in a HIP graph and time replays; for "
@@ -268,6 +353,9 @@ def main():
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build measures the capsule convolution on ONE GPU only "
                  "(the forward pass shards over the batch with no exchange step); run with --gpus 1")
+
+    if args.record_traffic:
+        return record_traffic(args.config, *args.record_traffic)
 
     import numpy as np
     import torch
@@ -439,8 +527,8 @@ def main():
             "unit": "TFLOP/s",
             "frac": round(achieved_tflops / (PEAK_ALU_TFLOPS if chosen == cc.PATH_DIRECT and
                                              args.op == "fwd" else PEAK_TFLOPS[dname]), 4),
-            "traffic": (MEASURED_TRAFFIC_BYTES.get(args.config)
-                        if args.op == "fwd" and not args.shape else None),
+            "traffic": (measured_traffic_bytes(args.config)
+                        if args.op == "fwd" and not args.shape and args.path == "auto" else None),
             "kernel_ms": round(kernel_ms, 4),
         },
     }

@@ -237,21 +237,42 @@ def test_benchmark_configs_reduced_full_tensor(num, batch, hw, path):
     full_compare(w, PATHS[path])
 
 
-@pytest.mark.parametrize("num,count", [(2, 20000), (3, 6000), (5, 2500)])
-def test_benchmark_configs_full_size_sampled(num, count):
-    """Configs 2, 3, 5 at full size, in the launch configuration the bench times: sampled
-    output capsules (a quarter of them on image borders) against the oracle, and the whole
-    tensor checked for finiteness."""
+@functools.lru_cache(maxsize=1)
+def full_size_run(num):
+    """A benchmark configuration at full size in the launch configuration the bench times: its
+    fp32 inputs and the GPU's output (kept on the device), shared by the checks below."""
+    import torch
     w = wl.config(num)
     i_st, k_st, i32, k32 = wl.generate(w)
-    which = wl.sample_capsules(w, count, seed=77 + num)
-    ref, S = capsconv.conv_fwd_subset(i32, k32, which, w.stride, w.pad, with_abs_sum=True)
     out = run_gpu(w, to_device(i_st, w.dtype), to_device(k_st, w.dtype), cc.PATH_AUTO)
+    torch.cuda.synchronize()
+    return w, i32, k32, out
+
+
+# (configuration, part): 12000 / 12000 / 10000 sampled output capsules (a quarter of them on
+# image borders) plus finiteness of the whole tensor; for the two 16-bit configurations also the
+# first and the last image whole -- every border, tile edge and tile tail of an image, and the
+# last tiles of the launch
+FULL_SIZE_PARTS = [(2, "sampled"), (3, "sampled"), (3, "first image"), (3, "last image"),
+                   (5, "sampled"), (5, "first image"), (5, "last image")]
+
+
+@pytest.mark.parametrize("num,part", FULL_SIZE_PARTS,
+                         ids=[f"config{n}-{p.replace(' ', '-')}" for n, p in FULL_SIZE_PARTS])
+def test_benchmark_configs_full_size(num, part):
     import torch
-    assert bool(torch.isfinite(out).all())
-    idx = torch.from_numpy(which.astype(np.int64)).cuda()
-    got = out[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
-    check(w, got, ref, S, "sampled")
+    w, i32, k32, out = full_size_run(num)
+    if part == "sampled":
+        assert bool(torch.isfinite(out).all())
+        which = wl.sample_capsules(w, {2: 12000, 3: 12000, 5: 10000}[num], seed=77 + num)
+        ref, S = capsconv.conv_fwd_subset(i32, k32, which, w.stride, w.pad, with_abs_sum=True)
+        idx = torch.from_numpy(which.astype(np.int64)).cuda()
+        got = out[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].cpu().numpy()
+        check(w, got, ref, S, "sampled")
+        return
+    n = 0 if part == "first image" else w.N - 1
+    ref, S = capsconv.conv_fwd(i32[n:n + 1], k32, w.stride, w.pad, with_abs_sum=True)
+    check(w, out[n:n + 1].cpu().numpy(), ref, S, part)
 
 
 @pytest.mark.parametrize("num", [3, 5])
