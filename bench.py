@@ -96,7 +96,9 @@ def record_traffic(config, fetch_dir, write_dir):
     probe_kib = float(1 << 20)
     pieces = max(1, round(probe_kib / write_copy))
     entry = {
-        "config": config, "kernel": kernel.split("(")[0][-60:],
+        "config": config,
+        "kernel": kernel.replace("(anonymous namespace)::", "").replace("capscaps::", "")
+                        .replace("void ", "").split("(")[0][:80],
         "fetch_kib": round(fetch[kernel], 1), "write_kib": round(write.get(kernel, 0.0), 1),
         "fetch_scale": round(probe_kib / pieces / fetch_copy, 4),
         "write_scale": round(probe_kib / pieces / write_copy, 4),

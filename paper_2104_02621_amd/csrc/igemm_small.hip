@@ -551,7 +551,11 @@ bool igemm_small_preferred(const ConvShape& s)
     // convolution and fully-connected shapes: fp32 problems win up to about 2.4e9 nominal FLOPs
     // and tie at 1e10; 16-bit problems win up to 3e8 -- up to 1.2e9 when the capsule rows are
     // shorter than the 8 elements that kernel moves in one piece.
+    // A layer of very many tiles with a short K loop each (the fully-connected layer's input
+    // gradient: a 1x1 convolution with 4608 output columns and K = 40) pays this kernel's fixed
+    // cost per tile too often: measured 40 us against 29 us.
     const double flops = 2.0 * (double)s.out_elems() * s.kh * s.kw * s.C * s.D2;
+    if (small_plan(s).blocks > 1024) return false;
     return flops <= (s.dtype == 0 ? 4e9 : s.D2 % 8 == 0 ? 4e8 : 1.5e9);
 }
 
