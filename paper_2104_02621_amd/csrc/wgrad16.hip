@@ -27,6 +27,20 @@
 // LDS stage: [side: It rows, Gt columns][chunk 0..3][row 0..255][16 bytes]; chunk kc holds d1
 // values (kc % (D1/8))*8 .. +7 of pixel kc / (D1/8) of the stage.  Operand reads are 512
 // contiguous bytes per 32 lanes.
+//
+// When D2 and D3 are multiples of 8 there is no pre-pass (template flag OWN): the two tensors
+// are copied to LDS as they lie in memory, a 16-byte chunk being 8 consecutive rows (c, d2) of
+// one (pixel, d1) line, and the matrix instruction's operands are gathered by the transposing
+// LDS read ds_read_b64_tr_b16: of a 16-lane group, lane 4a + b supplies the address of 4 rows
+// (b) of one line (a), and lane i receives row i's values from the four lines.  A stage then
+// holds 32 lines of 256 rows.  One copy instruction brings a unit of 8 lines x 64 rows (for
+// 8-row capsules: 8 whole capsules of 128 contiguous bytes; for 16-row ones: 4 half capsules of
+// 256 contiguous bytes), consecutive lanes taking consecutive memory; LDS per side is
+// [line / 8][row / 64][the unit's 64 chunks in lane order].  Within a unit the line index of
+// every other pair of chunk columns is XORed with 4, which makes the 16 chunks a half-wave
+// reads (4 lines x 32 rows) fall into 16 different 16-byte columns of the 64 banks.  Which
+// (pixel, d1) pair sits in which of an instruction's 16 contraction slots is the same on both
+// sides, which is all the contraction needs.
 #include <hip/hip_runtime.h>
 
 #include "igemm_common.h"
@@ -78,7 +92,10 @@ __global__ __launch_bounds__(256) void transpose_caps_kernel(const chunk_t* __re
     dst[base + t] = out;
 }
 
-template <typename Tag, int D1>
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) short4v lds_short4v;
+
+template <typename Tag, int D1, bool OWN>
 __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
 {
     constexpr int KCH = 4, NB = 4;
@@ -159,14 +176,33 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     const rsrc_t rs_it = make_rsrc(it_base, (unsigned)((n1 - n0) * P.it_img_bytes));
     const rsrc_t rs_gt = make_rsrc(gt_base, (unsigned)((n1 - n0) * P.gt_img_bytes));
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
-    // this wave copies rows (and columns) wave*64 .. +63 of the tile, all chunks
+    // this wave copies rows (and columns) wave*64 .. +63 of the tile, all chunks (OWN: copy kc
+    // brings lines 8*kc .. +7 of those rows)
     const unsigned lds_a = __builtin_amdgcn_readfirstlane((int)(lds0 + wave * 1024));
     const unsigned lds_b = lds_a + SIDE_BYTES;
 
     // ---- per-lane constants: byte offset of the lane's row (column) within a pixel, or the
     // out-of-range mark for rows (columns) past the end: those copy zeros
     unsigned a_voff, b_voff;
-    {
+    // OWN: place of chunk (line l8, chunk column r8) in its unit, and back.  `wide`: two chunk
+    // columns per capsule row (capsule width a multiple of 16), else one.
+    auto unit_slot = [](bool wide, int l8, int r8) {
+        const int l = l8 ^ (((r8 >> 1) & 1) * 4);
+        return wide ? (r8 >> 1) * 16 + l * 2 + (r8 & 1) : r8 * 8 + l;
+    };
+    const bool a_wide = P.D2 % 16 == 0, b_wide = P.D3 % 16 == 0;
+    if constexpr (OWN) {
+        const int ra = a_wide ? (lane >> 4) * 2 + (lane & 1) : lane >> 3;
+        const int la = (a_wide ? (lane & 15) >> 1 : lane & 7) ^ (((ra >> 1) & 1) * 4);
+        const int R = row_tile * BM + (wave * 8 + ra) * 8;
+        const int c = R / P.D2, d2 = R - c * P.D2;
+        a_voff = R < P.rows ? (unsigned)(((((c * P.D0 + d0) * D1 + la) * P.D2) + d2) * 2) : (unsigned)OOB;
+        const int rb = b_wide ? (lane >> 4) * 2 + (lane & 1) : lane >> 3;
+        const int lb = (b_wide ? (lane & 15) >> 1 : lane & 7) ^ (((rb >> 1) & 1) * 4);
+        const int J = col_tile * BN + (wave * 8 + rb) * 8;
+        const int m = J / P.D3, d3 = J - m * P.D3;
+        b_voff = J < P.cols ? (unsigned)(((((m * P.D0 + d0) * D1 + lb) * P.D3) + d3) * 2) : (unsigned)OOB;
+    } else {
         const int R = row_tile * BM + wave * 64 + lane;
         const int c = R / P.D2, d2 = R - c * P.D2;
         a_voff = R < P.rows ? (unsigned)((((c * P.D0 + d0) * P.D2 + d2) * D1) * 2) : (unsigned)OOB;
@@ -174,8 +210,25 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
         const int m = J / P.D3, d3 = J - m * P.D3;
         b_voff = J < P.cols ? (unsigned)((((m * P.D0 + d0) * P.D3 + d3) * D1) * 2) : (unsigned)OOB;
     }
-    const unsigned a_rd = (unsigned)((h * BM + wm * WM + lr) * 16);
-    const unsigned b_rd = (unsigned)(SIDE_BYTES + (h * BN + wn * WN + lr) * 16);
+    // Operand reads.  OWN: lane (h, lr) supplies, for the line group j = 0, 1 of its half h, the
+    // address of line (lr % 16) / 4 of that group, rows 16*(lr / 16) + 4*(lr % 4) .. +3 of a
+    // 32-row block; the block's place in the stage is added at the read.
+    unsigned a_rd[2], b_rd[2];
+    if constexpr (OWN) {
+        const int g16 = lr >> 4, li = (lr & 15) >> 2, quad = lr & 3;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int l8 = j * 4 + li, r8 = 2 * g16 + (quad >> 1);
+            a_rd[j] = (unsigned)(h * 4096 + wm * 2048 + unit_slot(a_wide, l8, r8) * 16 + (quad & 1) * 8);
+            b_rd[j] = (unsigned)(SIDE_BYTES + h * 4096 + wn * 2048 + unit_slot(b_wide, l8, r8) * 16 +
+                                 (quad & 1) * 8);
+        }
+    } else {
+        a_rd[0] = a_rd[1] = (unsigned)((h * BM + wm * WM + lr) * 16);
+        b_rd[0] = b_rd[1] = (unsigned)(SIDE_BYTES + (h * BN + wn * WN + lr) * 16);
+    }
+    // byte distance of 8 lines (the second half of a 16-row capsule) in either tensor
+    const int a_half = OWN ? 16 * P.D2 : 16, b_half = OWN ? 16 * P.D3 : 16;
 
     float16v acc[TN][TM];
 #pragma unroll
@@ -243,19 +296,28 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     auto copy_a = [&](auto SLOT, auto KC) {
         constexpr int slot = decltype(SLOT)::value, kc = decltype(KC)::value;
         copy_to_lds_16B<slot * STAGE_BYTES + kc * BM * 16>(rs_it, lds_a, a_voff, a_soff[kc / D1C],
-                                                           (kc % D1C) * 16);
+                                                           (kc % D1C) * a_half);
     };
     auto copy_b = [&](auto SLOT, auto KC) {
         constexpr int slot = decltype(SLOT)::value, kc = decltype(KC)::value;
         copy_to_lds_16B<slot * STAGE_BYTES + kc * BN * 16>(rs_gt, lds_b, b_voff, g_soff[kc / D1C],
-                                                           (kc % D1C) * 16);
+                                                           (kc % D1C) * b_half);
     };
     // operand fragment f of k-step t from ring slot: f < TN column side (Gt), else row side (It)
     auto read_frag = [&](int slot, int t, int f) -> chunk_t {
         const char* stage = smem + slot * STAGE_BYTES;
+        if constexpr (OWN) {
+            // lines 16t + 8h .. +7 of 32-row block f: two transposing reads of four lines each
+            const int ff = f < TN ? f : f - TN;
+            const char* p = stage + t * 8192 + (ff / 2) * 1024 + (ff % 2) * 512;
+            struct { short4v lo, hi; } v;
+            v.lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4v*)(p + (f < TN ? b_rd[0] : a_rd[0])));
+            v.hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_short4v*)(p + (f < TN ? b_rd[1] : a_rd[1])));
+            return __builtin_bit_cast(chunk_t, v);
+        }
         if (f < TN)
-            return *reinterpret_cast<const chunk_t*>(stage + b_rd + (2 * t * BN + f * 32) * 16);
-        return *reinterpret_cast<const chunk_t*>(stage + a_rd + (2 * t * BM + (f - TN) * 32) * 16);
+            return *reinterpret_cast<const chunk_t*>(stage + b_rd[0] + (2 * t * BN + f * 32) * 16);
+        return *reinterpret_cast<const chunk_t*>(stage + a_rd[0] + (2 * t * BM + (f - TN) * 32) * 16);
     };
 
     // An MFMA has no side effect the compiler must order, so by itself it may drift away from
@@ -436,10 +498,10 @@ hipError_t launch_transpose(const void* src, void* dst, size_t nmat, int A, int 
     return hipGetLastError();
 }
 
-template <typename Tag, int D1>
+template <typename Tag, int D1, bool OWN>
 hipError_t launch_kernel(const WgradParams& P, hipStream_t stream)
 {
-    auto kern = wgrad16_kernel<Tag, D1>;
+    auto kern = wgrad16_kernel<Tag, D1, OWN>;
     const size_t lds_bytes = (size_t)4 * 2 * 4 * 256 * 16;  // ring of 4 stages of 32 KB
     static std::atomic<unsigned long long> lds_set{0};
     hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes, lds_set);
@@ -468,9 +530,14 @@ bool wgrad16_eligible(const ConvShape& s)
     return true;
 }
 
+// Both tensors can be read as they lie in memory when 8 consecutive rows (c, d2) and columns
+// (m, d3) of a line are one aligned 16-byte chunk.
+static bool reads_in_place(const ConvShape& s) { return s.D2 % 8 == 0 && s.D3 % 8 == 0; }
+
 size_t wgrad16_workspace_bytes(const ConvShape& s)
 {
     const WgradPlan pl = make_plan(s);
+    if (reads_in_place(s)) return pl.partial_bytes;
     return align256(pl.it_bytes) + align256(pl.gt_bytes) + pl.partial_bytes;
 }
 
@@ -479,23 +546,40 @@ hipError_t launch_wgrad16(const ConvShape& s, const void* input, const void* dou
 {
     WgradPlan pl = make_plan(s);
     char* ws = static_cast<char*>(workspace);
-    void* it = ws;
-    void* gt = ws + align256(pl.it_bytes);
-    float* partial = reinterpret_cast<float*>(ws + align256(pl.it_bytes) + align256(pl.gt_bytes));
-    hipError_t err = launch_transpose(input, it, (size_t)s.N * s.H * s.W * s.C * s.D0, s.D1, s.D2,
-                                      stream);
-    if (err != hipSuccess) return err;
-    err = launch_transpose(dout, gt, (size_t)s.N * s.Ho * s.Wo * s.M * s.D0, s.D1, s.D3, stream);
-    if (err != hipSuccess) return err;
-    pl.P.it = it;
-    pl.P.gt = gt;
+    const bool own = reads_in_place(s);
+    float* partial;
+    hipError_t err = hipSuccess;
+    if (own) {
+        pl.P.it = input;
+        pl.P.gt = dout;
+        partial = reinterpret_cast<float*>(ws);
+    } else {
+        void* it = ws;
+        void* gt = ws + align256(pl.it_bytes);
+        partial = reinterpret_cast<float*>(ws + align256(pl.it_bytes) + align256(pl.gt_bytes));
+        err = launch_transpose(input, it, (size_t)s.N * s.H * s.W * s.C * s.D0, s.D1, s.D2, stream);
+        if (err != hipSuccess) return err;
+        err = launch_transpose(dout, gt, (size_t)s.N * s.Ho * s.Wo * s.M * s.D0, s.D1, s.D3, stream);
+        if (err != hipSuccess) return err;
+        pl.P.it = it;
+        pl.P.gt = gt;
+    }
     pl.P.out = pl.P.nsplit > 1 ? partial : dkernel;
-    if (s.dtype == 2)
-        err = s.D1 == 16 ? launch_kernel<f16_tag, 16>(pl.P, stream)
-                         : launch_kernel<f16_tag, 8>(pl.P, stream);
-    else
-        err = s.D1 == 16 ? launch_kernel<bf16_tag, 16>(pl.P, stream)
-                         : launch_kernel<bf16_tag, 8>(pl.P, stream);
+    if (s.dtype == 2) {
+        if (own)
+            err = s.D1 == 16 ? launch_kernel<f16_tag, 16, true>(pl.P, stream)
+                             : launch_kernel<f16_tag, 8, true>(pl.P, stream);
+        else
+            err = s.D1 == 16 ? launch_kernel<f16_tag, 16, false>(pl.P, stream)
+                             : launch_kernel<f16_tag, 8, false>(pl.P, stream);
+    } else {
+        if (own)
+            err = s.D1 == 16 ? launch_kernel<bf16_tag, 16, true>(pl.P, stream)
+                             : launch_kernel<bf16_tag, 8, true>(pl.P, stream);
+        else
+            err = s.D1 == 16 ? launch_kernel<bf16_tag, 16, false>(pl.P, stream)
+                             : launch_kernel<bf16_tag, 8, false>(pl.P, stream);
+    }
     if (err != hipSuccess) return err;
     if (pl.P.nsplit > 1)
         err = launch_splitk_reduce(partial, dkernel, pl.P.out_elems, pl.P.nsplit, stream);

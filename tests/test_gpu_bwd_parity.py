@@ -85,6 +85,10 @@ BWD_SHAPES = SMALL_SHAPES + [
     ("wg_empty", 2, 1, 1, 3, 2, 5, 5, 1, 2, 1, 8, 4, 4),
     ("wg_d16s3", 2, 10, 9, 20, 18, 3, 3, 3, 1, 1, 16, 16, 16),
     ("wg_many", 70, 5, 5, 4, 4, 2, 2, 1, 0, 1, 16, 8, 8),
+    # capsule widths that are multiples of 8 are read in place (no transposed copies): ragged
+    # row and column tiles with a leading capsule index, and widths of 24 and 8 under 16 rows
+    ("wg_own_rag", 3, 7, 6, 37, 35, 3, 3, 2, 1, 2, 8, 8, 16),
+    ("wg_own_d24", 2, 5, 6, 3, 5, 2, 3, 1, 1, 1, 16, 24, 8),
     # for the fp32 kernel-gradient kernel: capsule heights of 6 and 12 floats (two and four
     # chunks of 3), several row and column tiles with ragged ends
     ("wg32_d6", 2, 6, 6, 3, 5, 3, 3, 1, 1, 2, 6, 4, 3),
