@@ -15,9 +15,10 @@
 //        same padding; the result [C][kh][kw][M][D0][D2][D3] is permuted into the kernel layout.
 // A stride s > 1 splits dI into s*s phases, the pixels with equal ((h+pad) mod s, (w+pad) mod s):
 // phase (a,b) is a stride-1 convolution of G with the window taps p = a, a+s, ..., q = b, b+s, ...
-// (flipped), whose output pixels lie s apart in dI.  For 16-bit capsules the tuned forward kernel
-// runs each phase with its own row and column padding and writes through an output stride: no
-// multiplication by zeros.  Otherwise the output gradient is spread out: G is copied into a zero
+// (flipped), whose output pixels lie s apart in dI.  Where every phase fits a tuned forward
+// kernel (16-bit, or fp32 with enough rows for its four-wave tiles) that kernel runs each phase
+// with its own row and column padding and writes through an output stride: no multiplication
+// by zeros.  Otherwise the output gradient is spread out: G is copied into a zero
 // buffer of the stride-1 output extent (H+2*pad-kh+1 rows), pixel (x,y) at (x*s, y*s).  The
 // contraction then runs over s*s times the needed terms (the zeros), but on the matrix cores.
 // The fully-connected layer's dI (one output pixel, window = image) is a 1x1 convolution whose
@@ -198,7 +199,7 @@ PhaseDim phase_dim(int extent, int k, int s, int pad, int a)
     d.count = hi - d.lo + 1 > 0 ? hi - d.lo + 1 : 0;
     return d;
 }
-// phase (a,b) as a forward convolution for the tuned 16-bit kernel
+// phase (a,b) as a forward convolution for the tuned kernels (16-bit or fp32)
 ConvShape bwd_input_phase_shape(const ConvShape& s, const PhaseDim& ph, const PhaseDim& pw, int a,
                                 int b)
 {
@@ -218,15 +219,21 @@ ConvShape bwd_input_phase_shape(const ConvShape& s, const PhaseDim& ph, const Ph
 // every phase that has both pixels and taps must fit the tuned kernel and fill the chip
 bool bwd_input_as_phases(const ConvShape& s)
 {
-    if (s.stride == 1 || s.stride > 4 || (s.dtype != 1 && s.dtype != 2)) return false;
+    if (s.stride == 1 || s.stride > 4) return false;
     for (int a = 0; a < s.stride; ++a)
         for (int b = 0; b < s.stride; ++b) {
             const PhaseDim ph = phase_dim(s.H, s.kh, s.stride, s.pad, a);
             const PhaseDim pw = phase_dim(s.W, s.kw, s.stride, s.pad, b);
             if (ph.count == 0 || pw.count == 0 || ph.taps == 0 || pw.taps == 0) continue;
             const ConvShape f = bwd_input_phase_shape(s, ph, pw, a, b);
-            if (!mfma_supported(f) || !mfma_tuned16_supported(f)) return false;
-            if ((long long)f.N * f.Ho * f.Wo * f.D1 < 256LL * 128) return false;
+            if (!mfma_supported(f)) return false;
+            if (s.dtype == 0) {
+                // fp32: the tuned kernel with its four-wave tiles and an unsplit K loop
+                if (!mfma_dma32_supported(f) || !igemm32_dma_preferred(f)) return false;
+            } else {
+                if (!mfma_tuned16_supported(f)) return false;
+                if ((long long)f.N * f.Ho * f.Wo * f.D1 < 256LL * 128) return false;
+            }
         }
     return true;
 }
@@ -367,8 +374,10 @@ int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, f
                 f.k_sd0 = sD0;
                 f.k_sd2 = sD3;  // ... and its contracted capsule index the layer's d3
                 f.k_sd3 = sD2;
-                const int rc = forward_tuned16(f, dout, kernel, din, ws + kbytes,
-                                               workspace_bytes - kbytes, stream);
+                const int rc = s.dtype == 0 ? forward_tuned32(f, dout, kernel, din, ws + kbytes,
+                                                              workspace_bytes - kbytes, stream)
+                                            : forward_tuned16(f, dout, kernel, din, ws + kbytes,
+                                                              workspace_bytes - kbytes, stream);
                 if (rc != 0) return rc;
             }
         return 0;

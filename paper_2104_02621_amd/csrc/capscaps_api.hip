@@ -169,6 +169,12 @@ int forward_tuned16(const ConvShape& s, const void* in, const void* kernel, floa
     return run(in, kernel, out, s, CAPSCAPS_PATH_MFMA_TUNED16, workspace, workspace_bytes, stream);
 }
 
+int forward_tuned32(const ConvShape& s, const void* in, const void* kernel, float* out,
+                    void* workspace, size_t workspace_bytes, hipStream_t stream)
+{
+    return run(in, kernel, out, s, CAPSCAPS_PATH_MFMA_TUNED32, workspace, workspace_bytes, stream);
+}
+
 }  // namespace capscaps
 
 extern "C" {

@@ -98,6 +98,9 @@ bool forward_auto_repacks_kernel(const ConvShape& s);
 // the tuned 16-bit kernel, geometry overrides allowed (EUNSUPPORTED if it cannot run the shape)
 int forward_tuned16(const ConvShape& s, const void* in, const void* kernel, float* out,
                     void* workspace, size_t workspace_bytes, hipStream_t stream);
+// ... and the tuned fp32 kernel
+int forward_tuned32(const ConvShape& s, const void* in, const void* kernel, float* out,
+                    void* workspace, size_t workspace_bytes, hipStream_t stream);
 int status_from_hip(hipError_t err);
 
 // Backward pass (backward.hip): gradients with respect to input and kernel, fp32 results.

@@ -87,7 +87,7 @@ __global__ __launch_bounds__(64 * NW) void igemm32_dma_kernel(const Dma32Params 
     // wrapping), but a window's first pixel may lie in the padding: the descriptor's base is
     // moved back by the largest such distance and every lane offset forward by the same.
     // Nothing is read below the tensor: only in-range taps are ever addressed.
-    const int bias = (P.pad * P.W + P.pad) * pix_bytes;
+    const int bias = ((P.pad > 0 ? P.pad : 0) * P.W + (P.pad_w > 0 ? P.pad_w : 0)) * pix_bytes;
     const char* in_base = static_cast<const char*>(P.in) + n_first * img_bytes - bias;
     int row_off;
     unsigned long long tap_ok = 0;
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(64 * NW) void igemm32_dma_kernel(const Dma32Params 
         const int n_rel = (int)(pixel / hw - n_first);
         const int rem = (int)(pixel % hw);
         const int x = rem / P.Wo, y = rem - x * P.Wo;
-        const int ih0 = x * P.stride - P.pad, iw0 = y * P.stride - P.pad;
+        const int ih0 = x * P.stride - P.pad, iw0 = y * P.stride - P.pad_w;
         row_off = (int)((((long long)n_rel * P.H + ih0) * P.W + iw0) * pix_bytes) +
                   (d0 * P.D1 + d1) * P.D2 * 4 + bias;
         if (exists) {
@@ -249,7 +249,14 @@ __global__ __launch_bounds__(64 * NW) void igemm32_dma_kernel(const Dma32Params 
         if (orow >= P.rows) continue;
         const long long pixel = orow / P.D1;
         const int d1 = (int)(orow % P.D1);
-        float* orow_ptr = out + pixel * P.M * caps_out + (long long)(d0 * P.D1 + d1) * P.D3;
+        long long pix_at = pixel * P.M * caps_out;
+        if (P.out_view) {
+            const long long n = pixel / hw;
+            const int rem = (int)(pixel - n * hw);
+            const int x = rem / P.Wo, y = rem - x * P.Wo;
+            pix_at = P.out_base + n * P.out_sn + x * P.out_sx + y * P.out_sy;
+        }
+        float* orow_ptr = out + pix_at + (long long)(d0 * P.D1 + d1) * P.D3;
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
 #pragma unroll
@@ -339,9 +346,12 @@ bool igemm32_dma_eligible(const ConvShape& s)
     const long long hw = (long long)s.Ho * s.Wo;
     const long long pix = (256 + s.D1 - 1) / s.D1 + 1;
     const long long images_spanned = (pix + hw - 2) / hw + 1;
-    const long long bias = ((long long)s.pad * s.W + s.pad) * s.C * s.D0 * s.D1 * s.D2 * 4;
+    const long long bias = ((long long)(s.pad > 0 ? s.pad : 0) * s.W + (s.padw() > 0 ? s.padw() : 0)) *
+                           s.C * s.D0 * s.D1 * s.D2 * 4;
     if (images_spanned * img_bytes + bias >= (1LL << 31)) return false;
     const Dma32Plan pl = igemm32_dma_plan(s);
+    // an output view is written by the kernel itself: no partial sums over a split K loop
+    if (s.out_view && (pl.P.nsplit != 1 || s.out_sn < 0 || s.out_sx < 0 || s.out_sy < 0)) return false;
     if ((long long)pl.repack_bytes >= (1LL << 31) - (1 << 24)) return false;
     return pl.blocks > 0 && pl.blocks < 0x7fffffffLL;
 }
@@ -354,6 +364,9 @@ Dma32Plan igemm32_dma_plan(const ConvShape& s)
     const int cw = igemm32_dma_chunk_width(s);
     pl.cw = cw;
     P.H = s.H; P.W = s.W; P.C = s.C; P.M = s.M; P.stride = s.stride; P.pad = s.pad;
+    P.pad_w = s.padw();
+    P.out_view = s.out_view ? 1 : 0;
+    P.out_base = s.out_base; P.out_sn = s.out_sn; P.out_sx = s.out_sx; P.out_sy = s.out_sy;
     P.D0 = s.D0; P.D1 = s.D1; P.D2 = s.D2; P.D3 = s.D3; P.Ho = s.Ho; P.Wo = s.Wo;
     P.kh = s.kh; P.kw = s.kw; P.ntaps = s.kh * s.kw;
     P.rows = s.pixels() * s.D1;

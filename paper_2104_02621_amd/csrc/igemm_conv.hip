@@ -708,9 +708,10 @@ bool mfma_tuned16_supported(const ConvShape& s)
 hipError_t launch_mfma(const ConvShape& s, const void* in, const void* kernel, float* out,
                        void* workspace, hipStream_t stream, MfmaKernel which)
 {
-    // geometry overrides exist in the tuned 16-bit kernel only (a kernel view in all: it is the
+    // geometry overrides exist in the two tuned kernels only (a kernel view in all: it is the
     // repack pass that reads the kernel tensor)
-    if ((s.pad_w_set || s.out_view) && !(which == MfmaKernel::Tuned16 && igemm16_fast_eligible(s)))
+    if ((s.pad_w_set || s.out_view) && !(which == MfmaKernel::Tuned16 && igemm16_fast_eligible(s)) &&
+        !(which == MfmaKernel::Dma32 && igemm32_dma_eligible(s)))
         return hipErrorInvalidValue;
     if (which == MfmaKernel::Dma32 || (which == MfmaKernel::Auto && igemm32_dma_preferred(s)))
         return launch_dma32(s, in, kernel, out, workspace, stream);

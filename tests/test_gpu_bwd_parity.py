@@ -109,6 +109,11 @@ BWD_SHAPES = SMALL_SHAPES + [
     ("ph_s2", 3, 80, 80, 4, 8, 3, 3, 2, 1, 1, 8, 8, 8),
     ("ph_s3", 3, 120, 118, 4, 8, 2, 2, 3, 0, 1, 8, 4, 8),
     ("ph_ns", 2, 90, 61, 3, 4, 4, 3, 2, 3, 2, 16, 8, 16),
+    # ... and for fp32 on the tuned fp32 kernel (which wants 256 tiles of 256 rows per phase):
+    # 8x8 capsules at stride 2, and 3x3x3 capsules (12-byte rows, a leading capsule index) at
+    # stride 3 with a 4x4 window, whose phases have 2 or 1 taps a side and different paddings
+    ("ph32_s2", 7, 80, 78, 4, 8, 3, 3, 2, 1, 1, 8, 8, 8),
+    ("ph32_d3", 8, 100, 97, 5, 6, 4, 4, 3, 2, 3, 3, 3, 3),
 ]
 
 
