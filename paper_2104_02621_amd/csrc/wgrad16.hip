@@ -357,13 +357,16 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     // ---- main loop, unrolled over the ring so that slots are compile-time constants.
     // Iteration st: k-step 0 issues the Gt copies of stage st+NB-1 (one after every fourth
     // MFMA); after the barrier, k-step 1 issues the It copies of stage st+NB into the slot just
-    // released.  The walk over the pixels of stage st+NB runs through both k-steps, in gaps
-    // without a copy: pixel j's first piece after the last Gt copy that still reads the previous
+    // released.  The walk over the pixels of stage st+NB runs through both k-steps: pixel j's
+    // first piece after the last Gt copy that still reads the previous
     // stage's offset of slot j (k-step 0) and before the first It copy that reads the new one
     // (k-step 1).  Gaps 0..15 are k-step 0's, 16..31 k-step 1's.
     constexpr int NPIECE = 4 * PPS;
     constexpr auto piece_gap = [](int q) {
-        constexpr int four[16] = {3, 4, 5, 7, 8, 9, 11, 12, 13, 15, 16, 17, 19, 20, 21, 23};
+        // four pixels per stage: the second halves of both k-steps, whose gaps hold no operand
+        // reads (config 3: 2.7 % faster than pieces in the read gaps); two pixels: measured the
+        // other way round (config 5: 2 % slower in the second halves)
+        constexpr int four[16] = {8, 9, 10, 11, 12, 13, 14, 15, 24, 25, 26, 27, 28, 29, 30, 31};
         constexpr int two[8] = {7, 8, 9, 11, 15, 16, 17, 19};
         return PPS == 4 ? four[q] : two[q];
     };
