@@ -30,7 +30,13 @@ namespace {
 // small stages keep the LDS footprint of a workgroup low, so that two or more waves share each
 // SIMD and one wave's copies and scalar work run under another's MFMAs.
 constexpr int stage_chunks(int d1c, int nw) { return d1c == 4 || nw == 4 ? 4 : 2; }
-constexpr int ring_depth(int kch) { return kch == 2 ? 4 : 3; }
+// waves per SIMD the kernel is compiled for: three where 168 registers hold the accumulators
+// of the column tiles and a small stage's operands, else two
+constexpr int waves_per_simd(int tn, int kch) { return tn <= 3 && kch == 2 ? 3 : 2; }
+// three stages where six two-wave workgroups are to share a CU (24 KB each; measured on config 2
+// against four stages and five workgroups: 0.98 against 1.07 ms), four for the other small stages
+constexpr int ring_depth(int kch, int tn) { return kch == 2 && waves_per_simd(tn, kch) == 2 ? 4 : 3; }
+
 
 struct Wgrad32Params {
     const void* it;  // capsule-transposed input
@@ -69,9 +75,9 @@ __global__ __launch_bounds__(256) void transpose_caps32_kernel(const float* __re
 // offsets -- and the MFMA operands, single floats, are picked out of the slots one by one:
 // row (c, d2) at K index (pixel, d1) is element d2 of slot (pixel, c, d1).
 template <int CW, int TN, int NW, int KCH, bool NAT>
-__global__ __launch_bounds__(64 * NW) void wgrad32_kernel(const Wgrad32Params P)
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(waves_per_simd(TN, KCH)))) void wgrad32_kernel(const Wgrad32Params P)
 {
-    constexpr int NB = ring_depth(KCH);
+    constexpr int NB = ring_depth(KCH, TN);
     constexpr int BM = 64 * NW, BN = 32 * TN, BNL = (BN + 63) / 64 * 64, TM = 2;
     constexpr int A_BYTES = KCH * BM * 16, B_BYTES = KCH * BNL * 16;
     constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
@@ -466,9 +472,10 @@ Wgrad32Plan make_plan(const ConvShape& s)
     // pixels touches at most N/nsplit + 3 images: their bytes must stay below 2^31 (a lower
     // bound on nsplit), and the partial sums below 1 GiB (an upper bound).
     const int kch = stage_chunks(P.D1C, pl.nw);
-    const size_t lds = (size_t)ring_depth(kch) * kch * (64 * pl.nw + (32 * pl.tn + 63) / 64 * 64) * 16;
+    const size_t lds = (size_t)ring_depth(kch, pl.tn) * kch * (64 * pl.nw + (32 * pl.tn + 63) / 64 * 64) * 16;
     long long per_cu = (long long)(160 * 1024 / lds);
-    if (per_cu > 8 / pl.nw) per_cu = 8 / pl.nw;  // two waves per SIMD by registers
+    const int wps = waves_per_simd(pl.tn, kch);  // by registers
+    if (per_cu > 4 * wps / pl.nw) per_cu = 4 * wps / pl.nw;
     if (per_cu < 1) per_cu = 1;
     const long long slots = 256 * per_cu;
     const long long full = (long long)s.N * s.Ho * s.Wo;
@@ -502,7 +509,7 @@ hipError_t launch_nat(const Wgrad32Params& P, hipStream_t stream)
 {
     constexpr int BM = 64 * NW, BNL = (32 * TN + 63) / 64 * 64;
     auto kern = wgrad32_kernel<CW, TN, NW, KCH, NAT>;
-    const size_t lds_bytes = (size_t)ring_depth(KCH) * KCH * (BM + BNL) * 16;
+    const size_t lds_bytes = (size_t)ring_depth(KCH, TN) * KCH * (BM + BNL) * 16;
     static std::atomic<unsigned long long> lds_set{0};
     hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes, lds_set);
     if (err != hipSuccess) return err;
