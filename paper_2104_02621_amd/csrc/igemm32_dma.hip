@@ -24,15 +24,20 @@
 namespace capscaps {
 namespace {
 
-// KCH chunks per row and stage, ring of NB stages.  Small stages (2 chunks, ring of 4) halve the
-// LDS footprint of a workgroup, so that three instead of two share a CU and one wave's copies
-// and waits run under the others' MFMAs; they need capsule rows of at most 2 chunks.
-constexpr int ring_depth(int kch) { return kch == 2 ? 4 : 3; }
+// KCH chunks per row and stage, ring of NB stages.  Small stages (2 chunks) halve the LDS
+// footprint of a workgroup, so that more of them share a CU and one wave's copies and waits run
+// under the others' MFMAs; they need capsule rows of at most 2 chunks.  With up to three column
+// tiles the kernel is compiled for four waves per SIMD (126 registers: the accumulators and a
+// small stage's operands) and takes a ring of three stages, so that four four-wave workgroups
+// share a CU (config 2: 0.877 -> 0.860 ms against three workgroups with a ring of four);
+// elsewhere the compiler's own register budget and the deeper ring of the small stages.
+constexpr int waves_per_simd(int tn, int nw, int kch) { return nw == 4 && tn <= 3 && kch == 2 ? 4 : 1; }
+constexpr int ring_depth(int kch, int tn, int nw) { return kch == 2 && waves_per_simd(tn, nw, kch) == 1 ? 4 : 3; }
 
 template <int CW, int TN, int NW, int KCH>
-__global__ __launch_bounds__(64 * NW) void igemm32_dma_kernel(const Dma32Params P)
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(waves_per_simd(TN, NW, KCH)))) void igemm32_dma_kernel(const Dma32Params P)
 {
-    constexpr int NB = ring_depth(KCH);
+    constexpr int NB = ring_depth(KCH, TN, NW);
     constexpr int BM = 64 * NW, BN = 32 * TN, BNL = (BN + 63) / 64 * 64, TM = 2;
     constexpr int A_BYTES = KCH * BM * 16, B_BYTES = KCH * BNL * 16;
     constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
@@ -291,7 +296,7 @@ hipError_t launch_kch(const Dma32Params& P, long long blocks, hipStream_t stream
 {
     constexpr int BM = 64 * NW, BNL = (32 * TN + 63) / 64 * 64;
     auto kern = igemm32_dma_kernel<CW, TN, NW, KCH>;
-    const size_t lds_bytes = (size_t)ring_depth(KCH) * KCH * (BM + BNL) * 16;
+    const size_t lds_bytes = (size_t)ring_depth(KCH, TN, NW) * KCH * (BM + BNL) * 16;
     static std::atomic<unsigned long long> lds_set{0};
     hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes, lds_set);
     if (err != hipSuccess) return err;
