@@ -1,0 +1,82 @@
+"""GPU parity on seeded random layer shapes: forward pass (the library's own path choice) and
+both gradients against the CPU oracle.  The hand-picked shapes of the other files aim at
+known tile edges; these reach combinations nobody thought of (capsule shapes, windows wider
+than high, strides up to 3, paddings up to the window, one to many channels).  Needs an MI355X."""
+import numpy as np
+import pytest
+
+from paper_2104_02621_amd import workloads as wl
+from tests.test_gpu_bwd_parity import both_gradients
+from tests.test_gpu_parity import full_compare, small
+from paper_2104_02621_amd import capscaps as cc
+
+pytestmark = pytest.mark.gpu
+
+CAPSULE_DIMS = [1, 2, 3, 4, 5, 6, 8, 12, 16]
+
+
+def random_shape(seed):
+    """A layer small enough for the oracle to take well under a second."""
+    rng = np.random.default_rng(90000 + seed)
+    while True:
+        kh, kw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        s = int(rng.integers(1, 4))
+        p = int(rng.integers(0, max(kh, kw) + 1))
+        H, W = int(rng.integers(1, 20)), int(rng.integers(1, 20))
+        if kh > H + 2 * p or kw > W + 2 * p:
+            continue
+        N = int(rng.integers(1, 6))
+        C, M = int(rng.integers(1, 40)), int(rng.integers(1, 40))
+        D0 = int(rng.choice([1, 1, 1, 2, 3]))
+        if rng.random() < 0.5:  # square capsules, the kind the tuned kernels take
+            D1 = D2 = D3 = int(rng.choice([3, 4, 8, 16]))
+        else:
+            D1, D2, D3 = (int(rng.choice(CAPSULE_DIMS)) for _ in range(3))
+        Ho, Wo = (H + 2 * p - kh) // s + 1, (W + 2 * p - kw) // s + 1
+        flops = 2.0 * N * Ho * Wo * M * D0 * D1 * D3 * kh * kw * C * D2
+        if flops <= 3e8:
+            return (N, H, W, C, M, kh, kw, s, p, D0, D1, D2, D3)
+
+
+def random_medium_shape(seed):
+    """A layer with enough rows for the tuned kernels' 256-row tiles to fill the chip (or nearly):
+    square capsules of the element type's kind, a few seconds of oracle."""
+    rng = np.random.default_rng(95000 + seed)
+    dtype = [wl.FP32, wl.BF16, wl.FP16][seed % 3]
+    while True:
+        D = int(rng.choice([3, 4, 6, 8] if dtype == wl.FP32 else [8, 16]))
+        D0 = int(rng.choice([1, 1, 2, 3])) if dtype == wl.FP32 else 1
+        kh, kw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        s = int(rng.integers(1, 3))
+        p = int(rng.integers(0, 3))
+        H, W = int(rng.integers(12, 41)), int(rng.integers(12, 41))
+        N = int(rng.integers(4, 33))
+        C, M = 8 * int(rng.integers(1, 9)), 8 * int(rng.integers(1, 9))
+        Ho, Wo = (H + 2 * p - kh) // s + 1, (W + 2 * p - kw) // s + 1
+        rows = N * Ho * Wo * D
+        flops = 2.0 * rows * M * D0 * D * kh * kw * C * D
+        if rows >= 200 * 256 and flops <= 8e9:
+            return dtype, (N, H, W, C, M, kh, kw, s, p, D0, D, D, D)
+
+
+SEEDS = list(range(60))
+MEDIUM_SEEDS = list(range(15))
+
+
+@pytest.mark.parametrize("seed", SEEDS)
+def test_random_layer_forward_and_gradients(seed):
+    shape = random_shape(seed)
+    dtype = [wl.FP32, wl.BF16, wl.FP16][seed % 3]
+    w = small("rand%d_" % seed + "x".join(map(str, shape)), dtype, *shape, seed=700 + seed)
+    print(w.name, flush=True)
+    full_compare(w, cc.PATH_AUTO)
+    both_gradients(w)
+
+
+@pytest.mark.parametrize("seed", MEDIUM_SEEDS)
+def test_random_medium_layer_forward_and_gradients(seed):
+    dtype, shape = random_medium_shape(seed)
+    w = small("randm%d_" % seed + "x".join(map(str, shape)), dtype, *shape, seed=800 + seed)
+    print(w.name, cc.capscaps_select_path(*shape, dtype), flush=True)
+    full_compare(w, cc.PATH_AUTO)
+    both_gradients(w)
