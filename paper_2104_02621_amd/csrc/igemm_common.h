@@ -92,6 +92,7 @@ struct IgemmParams {
     int KT;                // C*D2: K extent of one tap
     int KQP;               // chunks per tap, padded to a multiple of 8
     int d2c_shift;         // vector loader: log2(chunks per capsule row)
+    unsigned d2_magic;     // half-chunk loader: ceil(2^32 / D2), K index / D2 as a multiplication; 0 = divide
     int spt;               // stages per tap
     int stages;            // ntaps * spt
     int stages_per_split;  // K-loop share of one split

@@ -114,9 +114,12 @@ __global__ __launch_bounds__(256) void splitk_reduce4_kernel(const float4v* __re
 }
 
 // ---------------------------------------------------------------------------------------------
-// VEC: a chunk never straddles a capsule row (D2 % CH == 0, D2/CH a power of two) -> one
+// VB: bytes the input-side loader moves at a time.  16: a chunk never straddles a capsule row
+// (D2 % CH == 0, D2/CH a power of two); 8: half a chunk never does (16-bit capsule rows of 4,
+// 12, 20 .. elements, fp32 rows of 2, 6, 10 ..): two 8-byte loads per chunk; 0: element-wise.
+// VB == 16 -> one
 // 16-byte load per chunk; otherwise element-wise gather.   ST4: D3 % 4 == 0 -> 16-byte stores.
-template <typename Tag, bool VEC, bool ST4, int BM, int BN, int WGM, int WGN>
+template <typename Tag, int VB, bool ST4, int BM, int BN, int WGM, int WGN>
 __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmParams P)
 {
     typedef typename Tag::elem E;
@@ -193,13 +196,26 @@ __global__ __launch_bounds__(64 * WGM * WGN) void igemm_kernel(const IgemmParams
         for (int i = 0; i < ACH; ++i) {
             const int kq = kq_stage + a_kq0 + i * A_STEP;
             chunk_t v = {0u, 0u, 0u, 0u};
-            if (VEC) {
+            if (VB == 16) {
                 const int k0 = kq * CH;
                 if (ok && k0 < P.KT) {
                     const int c = kq >> P.d2c_shift;
                     const int d2 = k0 - c * P.D2;
                     v = *reinterpret_cast<const chunk_t*>(src + (long long)c * P.cs + d2);
                 }
+            } else if (VB == 8) {
+                typedef unsigned int half_chunk_t __attribute__((ext_vector_type(2)));
+                half_chunk_t piece[2] = {{0u, 0u}, {0u, 0u}};
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int k0 = kq * CH + u * (CH / 2);
+                    if (ok && k0 < P.KT) {
+                        const int c = P.d2_magic ? (int)__umulhi((unsigned)k0, P.d2_magic) : k0 / P.D2;
+                        const int d2 = k0 - c * P.D2;
+                        piece[u] = *reinterpret_cast<const half_chunk_t*>(src + (long long)c * P.cs + d2);
+                    }
+                }
+                v = chunk_t{piece[0][0], piece[0][1], piece[1][0], piece[1][1]};
             } else {
                 E tmp[CH];
 #pragma unroll
@@ -318,7 +334,8 @@ inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
 struct Plan {
     IgemmParams P;
     TileChoice tile;
-    bool vec, st4;
+    int vb;  // bytes per input-side load: 16, 8, or 0 = element-wise
+    bool st4;
     bool fast;  // tuned 16-bit kernel
     bool via_scratch;  // results go to fp32 scratch first, then through splitk_reduce_kernel
     size_t tail_bytes;  // tuned kernel: scratch for the partial results of its last round
@@ -349,10 +366,15 @@ Plan make_plan(const ConvShape& s, MfmaKernel which)
     P.stages = P.ntaps * P.spt;
 
     const int d2c = s.D2 / CH;
-    pl.vec = (s.D2 % CH == 0) && (d2c & (d2c - 1)) == 0;
+    const bool vec = (s.D2 % CH == 0) && (d2c & (d2c - 1)) == 0;
+    pl.vb = vec ? 16 : s.D2 % (CH / 2) == 0 ? 8 : 0;
     P.d2c_shift = 0;
-    if (pl.vec)
+    if (vec)
         while ((1 << P.d2c_shift) < d2c) ++P.d2c_shift;
+    // k / D2 by multiplication: exact while k * D2 < 2^32 (k < KT + 64)
+    P.d2_magic = s.D2 > 1 && ((long long)P.KT + 64) * s.D2 < (1LL << 32)
+                     ? (unsigned)(((1ULL << 32) + s.D2 - 1) / s.D2)
+                     : 0u;
     pl.st4 = s.D3 % 4 == 0;
 
     // tile: the largest whose grid still gives every CU a few blocks; small problems take
@@ -491,10 +513,10 @@ Plan make_plan(const ConvShape& s, MfmaKernel which)
     return pl;
 }
 
-template <typename Tag, bool VEC, bool ST4, int BM, int BN>
+template <typename Tag, int VB, bool ST4, int BM, int BN>
 hipError_t launch_tile(const Plan& pl, hipStream_t stream)
 {
-    auto kern = igemm_kernel<Tag, VEC, ST4, BM, BN, 2, 2>;
+    auto kern = igemm_kernel<Tag, VB, ST4, BM, BN, 2, 2>;
     const size_t lds_bytes = (size_t)2 * 8 * (BM + BN) * 16;
     static std::atomic<unsigned long long> lds_set{0};
     hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes, lds_set);
@@ -503,25 +525,29 @@ hipError_t launch_tile(const Plan& pl, hipStream_t stream)
     return hipGetLastError();
 }
 
-template <typename Tag, bool VEC, bool ST4>
+template <typename Tag, int VB, bool ST4>
 hipError_t launch_flags(const Plan& pl, hipStream_t stream)
 {
     switch (pl.tile.BM) {
-        case 256: return launch_tile<Tag, VEC, ST4, 256, 256>(pl, stream);
-        case 128: return launch_tile<Tag, VEC, ST4, 128, 128>(pl, stream);
-        default: return launch_tile<Tag, VEC, ST4, 64, 64>(pl, stream);
+        case 256: return launch_tile<Tag, VB, ST4, 256, 256>(pl, stream);
+        case 128: return launch_tile<Tag, VB, ST4, 128, 128>(pl, stream);
+        default: return launch_tile<Tag, VB, ST4, 64, 64>(pl, stream);
     }
 }
 
 template <typename Tag>
 hipError_t launch_typed(const Plan& pl, hipStream_t stream)
 {
-    if (pl.vec) {
-        return pl.st4 ? launch_flags<Tag, true, true>(pl, stream)
-                      : launch_flags<Tag, true, false>(pl, stream);
+    if (pl.vb == 16) {
+        return pl.st4 ? launch_flags<Tag, 16, true>(pl, stream)
+                      : launch_flags<Tag, 16, false>(pl, stream);
     }
-    return pl.st4 ? launch_flags<Tag, false, true>(pl, stream)
-                  : launch_flags<Tag, false, false>(pl, stream);
+    if (pl.vb == 8) {
+        return pl.st4 ? launch_flags<Tag, 8, true>(pl, stream)
+                      : launch_flags<Tag, 8, false>(pl, stream);
+    }
+    return pl.st4 ? launch_flags<Tag, 0, true>(pl, stream)
+                  : launch_flags<Tag, 0, false>(pl, stream);
 }
 
 bool shape_supported(const ConvShape& s)

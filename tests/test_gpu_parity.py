@@ -52,6 +52,10 @@ SMALL_SHAPES = [
     ("fc", 5, 4, 3, 6, 7, 4, 3, 1, 0, 1, 4, 4, 4),
     ("odd", 1, 10, 9, 7, 3, 5, 4, 1, 2, 1, 3, 5, 7),
     ("manyrows", 4, 20, 20, 4, 20, 3, 3, 1, 1, 1, 8, 8, 8),
+    # capsule rows that are half a 16-byte chunk, or an odd number of halves (the any-shape
+    # kernel's 8-byte loads): 2 and 6 floats, 12 halves
+    ("d2two", 2, 6, 7, 5, 4, 3, 3, 1, 1, 1, 3, 2, 4),
+    ("d2twelve", 1, 6, 6, 3, 4, 3, 3, 1, 1, 1, 4, 12, 4),
     # degenerate geometries: a single pixel, a window equal to the padded input, a stride
     # larger than the window, padding wider than the window's reach, scalar capsules
     ("pixel", 1, 1, 1, 3, 2, 1, 1, 1, 0, 1, 2, 3, 2),
