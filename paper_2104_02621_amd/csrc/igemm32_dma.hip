@@ -16,6 +16,13 @@
 // (tap, channel group, chunk) is a scalar offset.  K runs channel group outermost, tap inside,
 // 4 chunks per stage, ring of 3 LDS stages, one barrier per stage; the K loop can be split over
 // blocks (partial sums are reduced in a fixed order by the caller's reduce kernel).
+//
+// The same kernel serves 16-bit capsules with rows of 4 elements (4x4 capsules), which no
+// 16-byte copy can stage as they lie in memory: the 8 K values a 16-bit matrix instruction takes
+// per lane are the rows of two channels, 32 bytes apart.  A pre-pass (pair_channels_kernel, at
+// HBM speed) writes the input with channels paired, [pixel][c/2][d0][d1][c%2][d2]; in units of
+// 4 bytes that is an fp32 layer with half the channels and rows of 4 "floats", so every offset
+// and copy of this kernel stays as it is, and a chunk pair feeds one MFMA 32x32x16 per tile.
 #include <hip/hip_runtime.h>
 
 #include "igemm_common.h"
@@ -34,9 +41,15 @@ namespace {
 constexpr int waves_per_simd(int tn, int nw, int kch) { return nw == 4 && tn <= 3 && kch == 2 ? 4 : 1; }
 constexpr int ring_depth(int kch, int tn, int nw) { return kch == 2 && waves_per_simd(tn, nw, kch) == 1 ? 4 : 3; }
 
-template <int CW, int TN, int NW, int KCH>
+// Tag: f32_tag, or a 16-bit tag for capsule rows of 4 halves whose channels a pre-pass has paired
+// (pair_channels_kernel): a 16-byte chunk then holds the 8 K values (c, c+1) x d2 of one row, all
+// offsets are those of an fp32 layer with half the channels and rows of 4 floats, and a chunk pair
+// feeds one 16-bit MFMA 32x32x16 per tile instead of CW fp32 ones.
+template <typename Tag, int CW, int TN, int NW, int KCH>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(waves_per_simd(TN, NW, KCH)))) void igemm32_dma_kernel(const Dma32Params P)
 {
+    constexpr bool F32 = std::is_same<Tag, f32_tag>::value;
+    static_assert(F32 || CW == 4, "16-bit chunks are whole 16-byte slots");
     constexpr int NB = ring_depth(KCH, TN, NW);
     constexpr int BM = 64 * NW, BN = 32 * TN, BNL = (BN + 63) / 64 * 64, TM = 2;
     constexpr int A_BYTES = KCH * BM * 16, B_BYTES = KCH * BNL * 16;
@@ -214,14 +227,23 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(waves_p
             for (int b = 0; b < TM; ++b)
                 ib[b] = *reinterpret_cast<const float4v*>(
                     stage + ((2 * t + h) * BM + 64 * wave + b * 32 + lr) * 16);
+            if constexpr (F32) {
 #pragma unroll
-            for (int u = 0; u < CW; ++u)
+                for (int u = 0; u < CW; ++u)
+#pragma unroll
+                    for (int a = 0; a < TN; ++a)
+#pragma unroll
+                        for (int b = 0; b < TM; ++b)
+                            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(ka[a][u], ib[b][u],
+                                                                             acc[a][b], 0, 0, 0);
+            } else {
 #pragma unroll
                 for (int a = 0; a < TN; ++a)
 #pragma unroll
                     for (int b = 0; b < TM; ++b)
-                        acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(ka[a][u], ib[b][u],
-                                                                         acc[a][b], 0, 0, 0);
+                        Mma<Tag>::run(__builtin_bit_cast(chunk_t, ka[a]),
+                                      __builtin_bit_cast(chunk_t, ib[b]), acc[a][b]);
+            }
         }
     };
 
@@ -291,11 +313,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(waves_p
     }
 }
 
-template <int CW, int TN, int NW, int KCH>
+template <typename Tag, int CW, int TN, int NW, int KCH>
 hipError_t launch_kch(const Dma32Params& P, long long blocks, hipStream_t stream)
 {
     constexpr int BM = 64 * NW, BNL = (32 * TN + 63) / 64 * 64;
-    auto kern = igemm32_dma_kernel<CW, TN, NW, KCH>;
+    auto kern = igemm32_dma_kernel<Tag, CW, TN, NW, KCH>;
     const size_t lds_bytes = (size_t)ring_depth(KCH, TN, NW) * KCH * (BM + BNL) * 16;
     static std::atomic<unsigned long long> lds_set{0};
     hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes, lds_set);
@@ -305,24 +327,43 @@ hipError_t launch_kch(const Dma32Params& P, long long blocks, hipStream_t stream
 }
 
 // 2-chunk stages where the column copies still divide over the waves
-template <int CW, int TN, int NW>
+template <typename Tag, int CW, int TN, int NW>
 hipError_t launch_one(const Dma32Params& P, long long blocks, hipStream_t stream)
 {
-    if constexpr ((2 * ((32 * TN + 63) / 64)) % NW == 0) {
-        if (P.kch == 2) return launch_kch<CW, TN, NW, 2>(P, blocks, stream);
+    // 16-bit operands always take 4-chunk stages (a 2-chunk stage is a single matrix instruction
+    // per tile)
+    if constexpr (std::is_same<Tag, f32_tag>::value && (2 * ((32 * TN + 63) / 64)) % NW == 0) {
+        if (P.kch == 2) return launch_kch<Tag, CW, TN, NW, 2>(P, blocks, stream);
     }
-    return launch_kch<CW, TN, NW, 4>(P, blocks, stream);
+    return launch_kch<Tag, CW, TN, NW, 4>(P, blocks, stream);
 }
 
-template <int CW, int NW>
+template <typename Tag, int CW, int NW>
 hipError_t launch_tn(const Dma32Params& P, int tn, long long blocks, hipStream_t stream)
 {
     switch (tn) {
-        case 1: return launch_one<CW, 1, NW>(P, blocks, stream);
-        case 2: return launch_one<CW, 2, NW>(P, blocks, stream);
-        case 3: return launch_one<CW, 3, NW>(P, blocks, stream);
-        default: return launch_one<CW, 4, NW>(P, blocks, stream);
+        case 1: return launch_one<Tag, CW, 1, NW>(P, blocks, stream);
+        case 2: return launch_one<Tag, CW, 2, NW>(P, blocks, stream);
+        case 3: return launch_one<Tag, CW, 3, NW>(P, blocks, stream);
+        default: return launch_one<Tag, CW, 4, NW>(P, blocks, stream);
     }
+}
+
+// 8-byte units: dst[pixel][c/2][d0*D1 + d1][c%2] = src[pixel][c][d0*D1 + d1]; a thread moves
+// the two units of one (pixel, channel pair, row): one 16-byte store
+__global__ __launch_bounds__(256) void pair_channels_kernel(const uint2* __restrict__ src,
+                                                            uint4* __restrict__ dst, int C,
+                                                            int rows_per_capsule, size_t pairs)
+{
+    const size_t id = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= pairs) return;
+    size_t r = id;
+    const int row = (int)(r % rows_per_capsule); r /= rows_per_capsule;
+    const int c2 = (int)(r % (C / 2));
+    const size_t pixel = r / (C / 2);
+    const uint2* p = src + (pixel * C + 2 * c2) * rows_per_capsule + row;
+    const uint2 lo = p[0], hi = p[rows_per_capsule];
+    dst[id] = uint4{lo.x, lo.y, hi.x, hi.y};
 }
 
 inline int ceil_div_ll(long long a, long long b) { return (int)((a + b - 1) / b); }
@@ -333,6 +374,9 @@ inline int ceil_div_ll(long long a, long long b) { return (int)((a + b - 1) / b)
 // the 4 chunks of a stage never split a row); 0 if neither fits.
 int igemm32_dma_chunk_width(const ConvShape& s)
 {
+    // 16-bit operands: capsule rows of 4 halves and an even number of channels, which a pre-pass
+    // pairs so that a chunk is (c, c+1) x 4 halves = "4 floats"; fp32 output only
+    if (s.dtype != 0) return s.D2 == 4 && s.C % 2 == 0 && s.out16 == 0 ? 4 : 0;
     for (int cw : {4, 3}) {
         if (s.D2 % cw) continue;
         const int d2c = s.D2 / cw;
@@ -343,16 +387,16 @@ int igemm32_dma_chunk_width(const ConvShape& s)
 
 bool igemm32_dma_eligible(const ConvShape& s)
 {
-    if (s.dtype != 0) return false;
     const int cw = igemm32_dma_chunk_width(s);
     if (cw == 0) return false;
     if (s.kh * s.kw > 64) return false;                   // one mask bit per window tap
-    const long long img_bytes = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 4;
+    const int es = s.dtype == 0 ? 4 : 2;
+    const long long img_bytes = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * es;
     const long long hw = (long long)s.Ho * s.Wo;
     const long long pix = (256 + s.D1 - 1) / s.D1 + 1;
     const long long images_spanned = (pix + hw - 2) / hw + 1;
     const long long bias = ((long long)(s.pad > 0 ? s.pad : 0) * s.W + (s.padw() > 0 ? s.padw() : 0)) *
-                           s.C * s.D0 * s.D1 * s.D2 * 4;
+                           s.C * s.D0 * s.D1 * s.D2 * es;
     if (images_spanned * img_bytes + bias >= (1LL << 31)) return false;
     const Dma32Plan pl = igemm32_dma_plan(s);
     // an output view is written by the kernel itself: no partial sums over a split K loop
@@ -368,19 +412,25 @@ Dma32Plan igemm32_dma_plan(const ConvShape& s)
     Dma32Params& P = pl.P;
     const int cw = igemm32_dma_chunk_width(s);
     pl.cw = cw;
-    P.H = s.H; P.W = s.W; P.C = s.C; P.M = s.M; P.stride = s.stride; P.pad = s.pad;
+    pl.dtype = s.dtype;
+    // 16-bit operands: in units of 4 bytes the channel-paired input is an fp32 layer with half
+    // the channels and capsule rows of 4 "floats"
+    const int C = s.dtype == 0 ? s.C : s.C / 2;
+    const int D2 = s.dtype == 0 ? s.D2 : 4;
+    pl.pair_bytes = s.dtype == 0 ? 0 : (size_t)s.in_elems() * 2;
+    P.H = s.H; P.W = s.W; P.C = C; P.M = s.M; P.stride = s.stride; P.pad = s.pad;
     P.pad_w = s.padw();
     P.out_view = s.out_view ? 1 : 0;
     P.out_base = s.out_base; P.out_sn = s.out_sn; P.out_sx = s.out_sx; P.out_sy = s.out_sy;
-    P.D0 = s.D0; P.D1 = s.D1; P.D2 = s.D2; P.D3 = s.D3; P.Ho = s.Ho; P.Wo = s.Wo;
+    P.D0 = s.D0; P.D1 = s.D1; P.D2 = D2; P.D3 = s.D3; P.Ho = s.Ho; P.Wo = s.Wo;
     P.kh = s.kh; P.kw = s.kw; P.ntaps = s.kh * s.kw;
     P.rows = s.pixels() * s.D1;
     P.out_elems = (long long)s.out_elems();
-    P.pixsz = (long long)s.C * s.D0 * s.D1 * s.D2;
-    P.cs = s.D0 * s.D1 * s.D2;
+    P.pixsz = (long long)C * s.D0 * s.D1 * D2;
+    P.cs = s.D0 * s.D1 * D2;
     P.cols = s.M * s.D3;
-    P.D2C = cw ? s.D2 / cw : 1;
-    const int KK = s.C * P.D2C;                 // chunks per row and tap
+    P.D2C = cw ? D2 / cw : 1;
+    const int KK = C * P.D2C;                   // chunks per row and tap
     pl.tn = P.cols <= 32 ? 1 : P.cols <= 64 ? 2 : P.cols <= 96 ? 3 : 4;
     // four waves per block (256 rows) when that still fills the chip, else one (64 rows)
     {
@@ -390,7 +440,8 @@ Dma32Plan igemm32_dma_plan(const ConvShape& s)
     }
     // chunks per stage: 2 for the four-wave tile with wide column tiles and short capsule rows
     // (measured on config 2: 0.955 ms against 0.987 ms), else 4
-    const int KCH = (pl.nw == 4 && pl.tn >= 3 && P.D2C <= 2) ? 2 : 4;
+    // (16-bit: 8-chunk stages, one workgroup per CU, measured 22 % slower than 4-chunk ones)
+    const int KCH = (s.dtype == 0 && pl.nw == 4 && pl.tn >= 3 && P.D2C <= 2) ? 2 : 4;
     P.kch = KCH;
     const int groups = (KK + KCH - 1) / KCH;
     pl.kqp = groups * KCH;
@@ -411,7 +462,7 @@ Dma32Plan igemm32_dma_plan(const ConvShape& s)
     pl.blocks = tiles * P.nsplit;
     pl.repack_bytes = (size_t)s.D0 * P.nstages * KCH * P.colsp * 16;
     pl.partial_bytes = P.nsplit > 1 ? (size_t)P.nsplit * P.out_elems * sizeof(float) : 0;
-    P.in_bytes = (long long)s.in_elems() * 4;
+    P.in_bytes = (long long)s.in_elems() * (s.dtype == 0 ? 4 : 2);
     P.kp_bytes = (long long)pl.repack_bytes;
     P.d3_magic = s.D3 > 1 && (long long)s.M * s.D3 * s.D3 < (1LL << 32)
                      ? (unsigned)(((1ULL << 32) + s.D3 - 1) / s.D3)
@@ -438,11 +489,27 @@ bool igemm32_dma_preferred(const ConvShape& s)
 
 hipError_t launch_igemm32_dma(const Dma32Plan& pl, hipStream_t stream)
 {
+    if (pl.dtype == 1)
+        return pl.nw == 4 ? launch_tn<bf16_tag, 4, 4>(pl.P, pl.tn, pl.blocks, stream)
+                          : launch_tn<bf16_tag, 4, 1>(pl.P, pl.tn, pl.blocks, stream);
+    if (pl.dtype == 2)
+        return pl.nw == 4 ? launch_tn<f16_tag, 4, 4>(pl.P, pl.tn, pl.blocks, stream)
+                          : launch_tn<f16_tag, 4, 1>(pl.P, pl.tn, pl.blocks, stream);
     if (pl.cw == 3)
-        return pl.nw == 4 ? launch_tn<3, 4>(pl.P, pl.tn, pl.blocks, stream)
-                          : launch_tn<3, 1>(pl.P, pl.tn, pl.blocks, stream);
-    return pl.nw == 4 ? launch_tn<4, 4>(pl.P, pl.tn, pl.blocks, stream)
-                      : launch_tn<4, 1>(pl.P, pl.tn, pl.blocks, stream);
+        return pl.nw == 4 ? launch_tn<f32_tag, 3, 4>(pl.P, pl.tn, pl.blocks, stream)
+                          : launch_tn<f32_tag, 3, 1>(pl.P, pl.tn, pl.blocks, stream);
+    return pl.nw == 4 ? launch_tn<f32_tag, 4, 4>(pl.P, pl.tn, pl.blocks, stream)
+                      : launch_tn<f32_tag, 4, 1>(pl.P, pl.tn, pl.blocks, stream);
+}
+
+hipError_t launch_pair_channels(const ConvShape& s, const void* src, void* dst, hipStream_t stream)
+{
+    const size_t pairs = (size_t)s.in_elems() / 8;  // D2 = 4 halves = 8 bytes, two per store
+    const size_t blocks = (pairs + 255) / 256;
+    if (blocks == 0 || blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+    pair_channels_kernel<<<(unsigned)blocks, 256, 0, stream>>>(
+        static_cast<const uint2*>(src), static_cast<uint4*>(dst), s.C, s.D0 * s.D1, pairs);
+    return hipGetLastError();
 }
 
 }  // namespace capscaps

@@ -164,14 +164,18 @@ struct Dma32Params {
 struct Dma32Plan {
     Dma32Params P;
     int cw, tn, nw, kqp;
+    int dtype;          // 0: fp32; 1, 2: 16-bit capsule rows of 4 elements, channels paired
     long long blocks;
     size_t repack_bytes, partial_bytes;
+    size_t pair_bytes;  // 16-bit: the input with its channels paired (same size as the input)
 };
 int igemm32_dma_chunk_width(const ConvShape& s);
 Dma32Plan igemm32_dma_plan(const ConvShape& s);
 bool igemm32_dma_eligible(const ConvShape& s);   // the kernel can run the shape
 bool igemm32_dma_preferred(const ConvShape& s);  // ... and is the library's choice for it
 hipError_t launch_igemm32_dma(const Dma32Plan& pl, hipStream_t stream);
+// 16-bit operands: dst[pixel][c/2][d0][d1][c%2][4] = src[pixel][c][d0][d1][4] (8-byte units)
+hipError_t launch_pair_channels(const ConvShape& s, const void* src, void* dst, hipStream_t stream);
 
 // Tuned 16-bit kernel (igemm16_fast.hip): 256x256 tiles, direct-to-LDS copies.
 bool igemm16_fast_eligible(const ConvShape& s);   // the kernel can run the shape

@@ -599,6 +599,13 @@ hipError_t launch_igemm(const ConvShape& s, const void* in, const void* kernel, 
     return err;
 }
 
+// scratch of the lane-per-row tuned kernel: repacked kernel, partial sums, paired input
+size_t dma32_workspace_bytes(const Dma32Plan& pl)
+{
+    return ((pl.repack_bytes + 255) & ~(size_t)255) + ((pl.partial_bytes + 255) & ~(size_t)255) +
+           pl.pair_bytes;
+}
+
 hipError_t launch_dma32(const ConvShape& s, const void* in, const void* kernel, float* out,
                         void* workspace, hipStream_t stream)
 {
@@ -608,8 +615,16 @@ hipError_t launch_dma32(const ConvShape& s, const void* in, const void* kernel, 
     pl.P.in = in;
     pl.P.kp = ws;
     pl.P.out = pl.P.nsplit > 1 ? partial : out;
-    hipError_t err = launch_repack(s, kernel, ws, pl.cw, pl.kqp, pl.P.colsp, pl.P.kch,
-                                   pl.repack_bytes / 16, stream);
+    hipError_t err = hipSuccess;
+    if (pl.pair_bytes) {
+        // 16-bit: the kernel reads the input with its channels paired, and 8 halves per chunk
+        void* paired = ws + dma32_workspace_bytes(pl) - pl.pair_bytes;
+        err = launch_pair_channels(s, in, paired, stream);
+        if (err != hipSuccess) return err;
+        pl.P.in = paired;
+    }
+    err = launch_repack(s, kernel, ws, s.dtype == 0 ? pl.cw : 8, pl.kqp, pl.P.colsp, pl.P.kch,
+                        pl.repack_bytes / 16, stream);
     if (err != hipSuccess) return err;
     err = launch_igemm32_dma(pl, stream);
     if (err != hipSuccess) return err;
@@ -686,8 +701,7 @@ size_t mfma_workspace_bytes(const ConvShape& s)
         if (bytes > need) need = bytes;
     }
     if (igemm32_dma_eligible(s)) {
-        const Dma32Plan pl = igemm32_dma_plan(s);
-        const size_t bytes = ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
+        const size_t bytes = dma32_workspace_bytes(igemm32_dma_plan(s));
         if (bytes > need) need = bytes;
     }
     if (igemm_small_workspace_bytes(s) > need) need = igemm_small_workspace_bytes(s);
@@ -701,8 +715,7 @@ size_t mfma_auto_workspace_bytes(const ConvShape& s)
     if (which == MfmaKernel::Small) return igemm_small_workspace_bytes(s);
     if (which == MfmaKernel::Dma32) {
         if (s.out16 != 0) return 0;
-        const Dma32Plan pl = igemm32_dma_plan(s);
-        return ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
+        return dma32_workspace_bytes(igemm32_dma_plan(s));
     }
     const Plan pl = make_plan(s, which);
     return ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;

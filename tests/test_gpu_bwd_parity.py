@@ -112,6 +112,9 @@ BWD_SHAPES = SMALL_SHAPES + [
     # ... and for fp32 on the tuned fp32 kernel (which wants 256 tiles of 256 rows per phase):
     # 8x8 capsules at stride 2, and 3x3x3 capsules (12-byte rows, a leading capsule index) at
     # stride 3 with a 4x4 window, whose phases have 2 or 1 taps a side and different paddings
+    # 4x4 capsules on enough pixels for the 16-bit input gradient to run on the lane-per-row
+    # kernel (the output gradient's channels paired)
+    ("p4big", 12, 40, 40, 8, 8, 3, 3, 1, 1, 1, 4, 4, 4),
     ("ph32_s2", 7, 80, 78, 4, 8, 3, 3, 2, 1, 1, 8, 8, 8),
     ("ph32_d3", 8, 100, 97, 5, 6, 4, 4, 3, 2, 3, 3, 3, 3),
 ]

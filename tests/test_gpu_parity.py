@@ -100,6 +100,35 @@ def test_tuned_fp32_kernel_matches_oracle(shape):
     assert np.array_equal(got.cpu().numpy().astype(np.float64), ref), wi.name
 
 
+# 16-bit capsule rows of 4 elements with an even number of channels run on the same lane-per-row
+# kernel after a pre-pass has paired the channels: capsules 4x4 (the matrix-capsule shape) and
+# non-square, one and many channel pairs (a ragged last stage), a leading capsule index, strides,
+# padding, several column tiles, many rows (four-wave tiles), a 1x1 window and an FC layer
+PAIRED16_SHAPES = [
+    #        N  H   W   C   M  kh kw s  p D0  D1  D2  D3
+    ("p4a", 3, 9, 10, 6, 5, 3, 3, 1, 1, 1, 4, 4, 4),
+    ("p4b", 2, 8, 7, 2, 3, 3, 3, 2, 1, 2, 4, 4, 4),
+    ("p4c", 2, 7, 9, 10, 4, 2, 3, 2, 1, 1, 3, 4, 5),
+    ("p4d", 1, 6, 6, 14, 40, 3, 2, 1, 0, 3, 8, 4, 8),
+    ("p4rows", 5, 24, 24, 4, 12, 3, 3, 1, 1, 1, 4, 4, 4),
+    ("p4k1", 2, 9, 9, 16, 12, 1, 1, 3, 0, 1, 4, 4, 4),
+    ("p4fc", 5, 4, 3, 6, 7, 4, 3, 1, 0, 1, 4, 4, 4),
+    ("p4pad", 1, 3, 3, 2, 2, 3, 3, 2, 3, 1, 4, 4, 4),
+]
+
+
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.FP16], ids=["bf16", "fp16"])
+@pytest.mark.parametrize("shape", PAIRED16_SHAPES, ids=[s[0] for s in PAIRED16_SHAPES])
+def test_lane_per_row_kernel_on_16bit_rows_of_4(shape, dtype):
+    w = small(shape[0], dtype, *shape[1:], seed=len(shape[0]) + 75)
+    full_compare(w, PATHS["tuned32"])
+    wi = small(shape[0] + "_int", dtype, *shape[1:], dist="int", seed=76)
+    i_st, k_st, i32, k32 = wl.generate(wi)
+    ref = capsconv.conv_fwd(i32, k32, wi.stride, wi.pad)
+    got = run_gpu(wi, to_device(i_st, dtype), to_device(k_st, dtype), PATHS["tuned32"])
+    assert np.array_equal(got.cpu().numpy().astype(np.float64), ref), wi.name
+
+
 # shapes the 256x256-tile 16-bit kernel accepts (D1 = D2 in {8, 16}, C*D2 a multiple of 64):
 # ragged row tiles, tiles that straddle images, several column tiles with a ragged last one,
 # leading capsule dimension, strides, padding wider than the window reach, D3 != D1

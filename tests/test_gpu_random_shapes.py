@@ -44,7 +44,7 @@ def random_medium_shape(seed):
     rng = np.random.default_rng(95000 + seed)
     dtype = [wl.FP32, wl.BF16, wl.FP16][seed % 3]
     while True:
-        D = int(rng.choice([3, 4, 6, 8] if dtype == wl.FP32 else [8, 16]))
+        D = int(rng.choice([3, 4, 6, 8] if dtype == wl.FP32 else [4, 8, 16]))
         D0 = int(rng.choice([1, 1, 2, 3])) if dtype == wl.FP32 else 1
         kh, kw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
         s = int(rng.integers(1, 3))
