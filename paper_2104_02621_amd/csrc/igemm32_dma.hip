@@ -502,14 +502,20 @@ hipError_t launch_igemm32_dma(const Dma32Plan& pl, hipStream_t stream)
                       : launch_tn<f32_tag, 4, 1>(pl.P, pl.tn, pl.blocks, stream);
 }
 
-hipError_t launch_pair_channels(const ConvShape& s, const void* src, void* dst, hipStream_t stream)
+hipError_t launch_pair_channels(const void* src, void* dst, size_t pixels, int C,
+                                int rows_per_capsule, hipStream_t stream)
 {
-    const size_t pairs = (size_t)s.in_elems() / 8;  // D2 = 4 halves = 8 bytes, two per store
+    const size_t pairs = pixels * (size_t)(C / 2) * rows_per_capsule;  // 16 bytes each
     const size_t blocks = (pairs + 255) / 256;
     if (blocks == 0 || blocks > 0x7fffffffULL) return hipErrorInvalidValue;
     pair_channels_kernel<<<(unsigned)blocks, 256, 0, stream>>>(
-        static_cast<const uint2*>(src), static_cast<uint4*>(dst), s.C, s.D0 * s.D1, pairs);
+        static_cast<const uint2*>(src), static_cast<uint4*>(dst), C, rows_per_capsule, pairs);
     return hipGetLastError();
+}
+
+hipError_t launch_pair_channels(const ConvShape& s, const void* src, void* dst, hipStream_t stream)
+{
+    return launch_pair_channels(src, dst, (size_t)s.N * s.H * s.W, s.C, s.D0 * s.D1, stream);
 }
 
 }  // namespace capscaps

@@ -176,6 +176,9 @@ bool igemm32_dma_preferred(const ConvShape& s);  // ... and is the library's cho
 hipError_t launch_igemm32_dma(const Dma32Plan& pl, hipStream_t stream);
 // 16-bit operands: dst[pixel][c/2][d0][d1][c%2][4] = src[pixel][c][d0][d1][4] (8-byte units)
 hipError_t launch_pair_channels(const ConvShape& s, const void* src, void* dst, hipStream_t stream);
+// the same for any tensor [pixels][C][rows_per_capsule][4 halves]
+hipError_t launch_pair_channels(const void* src, void* dst, size_t pixels, int C,
+                                int rows_per_capsule, hipStream_t stream);
 
 // Tuned 16-bit kernel (igemm16_fast.hip): 256x256 tiles, direct-to-LDS copies.
 bool igemm16_fast_eligible(const ConvShape& s);   // the kernel can run the shape

@@ -1,6 +1,6 @@
 // Kernel gradient of the capsule convolution (the K_diff result of the paper's Algorithm 4,
 // taken as the derivative of Algorithm 2's sum) on the matrix cores, for 16-bit element types
-// and D1 in {8, 16}.  With G = dL/dO, per window tap (p,q) and leading capsule index d0 it is
+// and D1 in {8, 16}, and for 4x4 capsules (see the end of this comment).  With G = dL/dO, per window tap (p,q) and leading capsule index d0 it is
 // one GEMM
 //
 //     rows     r = (c, d2)                                           C*D2 of them
@@ -41,6 +41,12 @@
 // reads (4 lines x 32 rows) fall into 16 different 16-byte columns of the 64 banks.  Which
 // (pixel, d1) pair sits in which of an instruction's 16 contraction slots is the same on both
 // sides, which is all the contraction needs.
+//
+// 4x4 capsules (D1 = D2 = D3 = 4, even channel counts) take the same path on channel-paired copies
+// of both tensors, [pixel][c/2][d0][d1][c%2][4 halves] (a pre-pass at HBM speed): 8 consecutive
+// rows (c, d2) of a line are then one 16-byte chunk as above.  A pixel has only 4 lines, so a
+// stage is 8 pixels and a copy's 8 lines are two pixels: the second pixel's offset travels in
+// the lane offset of its lanes.
 #include <hip/hip_runtime.h>
 
 #include "igemm_common.h"
@@ -99,8 +105,9 @@ template <typename Tag, int D1, bool OWN>
 __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
 {
     constexpr int KCH = 4, NB = 4;
-    constexpr int D1C = D1 / 8;     // chunks per pixel and row
-    constexpr int PPS = KCH / D1C;  // pixels per stage
+    constexpr int D1C = D1 >= 8 ? D1 / 8 : 1;  // chunks per pixel and row (copies per pixel, D1 >= 8)
+    constexpr int PPS = 32 / D1;               // pixels per stage
+    static_assert(D1 >= 8 || OWN, "4-row capsules are read in place (channel-paired tensors)");
     constexpr int NWM = 2, NWN = 2;
     constexpr int BM = 256, BN = 256;
     constexpr int SIDE_BYTES = KCH * BM * 16, STAGE_BYTES = 2 * SIDE_BYTES;
@@ -112,7 +119,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     constexpr int KEEP = (NB - 2) * NCOPY;
     static_assert(KEEP < 64, "vmcnt is a 6-bit counter");
     constexpr int VMCNT_KEEP = 0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14);
-    static_assert(D1 == 8 || D1 == 16, "D1");
+    static_assert(D1 == 4 || D1 == 8 || D1 == 16, "D1");
     static_assert(NMMA == 16 && KCH == 4, "the schedule below is written for this shape");
 
     extern __shared__ char smem[];
@@ -184,6 +191,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     // ---- per-lane constants: byte offset of the lane's row (column) within a pixel, or the
     // out-of-range mark for rows (columns) past the end: those copy zeros
     unsigned a_voff, b_voff;
+    int pair_hi = 0;
     // OWN: place of chunk (line l8, chunk column r8) in its unit, and back.  `wide`: two chunk
     // columns per capsule row (capsule width a multiple of 16), else one.
     auto unit_slot = [](bool wide, int l8, int r8) {
@@ -196,12 +204,20 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
         const int la = (a_wide ? (lane & 15) >> 1 : lane & 7) ^ (((ra >> 1) & 1) * 4);
         const int R = row_tile * BM + (wave * 8 + ra) * 8;
         const int c = R / P.D2, d2 = R - c * P.D2;
-        a_voff = R < P.rows ? (unsigned)(((((c * P.D0 + d0) * D1 + la) * P.D2) + d2) * 2) : (unsigned)OOB;
+        if constexpr (D1 == 4)  // channel-paired tensor: chunk R / 8 of line la % 4 (la / 4: which pixel)
+            a_voff = R < P.rows ? (unsigned)((((R >> 3) * P.D0 + d0) * D1 + (la & 3)) * 16) : (unsigned)OOB;
+        else
+            a_voff = R < P.rows ? (unsigned)(((((c * P.D0 + d0) * D1 + la) * P.D2) + d2) * 2) : (unsigned)OOB;
         const int rb = b_wide ? (lane >> 4) * 2 + (lane & 1) : lane >> 3;
         const int lb = (b_wide ? (lane & 15) >> 1 : lane & 7) ^ (((rb >> 1) & 1) * 4);
         const int J = col_tile * BN + (wave * 8 + rb) * 8;
         const int m = J / P.D3, d3 = J - m * P.D3;
-        b_voff = J < P.cols ? (unsigned)(((((m * P.D0 + d0) * D1 + lb) * P.D3) + d3) * 2) : (unsigned)OOB;
+        if constexpr (D1 == 4)
+            b_voff = J < P.cols ? (unsigned)((((J >> 3) * P.D0 + d0) * D1 + (lb & 3)) * 16) : (unsigned)OOB;
+        else
+            b_voff = J < P.cols ? (unsigned)(((((m * P.D0 + d0) * D1 + lb) * P.D3) + d3) * 2) : (unsigned)OOB;
+        // 4-row capsules: a copy's 8 lines are two pixels; all ones in the lanes of the second
+        pair_hi = -(int)(la >> 2);
     } else {
         const int R = row_tile * BM + wave * 64 + lane;
         const int c = R / P.D2, d2 = R - c * P.D2;
@@ -295,13 +311,27 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     };
     auto copy_a = [&](auto SLOT, auto KC) {
         constexpr int slot = decltype(SLOT)::value, kc = decltype(KC)::value;
-        copy_to_lds_16B<slot * STAGE_BYTES + kc * BM * 16>(rs_it, lds_a, a_voff, a_soff[kc / D1C],
-                                                           (kc % D1C) * a_half);
+        if constexpr (D1 == 4) {
+            // the pixel's offset travels in the lane offset (an out-of-range mark in either
+            // pixel keeps that pixel's lanes out of range)
+            const int lo = a_soff[2 * kc], hi = a_soff[2 * kc + 1];
+            const unsigned v = a_voff + (unsigned)lo + ((unsigned)(hi - lo) & (unsigned)pair_hi);
+            copy_to_lds_16B<slot * STAGE_BYTES + kc * BM * 16>(rs_it, lds_a, v, 0, 0);
+        } else {
+            copy_to_lds_16B<slot * STAGE_BYTES + kc * BM * 16>(rs_it, lds_a, a_voff, a_soff[kc / D1C],
+                                                               (kc % D1C) * a_half);
+        }
     };
     auto copy_b = [&](auto SLOT, auto KC) {
         constexpr int slot = decltype(SLOT)::value, kc = decltype(KC)::value;
-        copy_to_lds_16B<slot * STAGE_BYTES + kc * BN * 16>(rs_gt, lds_b, b_voff, g_soff[kc / D1C],
-                                                           (kc % D1C) * b_half);
+        if constexpr (D1 == 4) {
+            const int lo = g_soff[2 * kc], hi = g_soff[2 * kc + 1];
+            const unsigned v = b_voff + (unsigned)lo + ((unsigned)(hi - lo) & (unsigned)pair_hi);
+            copy_to_lds_16B<slot * STAGE_BYTES + kc * BN * 16>(rs_gt, lds_b, v, 0, 0);
+        } else {
+            copy_to_lds_16B<slot * STAGE_BYTES + kc * BN * 16>(rs_gt, lds_b, b_voff, g_soff[kc / D1C],
+                                                               (kc % D1C) * b_half);
+        }
     };
     // operand fragment f of k-step t from ring slot: f < TN column side (Gt), else row side (It)
     auto read_frag = [&](int slot, int t, int f) -> chunk_t {
@@ -368,9 +398,12 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
         // other way round (config 5: 2 % slower in the second halves)
         constexpr int four[16] = {8, 9, 10, 11, 12, 13, 14, 15, 24, 25, 26, 27, 28, 29, 30, 31};
         constexpr int two[8] = {7, 8, 9, 11, 15, 16, 17, 19};
-        return PPS == 4 ? four[q] : two[q];
+        // eight pixels: 32 pieces spread over gaps 3 .. 29; pixel j's first piece falls after the
+        // Gt copy of chunk j / 2 (gap 4 (j / 2) + 2) and before the It copy of that chunk (gap
+        // 18 + 4 (j / 2))
+        return PPS == 8 ? 3 + q * 27 / 32 : PPS == 4 ? four[q] : two[q];
     };
-    static_assert(PPS == 4 || PPS == 2, "the walk's schedule is written for these stage shapes");
+    static_assert(PPS == 8 || PPS == 4 || PPS == 2, "the walk's schedule is written for these stage shapes");
     for (int st = 0; st < nstages_pad; st += NB) {
         static_for<NB>([&](auto SLOT) {
             constexpr int slot = decltype(SLOT)::value;
@@ -465,7 +498,7 @@ WgradPlan make_plan(const ConvShape& s)
     long long imgs_cap = ((1LL << 31) - 1) / (img_max > 0 ? img_max : 1);
     if (imgs_cap > s.N) imgs_cap = s.N;
     const double pix_per_img = (double)s.Ho * s.Wo;
-    const double fixed = s.D1 == 16 ? 70.0 : 140.0;
+    const double fixed = s.D1 == 16 ? 70.0 : s.D1 == 8 ? 140.0 : 280.0;
     double best = 0;
     int best_imgs = (int)imgs_cap;
     for (int imgs = (int)imgs_cap; imgs >= 1; --imgs) {
@@ -518,9 +551,11 @@ hipError_t launch_kernel(const WgradParams& P, hipStream_t stream)
 bool wgrad16_eligible(const ConvShape& s)
 {
     if (s.dtype != 1 && s.dtype != 2) return false;
-    if (s.D1 != 8 && s.D1 != 16) return false;
+    // 4x4 capsules with even channel counts run on channel-paired copies of both tensors
+    const bool paired = s.D1 == 4 && s.D2 == 4 && s.D3 == 4 && s.C % 2 == 0 && s.M % 2 == 0;
+    if (s.D1 != 8 && s.D1 != 16 && !paired) return false;
     if (s.D3 % 4 != 0) return false;
-    if ((s.D1 / 8) * s.D2 > 256 || (s.D1 / 8) * s.D3 > 256) return false;  // the transpose's tile
+    if (!paired && ((s.D1 / 8) * s.D2 > 256 || (s.D1 / 8) * s.D3 > 256)) return false;  // the transpose's tile
     // 31-bit byte offsets within one image of either tensor, 31-bit row/column/pixel counts
     const long long it_img = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 2;
     const long long gt_img = (long long)s.Ho * s.Wo * s.M * s.D0 * s.D1 * s.D3 * 2;
@@ -535,12 +570,13 @@ bool wgrad16_eligible(const ConvShape& s)
 
 // Both tensors can be read as they lie in memory when 8 consecutive rows (c, d2) and columns
 // (m, d3) of a line are one aligned 16-byte chunk.
-static bool reads_in_place(const ConvShape& s) { return s.D2 % 8 == 0 && s.D3 % 8 == 0; }
+static bool reads_in_place(const ConvShape& s) { return s.D1 >= 8 && s.D2 % 8 == 0 && s.D3 % 8 == 0; }
 
 size_t wgrad16_workspace_bytes(const ConvShape& s)
 {
     const WgradPlan pl = make_plan(s);
     if (reads_in_place(s)) return pl.partial_bytes;
+    // transposed copies, or (4x4 capsules) channel-paired ones, of both tensors
     return align256(pl.it_bytes) + align256(pl.gt_bytes) + pl.partial_bytes;
 }
 
@@ -556,6 +592,18 @@ hipError_t launch_wgrad16(const ConvShape& s, const void* input, const void* dou
         pl.P.it = input;
         pl.P.gt = dout;
         partial = reinterpret_cast<float*>(ws);
+    } else if (s.D1 == 4) {
+        // 4x4 capsules: [pixel][c/2][d0][d1][c%2][d2], so that 8 consecutive rows (c, d2) of a line
+        // are one 16-byte chunk; the kernel then reads them like tensors it takes in place
+        void* it = ws;
+        void* gt = ws + align256(pl.it_bytes);
+        partial = reinterpret_cast<float*>(ws + align256(pl.it_bytes) + align256(pl.gt_bytes));
+        err = launch_pair_channels(input, it, (size_t)s.N * s.H * s.W, s.C, s.D0 * s.D1, stream);
+        if (err != hipSuccess) return err;
+        err = launch_pair_channels(dout, gt, (size_t)s.N * s.Ho * s.Wo, s.M, s.D0 * s.D1, stream);
+        if (err != hipSuccess) return err;
+        pl.P.it = it;
+        pl.P.gt = gt;
     } else {
         void* it = ws;
         void* gt = ws + align256(pl.it_bytes);
@@ -568,7 +616,10 @@ hipError_t launch_wgrad16(const ConvShape& s, const void* input, const void* dou
         pl.P.gt = gt;
     }
     pl.P.out = pl.P.nsplit > 1 ? partial : dkernel;
-    if (s.dtype == 2) {
+    if (s.D1 == 4) {
+        err = s.dtype == 2 ? launch_kernel<f16_tag, 4, true>(pl.P, stream)
+                           : launch_kernel<bf16_tag, 4, true>(pl.P, stream);
+    } else if (s.dtype == 2) {
         if (own)
             err = s.D1 == 16 ? launch_kernel<f16_tag, 16, true>(pl.P, stream)
                              : launch_kernel<f16_tag, 8, true>(pl.P, stream);
