@@ -78,10 +78,11 @@ extern "C" {
 #define CAPSCAPS_PATH_MFMA_TUNED16 4 /* ... the 256x256-tile variant for 16-bit types with
                                         D1 = D2 in {8, 16}; other shapes: CAPSCAPS_EUNSUPPORTED */
 #define CAPSCAPS_PATH_MFMA_TUNED32 5 /* ... the lane-per-row variant with direct-to-LDS copies:
-                                        fp32 capsule rows of 3, 4, 6, 8, 12 or 16 floats, and
-                                        16-bit capsule rows of 4 elements (4x4 capsules) with an
-                                        even number of input channels, whose channels a pre-pass
-                                        pairs in `workspace`; other shapes:
+                                        fp32 capsule rows of 3, 4, 6, 8, 12 or 16 floats; 16-bit
+                                        rows of 8, 16 or 32 elements (any D1, D3: non-square and
+                                        vector capsules), and of 4 elements (4x4 capsules) with
+                                        an even number of input channels, whose channels a
+                                        pre-pass pairs in `workspace`; other shapes:
                                         CAPSCAPS_EUNSUPPORTED */
 #define CAPSCAPS_PATH_MFMA_SMALL 6   /* ... the variant for small problems (a few thousand output
                                         rows, the fully-connected layer): one launch, kernel

@@ -17,8 +17,11 @@
 // 4 chunks per stage, ring of 3 LDS stages, one barrier per stage; the K loop can be split over
 // blocks (partial sums are reduced in a fixed order by the caller's reduce kernel).
 //
-// The same kernel serves 16-bit capsules with rows of 4 elements (4x4 capsules), which no
-// 16-byte copy can stage as they lie in memory: the 8 K values a 16-bit matrix instruction takes
+// The same kernel serves 16-bit operands (one MFMA 32x32x16 per chunk pair and tile instead of CW
+// fp32 ones).  Capsule rows of 8, 16 or 32 halves are, in units of 4 bytes, rows of 4, 8 or 16
+// "floats": nothing else changes (any D1 and D3: non-square and vector capsules, which the
+// 256x256-tile 16-bit kernel does not take).  Rows of 4 halves (4x4 capsules) no 16-byte copy can
+// stage as they lie in memory: the 8 K values a 16-bit matrix instruction takes
 // per lane are the rows of two channels, 32 bytes apart.  A pre-pass (pair_channels_kernel, at
 // HBM speed) writes the input with channels paired, [pixel][c/2][d0][d1][c%2][d2]; in units of
 // 4 bytes that is an fp32 layer with half the channels and rows of 4 "floats", so every offset
@@ -374,9 +377,14 @@ inline int ceil_div_ll(long long a, long long b) { return (int)((a + b - 1) / b)
 // the 4 chunks of a stage never split a row); 0 if neither fits.
 int igemm32_dma_chunk_width(const ConvShape& s)
 {
-    // 16-bit operands: capsule rows of 4 halves and an even number of channels, which a pre-pass
-    // pairs so that a chunk is (c, c+1) x 4 halves = "4 floats"; fp32 output only
-    if (s.dtype != 0) return s.D2 == 4 && s.C % 2 == 0 && s.out16 == 0 ? 4 : 0;
+    // 16-bit operands, fp32 output only: capsule rows of 8, 16 or 32 halves are rows of 4, 8 or 16
+    // "floats" as they lie in memory; rows of 4 halves need an even number of channels, which a
+    // pre-pass pairs so that a chunk is (c, c+1) x 4 halves
+    if (s.dtype != 0) {
+        if (s.out16 != 0) return 0;
+        if (s.D2 == 8 || s.D2 == 16 || s.D2 == 32) return 4;
+        return s.D2 == 4 && s.C % 2 == 0 ? 4 : 0;
+    }
     for (int cw : {4, 3}) {
         if (s.D2 % cw) continue;
         const int d2c = s.D2 / cw;
@@ -415,9 +423,10 @@ Dma32Plan igemm32_dma_plan(const ConvShape& s)
     pl.dtype = s.dtype;
     // 16-bit operands: in units of 4 bytes the channel-paired input is an fp32 layer with half
     // the channels and capsule rows of 4 "floats"
-    const int C = s.dtype == 0 ? s.C : s.C / 2;
-    const int D2 = s.dtype == 0 ? s.D2 : 4;
-    pl.pair_bytes = s.dtype == 0 ? 0 : (size_t)s.in_elems() * 2;
+    const bool paired = s.dtype != 0 && s.D2 == 4;
+    const int C = paired ? s.C / 2 : s.C;
+    const int D2 = s.dtype == 0 ? s.D2 : paired ? 4 : s.D2 / 2;
+    pl.pair_bytes = paired ? (size_t)s.in_elems() * 2 : 0;
     P.H = s.H; P.W = s.W; P.C = C; P.M = s.M; P.stride = s.stride; P.pad = s.pad;
     P.pad_w = s.padw();
     P.out_view = s.out_view ? 1 : 0;
@@ -483,6 +492,15 @@ bool igemm32_dma_preferred(const ConvShape& s)
     if (!igemm32_dma_eligible(s)) return false;
     // measured on MI355X: 1.8x faster than the generic kernel on config 2 (many 256-row tiles);
     // on problems so small that the K loop is split the generic kernel's 64x64 tiles win
+    // 16-bit: square capsules of 8 or 16 rows belong to the 256x256-tile kernel, which is 1.12 ..
+    // 1.17x faster on whole column tiles (configs 3 and 5: 0.92 against 1.03 ms, 14.2 against
+    // 16.6 ms) -- unless its 256-column tiles pad the columns much further than this kernel's
+    // 128-column ones (320 or 384 columns: this kernel 14 % and 7 % faster)
+    if (s.dtype != 0 && igemm16_fast_preferred(s)) {
+        const long long cols = (long long)s.M * s.D3;
+        const long long pad256 = (cols + 255) / 256 * 256, pad128 = (cols + 127) / 128 * 128;
+        if (pad256 * 100 < pad128 * 115) return false;
+    }
     const Dma32Plan pl = igemm32_dma_plan(s);
     return pl.nw == 4 && pl.P.nsplit == 1;
 }

@@ -114,12 +114,21 @@ PAIRED16_SHAPES = [
     ("p4k1", 2, 9, 9, 16, 12, 1, 1, 3, 0, 1, 4, 4, 4),
     ("p4fc", 5, 4, 3, 6, 7, 4, 3, 1, 0, 1, 4, 4, 4),
     ("p4pad", 1, 3, 3, 2, 2, 3, 3, 2, 3, 1, 4, 4, 4),
+    # ... and rows of 8, 16 and 32 elements, which it takes as they lie in memory: square and
+    # non-square capsules, vector capsules (one row), odd channel counts
+    ("r8sq", 1, 12, 11, 8, 9, 3, 3, 2, 2, 1, 8, 8, 8),
+    ("r16sq", 1, 6, 7, 4, 5, 3, 3, 1, 1, 1, 16, 16, 16),
+    ("r16mix", 2, 5, 6, 3, 7, 1, 1, 1, 0, 2, 4, 16, 8),
+    ("r8tall", 2, 6, 6, 5, 3, 3, 2, 1, 0, 1, 5, 8, 4),
+    ("r8vec", 2, 9, 8, 7, 5, 3, 3, 1, 1, 1, 1, 8, 16),
+    ("r32", 1, 5, 6, 3, 4, 2, 2, 1, 0, 1, 2, 32, 4),
+    ("r8rows", 4, 20, 20, 4, 20, 3, 3, 1, 1, 1, 8, 8, 8),
 ]
 
 
 @pytest.mark.parametrize("dtype", [wl.BF16, wl.FP16], ids=["bf16", "fp16"])
 @pytest.mark.parametrize("shape", PAIRED16_SHAPES, ids=[s[0] for s in PAIRED16_SHAPES])
-def test_lane_per_row_kernel_on_16bit_rows_of_4(shape, dtype):
+def test_lane_per_row_kernel_on_16bit_operands(shape, dtype):
     w = small(shape[0], dtype, *shape[1:], seed=len(shape[0]) + 75)
     full_compare(w, PATHS["tuned32"])
     wi = small(shape[0] + "_int", dtype, *shape[1:], dist="int", seed=76)
@@ -265,8 +274,6 @@ def test_benchmark_configs_reduced_full_tensor(num, batch, hw, path):
     w = dataclasses.replace(w, N=batch, H=hw, W=hw, name=f"{w.name}[N={batch},HW={hw}]")
     if path == "tuned16" and w.dtype == wl.FP32:
         pytest.skip("the tuned 16-bit kernel is for 16-bit element types")
-    if path == "tuned32" and w.dtype != wl.FP32:
-        pytest.skip("the tuned fp32 kernel is for fp32")
     full_compare(w, PATHS[path])
 
 
