@@ -48,10 +48,15 @@ constexpr int ring_depth(int kch, int tn, int nw) { return kch == 2 && waves_per
 // (pair_channels_kernel): a 16-byte chunk then holds the 8 K values (c, c+1) x d2 of one row, all
 // offsets are those of an fp32 layer with half the channels and rows of 4 floats, and a chunk pair
 // feeds one 16-bit MFMA 32x32x16 per tile instead of CW fp32 ones.
-template <typename Tag, int CW, int TN, int NW, int KCH>
+// OUT16 (16-bit operands only): the output has the operands' type, rounded at the store.
+template <typename Tag, int CW, int TN, int NW, int KCH, bool OUT16 = false>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(waves_per_simd(TN, NW, KCH)))) void igemm32_dma_kernel(const Dma32Params P)
 {
     constexpr bool F32 = std::is_same<Tag, f32_tag>::value;
+    static_assert(!(F32 && OUT16), "fp32 operands have fp32 output");
+    // a compile-time constant: with the choice made at run time the register allocator fails
+    // to keep the copies' buffer descriptors in scalar registers
+    constexpr int o16 = !OUT16 ? 0 : std::is_same<Tag, f16_tag>::value ? 2 : 1;
     static_assert(F32 || CW == 4, "16-bit chunks are whole 16-byte slots");
     constexpr int NB = ring_depth(KCH, TN, NW);
     constexpr int BM = 64 * NW, BN = 32 * TN, BNL = (BN + 63) / 64 * 64, TM = 2;
@@ -270,6 +275,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(waves_p
 
     // ---- epilogue: lane (h, lr) of tile (a, b) holds in registers 4g..4g+3 the columns
     // 8g + 4h + 0..3 of the tile for output row lr of the tile
+    // (partial sums of a split K loop are fp32; the reduction rounds)
     float* __restrict__ out = P.out + (long long)split * P.out_elems;
     const int caps_out = P.D0 * P.D1 * P.D3;
     const bool st4 = (P.D3 & 3) == 0;
@@ -280,13 +286,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(waves_p
         const long long pixel = orow / P.D1;
         const int d1 = (int)(orow % P.D1);
         long long pix_at = pixel * P.M * caps_out;
-        if (P.out_view) {
+        if (P.out_mode & 1) {
             const long long n = pixel / hw;
             const int rem = (int)(pixel - n * hw);
             const int x = rem / P.Wo, y = rem - x * P.Wo;
             pix_at = P.out_base + n * P.out_sn + x * P.out_sx + y * P.out_sy;
         }
-        float* orow_ptr = out + pix_at + (long long)(d0 * P.D1 + d1) * P.D3;
+        const long long orow_off = pix_at + (long long)(d0 * P.D1 + d1) * P.D3;
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
 #pragma unroll
@@ -297,7 +303,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(waves_p
                         const int m = j0 / P.D3, d3 = j0 - m * P.D3;
                         float4v v = {acc[a][b][4 * g], acc[a][b][4 * g + 1], acc[a][b][4 * g + 2],
                                      acc[a][b][4 * g + 3]};
-                        *reinterpret_cast<float4v*>(orow_ptr + (long long)m * caps_out + d3) = v;
+                        if constexpr (F32)
+                            *reinterpret_cast<float4v*>(out + orow_off + (long long)m * caps_out + d3) = v;
+                        else
+                            store4(out, orow_off + (long long)m * caps_out + d3, v, o16);
                     }
                 } else {
 #pragma unroll
@@ -307,7 +316,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(waves_p
                             // j / D3 by multiplication (exact while j * D3 < 2^32, which the host has checked)
                             const int m = P.d3_magic ? (int)__umulhi((unsigned)j, P.d3_magic) : j / P.D3;
                             const int d3 = j - m * P.D3;
-                            orow_ptr[(long long)m * caps_out + d3] = acc[a][b][4 * g + u];
+                            if constexpr (F32)
+                                out[orow_off + (long long)m * caps_out + d3] = acc[a][b][4 * g + u];
+                            else
+                                store1(out, orow_off + (long long)m * caps_out + d3, acc[a][b][4 * g + u], o16);
                         }
                     }
                 }
@@ -316,11 +328,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(waves_p
     }
 }
 
-template <typename Tag, int CW, int TN, int NW, int KCH>
+template <typename Tag, int CW, int TN, int NW, int KCH, bool OUT16 = false>
 hipError_t launch_kch(const Dma32Params& P, long long blocks, hipStream_t stream)
 {
     constexpr int BM = 64 * NW, BNL = (32 * TN + 63) / 64 * 64;
-    auto kern = igemm32_dma_kernel<Tag, CW, TN, NW, KCH>;
+    auto kern = igemm32_dma_kernel<Tag, CW, TN, NW, KCH, OUT16>;
     const size_t lds_bytes = (size_t)ring_depth(KCH, TN, NW) * KCH * (BM + BNL) * 16;
     static std::atomic<unsigned long long> lds_set{0};
     hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes, lds_set);
@@ -337,6 +349,11 @@ hipError_t launch_one(const Dma32Params& P, long long blocks, hipStream_t stream
     // per tile)
     if constexpr (std::is_same<Tag, f32_tag>::value && (2 * ((32 * TN + 63) / 64)) % NW == 0) {
         if (P.kch == 2) return launch_kch<Tag, CW, TN, NW, 2>(P, blocks, stream);
+    }
+    if constexpr (!std::is_same<Tag, f32_tag>::value) {
+        // 16-bit output straight from the kernel unless a split K loop leaves fp32 partial sums
+        if ((P.out_mode >> 1) != 0 && P.nsplit == 1)
+            return launch_kch<Tag, CW, TN, NW, 4, true>(P, blocks, stream);
     }
     return launch_kch<Tag, CW, TN, NW, 4>(P, blocks, stream);
 }
@@ -377,11 +394,10 @@ inline int ceil_div_ll(long long a, long long b) { return (int)((a + b - 1) / b)
 // the 4 chunks of a stage never split a row); 0 if neither fits.
 int igemm32_dma_chunk_width(const ConvShape& s)
 {
-    // 16-bit operands, fp32 output only: capsule rows of 8, 16 or 32 halves are rows of 4, 8 or 16
-    // "floats" as they lie in memory; rows of 4 halves need an even number of channels, which a
-    // pre-pass pairs so that a chunk is (c, c+1) x 4 halves
+    // 16-bit operands: capsule rows of 8, 16 or 32 halves are rows of 4, 8 or 16 "floats" as they
+    // lie in memory; rows of 4 halves need an even number of channels, which a pre-pass pairs so
+    // that a chunk is (c, c+1) x 4 halves
     if (s.dtype != 0) {
-        if (s.out16 != 0) return 0;
         if (s.D2 == 8 || s.D2 == 16 || s.D2 == 32) return 4;
         return s.D2 == 4 && s.C % 2 == 0 ? 4 : 0;
     }
@@ -429,7 +445,7 @@ Dma32Plan igemm32_dma_plan(const ConvShape& s)
     pl.pair_bytes = paired ? (size_t)s.in_elems() * 2 : 0;
     P.H = s.H; P.W = s.W; P.C = C; P.M = s.M; P.stride = s.stride; P.pad = s.pad;
     P.pad_w = s.padw();
-    P.out_view = s.out_view ? 1 : 0;
+    P.out_mode = (s.out_view ? 1 : 0) | (s.out16 << 1);
     P.out_base = s.out_base; P.out_sn = s.out_sn; P.out_sx = s.out_sx; P.out_sy = s.out_sy;
     P.D0 = s.D0; P.D1 = s.D1; P.D2 = D2; P.D3 = s.D3; P.Ho = s.Ho; P.Wo = s.Wo;
     P.kh = s.kh; P.kw = s.kw; P.ntaps = s.kh * s.kw;

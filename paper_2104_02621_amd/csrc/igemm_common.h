@@ -143,8 +143,10 @@ struct Dma32Params {
     float* out;  // final output, or split-K partial buffers [split][out_elems]
     int H, W, C, M, stride, pad, D0, D1, D2, D3, Ho, Wo, kh, kw, ntaps;
     int pad_w;     // padding of the columns (pad: of the rows); either may be negative
-    // out_view: output pixel (n, x, y) begins at element out_base + n*out_sn + x*out_sx + y*out_sy
-    int out_view;
+    // out_mode bit 0 ("view"): output pixel (n, x, y) begins at element out_base + n*out_sn +
+    // x*out_sx + y*out_sy; bits 1..2: 0 = fp32 output, 1 / 2 = bf16 / fp16 output (rounded at the
+    // store).  One field: the kernel has no scalar register to spare.
+    int out_mode;
     long long out_base, out_sn, out_sx, out_sy;
     long long rows, out_elems, pixsz, in_bytes, kp_bytes;
     int cs;        // D0*D1*D2: input channel stride (elements)

@@ -628,7 +628,8 @@ hipError_t launch_dma32(const ConvShape& s, const void* in, const void* kernel, 
     if (err != hipSuccess) return err;
     err = launch_igemm32_dma(pl, stream);
     if (err != hipSuccess) return err;
-    if (pl.P.nsplit > 1) err = launch_splitk_reduce(partial, out, pl.P.out_elems, pl.P.nsplit, stream);
+    if (pl.P.nsplit > 1)
+        err = launch_splitk_reduce(partial, out, pl.P.out_elems, pl.P.nsplit, stream, s.out16);
     return err;
 }
 
@@ -688,7 +689,7 @@ size_t mfma_workspace_bytes(const ConvShape& s)
     if (s.out16 != 0) {
         // 16-bit output is offered with the library's own kernel choice only
         const MfmaKernel which = mfma_auto_kernel(s);
-        if (which == MfmaKernel::Dma32) return 0;  // fp32 operands: not a 16-bit-output shape
+        if (which == MfmaKernel::Dma32) return dma32_workspace_bytes(igemm32_dma_plan(s));
         if (which == MfmaKernel::Small) return igemm_small_workspace_bytes(s);
         const Plan pl = make_plan(s, which);
         return ((pl.repack_bytes + 255) & ~(size_t)255) + pl.partial_bytes;
@@ -714,7 +715,6 @@ size_t mfma_auto_workspace_bytes(const ConvShape& s)
     const MfmaKernel which = mfma_auto_kernel(s);
     if (which == MfmaKernel::Small) return igemm_small_workspace_bytes(s);
     if (which == MfmaKernel::Dma32) {
-        if (s.out16 != 0) return 0;
         return dma32_workspace_bytes(igemm32_dma_plan(s));
     }
     const Plan pl = make_plan(s, which);

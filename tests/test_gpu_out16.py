@@ -81,13 +81,24 @@ def check_out16(w, ref=None, S=None, sample=None, exact_order=True):
     assert worst <= 1.0, w.name
 
 
-SHAPES = SMALL_SHAPES + TUNED_SHAPES
+# enough rows for the lane-per-row kernel to be the library's choice: 4x4 capsules (channels
+# paired by a pre-pass), non-square capsules, and square ones on 384 columns
+LANE_PER_ROW_SHAPES = [
+    #        N  H   W   C   M  kh kw s  p D0  D1  D2  D3
+    ("o4x4", 12, 40, 40, 8, 8, 3, 3, 1, 1, 1, 4, 4, 4),
+    ("o4x8", 12, 40, 40, 6, 5, 3, 3, 1, 1, 1, 4, 8, 16),
+    ("o384", 6, 40, 40, 8, 48, 3, 3, 1, 1, 1, 8, 8, 8),
+]
+SHAPES = SMALL_SHAPES + TUNED_SHAPES + LANE_PER_ROW_SHAPES
 
 
 @pytest.mark.parametrize("dtype", [wl.BF16, wl.FP16], ids=["bf16", "fp16"])
 @pytest.mark.parametrize("shape", SHAPES, ids=[s[0] for s in SHAPES])
 def test_small_shapes(shape, dtype):
-    check_out16(small(shape[0], dtype, *shape[1:], seed=len(shape[0]) + 120))
+    w = small(shape[0], dtype, *shape[1:], seed=len(shape[0]) + 120)
+    if shape in LANE_PER_ROW_SHAPES:
+        assert cc.capscaps_select_path(*shape_args(w)) == cc.PATH_MFMA_TUNED32
+    check_out16(w)
 
 
 @pytest.mark.parametrize("number", [3, 5])
