@@ -341,19 +341,23 @@ hipError_t launch_kch(const Dma32Params& P, long long blocks, hipStream_t stream
     return hipGetLastError();
 }
 
-// 2-chunk stages where the column copies still divide over the waves
+// 2-chunk stages where the column copies still divide over the waves; 16-bit output straight from
+// the kernel (16-bit operands) unless a split K loop leaves fp32 partial sums for the reduction
 template <typename Tag, int CW, int TN, int NW>
 hipError_t launch_one(const Dma32Params& P, long long blocks, hipStream_t stream)
 {
-    // 16-bit operands always take 4-chunk stages (a 2-chunk stage is a single matrix instruction
-    // per tile)
-    if constexpr (std::is_same<Tag, f32_tag>::value && (2 * ((32 * TN + 63) / 64)) % NW == 0) {
-        if (P.kch == 2) return launch_kch<Tag, CW, TN, NW, 2>(P, blocks, stream);
+    constexpr bool F32 = std::is_same<Tag, f32_tag>::value;
+    const bool o16 = !F32 && (P.out_mode >> 1) != 0 && P.nsplit == 1;
+    if constexpr ((2 * ((32 * TN + 63) / 64)) % NW == 0) {
+        if (P.kch == 2) {
+            if constexpr (!F32) {
+                if (o16) return launch_kch<Tag, CW, TN, NW, 2, true>(P, blocks, stream);
+            }
+            return launch_kch<Tag, CW, TN, NW, 2>(P, blocks, stream);
+        }
     }
-    if constexpr (!std::is_same<Tag, f32_tag>::value) {
-        // 16-bit output straight from the kernel unless a split K loop leaves fp32 partial sums
-        if ((P.out_mode >> 1) != 0 && P.nsplit == 1)
-            return launch_kch<Tag, CW, TN, NW, 4, true>(P, blocks, stream);
+    if constexpr (!F32) {
+        if (o16) return launch_kch<Tag, CW, TN, NW, 4, true>(P, blocks, stream);
     }
     return launch_kch<Tag, CW, TN, NW, 4>(P, blocks, stream);
 }
@@ -465,8 +469,9 @@ Dma32Plan igemm32_dma_plan(const ConvShape& s)
     }
     // chunks per stage: 2 for the four-wave tile with wide column tiles and short capsule rows
     // (measured on config 2: 0.955 ms against 0.987 ms), else 4
-    // (16-bit: 8-chunk stages, one workgroup per CU, measured 22 % slower than 4-chunk ones)
-    const int KCH = (s.dtype == 0 && pl.nw == 4 && pl.tn >= 3 && P.D2C <= 2) ? 2 : 4;
+    // (16-bit: 8-chunk stages, one workgroup per CU, measured 22 % slower than 4-chunk ones; 2-chunk
+    // stages 4 .. 5 % faster, as for fp32)
+    const int KCH = (pl.nw == 4 && pl.tn >= 3 && P.D2C <= 2) ? 2 : 4;
     P.kch = KCH;
     const int groups = (KK + KCH - 1) / KCH;
     pl.kqp = groups * KCH;
