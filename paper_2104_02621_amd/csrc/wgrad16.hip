@@ -191,7 +191,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     // ---- per-lane constants: byte offset of the lane's row (column) within a pixel, or the
     // out-of-range mark for rows (columns) past the end: those copy zeros
     unsigned a_voff, b_voff;
-    int pair_hi = 0;
+    int pair_hi_a = 0, pair_hi_b = 0;
     // OWN: place of chunk (line l8, chunk column r8) in its unit, and back.  `wide`: two chunk
     // columns per capsule row (capsule width a multiple of 16), else one.
     auto unit_slot = [](bool wide, int l8, int r8) {
@@ -204,20 +204,29 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
         const int la = (a_wide ? (lane & 15) >> 1 : lane & 7) ^ (((ra >> 1) & 1) * 4);
         const int R = row_tile * BM + (wave * 8 + ra) * 8;
         const int c = R / P.D2, d2 = R - c * P.D2;
-        if constexpr (D1 == 4)  // channel-paired tensor: chunk R / 8 of line la % 4 (la / 4: which pixel)
-            a_voff = R < P.rows ? (unsigned)((((R >> 3) * P.D0 + d0) * D1 + (la & 3)) * 16) : (unsigned)OOB;
-        else
+        if constexpr (D1 == 4) {
+            // line la % 4 of the pixel (la / 4: which of the copy's two pixels); 4x4 capsules:
+            // channel-paired tensor, chunk R / 8 of the line is 16 bytes of its own
+            if (P.D2 == 4)
+                a_voff = R < P.rows ? (unsigned)((((R >> 3) * P.D0 + d0) * D1 + (la & 3)) * 16) : (unsigned)OOB;
+            else
+                a_voff = R < P.rows ? (unsigned)(((((c * P.D0 + d0) * D1 + (la & 3)) * P.D2) + d2) * 2) : (unsigned)OOB;
+        } else
             a_voff = R < P.rows ? (unsigned)(((((c * P.D0 + d0) * D1 + la) * P.D2) + d2) * 2) : (unsigned)OOB;
         const int rb = b_wide ? (lane >> 4) * 2 + (lane & 1) : lane >> 3;
         const int lb = (b_wide ? (lane & 15) >> 1 : lane & 7) ^ (((rb >> 1) & 1) * 4);
         const int J = col_tile * BN + (wave * 8 + rb) * 8;
         const int m = J / P.D3, d3 = J - m * P.D3;
-        if constexpr (D1 == 4)
-            b_voff = J < P.cols ? (unsigned)((((J >> 3) * P.D0 + d0) * D1 + (lb & 3)) * 16) : (unsigned)OOB;
-        else
+        if constexpr (D1 == 4) {
+            if (P.D3 == 4)
+                b_voff = J < P.cols ? (unsigned)((((J >> 3) * P.D0 + d0) * D1 + (lb & 3)) * 16) : (unsigned)OOB;
+            else
+                b_voff = J < P.cols ? (unsigned)(((((m * P.D0 + d0) * D1 + (lb & 3)) * P.D3) + d3) * 2) : (unsigned)OOB;
+        } else
             b_voff = J < P.cols ? (unsigned)(((((m * P.D0 + d0) * D1 + lb) * P.D3) + d3) * 2) : (unsigned)OOB;
         // 4-row capsules: a copy's 8 lines are two pixels; all ones in the lanes of the second
-        pair_hi = -(int)(la >> 2);
+        pair_hi_a = -(int)(la >> 2);
+        pair_hi_b = -(int)(lb >> 2);
     } else {
         const int R = row_tile * BM + wave * 64 + lane;
         const int c = R / P.D2, d2 = R - c * P.D2;
@@ -315,7 +324,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
             // the pixel's offset travels in the lane offset (an out-of-range mark in either
             // pixel keeps that pixel's lanes out of range)
             const int lo = a_soff[2 * kc], hi = a_soff[2 * kc + 1];
-            const unsigned v = a_voff + (unsigned)lo + ((unsigned)(hi - lo) & (unsigned)pair_hi);
+            const unsigned v = a_voff + (unsigned)lo + ((unsigned)(hi - lo) & (unsigned)pair_hi_a);
             copy_to_lds_16B<slot * STAGE_BYTES + kc * BM * 16>(rs_it, lds_a, v, 0, 0);
         } else {
             copy_to_lds_16B<slot * STAGE_BYTES + kc * BM * 16>(rs_it, lds_a, a_voff, a_soff[kc / D1C],
@@ -326,7 +335,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
         constexpr int slot = decltype(SLOT)::value, kc = decltype(KC)::value;
         if constexpr (D1 == 4) {
             const int lo = g_soff[2 * kc], hi = g_soff[2 * kc + 1];
-            const unsigned v = b_voff + (unsigned)lo + ((unsigned)(hi - lo) & (unsigned)pair_hi);
+            const unsigned v = b_voff + (unsigned)lo + ((unsigned)(hi - lo) & (unsigned)pair_hi_b);
             copy_to_lds_16B<slot * STAGE_BYTES + kc * BN * 16>(rs_gt, lds_b, v, 0, 0);
         } else {
             copy_to_lds_16B<slot * STAGE_BYTES + kc * BN * 16>(rs_gt, lds_b, b_voff, g_soff[kc / D1C],
@@ -552,10 +561,13 @@ bool wgrad16_eligible(const ConvShape& s)
 {
     if (s.dtype != 1 && s.dtype != 2) return false;
     // 4x4 capsules with even channel counts run on channel-paired copies of both tensors
+    // ... and 4-row capsules whose widths are multiples of 8 are read in place
     const bool paired = s.D1 == 4 && s.D2 == 4 && s.D3 == 4 && s.C % 2 == 0 && s.M % 2 == 0;
-    if (s.D1 != 8 && s.D1 != 16 && !paired) return false;
+    const bool four_in_place = s.D1 == 4 && s.D2 % 8 == 0 && s.D3 % 8 == 0;
+    if (s.D1 != 8 && s.D1 != 16 && !paired && !four_in_place) return false;
     if (s.D3 % 4 != 0) return false;
-    if (!paired && ((s.D1 / 8) * s.D2 > 256 || (s.D1 / 8) * s.D3 > 256)) return false;  // the transpose's tile
+    if (!paired && !four_in_place && ((s.D1 / 8) * s.D2 > 256 || (s.D1 / 8) * s.D3 > 256))
+        return false;  // the transpose's tile
     // 31-bit byte offsets within one image of either tensor, 31-bit row/column/pixel counts
     const long long it_img = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 2;
     const long long gt_img = (long long)s.Ho * s.Wo * s.M * s.D0 * s.D1 * s.D3 * 2;
@@ -570,7 +582,7 @@ bool wgrad16_eligible(const ConvShape& s)
 
 // Both tensors can be read as they lie in memory when 8 consecutive rows (c, d2) and columns
 // (m, d3) of a line are one aligned 16-byte chunk.
-static bool reads_in_place(const ConvShape& s) { return s.D1 >= 8 && s.D2 % 8 == 0 && s.D3 % 8 == 0; }
+static bool reads_in_place(const ConvShape& s) { return s.D2 % 8 == 0 && s.D3 % 8 == 0; }
 
 size_t wgrad16_workspace_bytes(const ConvShape& s)
 {
@@ -616,7 +628,7 @@ hipError_t launch_wgrad16(const ConvShape& s, const void* input, const void* dou
         pl.P.gt = gt;
     }
     pl.P.out = pl.P.nsplit > 1 ? partial : dkernel;
-    if (s.D1 == 4) {
+    if (s.D1 == 4) {  // in place, or on the channel-paired copies
         err = s.dtype == 2 ? launch_kernel<f16_tag, 4, true>(pl.P, stream)
                            : launch_kernel<bf16_tag, 4, true>(pl.P, stream);
     } else if (s.dtype == 2) {

@@ -115,6 +115,9 @@ BWD_SHAPES = SMALL_SHAPES + [
     # 4x4 capsules on enough pixels for the 16-bit input gradient to run on the lane-per-row
     # kernel (the output gradient's channels paired)
     ("p4big", 12, 40, 40, 8, 8, 3, 3, 1, 1, 1, 4, 4, 4),
+    # 4-row capsules with widths of 8 and 16: the 16-bit kernel gradient reads them in place
+    ("wg4_inpl", 3, 9, 8, 5, 6, 3, 3, 1, 1, 1, 4, 8, 16),
+    ("wg4_wide", 2, 7, 7, 3, 3, 2, 2, 2, 0, 2, 4, 16, 8),
     ("ph32_s2", 7, 80, 78, 4, 8, 3, 3, 2, 1, 1, 8, 8, 8),
     ("ph32_d3", 8, 100, 97, 5, 6, 4, 4, 3, 2, 3, 3, 3, 3),
 ]
