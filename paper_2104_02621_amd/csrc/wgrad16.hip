@@ -107,7 +107,12 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     constexpr int KCH = 4, NB = 4;
     constexpr int D1C = D1 >= 8 ? D1 / 8 : 1;  // chunks per pixel and row (copies per pixel, D1 >= 8)
     constexpr int PPS = 32 / D1;               // pixels per stage
-    static_assert(D1 >= 8 || OWN, "4-row capsules are read in place (channel-paired tensors)");
+    static_assert(D1 >= 8 || OWN, "short capsules are read in place (or as channel-paired tensors)");
+    // capsules of one or two rows: 32 or 16 pixels per stage are too many for the scalar walk;
+    // every lane follows one pixel of the stage instead (vector arithmetic), and a copy, whose 8
+    // lines are PPC pixels, fetches its lanes' pixel offsets with a cross-lane read
+    constexpr bool VW = D1 <= 2;
+    constexpr int PPC = VW ? 8 / D1 : 1;
     constexpr int NWM = 2, NWN = 2;
     constexpr int BM = 256, BN = 256;
     constexpr int SIDE_BYTES = KCH * BM * 16, STAGE_BYTES = 2 * SIDE_BYTES;
@@ -119,7 +124,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     constexpr int KEEP = (NB - 2) * NCOPY;
     static_assert(KEEP < 64, "vmcnt is a 6-bit counter");
     constexpr int VMCNT_KEEP = 0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14);
-    static_assert(D1 == 4 || D1 == 8 || D1 == 16, "D1");
+    static_assert(D1 == 1 || D1 == 2 || D1 == 4 || D1 == 8 || D1 == 16, "D1");
     static_assert(NMMA == 16 && KCH == 4, "the schedule below is written for this shape");
 
     extern __shared__ char smem[];
@@ -191,7 +196,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     // ---- per-lane constants: byte offset of the lane's row (column) within a pixel, or the
     // out-of-range mark for rows (columns) past the end: those copy zeros
     unsigned a_voff, b_voff;
-    int pair_hi_a = 0, pair_hi_b = 0;
+    int pair_hi_a = 0, pair_hi_b = 0, bp_a = 0, bp_b = 0;
     // OWN: place of chunk (line l8, chunk column r8) in its unit, and back.  `wide`: two chunk
     // columns per capsule row (capsule width a multiple of 16), else one.
     auto unit_slot = [](bool wide, int l8, int r8) {
@@ -204,7 +209,10 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
         const int la = (a_wide ? (lane & 15) >> 1 : lane & 7) ^ (((ra >> 1) & 1) * 4);
         const int R = row_tile * BM + (wave * 8 + ra) * 8;
         const int c = R / P.D2, d2 = R - c * P.D2;
-        if constexpr (D1 == 4) {
+        if constexpr (VW) {
+            // line la % D1 of pixel la / D1 of the copy
+            a_voff = R < P.rows ? (unsigned)(((((c * P.D0 + d0) * D1 + (la % D1)) * P.D2) + d2) * 2) : (unsigned)OOB;
+        } else if constexpr (D1 == 4) {
             // line la % 4 of the pixel (la / 4: which of the copy's two pixels); 4x4 capsules:
             // channel-paired tensor, chunk R / 8 of the line is 16 bytes of its own
             if (P.D2 == 4)
@@ -217,7 +225,9 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
         const int lb = (b_wide ? (lane & 15) >> 1 : lane & 7) ^ (((rb >> 1) & 1) * 4);
         const int J = col_tile * BN + (wave * 8 + rb) * 8;
         const int m = J / P.D3, d3 = J - m * P.D3;
-        if constexpr (D1 == 4) {
+        if constexpr (VW) {
+            b_voff = J < P.cols ? (unsigned)(((((m * P.D0 + d0) * D1 + (lb % D1)) * P.D3) + d3) * 2) : (unsigned)OOB;
+        } else if constexpr (D1 == 4) {
             if (P.D3 == 4)
                 b_voff = J < P.cols ? (unsigned)((((J >> 3) * P.D0 + d0) * D1 + (lb & 3)) * 16) : (unsigned)OOB;
             else
@@ -227,6 +237,10 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
         // 4-row capsules: a copy's 8 lines are two pixels; all ones in the lanes of the second
         pair_hi_a = -(int)(la >> 2);
         pair_hi_b = -(int)(lb >> 2);
+        // (vector walk) byte address, for the cross-lane read, of the lane that follows this
+        // lane's pixel of copy 0
+        bp_a = (la / D1) * 4;
+        bp_b = (lb / D1) * 4;
     } else {
         const int R = row_tile * BM + wave * 64 + lane;
         const int c = R / P.D2, d2 = R - c * P.D2;
@@ -269,7 +283,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     // Pixel offsets of the stage whose It copies go out next (a_soff) and of the stage whose
     // Gt copies go out next (g_soff): the same stage, the Gt copies follow one k-step later.
     // All scalar.
-    int a_soff[PPS], g_soff[PPS];
+    int a_soff[VW ? 1 : PPS], g_soff[VW ? 1 : PPS];
     // One pixel step of the walker, in four branch-free pieces that the main loop puts into
     // different gaps between MFMAs: (0) record the pixel's offsets for slot j of the stage, or
     // past the last pixel the out-of-range mark (zero fill, touches no memory); (1) count down
@@ -318,9 +332,70 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
                          : "scc");
         }
     };
+    // ---- vector walk (VW): lane j follows pixel j of the stage whose offsets are being worked out:
+    // its place (vx, vy) in the tap's rectangle, its image vn (relative to n0) and how many pixels
+    // of the range begin at or after it (v_left <= 0: past the end).  A stage on, every lane moves
+    // PPS pixels forward: two divisions of small numbers (by the rectangle's width and height),
+    // done as a float multiplication with one correction step (exact for quotients below 2^20).
+    int vx = 0, vy = 0, vn = 0, v_left = npix - lane;  // a range begins with an image
+    const int ny1 = ny > 0 ? ny : 1, nx1 = nx > 0 ? nx : 1;
+    const float inv_ny = 1.0f / (float)ny1, inv_nx = 1.0f / (float)nx1;
+    auto small_div = [](int a, int d, float inv) {
+        int q = (int)((float)a * inv);
+        const int r = a - q * d;
+        q += r >= d ? 1 : 0;
+        q -= r < 0 ? 1 : 0;
+        return q;
+    };
+    auto vw_step_y = [&](int step) {
+        vy += step;
+        const int q = small_div(vy, ny1, inv_ny);
+        vy -= q * ny1;
+        vx += q;
+        asm volatile("" : "+v"(vx), "+v"(vy));
+    };
+    auto vw_step_x = [&]() {
+        const int q = small_div(vx, nx1, inv_nx);
+        vx -= q * nx1;
+        vn += q;
+        asm volatile("" : "+v"(vx), "+v"(vn));
+    };
+    // offsets of the lane's pixel in either tensor, relative to image n0 (or the out-of-range mark)
+    const int vi_base = ((x_lo * s - (P.pad - tp)) * P.W + (y_lo * s - (P.pad - tq))) * ipix;
+    const int vg_base = (x_lo * P.Wo + y_lo) * gpix;
+    const int vi_img = (int)P.it_img_bytes, vg_img = (int)P.gt_img_bytes;
+    const int vi_row = s * P.W * ipix, vg_row = P.Wo * gpix;
+    auto vw_offset_i = [&]() -> unsigned {
+        unsigned o = (unsigned)(vn * vi_img + vx * vi_row + vy * i_step + vi_base);
+        o = v_left > 0 ? o : (unsigned)OOB;
+        asm volatile("" : "+v"(o));
+        return o;
+    };
+    auto vw_offset_g = [&]() -> unsigned {
+        unsigned o = (unsigned)(vn * vg_img + vx * vg_row + vy * g_step + vg_base);
+        o = v_left > 0 ? o : (unsigned)OOB;
+        asm volatile("" : "+v"(o));
+        return o;
+    };
+    // offsets in use: i_offs for the next It copies, g_offs for the next Gt copies (lane j: pixel j)
+    unsigned i_offs = 0, g_offs = 0, i_new = 0, g_new = 0;
+    if constexpr (VW) {
+        vw_step_y(lane);  // lane j starts j pixels into the range
+        vw_step_x();
+    }
+    // pixel offsets of a copy's lanes, fetched one gap ahead of the copy
+    int bp_val_a = 0, bp_val_b = 0;
+    auto fetch_a = [&](int kc) {
+        bp_val_a = __builtin_amdgcn_ds_bpermute(bp_a + kc * PPC * 4, (int)i_offs);
+    };
+    auto fetch_b = [&](int kc) {
+        bp_val_b = __builtin_amdgcn_ds_bpermute(bp_b + kc * PPC * 4, (int)g_offs);
+    };
     auto copy_a = [&](auto SLOT, auto KC) {
         constexpr int slot = decltype(SLOT)::value, kc = decltype(KC)::value;
-        if constexpr (D1 == 4) {
+        if constexpr (VW) {
+            copy_to_lds_16B<slot * STAGE_BYTES + kc * BM * 16>(rs_it, lds_a, a_voff + (unsigned)bp_val_a, 0, 0);
+        } else if constexpr (D1 == 4) {
             // the pixel's offset travels in the lane offset (an out-of-range mark in either
             // pixel keeps that pixel's lanes out of range)
             const int lo = a_soff[2 * kc], hi = a_soff[2 * kc + 1];
@@ -333,7 +408,9 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     };
     auto copy_b = [&](auto SLOT, auto KC) {
         constexpr int slot = decltype(SLOT)::value, kc = decltype(KC)::value;
-        if constexpr (D1 == 4) {
+        if constexpr (VW) {
+            copy_to_lds_16B<slot * STAGE_BYTES + kc * BN * 16>(rs_gt, lds_b, b_voff + (unsigned)bp_val_b, 0, 0);
+        } else if constexpr (D1 == 4) {
             const int lo = g_soff[2 * kc], hi = g_soff[2 * kc + 1];
             const unsigned v = b_voff + (unsigned)lo + ((unsigned)(hi - lo) & (unsigned)pair_hi_b);
             copy_to_lds_16B<slot * STAGE_BYTES + kc * BN * 16>(rs_gt, lds_b, v, 0, 0);
@@ -370,19 +447,43 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     };
 
     // ---- prologue: stages 0..NB-2 whole and the It side of stage NB-1
-    static_for<NB - 1>([&](auto S0) {
+    if constexpr (VW) {
+        static_for<NB - 1>([&](auto S0) {
+            i_offs = vw_offset_i();
+            g_offs = vw_offset_g();
+            static_for<KCH>([&](auto KC) {
+                fetch_a(decltype(KC)::value);
+                copy_a(S0, KC);
+            });
+            static_for<KCH>([&](auto KC) {
+                fetch_b(decltype(KC)::value);
+                copy_b(S0, KC);
+            });
+            vw_step_y(PPS);
+            vw_step_x();
+            v_left -= PPS;
+        });
+        i_offs = vw_offset_i();
+        g_offs = vw_offset_g();
+        static_for<KCH>([&](auto KC) {
+            fetch_a(decltype(KC)::value);
+            copy_a(std::integral_constant<int, NB - 1>{}, KC);
+        });
+    } else {
+        static_for<NB - 1>([&](auto S0) {
+#pragma unroll
+            for (int j = 0; j < PPS; ++j)
+#pragma unroll
+                for (int piece = 0; piece < 4; ++piece) walk(j, piece);
+            static_for<KCH>([&](auto KC) { copy_a(S0, KC); });
+            static_for<KCH>([&](auto KC) { copy_b(S0, KC); });
+        });
 #pragma unroll
         for (int j = 0; j < PPS; ++j)
 #pragma unroll
             for (int piece = 0; piece < 4; ++piece) walk(j, piece);
-        static_for<KCH>([&](auto KC) { copy_a(S0, KC); });
-        static_for<KCH>([&](auto KC) { copy_b(S0, KC); });
-    });
-#pragma unroll
-    for (int j = 0; j < PPS; ++j)
-#pragma unroll
-        for (int piece = 0; piece < 4; ++piece) walk(j, piece);
-    static_for<KCH>([&](auto KC) { copy_a(std::integral_constant<int, NB - 1>{}, KC); });
+        static_for<KCH>([&](auto KC) { copy_a(std::integral_constant<int, NB - 1>{}, KC); });
+    }
     {
         constexpr int keep0 = (NB - 2) * NCOPY + KCH;
         static_assert(keep0 < 64, "vmcnt is a 6-bit counter");
@@ -400,7 +501,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     // first piece after the last Gt copy that still reads the previous
     // stage's offset of slot j (k-step 0) and before the first It copy that reads the new one
     // (k-step 1).  Gaps 0..15 are k-step 0's, 16..31 k-step 1's.
-    constexpr int NPIECE = 4 * PPS;
+    constexpr int NPIECE = VW ? 0 : 4 * PPS;
     constexpr auto piece_gap = [](int q) {
         // four pixels per stage: the second halves of both k-steps, whose gaps hold no operand
         // reads (config 3: 2.7 % faster than pieces in the read gaps); two pixels: measured the
@@ -412,7 +513,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
         // 18 + 4 (j / 2))
         return PPS == 8 ? 3 + q * 27 / 32 : PPS == 4 ? four[q] : two[q];
     };
-    static_assert(PPS == 8 || PPS == 4 || PPS == 2, "the walk's schedule is written for these stage shapes");
+    static_assert(VW || PPS == 8 || PPS == 4 || PPS == 2, "the walk's schedule is written for these stage shapes");
     for (int st = 0; st < nstages_pad; st += NB) {
         static_for<NB>([&](auto SLOT) {
             constexpr int slot = decltype(SLOT)::value;
@@ -422,6 +523,23 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
                 constexpr int i = decltype(I)::value;
                 pinned_mma(frag[0][i / TM], frag[0][TN + i % TM], acc[i / TM][i % TM]);
                 if constexpr (i < NFRAG) frag[1][i] = read_frag(slot, 1, i);
+                if constexpr (VW) {
+                    // the Gt copies' pixel offsets are fetched two gaps ahead; the lanes move on
+                    // to the next stage's pixels, whose offsets take effect after the last Gt copy
+                    if constexpr (i % 4 == 0) fetch_b(i / 4);
+                    if constexpr (i == 1) vw_step_y(PPS);
+                    if constexpr (i == 3) {
+                        vw_step_x();
+                        v_left -= PPS;
+                    }
+                    if constexpr (i == 5) i_new = vw_offset_i();
+                    if constexpr (i == 7) g_new = vw_offset_g();
+                    if constexpr (i == NMMA - 1) {
+                        i_offs = i_new;
+                        g_offs = g_new;
+                        asm volatile("" : "+v"(i_offs), "+v"(g_offs));
+                    }
+                }
                 if constexpr (i % 4 == 2) copy_b(SlotPrev{}, std::integral_constant<int, i / 4>{});
                 static_for<NPIECE>([&](auto Q) {
                     constexpr int q = decltype(Q)::value;
@@ -435,6 +553,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
                 constexpr int i = decltype(I)::value;
                 pinned_mma(frag[1][i / TM], frag[1][TN + i % TM], acc[i / TM][i % TM]);
                 if constexpr (i < NFRAG) frag[0][i] = read_frag(slot_next, 0, i);
+                if constexpr (VW && i % 4 == 0) fetch_a(i / 4);
                 if constexpr (i % 4 == 2) copy_a(SLOT, std::integral_constant<int, i / 4>{});
                 static_for<NPIECE>([&](auto Q) {
                     constexpr int q = decltype(Q)::value;
@@ -507,7 +626,7 @@ WgradPlan make_plan(const ConvShape& s)
     long long imgs_cap = ((1LL << 31) - 1) / (img_max > 0 ? img_max : 1);
     if (imgs_cap > s.N) imgs_cap = s.N;
     const double pix_per_img = (double)s.Ho * s.Wo;
-    const double fixed = s.D1 == 16 ? 70.0 : s.D1 == 8 ? 140.0 : 280.0;
+    const double fixed = 1120.0 / s.D1;  // D1 = 16: 70 pixels
     double best = 0;
     int best_imgs = (int)imgs_cap;
     for (int imgs = (int)imgs_cap; imgs >= 1; --imgs) {
@@ -563,7 +682,8 @@ bool wgrad16_eligible(const ConvShape& s)
     // 4x4 capsules with even channel counts run on channel-paired copies of both tensors
     // ... and 4-row capsules whose widths are multiples of 8 are read in place
     const bool paired = s.D1 == 4 && s.D2 == 4 && s.D3 == 4 && s.C % 2 == 0 && s.M % 2 == 0;
-    const bool four_in_place = s.D1 == 4 && s.D2 % 8 == 0 && s.D3 % 8 == 0;
+    // ... as are capsules of one or two rows (vector capsules)
+    const bool four_in_place = (s.D1 == 4 || s.D1 == 2 || s.D1 == 1) && s.D2 % 8 == 0 && s.D3 % 8 == 0;
     if (s.D1 != 8 && s.D1 != 16 && !paired && !four_in_place) return false;
     if (s.D3 % 4 != 0) return false;
     if (!paired && !four_in_place && ((s.D1 / 8) * s.D2 > 256 || (s.D1 / 8) * s.D3 > 256))
@@ -631,6 +751,12 @@ hipError_t launch_wgrad16(const ConvShape& s, const void* input, const void* dou
     if (s.D1 == 4) {  // in place, or on the channel-paired copies
         err = s.dtype == 2 ? launch_kernel<f16_tag, 4, true>(pl.P, stream)
                            : launch_kernel<bf16_tag, 4, true>(pl.P, stream);
+    } else if (s.D1 == 2) {
+        err = s.dtype == 2 ? launch_kernel<f16_tag, 2, true>(pl.P, stream)
+                           : launch_kernel<bf16_tag, 2, true>(pl.P, stream);
+    } else if (s.D1 == 1) {
+        err = s.dtype == 2 ? launch_kernel<f16_tag, 1, true>(pl.P, stream)
+                           : launch_kernel<bf16_tag, 1, true>(pl.P, stream);
     } else if (s.dtype == 2) {
         if (own)
             err = s.D1 == 16 ? launch_kernel<f16_tag, 16, true>(pl.P, stream)

@@ -118,6 +118,15 @@ BWD_SHAPES = SMALL_SHAPES + [
     # 4-row capsules with widths of 8 and 16: the 16-bit kernel gradient reads them in place
     ("wg4_inpl", 3, 9, 8, 5, 6, 3, 3, 1, 1, 1, 4, 8, 16),
     ("wg4_wide", 2, 7, 7, 3, 3, 2, 2, 2, 0, 2, 4, 16, 8),
+    # vector capsules (one or two rows): every lane of the 16-bit kernel gradient follows a pixel
+    # of its own; strides, a leading capsule index, many images (the contraction split over image
+    # ranges), a 1x1 image under a 5x5 window (taps that never meet it), rectangles narrower than
+    # a stage
+    ("wgv1", 3, 9, 8, 5, 6, 3, 3, 1, 1, 1, 1, 8, 16),
+    ("wgv2", 2, 7, 7, 3, 3, 2, 2, 2, 0, 2, 2, 16, 8),
+    ("wgv1many", 40, 5, 5, 4, 4, 2, 2, 1, 0, 1, 1, 8, 8),
+    ("wgv1tiny", 2, 1, 1, 3, 2, 5, 5, 1, 2, 1, 1, 8, 8),
+    ("wgv2wide", 1, 3, 70, 2, 35, 3, 3, 3, 1, 1, 2, 8, 8),
     ("ph32_s2", 7, 80, 78, 4, 8, 3, 3, 2, 1, 1, 8, 8, 8),
     ("ph32_d3", 8, 100, 97, 5, 6, 4, 4, 3, 2, 3, 3, 3, 3),
 ]
