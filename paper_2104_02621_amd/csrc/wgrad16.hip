@@ -1,6 +1,6 @@
 // Kernel gradient of the capsule convolution (the K_diff result of the paper's Algorithm 4,
 // taken as the derivative of Algorithm 2's sum) on the matrix cores, for 16-bit element types
-// and D1 in {8, 16}, and for 4x4 capsules (see the end of this comment).  With G = dL/dO, per window tap (p,q) and leading capsule index d0 it is
+// and D1 in {8, 16}, and for capsules of 1, 2 and 4 rows (see the end of this comment).  With G = dL/dO, per window tap (p,q) and leading capsule index d0 it is
 // one GEMM
 //
 //     rows     r = (c, d2)                                           C*D2 of them
@@ -46,7 +46,9 @@
 // of both tensors, [pixel][c/2][d0][d1][c%2][4 halves] (a pre-pass at HBM speed): 8 consecutive
 // rows (c, d2) of a line are then one 16-byte chunk as above.  A pixel has only 4 lines, so a
 // stage is 8 pixels and a copy's 8 lines are two pixels: the second pixel's offset travels in
-// the lane offset of its lanes.
+// the lane offset of its lanes.  Capsules of 4, 2 or 1 rows whose widths are multiples of 8 are
+// read in place; with 2 or 1 rows a stage is 16 or 32 pixels, which the lanes follow one each
+// (see VW in the kernel).
 #include <hip/hip_runtime.h>
 
 #include "igemm_common.h"
