@@ -59,8 +59,31 @@ def random_medium_shape(seed):
             return dtype, (N, H, W, C, M, kh, kw, s, p, D0, D, D, D)
 
 
+def random_mixed16_shape(seed):
+    """A 16-bit layer of non-square, vector (one or two rows) or 4-row capsules with enough rows for
+    the lane-per-row kernel's 256-row tiles and the in-place kernel-gradient kernel."""
+    rng = np.random.default_rng(97000 + seed)
+    dtype = [wl.BF16, wl.FP16][seed % 2]
+    while True:
+        D1 = int(rng.choice([1, 2, 4, 8, 16]))
+        D2 = int(rng.choice([4, 8, 16, 32]))
+        D3 = int(rng.choice([4, 8, 16]))
+        kh, kw = int(rng.integers(1, 4)), int(rng.integers(1, 4))
+        s = int(rng.integers(1, 3))
+        p = int(rng.integers(0, 3))
+        H, W = int(rng.integers(12, 49)), int(rng.integers(12, 49))
+        N = int(rng.integers(4, 49))
+        C, M = 2 * int(rng.integers(1, 25)), 2 * int(rng.integers(1, 25))
+        Ho, Wo = (H + 2 * p - kh) // s + 1, (W + 2 * p - kw) // s + 1
+        rows = N * Ho * Wo * D1
+        flops = 2.0 * rows * M * D3 * kh * kw * C * D2
+        if rows >= 260 * 256 and flops <= 8e9:
+            return dtype, (N, H, W, C, M, kh, kw, s, p, 1, D1, D2, D3)
+
+
 SEEDS = list(range(60))
 MEDIUM_SEEDS = list(range(15))
+MIXED16_SEEDS = list(range(14))
 
 
 @pytest.mark.parametrize("seed", SEEDS)
@@ -77,6 +100,15 @@ def test_random_layer_forward_and_gradients(seed):
 def test_random_medium_layer_forward_and_gradients(seed):
     dtype, shape = random_medium_shape(seed)
     w = small("randm%d_" % seed + "x".join(map(str, shape)), dtype, *shape, seed=800 + seed)
+    print(w.name, cc.capscaps_select_path(*shape, dtype), flush=True)
+    full_compare(w, cc.PATH_AUTO)
+    both_gradients(w)
+
+
+@pytest.mark.parametrize("seed", MIXED16_SEEDS)
+def test_random_mixed_16bit_layer_forward_and_gradients(seed):
+    dtype, shape = random_mixed16_shape(seed)
+    w = small("randx%d_" % seed + "x".join(map(str, shape)), dtype, *shape, seed=900 + seed)
     print(w.name, cc.capscaps_select_path(*shape, dtype), flush=True)
     full_compare(w, cc.PATH_AUTO)
     both_gradients(w)
