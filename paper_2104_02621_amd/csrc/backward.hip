@@ -216,7 +216,20 @@ ConvShape bwd_input_phase_shape(const ConvShape& s, const PhaseDim& ph, const Ph
     f.out_alloc = (long long)s.in_elems();
     return f;
 }
-// every phase that has both pixels and taps must fit the tuned kernel and fill the chip
+// which tuned kernel runs a phase: 16 = the 256x256-tile 16-bit kernel, 32 = the lane-per-row
+// kernel (fp32, or 16-bit shapes the other one does not take), 0 = neither fits or fills the chip
+int phase_kernel(const ConvShape& f)
+{
+    if (!mfma_supported(f)) return 0;
+    if (f.dtype != 0 && mfma_tuned16_supported(f) &&
+        (long long)f.N * f.Ho * f.Wo * f.D1 >= 256LL * 128)
+        return 16;
+    // the lane-per-row kernel with its four-wave tiles and an unsplit K loop
+    if (mfma_dma32_supported(f) && igemm32_dma_preferred(f)) return 32;
+    return 0;
+}
+
+// every phase that has both pixels and taps must fit a tuned kernel and fill the chip
 bool bwd_input_as_phases(const ConvShape& s)
 {
     if (s.stride == 1 || s.stride > 4) return false;
@@ -226,14 +239,7 @@ bool bwd_input_as_phases(const ConvShape& s)
             const PhaseDim pw = phase_dim(s.W, s.kw, s.stride, s.pad, b);
             if (ph.count == 0 || pw.count == 0 || ph.taps == 0 || pw.taps == 0) continue;
             const ConvShape f = bwd_input_phase_shape(s, ph, pw, a, b);
-            if (!mfma_supported(f)) return false;
-            if (s.dtype == 0) {
-                // fp32: the tuned kernel with its four-wave tiles and an unsplit K loop
-                if (!mfma_dma32_supported(f) || !igemm32_dma_preferred(f)) return false;
-            } else {
-                if (!mfma_tuned16_supported(f)) return false;
-                if ((long long)f.N * f.Ho * f.Wo * f.D1 < 256LL * 128) return false;
-            }
+            if (phase_kernel(f) == 0) return false;
         }
     return true;
 }
@@ -374,10 +380,11 @@ int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, f
                 f.k_sd0 = sD0;
                 f.k_sd2 = sD3;  // ... and its contracted capsule index the layer's d3
                 f.k_sd3 = sD2;
-                const int rc = s.dtype == 0 ? forward_tuned32(f, dout, kernel, din, ws + kbytes,
-                                                              workspace_bytes - kbytes, stream)
-                                            : forward_tuned16(f, dout, kernel, din, ws + kbytes,
-                                                              workspace_bytes - kbytes, stream);
+                const int rc = phase_kernel(f) == 32
+                                   ? forward_tuned32(f, dout, kernel, din, ws + kbytes,
+                                                     workspace_bytes - kbytes, stream)
+                                   : forward_tuned16(f, dout, kernel, din, ws + kbytes,
+                                                     workspace_bytes - kbytes, stream);
                 if (rc != 0) return rc;
             }
         return 0;

@@ -128,6 +128,10 @@ BWD_SHAPES = SMALL_SHAPES + [
     ("wgv1tiny", 2, 1, 1, 3, 2, 5, 5, 1, 2, 1, 1, 8, 8),
     ("wgv2wide", 1, 3, 70, 2, 35, 3, 3, 3, 1, 1, 2, 8, 8),
     ("ph32_s2", 7, 80, 78, 4, 8, 3, 3, 2, 1, 1, 8, 8, 8),
+    # ... and for 16-bit layers the 256x256-tile kernel does not take: 4x4 capsules, and 8-row
+    # capsules on too few channels for its stages
+    ("ph16_d4", 14, 80, 78, 4, 8, 3, 3, 2, 1, 1, 4, 4, 4),
+    ("ph16_ns", 10, 60, 62, 6, 4, 3, 3, 2, 1, 1, 8, 16, 8),
     ("ph32_d3", 8, 100, 97, 5, 6, 4, 4, 3, 2, 3, 3, 3, 3),
 ]
 
