@@ -195,9 +195,10 @@ int capscaps_select_path(int N, int H, int W, int C, int M, int kh, int kw, int 
  * The shape arguments are those of the forward call whose gradients are wanted.  The input
  * gradient is itself a capsule convolution of `dout` with the flipped, transposed kernel and runs
  * on the forward kernels (a stride s > 1 as s*s interleaved stride-1 convolutions where every one
- * of them fits a tuned kernel (see CAPSCAPS_PATH_MFMA_TUNED16 / _TUNED32) and has enough pixels, else on `dout` spread out to stride 1 in `workspace`); the kernel
- * gradient runs on dedicated matrix-core kernels for 16-bit capsules of 8 or 16 rows (4-row ones
- * that are 4x4 with even channel counts, and ones of 1, 2 or 4 rows whose widths are multiples of 8) and fp32
+ * of them fits a tuned kernel (see CAPSCAPS_PATH_MFMA_TUNED16 / _TUNED32) and has enough pixels,
+ * else on `dout` spread out to stride 1 in `workspace`); the kernel gradient runs on dedicated
+ * matrix-core kernels for 16-bit capsules of 8 or 16 rows (4-row ones that are 4x4 with even
+ * channel counts, and ones of 1, 2 or 4 rows whose widths are multiples of 8) and fp32
  * capsules of 3, 4, 6, 8, 12 or 16 rows, else as a convolution with images and channels
  * exchanged.  Shapes none of these forms cover (a non-square window with pad > kh-1, ...) take
  * plain gather kernels, which need no workspace.  Pointer, stream and error rules as for the forward
