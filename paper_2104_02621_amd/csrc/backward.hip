@@ -229,6 +229,10 @@ int phase_kernel(const ConvShape& f)
     return 0;
 }
 
+// 16-bit layers with capsule columns of 4 elements: the phases that run on the lane-per-row
+// kernel read the output gradient with its channels paired; it is paired once for all of them
+bool phases_pair_dout(const ConvShape& s) { return s.dtype != 0 && s.D3 == 4 && s.M % 2 == 0; }
+
 // every phase that has both pixels and taps must fit a tuned kernel and fill the chip
 bool bwd_input_as_phases(const ConvShape& s)
 {
@@ -300,10 +304,13 @@ size_t bwd_input_workspace_bytes(const ConvShape& s)
                 const PhaseDim ph = phase_dim(s.H, s.kh, s.stride, s.pad, a);
                 const PhaseDim pw = phase_dim(s.W, s.kw, s.stride, s.pad, b);
                 if (ph.count == 0 || pw.count == 0 || ph.taps == 0 || pw.taps == 0) continue;
-                const size_t need = mfma_workspace_bytes(bwd_input_phase_shape(s, ph, pw, a, b));
+                ConvShape f = bwd_input_phase_shape(s, ph, pw, a, b);
+                f.in_paired = phases_pair_dout(s);
+                const size_t need = mfma_workspace_bytes(f);
                 if (need > fwd) fwd = need;
             }
-        return kbytes + fwd;  // the phases' sub-kernels together are one kernel tensor
+        // the phases' sub-kernels together are one kernel tensor
+        return kbytes + fwd + (phases_pair_dout(s) ? align256(s.out_elems() * elem_bytes(s)) : 0);
     }
     if (!bwd_input_as_conv(s)) return 0;
     const size_t gbytes = s.stride > 1 ? align256(spread_elems(s) * elem_bytes(s)) : 0;
@@ -350,6 +357,16 @@ int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, f
         char* ws = static_cast<char*>(workspace);
         const size_t kbytes = align256(s.kernel_elems() * eb);
         const long long pix = (long long)s.C * s.D0 * s.D1 * s.D2;
+        size_t used = kbytes;
+        const void* dout_paired = nullptr;
+        if (phases_pair_dout(s)) {
+            void* dst = ws + used;
+            used += align256(s.out_elems() * eb);
+            const hipError_t err = launch_pair_channels(dout, dst, (size_t)s.N * s.Ho * s.Wo, s.M,
+                                                        s.D0 * s.D1, stream);
+            if (err != hipSuccess) return status_from_hip(err);
+            dout_paired = dst;
+        }
         for (int a = 0; a < s.stride; ++a)
             for (int b = 0; b < s.stride; ++b) {
                 const PhaseDim ph = phase_dim(s.H, s.kh, s.stride, s.pad, a);
@@ -380,11 +397,13 @@ int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, f
                 f.k_sd0 = sD0;
                 f.k_sd2 = sD3;  // ... and its contracted capsule index the layer's d3
                 f.k_sd3 = sD2;
-                const int rc = phase_kernel(f) == 32
-                                   ? forward_tuned32(f, dout, kernel, din, ws + kbytes,
-                                                     workspace_bytes - kbytes, stream)
-                                   : forward_tuned16(f, dout, kernel, din, ws + kbytes,
-                                                     workspace_bytes - kbytes, stream);
+                const bool lane_per_row = phase_kernel(f) == 32;
+                f.in_paired = lane_per_row && dout_paired != nullptr;
+                const int rc = lane_per_row
+                                   ? forward_tuned32(f, f.in_paired ? dout_paired : dout, kernel, din,
+                                                     ws + used, workspace_bytes - used, stream)
+                                   : forward_tuned16(f, dout, kernel, din, ws + used,
+                                                     workspace_bytes - used, stream);
                 if (rc != 0) return rc;
             }
         return 0;

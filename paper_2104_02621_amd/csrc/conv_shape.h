@@ -34,8 +34,8 @@ struct ConvShape {
     // output element type: 0 = fp32 (the accumulator as it is); CAPSCAPS_BF16 / FP16 = the
     // accumulator rounded to nearest even at the store (forward pass of 16-bit operands only)
     int out16 = 0;
-    // Geometry overrides understood by the tuned 16-bit kernel only (launch_mfma with
-    // MfmaKernel::Tuned16; everything else must be given shapes without them).  The backward
+    // Geometry overrides understood by the two tuned kernels only (launch_mfma with
+    // MfmaKernel::Tuned16 or ::Dma32; everything else must be given shapes without them).  The backward
     // pass uses them to run a strided layer's input gradient as stride*stride convolutions
     // whose outputs interleave.  pad_w_set: the columns' padding is pad_w instead of pad; both
     // may then be negative (the window starts inside the image) and Ho, Wo are taken as given.
@@ -51,9 +51,13 @@ struct ConvShape {
     // m*k_sm + d0*k_sd0 + d2*k_sd2 + d3*k_sd3 of `kernel` instead of densely (strides may be
     // negative: a flipped window).
     bool kernel_view = false;
+    // in_paired (lane-per-row kernel, 16-bit capsule rows of 4 elements): `input` already is the
+    // channel-paired copy [pixel][c/2][d0][d1][c%2][d2] (a caller that runs several convolutions
+    // on one input pairs it once)
+    bool in_paired = false;
     long long k_base = 0, k_sp = 0, k_sq = 0, k_sc = 0, k_sm = 0, k_sd0 = 0, k_sd2 = 0, k_sd3 = 0;
     int padw() const { return pad_w_set ? pad_w : pad; }
-    bool plain() const { return !pad_w_set && !out_view && !kernel_view; }
+    bool plain() const { return !pad_w_set && !out_view && !kernel_view && !in_paired; }
     long long pixels() const { return (long long)N * Ho * Wo; }
     size_t in_elems() const { return (size_t)N * H * W * C * D0 * D1 * D2; }
     size_t kernel_elems() const { return (size_t)kh * kw * C * M * D0 * D2 * D3; }

@@ -446,7 +446,7 @@ Dma32Plan igemm32_dma_plan(const ConvShape& s)
     const bool paired = s.dtype != 0 && s.D2 == 4;
     const int C = paired ? s.C / 2 : s.C;
     const int D2 = s.dtype == 0 ? s.D2 : paired ? 4 : s.D2 / 2;
-    pl.pair_bytes = paired ? (size_t)s.in_elems() * 2 : 0;
+    pl.pair_bytes = paired && !s.in_paired ? (size_t)s.in_elems() * 2 : 0;
     P.H = s.H; P.W = s.W; P.C = C; P.M = s.M; P.stride = s.stride; P.pad = s.pad;
     P.pad_w = s.padw();
     P.out_mode = (s.out_view ? 1 : 0) | (s.out16 << 1);
