@@ -166,6 +166,7 @@ def cpu_baseline_bwd(w, op, i32, k32, g32, gpu_grad, target_seconds=12.0):
     from oracle import capsconv
 
     rng = np.random.default_rng(4244)
+    op = "bwd_input" if op == "bwd_input_out16" else op
     slices = w.N * w.C if op == "bwd_input" else w.C * w.M
     flops_per_slice = w.flops_tap_exact() / slices
     done, spent, err, ref_max = 0, 0.0, 0.0, 0.0
@@ -176,7 +177,7 @@ def cpu_baseline_bwd(w, op, i32, k32, g32, gpu_grad, target_seconds=12.0):
             t0 = time.perf_counter()
             ref = capsconv.conv_bwd_input(a, b, (w.H, w.W), w.stride, w.pad)
             spent += time.perf_counter() - t0
-            got = gpu_grad[n:n + 1, :, :, c:c + 1].cpu().numpy()
+            got = gpu_grad[n:n + 1, :, :, c:c + 1].float().cpu().numpy()
         else:
             c, m = int(rng.integers(w.C)), int(rng.integers(w.M))
             a = np.ascontiguousarray(i32[:, :, :, c:c + 1])
@@ -331,8 +332,8 @@ def main():
     ap.add_argument("--path", default="auto",
                     choices=["auto", "mfma", "direct", "mfma-generic", "mfma-tuned16", "mfma-tuned32",
                              "mfma-small"])
-    ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_input", "bwd_kernel", "scheme1", "scheme2",
-                                                     "framework_conv", "net5"])
+    ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_input", "bwd_input_out16", "bwd_kernel",
+                                                     "scheme1", "scheme2", "framework_conv", "net5"])
     ap.add_argument("--shape", default=None,
                     help="N,H,W,C,M,kh,kw,stride,pad,D0,D1,D2,D3: time this layer instead of a "
                          "benchmark configuration (inputs N(0,1), kernel N(0, 1/fan-in); --dtype)")
@@ -419,6 +420,12 @@ def main():
         if args.op == "bwd_input":
             out = torch.empty(w.input_shape, dtype=torch.float32, device="cuda")
             need = cc.capscaps_conv_bwd_input_workspace_bytes(*shape)
+        elif args.op == "bwd_input_out16":
+            if w.dtype == wl.FP32:
+                sys.exit("bench.py: --op bwd_input_out16 needs a 16-bit workload")
+            out = torch.empty(w.input_shape, device="cuda",
+                              dtype=torch.bfloat16 if w.dtype == wl.BF16 else torch.float16)
+            need = cc.capscaps_conv_bwd_input_out16_workspace_bytes(*shape)
         else:
             out = torch.empty(w.kernel_shape, dtype=torch.float32, device="cuda")
             need = cc.capscaps_conv_bwd_kernel_workspace_bytes(*shape)
@@ -446,6 +453,9 @@ def main():
         elif args.op == "bwd_input":
             rc = cc.capscaps_conv_bwd_input(G.data_ptr(), K.data_ptr(), out.data_ptr(), *shape,
                                             ws.data_ptr(), ws.numel(), stream.cuda_stream)
+        elif args.op == "bwd_input_out16":
+            rc = cc.capscaps_conv_bwd_input_out16(G.data_ptr(), K.data_ptr(), out.data_ptr(), *shape,
+                                                  ws.data_ptr(), ws.numel(), stream.cuda_stream)
         else:
             rc = cc.capscaps_conv_bwd_kernel(I.data_ptr(), G.data_ptr(), out.data_ptr(), *shape,
                                              ws.data_ptr(), ws.numel(), stream.cuda_stream)

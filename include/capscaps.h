@@ -222,6 +222,24 @@ size_t capscaps_conv_bwd_kernel_workspace_bytes(int N, int H, int W, int C, int 
                                                 int D3, int dtype);
 
 /*
+ * As capscaps_conv_bwd_input for 16-bit operands (dtype CAPSCAPS_BF16 or CAPSCAPS_FP16; fp32 ->
+ * CAPSCAPS_EINVAL), with `dinput` holding elements of that same type: every element is the fp32
+ * sum of Algorithm 4's I_diff rounded to nearest even once, at the store.  The input gradient of a
+ * layer is the output gradient of the layer below it (its `dout`, which arrives in the storage
+ * type), so the backward pass through a stack (Sec. 3) chains without a conversion pass and with
+ * half the store traffic.  Same kernels and routes as capscaps_conv_bwd_input; `workspace` must
+ * hold capscaps_conv_bwd_input_out16_workspace_bytes(...) bytes (host-only; 0 also for invalid
+ * arguments).
+ */
+size_t capscaps_conv_bwd_input_out16_workspace_bytes(int N, int H, int W, int C, int M, int kh,
+                                                     int kw, int stride, int pad, int D0, int D1,
+                                                     int D2, int D3, int dtype);
+int capscaps_conv_bwd_input_out16(const void* dout, const void* kernel, void* dinput, int N, int H,
+                                  int W, int C, int M, int kh, int kw, int stride, int pad, int D0,
+                                  int D1, int D2, int D3, int dtype, void* workspace,
+                                  size_t workspace_bytes, void* stream);
+
+/*
  * Comparison implementation of the paper's second scheme (Algorithm 5; Sec. 2, last paragraph):
  * the three operand positions of every small matrix product are calculated beforehand
  * (capscaps_scheme2_build_index, once per shape), then one flat parallel loop multiplies and

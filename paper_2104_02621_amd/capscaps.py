@@ -75,6 +75,10 @@ def _load():
         getattr(lib, name).restype = i
         getattr(lib, name + "_workspace_bytes").argtypes = [i] * 14
         getattr(lib, name + "_workspace_bytes").restype = sz
+    lib.capscaps_conv_bwd_input_out16.argtypes = [p, p, p] + [i] * 14 + [p, sz, p]
+    lib.capscaps_conv_bwd_input_out16.restype = i
+    lib.capscaps_conv_bwd_input_out16_workspace_bytes.argtypes = [i] * 14
+    lib.capscaps_conv_bwd_input_out16_workspace_bytes.restype = sz
     lib.capscaps_scheme2_index_bytes.argtypes = [i] * 14
     lib.capscaps_scheme2_index_bytes.restype = sz
     lib.capscaps_scheme2_build_index.argtypes = [p, sz] + [i] * 14 + [p]
@@ -164,6 +168,19 @@ def capscaps_conv_bwd_input(dout, kernel, dinput, N, H, W, C, M, kh, kw, stride,
     return _load().capscaps_conv_bwd_input(dout, kernel, dinput, N, H, W, C, M, kh, kw, stride,
                                            pad, D0, D1, D2, D3, dtype, workspace, workspace_bytes,
                                            stream)
+
+
+def capscaps_conv_bwd_input_out16(dout, kernel, dinput, N, H, W, C, M, kh, kw, stride, pad, D0, D1,
+                                  D2, D3, dtype, workspace, workspace_bytes, stream=None) -> int:
+    return _load().capscaps_conv_bwd_input_out16(dout, kernel, dinput, N, H, W, C, M, kh, kw,
+                                                 stride, pad, D0, D1, D2, D3, dtype, workspace,
+                                                 workspace_bytes, stream)
+
+
+def capscaps_conv_bwd_input_out16_workspace_bytes(N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2,
+                                                  D3, dtype) -> int:
+    return int(_load().capscaps_conv_bwd_input_out16_workspace_bytes(N, H, W, C, M, kh, kw, stride,
+                                                                     pad, D0, D1, D2, D3, dtype))
 
 
 def capscaps_conv_bwd_kernel(input, dout, dkernel, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2,

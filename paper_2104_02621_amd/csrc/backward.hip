@@ -160,7 +160,7 @@ __global__ __launch_bounds__(256) void bwd_input_direct_kernel(const T* __restri
             }
         }
     }
-    dI[e] = acc;
+    store1(dI, (long long)e, acc, s.out16);
 }
 
 template <typename Kern, typename... Args>
@@ -205,6 +205,7 @@ ConvShape bwd_input_phase_shape(const ConvShape& s, const PhaseDim& ph, const Ph
 {
     ConvShape f{s.N, s.Ho, s.Wo, s.M, s.C, ph.taps, pw.taps, 1, ph.taps - 1 - ph.lo,
                 s.D0, s.D1, s.D3, s.D2, ph.count, pw.count, s.dtype};
+    f.out16 = s.out16;
     f.pad_w_set = true;
     f.pad_w = pw.taps - 1 - pw.lo;
     f.out_view = true;
@@ -248,8 +249,10 @@ bool bwd_input_as_phases(const ConvShape& s)
     return true;
 }
 
-// zero the pixels (n, h0 + i*sh, w0 + j*sw), i < nh, j < nw, of an fp32 tensor [N][H][W][pix]
-__global__ __launch_bounds__(256) void zero_pixels_kernel(float* __restrict__ out, int H, int W,
+// zero the pixels (n, h0 + i*sh, w0 + j*sw), i < nh, j < nw, of a tensor [N][H][W][pix] of fp32
+// (T = float) or 16-bit (T = unsigned short) elements
+template <typename T>
+__global__ __launch_bounds__(256) void zero_pixels_kernel(T* __restrict__ out, int H, int W,
                                                           long long pix, int h0, int sh, int nh,
                                                           int w0, int sw, int nw, size_t total)
 {
@@ -260,7 +263,7 @@ __global__ __launch_bounds__(256) void zero_pixels_kernel(float* __restrict__ ou
     const int j = (int)(r % nw); r /= nw;
     const int i = (int)(r % nh);
     const long long n = (long long)(r / nh);
-    out[((n * H + h0 + (long long)i * sh) * W + w0 + (long long)j * sw) * pix + e] = 0.f;
+    out[((n * H + h0 + (long long)i * sh) * W + w0 + (long long)j * sw) * pix + e] = T(0);
 }
 
 // fully-connected layer: one output pixel, the window is the whole unpadded image
@@ -271,16 +274,20 @@ bool bwd_input_as_fc(const ConvShape& s)
 ConvShape bwd_input_fc_shape(const ConvShape& s)
 {
     // input G [N][1][1][M][D0][D1][D3], kernel [1][1][M][(h,w,c)][D0][D3][D2] -> dI [N][(h,w,c)][D0][D1][D2]
-    return ConvShape{s.N, 1, 1, s.M, s.kh * s.kw * s.C, 1, 1, 1, 0, s.D0, s.D1, s.D3, s.D2, 1, 1,
-                     s.dtype};
+    ConvShape f{s.N, 1, 1, s.M, s.kh * s.kw * s.C, 1, 1, 1, 0, s.D0, s.D1, s.D3, s.D2, 1, 1,
+                s.dtype};
+    f.out16 = s.out16;
+    return f;
 }
 // dI as a forward convolution of the (spread-out) G with the flipped, transposed kernel
 bool bwd_input_as_conv(const ConvShape& s) { return s.kh == s.kw && s.pad <= s.kh - 1; }
 ConvShape bwd_input_conv_shape(const ConvShape& s)
 {
     // input Gs [N][Hs][Ws][M][D0][D1][D3], kernel K' [kh][kw][M][C][D0][D3][D2] -> dI [N][H][W][C][D0][D1][D2]
-    return ConvShape{s.N, spread_h(s), spread_w(s), s.M, s.C, s.kh, s.kw, 1, s.kh - 1 - s.pad,
-                     s.D0, s.D1, s.D3, s.D2, s.H, s.W, s.dtype};
+    ConvShape f{s.N, spread_h(s), spread_w(s), s.M, s.C, s.kh, s.kw, 1, s.kh - 1 - s.pad,
+                s.D0, s.D1, s.D3, s.D2, s.H, s.W, s.dtype};
+    f.out16 = s.out16;
+    return f;
 }
 // dK as a forward convolution of the re-laid-out input with the (spread-out) output gradient
 // as the window
@@ -377,8 +384,14 @@ int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, f
                     const size_t total = (size_t)s.N * ph.count * pw.count * pix;
                     const size_t blocks = (total + 255) / 256;
                     if (blocks > 0x7fffffffULL) return status_from_hip(hipErrorInvalidValue);
-                    zero_pixels_kernel<<<(unsigned)blocks, 256, 0, stream>>>(
-                        din, s.H, s.W, pix, h0, s.stride, ph.count, w0, s.stride, pw.count, total);
+                    if (s.out16 != 0)
+                        zero_pixels_kernel<unsigned short><<<(unsigned)blocks, 256, 0, stream>>>(
+                            reinterpret_cast<unsigned short*>(din), s.H, s.W, pix, h0, s.stride,
+                            ph.count, w0, s.stride, pw.count, total);
+                    else
+                        zero_pixels_kernel<float><<<(unsigned)blocks, 256, 0, stream>>>(
+                            din, s.H, s.W, pix, h0, s.stride, ph.count, w0, s.stride, pw.count,
+                            total);
                     const hipError_t err = hipGetLastError();
                     if (err != hipSuccess) return status_from_hip(err);
                     continue;

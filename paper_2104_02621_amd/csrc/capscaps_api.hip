@@ -342,6 +342,37 @@ int capscaps_conv_bwd_input(const void* dout, const void* kernel, void* dinput, 
                                       workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
+size_t capscaps_conv_bwd_input_out16_workspace_bytes(int N, int H, int W, int C, int M, int kh,
+                                                     int kw, int stride, int pad, int D0, int D1,
+                                                     int D2, int D3, int dtype)
+{
+    ConvShape s;
+    if (dtype != CAPSCAPS_BF16 && dtype != CAPSCAPS_FP16) return 0;
+    if (fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype) != CAPSCAPS_OK)
+        return 0;
+    s.out16 = dtype;
+    return capscaps::bwd_input_workspace_bytes(s);
+}
+
+int capscaps_conv_bwd_input_out16(const void* dout, const void* kernel, void* dinput, int N, int H,
+                                  int W, int C, int M, int kh, int kw, int stride, int pad, int D0,
+                                  int D1, int D2, int D3, int dtype, void* workspace,
+                                  size_t workspace_bytes, void* stream)
+{
+    if (dout == nullptr || kernel == nullptr || dinput == nullptr) return CAPSCAPS_EINVAL;
+    if (misaligned(dout) || misaligned(kernel) || misaligned(dinput)) return CAPSCAPS_EINVAL;
+    if (dtype != CAPSCAPS_BF16 && dtype != CAPSCAPS_FP16) return CAPSCAPS_EINVAL;
+    ConvShape s;
+    const int rc = fill_shape(s, N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dtype);
+    if (rc != CAPSCAPS_OK) return rc;
+    s.out16 = dtype;
+    const size_t need = capscaps::bwd_input_workspace_bytes(s);
+    if (need > 0 && (workspace == nullptr || workspace_bytes < need)) return CAPSCAPS_EWORKSPACE;
+    if (need > 0 && misaligned(workspace)) return CAPSCAPS_EINVAL;
+    return capscaps::launch_bwd_input(s, dout, kernel, static_cast<float*>(dinput), workspace,
+                                      workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
 int capscaps_conv_bwd_kernel(const void* input, const void* dout, void* dkernel, int N, int H,
                              int W, int C, int M, int kh, int kw, int stride, int pad, int D0,
                              int D1, int D2, int D3, int dtype, void* workspace,
