@@ -239,7 +239,11 @@ def mfma_yardstick(dtype, zero_data=False, seconds=0.05):
 
 def bench_net5(args):
     """Five chained layers (workloads.net5): layers 1-4 write bf16 activations that the next layer
-    reads as they are, layer 5 writes fp32.  One step = the five calls."""
+    reads as they are, layer 5 writes fp32.  One step = the five calls.  With --op net5_train a
+    step is a forward and a backward pass, the two columns of the paper's Table 1: top down, every
+    layer's kernel gradient (fp32) and, for layers 5..2, its input gradient in bf16, which is the
+    output gradient of the layer below (layer 1's input gradient is of no use to training and is
+    not computed); the last layer's output gradient is a seeded bf16 tensor."""
     import numpy as np
     import torch
     from oracle import capsconv
@@ -265,8 +269,18 @@ def bench_net5(args):
                                 device="cuda"))
         wss.append(torch.empty(max(need, 16), dtype=torch.uint8, device="cuda"))
         shapes.append(shape)
+    train = args.op == "net5_train"
+    if train:
+        g_top = torch.from_numpy(wl.generate_dout(layers[-1])[0].view(np.int16)).cuda().view(torch.bfloat16)
+        # gin[k]: gradient with respect to layer k's input = output gradient of layer k-1
+        gin = [None] + [torch.empty(w.input_shape, dtype=torch.bfloat16, device="cuda")
+                        for w in layers[1:]]
+        dks = [torch.empty(w.kernel_shape, dtype=torch.float32, device="cuda") for w in layers]
+        need = max(max(cc.capscaps_conv_bwd_kernel_workspace_bytes(*s) for s in shapes),
+                   max(cc.capscaps_conv_bwd_input_out16_workspace_bytes(*s) for s in shapes[1:]))
+        ws_bwd = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
 
-    def step():
+    def forward():
         x = x0
         for k in range(len(layers)):
             fn = cc.capscaps_conv_fwd_ex if k + 1 == len(layers) else cc.capscaps_conv_fwd_out16
@@ -275,6 +289,32 @@ def bench_net5(args):
             if rc != cc.OK:
                 sys.exit(f"bench.py: capscaps status {rc}: {cc.capscaps_strerror(rc)}")
             x = outs[k]
+
+    def backward():
+        g = g_top
+        for k in range(len(layers) - 1, -1, -1):
+            x = x0 if k == 0 else outs[k - 1]
+            rc = cc.capscaps_conv_bwd_kernel(x.data_ptr(), g.data_ptr(), dks[k].data_ptr(),
+                                             *shapes[k], ws_bwd.data_ptr(), ws_bwd.numel(),
+                                             stream.cuda_stream)
+            if rc == cc.OK and k > 0:
+                rc = cc.capscaps_conv_bwd_input_out16(g.data_ptr(), kernels[k].data_ptr(),
+                                                      gin[k].data_ptr(), *shapes[k],
+                                                      ws_bwd.data_ptr(), ws_bwd.numel(),
+                                                      stream.cuda_stream)
+                g = gin[k]
+            if rc != cc.OK:
+                sys.exit(f"bench.py: capscaps status {rc}: {cc.capscaps_strerror(rc)}")
+
+    fwd_ms = []
+
+    def step():
+        forward()
+        if train:
+            mid_ev = torch.cuda.Event(enable_timing=True)
+            mid_ev.record(stream)
+            fwd_ms.append(mid_ev)
+            backward()
 
     for _ in range(args.warmup):
         step()
@@ -290,21 +330,30 @@ def bench_net5(args):
     ms_per_step = wall * 1e3 / args.steps
     kernel_ms = float(np.mean([ev[k].elapsed_time(ev[k + 1]) for k in range(args.steps)]))
     flops = sum(w.flops_tap_exact() for w in layers)
+    fwd_flops = flops
+    if train:  # each gradient has the forward pass's terms; layer 1's input gradient is left out
+        flops = 3 * flops - layers[0].flops_tap_exact()
+        mids = fwd_ms[-args.steps:]
+        forward_ms = float(np.mean([ev[k].elapsed_time(mids[k]) for k in range(args.steps)]))
     achieved = flops / (kernel_ms * 1e-3) / 1e12
     result = {
-        "metric": "capsule-conv net5 useful GFLOP/s at 1 GPU",
+        "metric": ("capsule-conv net5 forward + backward useful GFLOP/s at 1 GPU" if train else
+                   "capsule-conv net5 useful GFLOP/s at 1 GPU"),
         "value": round(flops / (ms_per_step * 1e-3) / 1e9, 1), "unit": "GFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16 in, f32 accumulate, bf16 activations", "data": "synthetic",
         "config": {"workload": "net5: five chained capsule convolutions, 8x8 capsules, N=64, 32x32",
-                   "op": "net5", "layers": [w.name + " " + "x".join(map(str, w.out_shape))
-                                            for w in layers],
+                   "op": args.op, "layers": [w.name + " " + "x".join(map(str, w.out_shape))
+                                             for w in layers],
                    "flops_tap_exact": flops},
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_TFLOPS["bf16"],
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_TFLOPS["bf16"], 4),
                      "traffic": None, "kernel_ms": round(kernel_ms, 4)},
     }
+    if train:
+        result["config"]["forward_ms"] = round(forward_ms, 4)
+        result["config"]["backward_ms"] = round(kernel_ms - forward_ms, 4)
     if not args.no_cpu_baseline:
         # the oracle on image 0 through all five layers, activations rounded as on the GPU
         x32 = i32[:1]
@@ -316,9 +365,9 @@ def bench_net5(args):
         dt = time.perf_counter() - t0
         got = outs[-1][:1].cpu().numpy()
         result["cpu_baseline"] = {
-            "value": round(flops / 64 / dt / 1e9, 3), "unit": "GFLOP/s",
+            "value": round(fwd_flops / 64 / dt / 1e9, 3), "unit": "GFLOP/s",
             "cores": capsconv.threads(), "kind": "oracle",
-            "sample": f"image 0 of 64 through all five layers; {dt:.1f} s"}
+            "sample": f"image 0 of 64 through all five layers, forward; {dt:.1f} s"}
         result["config"]["max_err_vs_oracle_sample"] = float(np.abs(got - y).max() / np.abs(y).max())
     print(json.dumps(result), flush=True)
 
@@ -333,7 +382,7 @@ def main():
                     choices=["auto", "mfma", "direct", "mfma-generic", "mfma-tuned16", "mfma-tuned32",
                              "mfma-small"])
     ap.add_argument("--op", default="fwd", choices=["fwd", "bwd_input", "bwd_input_out16", "bwd_kernel",
-                                                     "scheme1", "scheme2", "framework_conv", "net5"])
+                                                     "scheme1", "scheme2", "framework_conv", "net5", "net5_train"])
     ap.add_argument("--shape", default=None,
                     help="N,H,W,C,M,kh,kw,stride,pad,D0,D1,D2,D3: time this layer instead of a "
                          "benchmark configuration (inputs N(0,1), kernel N(0, 1/fan-in); --dtype)")
@@ -367,7 +416,7 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
-    if args.op == "net5":
+    if args.op in ("net5", "net5_train"):
         return bench_net5(args)
     torch.cuda.set_device(0)
     w = wl.config(args.config)

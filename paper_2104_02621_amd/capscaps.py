@@ -286,9 +286,10 @@ def _bwd_common(a, b):
         raise ValueError("operands must be contiguous")
 
 
-def conv_bwd_input(dout, kernel, input_hw, stride=1, pad=0):
+def conv_bwd_input(dout, kernel, input_hw, stride=1, pad=0, out16=False):
     """dout [N,H',W',M,D0,D1,D3], kernel [kh,kw,C,M,D0,D2,D3] (one dtype), input_hw = (H, W) of
-    the forward input -> float32 dinput [N,H,W,C,D0,D1,D2]."""
+    the forward input -> float32 dinput [N,H,W,C,D0,D1,D2] (with `out16`: of the operands' 16-bit
+    type)."""
     import torch
     _bwd_common(dout, kernel)
     N, Ho, Wo, M, D0, D1, D3 = dout.shape
@@ -301,12 +302,14 @@ def conv_bwd_input(dout, kernel, input_hw, stride=1, pad=0):
         raise ValueError("dout, kernel and input_hw do not describe one convolution")
     dt = _torch_dtype_code(dout)
     shape = (N, H, W, C, M, kh, kw, stride, pad, D0, D1, D2, D3, dt)
-    need = capscaps_conv_bwd_input_workspace_bytes(*shape)
+    need = (capscaps_conv_bwd_input_out16_workspace_bytes if out16 else
+            capscaps_conv_bwd_input_workspace_bytes)(*shape)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dout.device)
-    din = torch.empty((N, H, W, C, D0, D1, D2), dtype=torch.float32, device=dout.device)
-    rc = capscaps_conv_bwd_input(dout.data_ptr(), kernel.data_ptr(), din.data_ptr(), *shape,
-                                 ws.data_ptr(), ws.numel(),
-                                 torch.cuda.current_stream(dout.device).cuda_stream)
+    din = torch.empty((N, H, W, C, D0, D1, D2), dtype=dout.dtype if out16 else torch.float32,
+                      device=dout.device)
+    call = capscaps_conv_bwd_input_out16 if out16 else capscaps_conv_bwd_input
+    rc = call(dout.data_ptr(), kernel.data_ptr(), din.data_ptr(), *shape, ws.data_ptr(), ws.numel(),
+              torch.cuda.current_stream(dout.device).cuda_stream)
     if rc != OK:
         raise CapscapsError(rc)
     return din

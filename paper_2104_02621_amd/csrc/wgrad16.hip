@@ -64,7 +64,9 @@ struct WgradParams {
     int N, H, W, C, M, kw, stride, pad, D0, D2, D3, Ho, Wo;
     int rows, cols;  // C*D2, M*D3
     int row_tiles, col_tiles, ntaps;
-    int tiles;       // ntaps * D0 * row_tiles * col_tiles
+    int tiles;       // ntap_items * D0 * row_tiles * col_tiles
+    int pair;        // 1: at most 128 rows; a tile holds two window taps (see PAIR in the kernel)
+    int ntap_items;  // ntaps, or with pair (ntaps + 1) / 2
     int nsplit, imgs_per_split;
     long long items;      // tiles * nsplit = workgroups
     long long out_elems;  // elements of dK
@@ -103,7 +105,14 @@ __global__ __launch_bounds__(256) void transpose_caps_kernel(const chunk_t* __re
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v lds_short4v;
 
-template <typename Tag, int D1, bool OWN>
+// PAIR: layers with at most 128 rows (c, d2) would leave half of the 256-row tile empty; their
+// tiles hold two window taps instead, tap 2i in rows 0..127 and tap 2i+1 in rows 128..255.  Both
+// multiply the same output-gradient pixels, so the column side is shared; the row side of the
+// second tap is the input one tap further on, a constant byte distance that travels in the lane
+// offsets of the waves that copy rows 128..255.  The pixels walked are the bounding rectangle of
+// the two taps' rectangles; where a wave's own tap reads outside the image its row-side copies
+// are zero fill (decided per pixel from the walker's row and column counters).
+template <typename Tag, int D1, bool OWN, bool PAIR = false>
 __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
 {
     constexpr int KCH = 4, NB = 4;
@@ -128,6 +137,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     constexpr int VMCNT_KEEP = 0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14);
     static_assert(D1 == 1 || D1 == 2 || D1 == 4 || D1 == 8 || D1 == 16, "D1");
     static_assert(NMMA == 16 && KCH == 4, "the schedule below is written for this shape");
+    static_assert(!PAIR || (OWN && !VW && WM == 128), "tap pairs: in-place reads, scalar walk");
 
     extern __shared__ char smem[];
 
@@ -145,12 +155,17 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     rest /= P.col_tiles;
     const int row_tile = rest % P.row_tiles;
     rest /= P.row_tiles;
-    const int tap = rest % P.ntaps;
-    const int d0 = rest / P.ntaps;
+    const int tap = (PAIR ? 2 : 1) * (rest % P.ntap_items);
+    const int d0 = rest / P.ntap_items;
     const int tp = tap / P.kw, tq = tap - tp * P.kw;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // (tap pairs) the second tap, and whether this wave copies its rows
+    const int tap_b = tap + 1;
+    const bool has_b = PAIR && tap_b < P.ntaps;
+    const int tp_b = tap_b / P.kw, tq_b = tap_b - tp_b * P.kw;
+    const bool copies_b = PAIR && wave >= 2;
     const int wm = wave % NWM, wn = wave / NWM;
     const int h = lane >> 5, lr = lane & 31;
 
@@ -160,7 +175,10 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     const int n1 = n0 + P.imgs_per_split < P.N ? n0 + P.imgs_per_split : P.N;
     const int s = P.stride;
     int nx, ny, x_lo, y_lo;
-    {
+    // (tap pairs) this wave's own tap lies inside the image where the walker's counters satisfy
+    // xb <= rows left <= xa and yb <= pixels left in the row <= ya
+    int pv_xa = 0, pv_xb = 0, pv_ya = 0, pv_yb = 0;
+    if constexpr (!PAIR) {
         const int tx = P.pad - tp, ty = P.pad - tq;  // need x*s >= tx and x*s <= H-1+tx
         x_lo = tx > 0 ? (tx + s - 1) / s : 0;
         y_lo = ty > 0 ? (ty + s - 1) / s : 0;
@@ -171,6 +189,43 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
         nx = x_hi - x_lo + 1;
         ny = y_hi - y_lo + 1;
         if (nx <= 0 || ny <= 0) nx = ny = 0;
+    } else {
+        // rectangle [xl, xh] x [yl, yh] of a tap; empty: xh < xl
+        auto tap_rect = [&](int tp_, int tq_, int& xl, int& xh, int& yl, int& yh) {
+            const int tx = P.pad - tp_, ty = P.pad - tq_;
+            xl = tx > 0 ? (tx + s - 1) / s : 0;
+            yl = ty > 0 ? (ty + s - 1) / s : 0;
+            const int hx = P.H - 1 + tx, hy = P.W - 1 + ty;
+            xh = hx >= 0 ? hx / s : -1;
+            yh = hy >= 0 ? hy / s : -1;
+            if (xh > P.Ho - 1) xh = P.Ho - 1;
+            if (yh > P.Wo - 1) yh = P.Wo - 1;
+            if (xh < xl || yh < yl) {
+                xl = yl = 0;
+                xh = yh = -1;
+            }
+        };
+        int axl, axh, ayl, ayh, bxl = 0, bxh = -1, byl = 0, byh = -1;
+        tap_rect(tp, tq, axl, axh, ayl, ayh);
+        if (has_b) tap_rect(tp_b, tq_b, bxl, bxh, byl, byh);
+        const bool ea = axh < axl, eb = bxh < bxl;
+        int x_hi, y_hi;
+        if (ea || eb) {  // one rectangle (or none)
+            x_lo = ea ? bxl : axl; x_hi = ea ? bxh : axh;
+            y_lo = ea ? byl : ayl; y_hi = ea ? byh : ayh;
+        } else {
+            x_lo = axl < bxl ? axl : bxl; x_hi = axh > bxh ? axh : bxh;
+            y_lo = ayl < byl ? ayl : byl; y_hi = ayh > byh ? ayh : byh;
+        }
+        nx = x_hi - x_lo + 1;
+        ny = y_hi - y_lo + 1;
+        if (nx <= 0 || ny <= 0) nx = ny = 0;
+        const int mxl = copies_b ? bxl : axl, mxh = copies_b ? bxh : axh;
+        const int myl = copies_b ? byl : ayl, myh = copies_b ? byh : ayh;
+        // pixel (x, y) of the walk has nx - (x - x_lo) rows and ny - (y - y_lo) pixels left
+        pv_xa = nx - (mxl - x_lo); pv_xb = nx - (mxh - x_lo);
+        pv_ya = ny - (myl - y_lo); pv_yb = ny - (myh - y_lo);
+        if (mxh < mxl) pv_xa = -1;  // never
     }
     const int npix = (n1 - n0) * nx * ny;
     const int ipix = P.C * P.D0 * P.D2 * D1 * 2;  // bytes per pixel of It / Gt
@@ -181,13 +236,22 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     const int i_rowjump = (s * P.W - (ny - 1) * s) * ipix, g_rowjump = (P.Wo - (ny - 1)) * gpix;
     const int i_imgjump = (P.H * P.W - nx * s * P.W) * ipix, g_imgjump = (P.Ho * P.Wo - nx * P.Wo) * gpix;
     // one walker over the pixel sequence with a position in either tensor
-    int i_cur = ((x_lo * s - (P.pad - tp)) * P.W + (y_lo * s - (P.pad - tq))) * ipix;
+    // (tap pairs) the walker follows the first tap's input pixel, which at the border lies up to
+    // `pad` rows and pixels before the image, and the second tap's lies up to kw - 1 pixels before
+    // that one: the descriptor's base is moved down by both, and the offsets up, so that all stay
+    // non-negative.  Only offsets of pixels inside an image are ever dereferenced.
+    const int bias_walk = PAIR ? (P.pad * P.W + P.pad) * ipix : 0;
+    const int bias_lane = PAIR ? P.kw * ipix : 0;
+    int i_cur = ((x_lo * s - (P.pad - tp)) * P.W + (y_lo * s - (P.pad - tq))) * ipix + bias_walk;
     int g_cur = (x_lo * P.Wo + y_lo) * gpix;
     int w_left = npix, w_yl = ny, w_xl = nx;
 
-    const char* it_base = static_cast<const char*>(P.it) + (long long)n0 * P.it_img_bytes;
+    const unsigned long long it_base = reinterpret_cast<unsigned long long>(P.it) +
+                                       (unsigned long long)((long long)n0 * P.it_img_bytes) -
+                                       (unsigned long long)(bias_walk + bias_lane);
     const char* gt_base = static_cast<const char*>(P.gt) + (long long)n0 * P.gt_img_bytes;
-    const rsrc_t rs_it = make_rsrc(it_base, (unsigned)((n1 - n0) * P.it_img_bytes));
+    const rsrc_t rs_it = make_rsrc(reinterpret_cast<const void*>(it_base),
+                                   (unsigned)((n1 - n0) * P.it_img_bytes + bias_walk + bias_lane));
     const rsrc_t rs_gt = make_rsrc(gt_base, (unsigned)((n1 - n0) * P.gt_img_bytes));
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) char*)smem;
     // this wave copies rows (and columns) wave*64 .. +63 of the tile, all chunks (OWN: copy kc
@@ -209,7 +273,12 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     if constexpr (OWN) {
         const int ra = a_wide ? (lane >> 4) * 2 + (lane & 1) : lane >> 3;
         const int la = (a_wide ? (lane & 15) >> 1 : lane & 7) ^ (((ra >> 1) & 1) * 4);
-        const int R = row_tile * BM + (wave * 8 + ra) * 8;
+        // (tap pairs: rows 128..255 are rows 0..127 of the second tap.  There the lanes of rows
+        // past the last one copy row 0 again instead of carrying the out-of-range mark -- those
+        // tile rows are never stored -- so that a lane offset plus a pixel's out-of-range mark
+        // can never wrap around to the bytes before the tensor that the moved base covers.)
+        const int R_pair = ((wave & 1) * 8 + ra) * 8;
+        const int R = PAIR ? (R_pair < P.rows ? R_pair : 0) : row_tile * BM + (wave * 8 + ra) * 8;
         const int c = R / P.D2, d2 = R - c * P.D2;
         if constexpr (VW) {
             // line la % D1 of pixel la / D1 of the copy
@@ -223,6 +292,11 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
                 a_voff = R < P.rows ? (unsigned)(((((c * P.D0 + d0) * D1 + (la & 3)) * P.D2) + d2) * 2) : (unsigned)OOB;
         } else
             a_voff = R < P.rows ? (unsigned)(((((c * P.D0 + d0) * D1 + la) * P.D2) + d2) * 2) : (unsigned)OOB;
+        if constexpr (PAIR) {
+            // the second tap's input pixel relative to the first one's
+            const int delta = ((tp_b - tp) * P.W + (tq_b - tq)) * ipix;
+            a_voff += (unsigned)(bias_lane + (copies_b ? delta : 0));
+        }
         const int rb = b_wide ? (lane >> 4) * 2 + (lane & 1) : lane >> 3;
         const int lb = (b_wide ? (lane & 15) >> 1 : lane & 7) ^ (((rb >> 1) & 1) * 4);
         const int J = col_tile * BN + (wave * 8 + rb) * 8;
@@ -303,6 +377,20 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
                          : "=&s"(a_soff[j]), "=&s"(g_soff[j]), "+s"(w_left)
                          : "s"(i_cur), "s"(g_cur)
                          : "scc");
+            if constexpr (PAIR) {
+                // this wave's tap outside the image at this pixel: zero fill
+                asm volatile("s_cmp_gt_i32 %1, %3\n\t"
+                             "s_cselect_b32 %0, 0x80000000, %0\n\t"
+                             "s_cmp_lt_i32 %1, %4\n\t"
+                             "s_cselect_b32 %0, 0x80000000, %0\n\t"
+                             "s_cmp_gt_i32 %2, %5\n\t"
+                             "s_cselect_b32 %0, 0x80000000, %0\n\t"
+                             "s_cmp_lt_i32 %2, %6\n\t"
+                             "s_cselect_b32 %0, 0x80000000, %0"
+                             : "+s"(a_soff[j])
+                             : "s"(w_xl), "s"(w_yl), "s"(pv_xa), "s"(pv_xb), "s"(pv_ya), "s"(pv_yb)
+                             : "scc");
+            }
         } else if (piece == 1) {
             // next pixel of the rectangle row, or (row done) first pixel of the next row
             asm volatile("s_add_i32 %0, %0, -1\n\t"
@@ -574,10 +662,12 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     const long long caps = (long long)P.D0 * P.D2 * P.D3;
 #pragma unroll
     for (int b = 0; b < TM; ++b) {
-        const int R = row_tile * BM + wm * WM + b * 32 + lr;
-        if (R >= P.rows) continue;
+        // (tap pairs: the waves of rows 128..255 hold the second tap's rows 0..127)
+        const int R = PAIR ? b * 32 + lr : row_tile * BM + wm * WM + b * 32 + lr;
+        const int tap_out = PAIR ? tap + wm : tap;
+        if (R >= P.rows || tap_out >= P.ntaps) continue;
         const int c = R / P.D2, d2 = R - c * P.D2;
-        float* orow = out + ((long long)tap * P.C + c) * P.M * caps +
+        float* orow = out + ((long long)tap_out * P.C + c) * P.M * caps +
                       ((long long)d0 * P.D2 + d2) * P.D3;
 #pragma unroll
         for (int a = 0; a < TN; ++a) {
@@ -602,6 +692,15 @@ struct WgradPlan {
 
 int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b); }
 
+// Shapes whose tiles can hold two window taps (PAIR in the kernel)
+bool tap_pairs_possible(const ConvShape& s)
+{
+    const bool paired4 = s.D1 == 4 && s.D2 == 4 && s.D3 == 4 && s.C % 2 == 0 && s.M % 2 == 0;
+    const bool in_place = s.D2 % 8 == 0 && s.D3 % 8 == 0;
+    return (s.D1 == 4 || s.D1 == 8 || s.D1 == 16) && (in_place || paired4) &&
+           s.C * s.D2 <= 128 && s.kh * s.kw >= 2;
+}
+
 // Tiles and the split over images (host side, pure arithmetic).
 WgradPlan make_plan(const ConvShape& s)
 {
@@ -614,18 +713,25 @@ WgradPlan make_plan(const ConvShape& s)
     P.row_tiles = ceil_div_i(P.rows, 256);
     P.col_tiles = ceil_div_i(P.cols, 256);
     P.ntaps = s.kh * s.kw;
-    P.tiles = P.ntaps * s.D0 * P.row_tiles * P.col_tiles;
     P.out_elems = (long long)s.kernel_elems();
     P.it_img_bytes = (long long)s.H * s.W * s.C * s.D0 * s.D1 * s.D2 * 2;
     P.gt_img_bytes = (long long)s.Ho * s.Wo * s.M * s.D0 * s.D1 * s.D3 * 2;
     pl.it_bytes = (size_t)s.N * P.it_img_bytes;
     pl.gt_bytes = (size_t)s.N * P.gt_img_bytes;
+    // Two window taps per tile where the rows fill at most half of it (tensors read in place or
+    // as channel-paired copies, capsules of 4, 8 or 16 rows); the byte offsets, moved up by the
+    // reach of the padding and of the window's width, must still fit 31 bits for one image.
+    const long long pair_bias = ((long long)s.pad * s.W + s.pad + s.kw) * s.C * s.D0 * s.D1 * s.D2 * 2;
+    P.pair = tap_pairs_possible(s) && P.it_img_bytes + 2 * pair_bias < (1LL << 31) - (1 << 20) ? 1 : 0;
+    P.ntap_items = P.pair ? (P.ntaps + 1) / 2 : P.ntaps;
+    P.tiles = P.ntap_items * s.D0 * P.row_tiles * P.col_tiles;
 
     // Images per workgroup: the cost of a choice is (rounds of 256 workgroups) x (pixels per
     // workgroup + the fixed cost of a workgroup, about 15 us, in pixel units); byte offsets
     // within a workgroup's images must stay below 2^31, and the partial sums below 1 GiB.
     const long long img_max = P.it_img_bytes > P.gt_img_bytes ? P.it_img_bytes : P.gt_img_bytes;
-    long long imgs_cap = ((1LL << 31) - 1) / (img_max > 0 ? img_max : 1);
+    long long imgs_cap = ((1LL << 31) - 1 - (P.pair ? 2 * pair_bias + (1 << 20) : 0)) / (img_max > 0 ? img_max : 1);
+    if (imgs_cap < 1) imgs_cap = 1;
     if (imgs_cap > s.N) imgs_cap = s.N;
     const double pix_per_img = (double)s.Ho * s.Wo;
     const double fixed = 1120.0 / s.D1;  // D1 = 16: 70 pixels
@@ -664,10 +770,10 @@ hipError_t launch_transpose(const void* src, void* dst, size_t nmat, int A, int 
     return hipGetLastError();
 }
 
-template <typename Tag, int D1, bool OWN>
+template <typename Tag, int D1, bool OWN, bool PAIR = false>
 hipError_t launch_kernel(const WgradParams& P, hipStream_t stream)
 {
-    auto kern = wgrad16_kernel<Tag, D1, OWN>;
+    auto kern = wgrad16_kernel<Tag, D1, OWN, PAIR>;
     const size_t lds_bytes = (size_t)4 * 2 * 4 * 256 * 16;  // ring of 4 stages of 32 KB
     static std::atomic<unsigned long long> lds_set{0};
     hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes, lds_set);
@@ -750,7 +856,17 @@ hipError_t launch_wgrad16(const ConvShape& s, const void* input, const void* dou
         pl.P.gt = gt;
     }
     pl.P.out = pl.P.nsplit > 1 ? partial : dkernel;
-    if (s.D1 == 4) {  // in place, or on the channel-paired copies
+    if (pl.P.pair) {  // two window taps per tile
+        if (s.D1 == 4)
+            err = s.dtype == 2 ? launch_kernel<f16_tag, 4, true, true>(pl.P, stream)
+                               : launch_kernel<bf16_tag, 4, true, true>(pl.P, stream);
+        else if (s.D1 == 8)
+            err = s.dtype == 2 ? launch_kernel<f16_tag, 8, true, true>(pl.P, stream)
+                               : launch_kernel<bf16_tag, 8, true, true>(pl.P, stream);
+        else
+            err = s.dtype == 2 ? launch_kernel<f16_tag, 16, true, true>(pl.P, stream)
+                               : launch_kernel<bf16_tag, 16, true, true>(pl.P, stream);
+    } else if (s.D1 == 4) {  // in place, or on the channel-paired copies
         err = s.dtype == 2 ? launch_kernel<f16_tag, 4, true>(pl.P, stream)
                            : launch_kernel<bf16_tag, 4, true>(pl.P, stream);
     } else if (s.D1 == 2) {

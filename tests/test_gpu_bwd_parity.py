@@ -133,6 +133,18 @@ BWD_SHAPES = SMALL_SHAPES + [
     ("ph16_d4", 14, 80, 78, 4, 8, 3, 3, 2, 1, 1, 4, 4, 4),
     ("ph16_ns", 10, 60, 62, 6, 4, 3, 3, 2, 1, 1, 8, 16, 8),
     ("ph32_d3", 8, 100, 97, 5, 6, 4, 4, 3, 2, 3, 3, 3, 3),
+    # at most 128 rows (c, d2): the 16-bit kernel gradient puts two window taps into a tile.  A 5x5
+    # window with padding 2 (25 taps: the last pair has one; neighbouring taps' pixel ranges
+    # differ by up to two), stride 3 with a leading capsule index and 16-row capsules, an image
+    # narrower than the window (the next row's first tap lies before the previous row's last),
+    # a 1x1 image (pairs of which one or no tap meets it), channel-paired 4x4 capsules, and
+    # exactly 128 rows under a 1x2 window
+    ("wgp_k5", 2, 6, 7, 3, 5, 5, 5, 1, 2, 1, 8, 8, 8),
+    ("wgp_s3", 2, 10, 9, 4, 3, 3, 2, 3, 1, 2, 16, 16, 8),
+    ("wgp_thin", 3, 2, 2, 2, 3, 5, 5, 1, 2, 1, 8, 8, 8),
+    ("wgp_1x1", 2, 1, 1, 3, 2, 5, 5, 1, 2, 1, 4, 8, 8),
+    ("wgp_44", 3, 9, 8, 6, 4, 3, 3, 2, 1, 1, 4, 4, 4),
+    ("wgp_128", 2, 7, 7, 16, 3, 1, 2, 1, 0, 1, 8, 8, 8),
 ]
 
 

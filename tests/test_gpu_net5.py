@@ -1,6 +1,8 @@
 """GPU parity of the chained five-layer stack: layers 1-4 through the 16-bit-output entry point
 (each layer's output is the next one's input, no conversion pass), layer 5 to fp32, against the
-oracle applied layer by layer with the same rounding of the activations to the 16-bit type."""
+oracle applied layer by layer with the same rounding of the activations to the 16-bit type; and
+the way back (Algorithm 4 per layer): every layer's kernel gradient, and the input gradients
+through the 16-bit entry point, each the output gradient of the layer below."""
 import numpy as np
 import pytest
 
@@ -44,3 +46,44 @@ def test_five_layer_stack_matches_oracle(dtype):
     # in different precision (fp32 vs fp64), so a few activations land on neighbouring 16-bit
     # values; what that leaves after four more layers is far below the 16-bit tolerance
     assert err <= 2e-2
+
+
+def oracle_backward(layers, acts32, g32):
+    """Kernel gradients of all layers, top down; the gradient handed to the layer below is rounded
+    to the storage type, as the activations are on the way up."""
+    dks = [None] * len(layers)
+    for k in range(len(layers) - 1, -1, -1):
+        w = layers[k]
+        k32 = wl.generate(w)[3]
+        dks[k] = capsconv.conv_bwd_kernel(acts32[k], g32, (w.kh, w.kw), w.stride, w.pad)
+        if k > 0:
+            d = capsconv.conv_bwd_input(g32, k32, (w.H, w.W), w.stride, w.pad)
+            _, g32 = wl.to_storage(d.astype(np.float32), w.dtype)
+    return dks
+
+
+@pytest.mark.parametrize("dtype", [wl.BF16, wl.FP16], ids=["bf16", "fp16"])
+def test_five_layer_stack_backward_matches_oracle(dtype):
+    layers = wl.net5(N=2, dtype=dtype)
+    i_st, _, i32, _ = wl.generate(layers[0])
+    # forward on both sides, keeping every layer's input
+    acts32, acts_dev = [i32], [to_device(i_st, dtype)]
+    kernels_dev = [to_device(wl.generate(w)[1], dtype) for w in layers]
+    for k, w in enumerate(layers[:-1]):
+        y = capsconv.conv_fwd(acts32[-1], wl.generate(w)[3], w.stride, w.pad)
+        acts32.append(wl.to_storage(y.astype(np.float32), dtype)[1])
+        acts_dev.append(cc.conv_fwd(acts_dev[-1], kernels_dev[k], w.stride, w.pad, out16=True))
+    g_st, g32 = wl.generate_dout(layers[-1])
+    ref = oracle_backward(layers, acts32, g32)
+    g = to_device(g_st, dtype)
+    for k in range(len(layers) - 1, -1, -1):
+        w = layers[k]
+        dk = cc.conv_bwd_kernel(acts_dev[k], g, (w.kh, w.kw), w.stride, w.pad).cpu().numpy()
+        err = np.abs(dk - ref[k]).max() / np.abs(ref[k]).max()
+        print(f"net5 {wl.DTYPE_NAMES[dtype]} layer {k + 1}: dK max|g-r|/max|r| = {err:.3e}", flush=True)
+        # the activations and gradients the two sides multiply differ where a rounding to the
+        # 16-bit type fell the other way (fp32 against fp64 sums); see the forward test
+        assert err <= 2e-2
+        if k > 0:
+            g = cc.conv_bwd_input(g, kernels_dev[k], (w.H, w.W), w.stride, w.pad, out16=True)
+            assert g.dtype == acts_dev[k].dtype and g.shape == acts_dev[k].shape
