@@ -67,7 +67,7 @@ struct WgradParams {
     int tiles;       // ntap_items * D0 * row_tiles * col_tiles
     int pair;        // 1: at most 128 rows; a tile holds two window taps (see PAIR in the kernel)
     int ntap_items;  // ntaps, or with pair (ntaps + 1) / 2
-    int nsplit, imgs_per_split;
+    int nsplit;      // ranges a tap's pixel sequence is cut into
     long long items;      // tiles * nsplit = workgroups
     long long out_elems;  // elements of dK
     long long it_img_bytes, gt_img_bytes;
@@ -169,10 +169,10 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     const int wm = wave % NWM, wn = wave / NWM;
     const int h = lane >> 5, lr = lane & 31;
 
-    // ---- the pixels of this item: images [n0, n1), and per image the rectangle of output
-    // pixels (x, y) whose tap (tp, tq) reads a real input pixel
-    const int n0 = split * P.imgs_per_split;
-    const int n1 = n0 + P.imgs_per_split < P.N ? n0 + P.imgs_per_split : P.N;
+    // ---- the pixels of this item.  Per image the output pixels (x, y) whose tap (tp, tq) reads a
+    // real input pixel form a rectangle; the rectangles of all images, image after image, row
+    // after row, are one sequence, which is cut into nsplit equal ranges: this item contracts the
+    // range [t0, t1), which begins at pixel (xs, ys) of the rectangle of image n0.
     const int s = P.stride;
     int nx, ny, x_lo, y_lo;
     // (tap pairs) this wave's own tap lies inside the image where the walker's counters satisfy
@@ -227,7 +227,17 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
         pv_ya = ny - (myl - y_lo); pv_yb = ny - (myh - y_lo);
         if (mxh < mxl) pv_xa = -1;  // never
     }
-    const int npix = (n1 - n0) * nx * ny;
+    const long long rect = (long long)nx * ny, total = rect * P.N;
+    const long long tps = (total + P.nsplit - 1) / P.nsplit;
+    long long t0 = (long long)split * tps;
+    if (t0 > total) t0 = total;
+    long long t1 = t0 + tps;
+    if (t1 > total) t1 = total;
+    const int npix = (int)(t1 - t0);
+    const int n0 = npix > 0 ? (int)(t0 / rect) : 0;
+    const int n1 = npix > 0 ? (int)((t1 - 1) / rect) + 1 : n0 + 1;
+    const int r0 = npix > 0 ? (int)(t0 - (long long)n0 * rect) : 0;  // position in image n0
+    const int xs = ny > 0 ? r0 / ny : 0, ys = ny > 0 ? r0 - xs * ny : 0;
     const int ipix = P.C * P.D0 * P.D2 * D1 * 2;  // bytes per pixel of It / Gt
     const int gpix = P.M * P.D0 * P.D3 * D1 * 2;
     const int i_step = s * ipix, g_step = gpix;
@@ -242,9 +252,9 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     // non-negative.  Only offsets of pixels inside an image are ever dereferenced.
     const int bias_walk = PAIR ? (P.pad * P.W + P.pad) * ipix : 0;
     const int bias_lane = PAIR ? P.kw * ipix : 0;
-    int i_cur = ((x_lo * s - (P.pad - tp)) * P.W + (y_lo * s - (P.pad - tq))) * ipix + bias_walk;
-    int g_cur = (x_lo * P.Wo + y_lo) * gpix;
-    int w_left = npix, w_yl = ny, w_xl = nx;
+    int i_cur = (((x_lo + xs) * s - (P.pad - tp)) * P.W + ((y_lo + ys) * s - (P.pad - tq))) * ipix + bias_walk;
+    int g_cur = ((x_lo + xs) * P.Wo + y_lo + ys) * gpix;
+    int w_left = npix, w_yl = ny - ys, w_xl = nx - xs;
 
     const unsigned long long it_base = reinterpret_cast<unsigned long long>(P.it) +
                                        (unsigned long long)((long long)n0 * P.it_img_bytes) -
@@ -427,7 +437,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     // of the range begin at or after it (v_left <= 0: past the end).  A stage on, every lane moves
     // PPS pixels forward: two divisions of small numbers (by the rectangle's width and height),
     // done as a float multiplication with one correction step (exact for quotients below 2^20).
-    int vx = 0, vy = 0, vn = 0, v_left = npix - lane;  // a range begins with an image
+    int vx = xs, vy = ys, vn = 0, v_left = npix - lane;
     const int ny1 = ny > 0 ? ny : 1, nx1 = nx > 0 ? nx : 1;
     const float inv_ny = 1.0f / (float)ny1, inv_nx = 1.0f / (float)nx1;
     auto small_div = [](int a, int d, float inv) {
@@ -726,30 +736,40 @@ WgradPlan make_plan(const ConvShape& s)
     P.ntap_items = P.pair ? (P.ntaps + 1) / 2 : P.ntaps;
     P.tiles = P.ntap_items * s.D0 * P.row_tiles * P.col_tiles;
 
-    // Images per workgroup: the cost of a choice is (rounds of 256 workgroups) x (pixels per
-    // workgroup + the fixed cost of a workgroup, about 15 us, in pixel units); byte offsets
-    // within a workgroup's images must stay below 2^31, and the partial sums below 1 GiB.
+    // Ranges per tap: the cost of a choice is (rounds of 256 workgroups) x (pixels per workgroup
+    // + the fixed cost of a workgroup, about 15 us, in pixel units).  A range of N*rect/nsplit
+    // pixels touches at most N/nsplit + 2 images, whose byte offsets must stay below 2^31 (where
+    // two images already exceed that, every range is one image); the partial sums stay below 1 GiB.
     const long long img_max = P.it_img_bytes > P.gt_img_bytes ? P.it_img_bytes : P.gt_img_bytes;
-    long long imgs_cap = ((1LL << 31) - 1 - (P.pair ? 2 * pair_bias + (1 << 20) : 0)) / (img_max > 0 ? img_max : 1);
-    if (imgs_cap < 1) imgs_cap = 1;
-    if (imgs_cap > s.N) imgs_cap = s.N;
-    const double pix_per_img = (double)s.Ho * s.Wo;
+    const long long room = (1LL << 31) - 1 - (P.pair ? 2 * pair_bias + (1 << 20) : 0);
+    const long long imgs_cap = room / (img_max > 0 ? img_max : 1);  // images a range may touch
+    const double pix_total = (double)s.N * s.Ho * s.Wo;
     const double fixed = 1120.0 / s.D1;  // D1 = 16: 70 pixels
+    int nsplit_min = 1, nsplit_max = s.N;
+    if (imgs_cap < 3) {
+        nsplit_min = s.N;  // image-aligned ranges
+    } else {
+        nsplit_min = ceil_div_i(s.N, imgs_cap - 2);
+        // at least 16 stages per range
+        const long long by_len = (long long)(pix_total / (16.0 * 32 / s.D1));
+        nsplit_max = (int)(by_len < 1 ? 1 : by_len > 4096 ? 4096 : by_len);
+        if (nsplit_max < nsplit_min) nsplit_max = nsplit_min;
+    }
     double best = 0;
-    int best_imgs = (int)imgs_cap;
-    for (int imgs = (int)imgs_cap; imgs >= 1; --imgs) {
-        const int nsplit = ceil_div_i(s.N, imgs);
-        if (nsplit > 1 && (double)nsplit * P.out_elems * 4 > (double)(1 << 30)) break;
+    int best_split = nsplit_min;
+    for (int nsplit = nsplit_min; nsplit <= nsplit_max; ++nsplit) {
+        if (nsplit > nsplit_min && (double)nsplit * P.out_elems * 4 > (double)(1 << 30)) break;
         const long long items = (long long)nsplit * P.tiles;
         const double rounds = (double)((items + 255) / 256);
-        const double cost = rounds * (imgs * pix_per_img + fixed);
-        if (imgs == (int)imgs_cap || cost < best * 0.98) {
+        const double cost = rounds * (pix_total / nsplit + fixed);
+        // (a finer cut must be cheaper by a margin; measured on config 5: 16 ranges, 9 full rounds,
+        // 15.14 ms against 15.54 ms for 7 ranges in 3.94 rounds, which this model puts level)
+        if (nsplit == nsplit_min || cost < best * 0.995) {
             best = cost;
-            best_imgs = imgs;
+            best_split = nsplit;
         }
     }
-    P.imgs_per_split = best_imgs < 1 ? 1 : best_imgs;
-    P.nsplit = ceil_div_i(s.N, P.imgs_per_split);
+    P.nsplit = best_split;
     P.items = (long long)P.nsplit * P.tiles;
     pl.partial_bytes = P.nsplit > 1 ? (size_t)P.nsplit * P.out_elems * sizeof(float) : 0;
     return pl;
@@ -804,7 +824,7 @@ bool wgrad16_eligible(const ConvShape& s)
     if ((long long)s.C * s.D2 >= (1 << 24) || (long long)s.M * s.D3 >= (1 << 24)) return false;
     const long long tiles = (long long)s.kh * s.kw * s.D0 * (((long long)s.C * s.D2 + 255) / 256) *
                             (((long long)s.M * s.D3 + 255) / 256);
-    if (tiles * s.N >= (1LL << 31)) return false;
+    if (tiles * (s.N > 4096 ? s.N : 4096) >= (1LL << 31)) return false;  // tiles x ranges
     return true;
 }
 

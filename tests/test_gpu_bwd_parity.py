@@ -214,7 +214,8 @@ def test_benchmark_configs_full_size_sampled(number):
 
 def test_workspace_too_small_is_refused():
     import torch
-    w = small("s1", wl.FP16, 2, 6, 6, 4, 4, 3, 3, 1, 1, 1, 8, 8, 8)
+    # enough pixels for the kernel gradient to cut its contraction into ranges (partial sums)
+    w = small("s1", wl.FP16, 40, 6, 6, 4, 4, 3, 3, 1, 1, 1, 8, 8, 8)
     args = shape_args(w)
     need_i = cc.capscaps_conv_bwd_input_workspace_bytes(*args)
     need_k = cc.capscaps_conv_bwd_kernel_workspace_bytes(*args)
@@ -226,6 +227,7 @@ def test_workspace_too_small_is_refused():
     assert cc.capscaps_conv_bwd_kernel(p, p, p, *args, 0, 0, st) == cc.EWORKSPACE
     assert cc.capscaps_conv_bwd_input(0, p, p, *args, p, need_i, st) == cc.EINVAL
     # a non-square window takes the gather kernel for dI, which needs no scratch
-    nonsq = small("ns", wl.FP16, 2, 6, 6, 4, 4, 3, 2, 1, 1, 1, 8, 8, 8)
+    # (its kernel gradient: capsule widths of 4 elements go through transposed copies)
+    nonsq = small("ns", wl.FP16, 2, 6, 6, 4, 4, 3, 2, 1, 1, 1, 8, 8, 4)
     assert cc.capscaps_conv_bwd_input_workspace_bytes(*shape_args(nonsq)) == 0
     assert cc.capscaps_conv_bwd_kernel_workspace_bytes(*shape_args(nonsq)) > 0
