@@ -333,6 +333,8 @@ size_t bwd_kernel_workspace_bytes(const ConvShape& s)
            forward_workspace_bytes(bwd_kernel_conv_shape(s));
 }
 
+// `din` holds fp32 elements, or with s.out16 set 16-bit elements of that kind (every route's
+// convolution shape carries s.out16 on, so its kernels round once at their stores).
 int launch_bwd_input(const ConvShape& s, const void* dout, const void* kernel, float* din,
                      void* workspace, size_t workspace_bytes, hipStream_t stream)
 {

@@ -107,8 +107,7 @@ int forward_tuned32(const ConvShape& s, const void* in, const void* kernel, floa
                     void* workspace, size_t workspace_bytes, hipStream_t stream);
 int status_from_hip(hipError_t err);
 
-// Backward pass (backward.hip): gradients with respect to input and kernel, fp32 results (the
-// input gradient in 16-bit elements of kind s.out16 when that is set).
+// Backward pass (backward.hip): gradients with respect to input and kernel, fp32 results.
 size_t bwd_input_workspace_bytes(const ConvShape& s);
 size_t bwd_kernel_workspace_bytes(const ConvShape& s);
 // Return a status code of the C ABI.
