@@ -427,13 +427,26 @@ def test_torch_wrapper_and_side_stream():
     check(w, out.cpu().numpy(), ref, S, "wrapper")
 
 
-def test_calls_can_be_captured_in_a_graph():
+GRAPH_CASES = {
+    # split-K path: repack, MFMA kernel, reduction; and both gradients
+    "config4": lambda: wl.config(4),
+    # a strided 16-bit layer of 4x4 capsules: channel-pairing pre-passes, the input gradient as four
+    # phase convolutions through output views, the kernel gradient with two taps per tile and a
+    # reduction over pixel ranges
+    "strided4x4": lambda: small("g4x4", wl.BF16, 14, 80, 78, 4, 8, 3, 3, 2, 1, 1, 4, 4, 4, seed=31),
+    # stride 3 under a 2x2 window: one phase of input pixels no window reaches (zeroed by a kernel)
+    "stride3": lambda: small("gs3", wl.FP16, 3, 120, 118, 4, 8, 2, 2, 3, 0, 1, 8, 4, 8, seed=32),
+}
+
+
+@pytest.mark.parametrize("case", list(GRAPH_CASES))
+def test_calls_can_be_captured_in_a_graph(case):
     """With caller-provided scratch the library only enqueues kernels on the stream it is given
     (no allocation, no memset, no synchronisation), so a call can be captured in a HIP graph.
     Replays, with eager work and synchronisations between them, must reproduce the eager
-    result every time (split-K path: repack, MFMA kernel, reduction; and both gradients)."""
+    result every time."""
     import torch
-    w = wl.config(4)
+    w = GRAPH_CASES[case]()
     i_st, k_st, _, _ = wl.generate(w)
     g_st, _ = wl.generate_dout(w)
     I, K, G = (to_device(a, w.dtype) for a in (i_st, k_st, g_st))
@@ -441,10 +454,13 @@ def test_calls_can_be_captured_in_a_graph():
     out = torch.zeros(w.out_shape, dtype=torch.float32, device="cuda")
     din = torch.zeros(w.input_shape, dtype=torch.float32, device="cuda")
     dk = torch.zeros(w.kernel_shape, dtype=torch.float32, device="cuda")
+    half = w.dtype != wl.FP32  # 16-bit operands: the 16-bit input gradient as well
+    din16 = torch.zeros(w.input_shape, dtype=I.dtype, device="cuda") if half else None
     ws = [torch.empty(max(n, 16), dtype=torch.uint8, device="cuda")
           for n in (cc.capscaps_conv_fwd_workspace_bytes(*args),
                     cc.capscaps_conv_bwd_input_workspace_bytes(*args),
-                    cc.capscaps_conv_bwd_kernel_workspace_bytes(*args))]
+                    cc.capscaps_conv_bwd_kernel_workspace_bytes(*args),
+                    cc.capscaps_conv_bwd_input_out16_workspace_bytes(*args) if half else 0)]
 
     def step(st):
         assert cc.capscaps_conv_fwd_ex(I.data_ptr(), K.data_ptr(), out.data_ptr(), *args,
@@ -453,23 +469,29 @@ def test_calls_can_be_captured_in_a_graph():
                                           ws[1].data_ptr(), ws[1].numel(), st) == cc.OK
         assert cc.capscaps_conv_bwd_kernel(I.data_ptr(), G.data_ptr(), dk.data_ptr(), *args,
                                            ws[2].data_ptr(), ws[2].numel(), st) == cc.OK
+        if half:
+            assert cc.capscaps_conv_bwd_input_out16(G.data_ptr(), K.data_ptr(), din16.data_ptr(),
+                                                    *args, ws[3].data_ptr(), ws[3].numel(),
+                                                    st) == cc.OK
 
+    results = (out, din, dk) + ((din16,) if half else ())
     step(torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
-    eager = [t.clone() for t in (out, din, dk)]
+    eager = [t.clone() for t in results]
     side = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.stream(side):
         with torch.cuda.graph(graph, stream=side):
             step(side.cuda_stream)
     for k in range(4):
-        for t in (out, din, dk):
+        for t in results:
             t.fill_(float(k))            # eager work between the replays
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
-        for t, e in zip((out, din, dk), eager):
+        for t, e in zip(results, eager):
             assert torch.equal(t, e), f"replay {k}"
+    assert all(bool(e.isfinite().all()) for e in eager)
 
 
 def test_workspace_too_small_is_refused_before_any_launch():
