@@ -147,10 +147,13 @@ def test_backward_comparison_and_out16_entry_points_reject_bad_shapes(over):
     a16 = _args(**{**over, "dtype": over.get("dtype", cc.FP16)})
     assert cc.capscaps_conv_fwd_out16(FAKE, FAKE, FAKE, *a16, FAKE, big, None) == cc.EINVAL
     assert cc.capscaps_conv_fwd_out16_workspace_bytes(*a16) == 0
+    assert cc.capscaps_conv_bwd_input_out16(FAKE, FAKE, FAKE, *a16, FAKE, big, None) == cc.EINVAL
+    assert cc.capscaps_conv_bwd_input_out16_workspace_bytes(*a16) == 0
 
 
 def test_backward_pointer_and_workspace_checks():
-    a = _args(dtype=cc.FP16, D1=8, D2=8, D3=8)
+    # (enough images for the kernel gradient to cut its contraction: partial sums in the scratch)
+    a = _args(N=40, dtype=cc.FP16, D1=8, D2=8, D3=8)
     need_i = cc.capscaps_conv_bwd_input_workspace_bytes(*a)
     need_k = cc.capscaps_conv_bwd_kernel_workspace_bytes(*a)
     assert need_i > 0 and need_k > 0 and need_i % 256 == 0
@@ -163,6 +166,40 @@ def test_backward_pointer_and_workspace_checks():
     # 16-bit output is for 16-bit operands only
     assert cc.capscaps_conv_fwd_out16(FAKE, FAKE, FAKE, *_args(), FAKE, 1 << 30, None) == cc.EINVAL
     assert cc.capscaps_conv_fwd_out16_workspace_bytes(*_args()) == 0
+
+
+def test_16bit_input_gradient_checks():
+    # fp32 operands are refused; for 16-bit ones the same pointer and workspace rules hold
+    assert cc.capscaps_conv_bwd_input_out16(FAKE, FAKE, FAKE, *_args(), FAKE, 1 << 30, None) == cc.EINVAL
+    assert cc.capscaps_conv_bwd_input_out16_workspace_bytes(*_args()) == 0
+    a = _args(dtype=cc.BF16, D1=8, D2=8, D3=8)
+    need = cc.capscaps_conv_bwd_input_out16_workspace_bytes(*a)
+    assert need > 0 and need % 256 == 0
+    fn = cc.capscaps_conv_bwd_input_out16
+    assert fn(0, FAKE, FAKE, *a, FAKE, need, None) == cc.EINVAL
+    assert fn(FAKE, FAKE, FAKE + 4, *a, FAKE, need, None) == cc.EINVAL
+    assert fn(FAKE, FAKE, FAKE, *a, FAKE, need - 1, None) == cc.EWORKSPACE
+    assert fn(FAKE, FAKE, FAKE, *a, 0, 0, None) == cc.EWORKSPACE
+
+
+def test_kernel_gradient_cuts_its_contraction_to_fill_the_chip():
+    """The 16-bit kernel gradient reads these tensors in place, so its scratch is only the partial
+    sums: (ranges a tap's pixel sequence is cut into) x (kernel tensor in fp32).  Tiles x ranges
+    is to come close to a multiple of the 256 CUs."""
+    def ranges(N, H, W, C, M, k, s, p, D, dtype):
+        a = (N, H, W, C, M, k, k, s, p, 1, D, D, D, dtype)
+        need = cc.capscaps_conv_bwd_kernel_workspace_bytes(*a)
+        kernel_bytes = k * k * C * M * D * D * 4
+        assert need % kernel_bytes == 0
+        return need // kernel_bytes
+    # config 5: 144 tiles (9 taps, 4 x 4 tiles of 256 x 256) x 16 = 9 full rounds
+    assert ranges(64, 32, 32, 64, 64, 3, 1, 1, 16, cc.FP16) == 16
+    # config 3: 9 tiles x 28 = 252 workgroups
+    assert ranges(128, 28, 28, 32, 32, 3, 2, 1, 8, cc.BF16) == 28
+    # 16 channels of 8x8 capsules are 128 rows: two taps per tile, 5 tiles x 51 = 255 workgroups
+    assert ranges(64, 32, 32, 16, 32, 3, 1, 1, 8, cc.BF16) == 51
+    # a layer too small to be worth cutting needs no scratch at all
+    assert cc.capscaps_conv_bwd_kernel_workspace_bytes(2, 6, 6, 4, 4, 3, 3, 1, 1, 1, 8, 8, 8, cc.FP16) == 0
 
 
 def test_scheme2_index_size_and_limits():
