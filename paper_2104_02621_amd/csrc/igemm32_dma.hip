@@ -42,6 +42,15 @@ namespace {
 // share a CU (config 2: 0.877 -> 0.860 ms against three workgroups with a ring of four);
 // elsewhere the compiler's own register budget and the deeper ring of the small stages.
 constexpr int waves_per_simd(int tn, int nw, int kch) { return nw == 4 && tn <= 3 && kch == 2 ? 4 : 1; }
+// The 16-bit-output variants are held to the waves per SIMD their fp32-output twins reach by
+// themselves (32 TN accumulator registers and about 30 others): left alone, the compiler reads
+// all accumulators out for the rounding at once (146 registers more with four column tiles), one
+// wave per SIMD remains, and a layer of 64 channels of 4x4 capsules runs 35 % slower with 16-bit
+// than with fp32 output.
+constexpr int waves_per_simd_out16(int tn, int nw, int kch)
+{
+    return waves_per_simd(tn, nw, kch) > 1 ? waves_per_simd(tn, nw, kch) : tn == 1 ? 6 : tn == 2 ? 4 : 3;
+}
 constexpr int ring_depth(int kch, int tn, int nw) { return kch == 2 && waves_per_simd(tn, nw, kch) == 1 ? 4 : 3; }
 
 // Tag: f32_tag, or a 16-bit tag for capsule rows of 4 halves whose channels a pre-pass has paired
@@ -50,7 +59,7 @@ constexpr int ring_depth(int kch, int tn, int nw) { return kch == 2 && waves_per
 // feeds one 16-bit MFMA 32x32x16 per tile instead of CW fp32 ones.
 // OUT16 (16-bit operands only): the output has the operands' type, rounded at the store.
 template <typename Tag, int CW, int TN, int NW, int KCH, bool OUT16 = false>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(waves_per_simd(TN, NW, KCH)))) void igemm32_dma_kernel(const Dma32Params P)
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(OUT16 ? waves_per_simd_out16(TN, NW, KCH) : waves_per_simd(TN, NW, KCH)))) void igemm32_dma_kernel(const Dma32Params P)
 {
     constexpr bool F32 = std::is_same<Tag, f32_tag>::value;
     static_assert(!(F32 && OUT16), "fp32 operands have fp32 output");
