@@ -65,8 +65,8 @@ struct WgradParams {
     int rows, cols;  // C*D2, M*D3
     int row_tiles, col_tiles, ntaps;
     int tiles;       // ntap_items * D0 * row_tiles * col_tiles
-    int pair;        // 1: at most 128 rows; a tile holds two window taps (see PAIR in the kernel)
-    int ntap_items;  // ntaps, or with pair (ntaps + 1) / 2
+    int nt;          // window taps per tile: 1, or with at most 128 / 64 rows 2 / 4 (see NT in the kernel)
+    int ntap_items;  // ceil(ntaps / nt)
     int nsplit;      // ranges a tap's pixel sequence is cut into
     long long items;      // tiles * nsplit = workgroups
     long long out_elems;  // elements of dK
@@ -105,14 +105,15 @@ __global__ __launch_bounds__(256) void transpose_caps_kernel(const chunk_t* __re
 typedef short short4v __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) short4v lds_short4v;
 
-// PAIR: layers with at most 128 rows (c, d2) would leave half of the 256-row tile empty; their
-// tiles hold two window taps instead, tap 2i in rows 0..127 and tap 2i+1 in rows 128..255.  Both
-// multiply the same output-gradient pixels, so the column side is shared; the row side of the
-// second tap is the input one tap further on, a constant byte distance that travels in the lane
-// offsets of the waves that copy rows 128..255.  The pixels walked are the bounding rectangle of
-// the two taps' rectangles; where a wave's own tap reads outside the image its row-side copies
-// are zero fill (decided per pixel from the walker's row and column counters).
-template <typename Tag, int D1, bool OWN, bool PAIR = false>
+// NT > 1: layers with at most 128 (64) rows (c, d2) would leave half (three quarters) of the
+// 256-row tile empty; their tiles hold NT = 2 (4) consecutive window taps instead, tap NT*i + k in
+// rows k*256/NT onwards.  All multiply the same output-gradient pixels, so the column side is
+// shared; the row side of tap k is the input k taps further on, a constant byte distance that
+// travels in the lane offsets of the waves that copy that tap's rows (a wave copies 64 rows: one
+// tap's).  The pixels walked are the bounding rectangle of the taps' rectangles; where a wave's
+// own tap reads outside the image its row-side copies are zero fill (decided per pixel from the
+// walker's row and column counters).
+template <typename Tag, int D1, bool OWN, int NT = 1>
 __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
 {
     constexpr int KCH = 4, NB = 4;
@@ -137,7 +138,10 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     constexpr int VMCNT_KEEP = 0x0F70 | (KEEP & 15) | ((KEEP >> 4) << 14);
     static_assert(D1 == 1 || D1 == 2 || D1 == 4 || D1 == 8 || D1 == 16, "D1");
     static_assert(NMMA == 16 && KCH == 4, "the schedule below is written for this shape");
-    static_assert(!PAIR || (OWN && !VW && WM == 128), "tap pairs: in-place reads, scalar walk");
+    constexpr bool PAIR = NT > 1;
+    constexpr int RT = BM / NT;  // tile rows per tap
+    static_assert(NT == 1 || NT == 2 || NT == 4, "taps per tile");
+    static_assert(!PAIR || (OWN && !VW && WM == 128), "several taps per tile: in-place reads, scalar walk");
 
     extern __shared__ char smem[];
 
@@ -155,17 +159,16 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     rest /= P.col_tiles;
     const int row_tile = rest % P.row_tiles;
     rest /= P.row_tiles;
-    const int tap = (PAIR ? 2 : 1) * (rest % P.ntap_items);
+    const int tap = NT * (rest % P.ntap_items);
     const int d0 = rest / P.ntap_items;
     const int tp = tap / P.kw, tq = tap - tp * P.kw;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    // (tap pairs) the second tap, and whether this wave copies its rows
-    const int tap_b = tap + 1;
-    const bool has_b = PAIR && tap_b < P.ntaps;
-    const int tp_b = tap_b / P.kw, tq_b = tap_b - tp_b * P.kw;
-    const bool copies_b = PAIR && wave >= 2;
+    // (several taps per tile) the tap whose rows this wave copies
+    const int k_mine = PAIR ? wave * NT / 4 : 0;
+    const int tap_m = tap + k_mine;
+    const int tp_m = tap_m / P.kw, tq_m = tap_m - tp_m * P.kw;
     const int wm = wave % NWM, wn = wave / NWM;
     const int h = lane >> 5, lr = lane & 31;
 
@@ -205,27 +208,40 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
                 xh = yh = -1;
             }
         };
-        int axl, axh, ayl, ayh, bxl = 0, bxh = -1, byl = 0, byh = -1;
-        tap_rect(tp, tq, axl, axh, ayl, ayh);
-        if (has_b) tap_rect(tp_b, tq_b, bxl, bxh, byl, byh);
-        const bool ea = axh < axl, eb = bxh < bxl;
-        int x_hi, y_hi;
-        if (ea || eb) {  // one rectangle (or none)
-            x_lo = ea ? bxl : axl; x_hi = ea ? bxh : axh;
-            y_lo = ea ? byl : ayl; y_hi = ea ? byh : ayh;
-        } else {
-            x_lo = axl < bxl ? axl : bxl; x_hi = axh > bxh ? axh : bxh;
-            y_lo = ayl < byl ? ayl : byl; y_hi = ayh > byh ? ayh : byh;
+        // bounding rectangle of the taps that exist and meet the image; this wave's own rectangle
+        int x_hi = -1, y_hi = -1, mxl = 0, mxh = -1, myl = 0, myh = -1;
+        x_lo = y_lo = 0;
+        bool any = false;
+#pragma unroll
+        for (int k = 0; k < NT; ++k) {
+            const int tk = tap + k;
+            if (tk >= P.ntaps) break;
+            int xl, xh, yl, yh;
+            tap_rect(tk / P.kw, tk % P.kw, xl, xh, yl, yh);
+            if (k == k_mine) {
+                mxl = xl; mxh = xh; myl = yl; myh = yh;
+            }
+            if (xh < xl) continue;
+            if (!any) {
+                x_lo = xl; x_hi = xh; y_lo = yl; y_hi = yh;
+                any = true;
+            } else {
+                x_lo = xl < x_lo ? xl : x_lo; x_hi = xh > x_hi ? xh : x_hi;
+                y_lo = yl < y_lo ? yl : y_lo; y_hi = yh > y_hi ? yh : y_hi;
+            }
         }
         nx = x_hi - x_lo + 1;
         ny = y_hi - y_lo + 1;
         if (nx <= 0 || ny <= 0) nx = ny = 0;
-        const int mxl = copies_b ? bxl : axl, mxh = copies_b ? bxh : axh;
-        const int myl = copies_b ? byl : ayl, myh = copies_b ? byh : ayh;
         // pixel (x, y) of the walk has nx - (x - x_lo) rows and ny - (y - y_lo) pixels left
         pv_xa = nx - (mxl - x_lo); pv_xb = nx - (mxh - x_lo);
         pv_ya = ny - (myl - y_lo); pv_yb = ny - (myh - y_lo);
         if (mxh < mxl) pv_xa = -1;  // never
+        // all of these are the same in every lane; say so (they feed scalar instructions)
+        x_lo = __builtin_amdgcn_readfirstlane(x_lo); y_lo = __builtin_amdgcn_readfirstlane(y_lo);
+        nx = __builtin_amdgcn_readfirstlane(nx); ny = __builtin_amdgcn_readfirstlane(ny);
+        pv_xa = __builtin_amdgcn_readfirstlane(pv_xa); pv_xb = __builtin_amdgcn_readfirstlane(pv_xb);
+        pv_ya = __builtin_amdgcn_readfirstlane(pv_ya); pv_yb = __builtin_amdgcn_readfirstlane(pv_yb);
     }
     const long long rect = (long long)nx * ny, total = rect * P.N;
     const long long tps = (total + P.nsplit - 1) / P.nsplit;
@@ -246,9 +262,9 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     const int i_rowjump = (s * P.W - (ny - 1) * s) * ipix, g_rowjump = (P.Wo - (ny - 1)) * gpix;
     const int i_imgjump = (P.H * P.W - nx * s * P.W) * ipix, g_imgjump = (P.Ho * P.Wo - nx * P.Wo) * gpix;
     // one walker over the pixel sequence with a position in either tensor
-    // (tap pairs) the walker follows the first tap's input pixel, which at the border lies up to
-    // `pad` rows and pixels before the image, and the second tap's lies up to kw - 1 pixels before
-    // that one: the descriptor's base is moved down by both, and the offsets up, so that all stay
+    // (several taps per tile) the walker follows the first tap's input pixel, which at the border
+    // lies up to `pad` rows and pixels before the image, and a later tap's lies up to kw - 1 pixels
+    // before that one: the descriptor's base is moved down by both, and the offsets up, so that all stay
     // non-negative.  Only offsets of pixels inside an image are ever dereferenced.
     const int bias_walk = PAIR ? (P.pad * P.W + P.pad) * ipix : 0;
     const int bias_lane = PAIR ? P.kw * ipix : 0;
@@ -283,11 +299,11 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     if constexpr (OWN) {
         const int ra = a_wide ? (lane >> 4) * 2 + (lane & 1) : lane >> 3;
         const int la = (a_wide ? (lane & 15) >> 1 : lane & 7) ^ (((ra >> 1) & 1) * 4);
-        // (tap pairs: rows 128..255 are rows 0..127 of the second tap.  There the lanes of rows
+        // (several taps per tile: the wave's 64 rows are rows of its own tap.  There the lanes of rows
         // past the last one copy row 0 again instead of carrying the out-of-range mark -- those
         // tile rows are never stored -- so that a lane offset plus a pixel's out-of-range mark
         // can never wrap around to the bytes before the tensor that the moved base covers.)
-        const int R_pair = ((wave & 1) * 8 + ra) * 8;
+        const int R_pair = (wave * 64 + ra * 8) % RT;
         const int R = PAIR ? (R_pair < P.rows ? R_pair : 0) : row_tile * BM + (wave * 8 + ra) * 8;
         const int c = R / P.D2, d2 = R - c * P.D2;
         if constexpr (VW) {
@@ -303,9 +319,9 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
         } else
             a_voff = R < P.rows ? (unsigned)(((((c * P.D0 + d0) * D1 + la) * P.D2) + d2) * 2) : (unsigned)OOB;
         if constexpr (PAIR) {
-            // the second tap's input pixel relative to the first one's
-            const int delta = ((tp_b - tp) * P.W + (tq_b - tq)) * ipix;
-            a_voff += (unsigned)(bias_lane + (copies_b ? delta : 0));
+            // this wave's tap's input pixel relative to the first tap's
+            const int delta = ((tp_m - tp) * P.W + (tq_m - tq)) * ipix;
+            a_voff += (unsigned)(bias_lane + delta);
         }
         const int rb = b_wide ? (lane >> 4) * 2 + (lane & 1) : lane >> 3;
         const int lb = (b_wide ? (lane & 15) >> 1 : lane & 7) ^ (((rb >> 1) & 1) * 4);
@@ -672,9 +688,10 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     const long long caps = (long long)P.D0 * P.D2 * P.D3;
 #pragma unroll
     for (int b = 0; b < TM; ++b) {
-        // (tap pairs: the waves of rows 128..255 hold the second tap's rows 0..127)
-        const int R = PAIR ? b * 32 + lr : row_tile * BM + wm * WM + b * 32 + lr;
-        const int tap_out = PAIR ? tap + wm : tap;
+        // (several taps per tile: tile row Rt is row Rt % RT of tap Rt / RT)
+        const int Rt = wm * WM + b * 32 + lr;
+        const int R = PAIR ? Rt % RT : row_tile * BM + Rt;
+        const int tap_out = PAIR ? tap + Rt / RT : tap;
         if (R >= P.rows || tap_out >= P.ntaps) continue;
         const int c = R / P.D2, d2 = R - c * P.D2;
         float* orow = out + ((long long)tap_out * P.C + c) * P.M * caps +
@@ -702,13 +719,16 @@ struct WgradPlan {
 
 int ceil_div_i(long long a, long long b) { return (int)((a + b - 1) / b); }
 
-// Shapes whose tiles can hold two window taps (PAIR in the kernel)
-bool tap_pairs_possible(const ConvShape& s)
+// Window taps a tile can hold (NT in the kernel): 4 with at most 64 rows, 2 with at most 128
+int taps_per_tile(const ConvShape& s)
 {
     const bool paired4 = s.D1 == 4 && s.D2 == 4 && s.D3 == 4 && s.C % 2 == 0 && s.M % 2 == 0;
     const bool in_place = s.D2 % 8 == 0 && s.D3 % 8 == 0;
-    return (s.D1 == 4 || s.D1 == 8 || s.D1 == 16) && (in_place || paired4) &&
-           s.C * s.D2 <= 128 && s.kh * s.kw >= 2;
+    if (!((s.D1 == 4 || s.D1 == 8 || s.D1 == 16) && (in_place || paired4))) return 1;
+    const long long rows = (long long)s.C * s.D2, ntaps = (long long)s.kh * s.kw;
+    if (rows <= 64 && ntaps >= 3) return 4;
+    if (rows <= 128 && ntaps >= 2) return 2;
+    return 1;
 }
 
 // Tiles and the split over images (host side, pure arithmetic).
@@ -728,12 +748,15 @@ WgradPlan make_plan(const ConvShape& s)
     P.gt_img_bytes = (long long)s.Ho * s.Wo * s.M * s.D0 * s.D1 * s.D3 * 2;
     pl.it_bytes = (size_t)s.N * P.it_img_bytes;
     pl.gt_bytes = (size_t)s.N * P.gt_img_bytes;
-    // Two window taps per tile where the rows fill at most half of it (tensors read in place or
+    // Two or four window taps per tile where the rows fill at most half or a quarter of it (tensors read in place or
     // as channel-paired copies, capsules of 4, 8 or 16 rows); the byte offsets, moved up by the
     // reach of the padding and of the window's width, must still fit 31 bits for one image.
     const long long pair_bias = ((long long)s.pad * s.W + s.pad + s.kw) * s.C * s.D0 * s.D1 * s.D2 * 2;
-    P.pair = tap_pairs_possible(s) && P.it_img_bytes + 2 * pair_bias < (1LL << 31) - (1 << 20) ? 1 : 0;
-    P.ntap_items = P.pair ? (P.ntaps + 1) / 2 : P.ntaps;
+    P.nt = P.it_img_bytes + 2 * pair_bias + 3 * (long long)s.W * s.C * s.D0 * s.D1 * s.D2 * 2 <
+                   (1LL << 31) - (1 << 20)
+               ? taps_per_tile(s)
+               : 1;
+    P.ntap_items = (P.ntaps + P.nt - 1) / P.nt;
     P.tiles = P.ntap_items * s.D0 * P.row_tiles * P.col_tiles;
 
     // Ranges per tap: the cost of a choice is (rounds of 256 workgroups) x (pixels per workgroup
@@ -741,7 +764,9 @@ WgradPlan make_plan(const ConvShape& s)
     // pixels touches at most N/nsplit + 2 images, whose byte offsets must stay below 2^31 (where
     // two images already exceed that, every range is one image); the partial sums stay below 1 GiB.
     const long long img_max = P.it_img_bytes > P.gt_img_bytes ? P.it_img_bytes : P.gt_img_bytes;
-    const long long room = (1LL << 31) - 1 - (P.pair ? 2 * pair_bias + (1 << 20) : 0);
+    const long long room =
+        (1LL << 31) - 1 -
+        (P.nt > 1 ? 2 * pair_bias + 3 * (long long)s.W * s.C * s.D0 * s.D1 * s.D2 * 2 + (1 << 20) : 0);
     const long long imgs_cap = room / (img_max > 0 ? img_max : 1);  // images a range may touch
     const double pix_total = (double)s.N * s.Ho * s.Wo;
     const double fixed = 1120.0 / s.D1;  // D1 = 16: 70 pixels
@@ -790,10 +815,10 @@ hipError_t launch_transpose(const void* src, void* dst, size_t nmat, int A, int 
     return hipGetLastError();
 }
 
-template <typename Tag, int D1, bool OWN, bool PAIR = false>
+template <typename Tag, int D1, bool OWN, int NT = 1>
 hipError_t launch_kernel(const WgradParams& P, hipStream_t stream)
 {
-    auto kern = wgrad16_kernel<Tag, D1, OWN, PAIR>;
+    auto kern = wgrad16_kernel<Tag, D1, OWN, NT>;
     const size_t lds_bytes = (size_t)4 * 2 * 4 * 256 * 16;  // ring of 4 stages of 32 KB
     static std::atomic<unsigned long long> lds_set{0};
     hipError_t err = set_dynamic_lds_once(reinterpret_cast<const void*>(kern), (int)lds_bytes, lds_set);
@@ -876,16 +901,26 @@ hipError_t launch_wgrad16(const ConvShape& s, const void* input, const void* dou
         pl.P.gt = gt;
     }
     pl.P.out = pl.P.nsplit > 1 ? partial : dkernel;
-    if (pl.P.pair) {  // two window taps per tile
+    if (pl.P.nt == 4) {  // four window taps per tile
         if (s.D1 == 4)
-            err = s.dtype == 2 ? launch_kernel<f16_tag, 4, true, true>(pl.P, stream)
-                               : launch_kernel<bf16_tag, 4, true, true>(pl.P, stream);
+            err = s.dtype == 2 ? launch_kernel<f16_tag, 4, true, 4>(pl.P, stream)
+                               : launch_kernel<bf16_tag, 4, true, 4>(pl.P, stream);
         else if (s.D1 == 8)
-            err = s.dtype == 2 ? launch_kernel<f16_tag, 8, true, true>(pl.P, stream)
-                               : launch_kernel<bf16_tag, 8, true, true>(pl.P, stream);
+            err = s.dtype == 2 ? launch_kernel<f16_tag, 8, true, 4>(pl.P, stream)
+                               : launch_kernel<bf16_tag, 8, true, 4>(pl.P, stream);
         else
-            err = s.dtype == 2 ? launch_kernel<f16_tag, 16, true, true>(pl.P, stream)
-                               : launch_kernel<bf16_tag, 16, true, true>(pl.P, stream);
+            err = s.dtype == 2 ? launch_kernel<f16_tag, 16, true, 4>(pl.P, stream)
+                               : launch_kernel<bf16_tag, 16, true, 4>(pl.P, stream);
+    } else if (pl.P.nt == 2) {  // two window taps per tile
+        if (s.D1 == 4)
+            err = s.dtype == 2 ? launch_kernel<f16_tag, 4, true, 2>(pl.P, stream)
+                               : launch_kernel<bf16_tag, 4, true, 2>(pl.P, stream);
+        else if (s.D1 == 8)
+            err = s.dtype == 2 ? launch_kernel<f16_tag, 8, true, 2>(pl.P, stream)
+                               : launch_kernel<bf16_tag, 8, true, 2>(pl.P, stream);
+        else
+            err = s.dtype == 2 ? launch_kernel<f16_tag, 16, true, 2>(pl.P, stream)
+                               : launch_kernel<bf16_tag, 16, true, 2>(pl.P, stream);
     } else if (s.D1 == 4) {  // in place, or on the channel-paired copies
         err = s.dtype == 2 ? launch_kernel<f16_tag, 4, true>(pl.P, stream)
                            : launch_kernel<bf16_tag, 4, true>(pl.P, stream);

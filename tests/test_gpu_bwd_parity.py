@@ -133,7 +133,7 @@ BWD_SHAPES = SMALL_SHAPES + [
     ("ph16_d4", 14, 80, 78, 4, 8, 3, 3, 2, 1, 1, 4, 4, 4),
     ("ph16_ns", 10, 60, 62, 6, 4, 3, 3, 2, 1, 1, 8, 16, 8),
     ("ph32_d3", 8, 100, 97, 5, 6, 4, 4, 3, 2, 3, 3, 3, 3),
-    # at most 128 rows (c, d2): the 16-bit kernel gradient puts two window taps into a tile.  A 5x5
+    # at most 128 rows (c, d2): the 16-bit kernel gradient puts several window taps into a tile.  A 5x5
     # window with padding 2 (25 taps: the last pair has one; neighbouring taps' pixel ranges
     # differ by up to two), stride 3 with a leading capsule index and 16-row capsules, an image
     # narrower than the window (the next row's first tap lies before the previous row's last),
@@ -145,6 +145,21 @@ BWD_SHAPES = SMALL_SHAPES + [
     ("wgp_1x1", 2, 1, 1, 3, 2, 5, 5, 1, 2, 1, 4, 8, 8),
     ("wgp_44", 3, 9, 8, 6, 4, 3, 3, 2, 1, 1, 4, 4, 4),
     ("wgp_128", 2, 7, 7, 16, 3, 1, 2, 1, 0, 1, 8, 8, 8),
+    # (the shapes above with at most 64 rows take four taps per tile.)  Two taps per tile with
+    # 65 .. 128 rows: 96 rows at stride 2, 80 rows of 16-wide capsules under a 5x5 window, a 1x1
+    # image, and a two-tap window on few rows
+    ("wgp_r96", 2, 8, 7, 12, 5, 3, 3, 2, 1, 1, 8, 8, 8),
+    ("wgp_r80k5", 2, 6, 7, 5, 3, 5, 5, 1, 2, 1, 8, 16, 8),
+    ("wgp_1x1b", 2, 1, 1, 9, 2, 5, 5, 1, 2, 1, 4, 8, 8),
+    ("wgq_1x2", 2, 7, 7, 4, 3, 1, 2, 1, 0, 1, 8, 8, 8),
+    # four taps per tile: 9 taps in tiles of 4, 4 and 1; 25 taps at stride 2 with a leading
+    # capsule index and 16-row capsules; channel-paired 4x4 capsules; a three-tap window; many
+    # images (pixel ranges that begin inside an image)
+    ("wgq_k3", 3, 9, 8, 4, 5, 3, 3, 1, 1, 1, 8, 8, 8),
+    ("wgq_k5s2", 2, 9, 10, 2, 3, 5, 5, 2, 2, 2, 16, 16, 8),
+    ("wgq_44", 3, 9, 8, 8, 4, 3, 3, 1, 1, 1, 4, 4, 4),
+    ("wgq_1x3", 2, 6, 9, 3, 4, 1, 3, 1, 1, 1, 8, 8, 8),
+    ("wgq_many", 90, 7, 6, 4, 4, 3, 3, 1, 1, 1, 8, 8, 8),
 ]
 
 
