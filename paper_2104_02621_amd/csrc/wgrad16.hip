@@ -14,11 +14,12 @@
 // values a matrix instruction wants side by side are then 16 or 32 contiguous bytes, and for
 // one pixel the 256 rows (or columns) of a tile are one contiguous run (D0 = 1) of It (Gt).
 //
-// A workgroup owns one 256 x 256 tile of one tap and a range of images (the K loop is split
-// over images when the tiles alone do not fill the chip; partial sums go to scratch and are
-// added in a fixed order by a second kernel).  It walks the valid output pixels of its tap, a
-// rectangle per image, so no multiplication by padding zeros is done and any stride costs the
-// same.  A K stage is 32 contracted values = 32/D1 pixels; per stage each wave copies 64 rows
+// A workgroup owns one 256 x 256 tile of one tap (of two or four taps where the rows fill at
+// most half or a quarter of it: see NT at the kernel) and a range of the tap's pixel sequence
+// (the valid output pixels, a rectangle per image, image after image; the sequence is cut into
+// equal ranges when the tiles alone do not fill the chip; partial sums go to scratch and are
+// added in a fixed order by a second kernel).  It walks only those pixels, so no multiplication
+// by padding zeros is done and any stride costs the same.  A K stage is 32 contracted values = 32/D1 pixels; per stage each wave copies 64 rows
 // and 64 columns (4 x 1 KB each) straight into LDS with buffer loads whose scalar offset is
 // the pixel.  The K loop has the shape of the tuned forward kernel's: a ring of 4 LDS stages,
 // operand fragments double-buffered in registers, one barrier per stage, copies and the scalar
@@ -146,7 +147,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     extern __shared__ char smem[];
 
     // ---- which item.  Consecutive workgroups go to the 8 XCDs in turn; each XCD is handed a
-    // contiguous range of items, ordered image range slowest, then tap, then tile, so the
+    // contiguous range of items, ordered pixel range slowest, then tap, then tile, so the
     // workgroups resident on one XCD at a time read the same pixels of It and Gt through its L2.
     long long item = blockIdx.x;
     {
@@ -178,7 +179,7 @@ __global__ __launch_bounds__(256) void wgrad16_kernel(const WgradParams P)
     // range [t0, t1), which begins at pixel (xs, ys) of the rectangle of image n0.
     const int s = P.stride;
     int nx, ny, x_lo, y_lo;
-    // (tap pairs) this wave's own tap lies inside the image where the walker's counters satisfy
+    // (several taps per tile) this wave's own tap lies inside the image where the walker's counters satisfy
     // xb <= rows left <= xa and yb <= pixels left in the row <= ya
     int pv_xa = 0, pv_xb = 0, pv_ya = 0, pv_yb = 0;
     if constexpr (!PAIR) {
