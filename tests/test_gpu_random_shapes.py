@@ -81,6 +81,30 @@ def random_mixed16_shape(seed):
             return dtype, (N, H, W, C, M, kh, kw, s, p, 1, D1, D2, D3)
 
 
+def random_few_rows_shape(seed):
+    """A 16-bit layer with at most 128 rows (c, d2), for the kernel gradient's tiles of two or four
+    window taps: windows up to 5x5, strides up to 3, paddings up to 3, one to many images (pixel
+    ranges that begin inside an image), 4x4 capsules with paired channels among them."""
+    rng = np.random.default_rng(99000 + seed)
+    while True:
+        if rng.random() < 0.25:
+            D1 = D2 = D3 = 4
+            C, M = 2 * int(rng.integers(1, 17)), 2 * int(rng.integers(1, 9))
+        else:
+            D1, D2, D3 = int(rng.choice([4, 8, 16])), int(rng.choice([8, 16, 24])), int(rng.choice([8, 16]))
+            C, M = int(rng.integers(1, 128 // D2 + 1)), int(rng.integers(1, 12))
+        kh, kw = int(rng.integers(1, 6)), int(rng.integers(1, 6))
+        s, p = int(rng.integers(1, 4)), int(rng.integers(0, 4))
+        H, W = int(rng.integers(1, 15)), int(rng.integers(1, 15))
+        if kh > H + 2 * p or kw > W + 2 * p:
+            continue
+        N = int(rng.choice([1, 2, 3, 7, 40, 130]))
+        D0 = int(rng.choice([1, 1, 2]))
+        Ho, Wo = (H + 2 * p - kh) // s + 1, (W + 2 * p - kw) // s + 1
+        if 2.0 * N * Ho * Wo * M * D0 * D1 * D3 * kh * kw * C * D2 <= 4e8:
+            return [wl.BF16, wl.FP16][seed % 2], (N, H, W, C, M, kh, kw, s, p, D0, D1, D2, D3)
+
+
 SEEDS = list(range(60))
 MEDIUM_SEEDS = list(range(15))
 MIXED16_SEEDS = list(range(14))
@@ -111,4 +135,12 @@ def test_random_mixed_16bit_layer_forward_and_gradients(seed):
     w = small("randx%d_" % seed + "x".join(map(str, shape)), dtype, *shape, seed=900 + seed)
     print(w.name, cc.capscaps_select_path(*shape, dtype), flush=True)
     full_compare(w, cc.PATH_AUTO)
+    both_gradients(w)
+
+
+@pytest.mark.parametrize("seed", list(range(40)))
+def test_random_few_rows_16bit_layer_gradients(seed):
+    dtype, shape = random_few_rows_shape(seed)
+    w = small("randr%d_" % seed + "x".join(map(str, shape)), dtype, *shape, seed=950 + seed)
+    print(w.name, flush=True)
     both_gradients(w)
