@@ -88,6 +88,9 @@ LANE_PER_ROW_SHAPES = [
     ("o4x4", 12, 40, 40, 8, 8, 3, 3, 1, 1, 1, 4, 4, 4),
     ("o4x8", 12, 40, 40, 6, 5, 3, 3, 1, 1, 1, 4, 8, 16),
     ("o384", 6, 40, 40, 8, 48, 3, 3, 1, 1, 1, 8, 8, 8),
+    # ... 64 and 128 columns (two and four 32-column tiles per wave)
+    ("o4x4c64", 12, 40, 40, 8, 16, 3, 3, 1, 1, 1, 4, 4, 4),
+    ("o4x4c128", 12, 40, 40, 8, 32, 3, 3, 1, 1, 1, 4, 4, 4),
 ]
 SHAPES = SMALL_SHAPES + TUNED_SHAPES + LANE_PER_ROW_SHAPES
 
